@@ -1,0 +1,272 @@
+// Routing and Dispatch bookkeeping kernels (paper Section 2.2 "top-k routing" and
+// Dispatch; Section 5.1 "routing-derived offsets").
+//
+// Three steps, each a device function so that the serialized launches and the
+// persistent scheduler run the same code:
+//   route_chunk  top-k + softmax for the 64 tokens of a chunk, per-chunk expert histogram
+//   scan_all     prefix sums over chunks and experts, counts/offsets, M-tile map
+//   rank_chunk   stable row of every local slot, inverse maps
+// The permutation is a stable counting sort keyed by expert: rows of one expert
+// ascend in token id, so every index is a pure function of the routing result
+// (no atomics decide an order).
+#pragma once
+#include "common.h"
+
+namespace moe {
+
+struct RouteParams {
+  const float* logits;   // [T,E]
+  int32_t* topk_idx;     // [T,k]
+  float* topk_w;         // [T,k]
+  int32_t* counts;       // [E_local]
+  int32_t* offsets;      // [E_local+1]
+  int32_t* row_of;       // [T,k]
+  int32_t* token_of;     // [R_max]
+  int32_t* slot_of;      // [R_max]
+  int32_t* chunk_cnt;    // [n_chunks, E_local]  histogram, then exclusive offsets
+  TileMap tiles;
+  int T, E, E_local, expert_base, k, n_chunks, BM;
+};
+
+// Monotone map float -> uint32 (larger float = larger key); -0.0 and NaN are
+// canonicalised first (-0.0 ties with +0.0, NaN ranks as -inf).
+__device__ __forceinline__ uint32_t float_order_key(float v) {
+  if (v != v) v = -__builtin_huge_valf();
+  if (v == 0.0f) v = 0.0f;
+  uint32_t u = __builtin_bit_cast(uint32_t, v);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float float_from_order_key(uint32_t k) {
+  uint32_t u = (k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k;
+  return __builtin_bit_cast(float, u);
+}
+
+__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    uint64_t o = __shfl_xor(v, off, kWave);
+    v = o > v ? o : v;
+  }
+  return v;
+}
+
+// Top-k of one token by one wave.  Key = (ordered logit << 32) | ~expert id, so
+// the wave maximum is the largest logit and, among equal logits, the lowest id.
+// Lane j < k ends up holding slot j.
+__device__ __forceinline__ void route_token(const RouteParams& p, int t, int lane, int32_t* s_idx) {
+  const float* row = p.logits + (size_t)t * p.E;
+  uint64_t key[kMaxE / kWave];
+#pragma unroll
+  for (int i = 0; i < kMaxE / kWave; ++i) {
+    int e = lane + i * kWave;
+    key[i] = 0;
+    if (e < p.E) key[i] = ((uint64_t)float_order_key(row[e]) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)e);
+  }
+  float my_val = 0.f;
+  int my_idx = 0;
+  for (int j = 0; j < p.k; ++j) {
+    uint64_t best = key[0];
+#pragma unroll
+    for (int i = 1; i < kMaxE / kWave; ++i) best = key[i] > best ? key[i] : best;
+    best = wave_max_u64(best);
+    int e = (int)(0xFFFFFFFFu - (uint32_t)best);
+#pragma unroll
+    for (int i = 0; i < kMaxE / kWave; ++i)
+      if (key[i] == best) key[i] = 0;   // keys are unique (they embed the id)
+    if (lane == j) {
+      my_val = float_from_order_key((uint32_t)(best >> 32));
+      my_idx = e;
+    }
+  }
+  // softmax over the k selected logits; slot 0 holds the maximum
+  float m = __shfl(my_val, 0, kWave);
+  float pj = lane < p.k ? expf(my_val - m) : 0.f;
+  float sum = pj;
+#pragma unroll
+  for (int off = 8; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, kWave);  // k <= 16 lanes hold mass
+  sum = __shfl(sum, 0, kWave);
+  if (lane < p.k) {
+    p.topk_idx[(size_t)t * p.k + lane] = my_idx;
+    p.topk_w[(size_t)t * p.k + lane] = pj / sum;
+    s_idx[lane] = my_idx;
+  }
+}
+
+// Bitmask of the local experts a token selected, from its k indices.
+__device__ __forceinline__ void local_mask(const int32_t* idx, int k, int base, int E_local,
+                                           uint64_t mask[kMaskWords]) {
+#pragma unroll
+  for (int w = 0; w < kMaskWords; ++w) mask[w] = 0;
+  for (int j = 0; j < k; ++j) {
+    int le = idx[j] - base;
+    if (le >= 0 && le < E_local) {
+      uint64_t bit = 1ull << (le & 63);
+#pragma unroll
+      for (int w = 0; w < kMaskWords; ++w)
+        if ((le >> 6) == w) mask[w] |= bit;
+    }
+  }
+}
+
+// One chunk of kChunk tokens by a workgroup of 512 threads (8 waves x 8 tokens),
+// then wave 0 (lane = token) builds the chunk's histogram with ballots.
+// s_idx: kChunk*kMaxK int32 of LDS.
+__device__ __forceinline__ void route_chunk(const RouteParams& p, int chunk, int32_t* s_idx) {
+  const int lane = lane_id();
+  const int wave = threadIdx.x / kWave;
+  const int n_waves = blockDim.x / kWave;
+  const int t0 = chunk * kChunk;
+  for (int i = wave; i < kChunk; i += n_waves) {
+    int t = t0 + i;
+    if (t < p.T) route_token(p, t, lane, s_idx + i * kMaxK);
+  }
+  __syncthreads();
+  if (wave == 0) {
+    uint64_t mask[kMaskWords];
+    int t = t0 + lane;
+    local_mask(s_idx + lane * kMaxK, t < p.T ? p.k : 0, p.expert_base, p.E_local, mask);
+    int32_t* out = p.chunk_cnt + (size_t)chunk * p.E_local;
+#pragma unroll
+    for (int w = 0; w < kMaskWords; ++w) {
+      if (w * 64 >= p.E_local) break;
+      int n = min(64, p.E_local - w * 64);
+      int cnt = 0;
+      for (int b = 0; b < n; ++b) {
+        uint64_t bal = __ballot((mask[w] >> b) & 1);
+        if (lane == b) cnt = __popcll(bal);
+      }
+      if (lane < n) out[w * 64 + lane] = cnt;
+    }
+  }
+  __syncthreads();
+}
+
+__device__ __forceinline__ int wave_incl_scan(int v, int lane) {
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    int o = __shfl_up(v, off, kWave);
+    if (lane >= off) v += o;
+  }
+  return v;
+}
+
+// Whole-problem scan by ONE workgroup: chunk histograms -> exclusive chunk
+// offsets (in place), counts, offsets, M-tile map.  s_cnt: (kMaxE + 2) int32 of LDS.
+__device__ __forceinline__ void scan_all(const RouteParams& p, int32_t* s_cnt) {
+  const int lane = lane_id();
+  const int wave = threadIdx.x / kWave;
+  const int n_waves = blockDim.x / kWave;
+  for (int e = wave; e < p.E_local; e += n_waves) {
+    int running = 0;
+    for (int c0 = 0; c0 < p.n_chunks; c0 += kWave) {
+      int c = c0 + lane;
+      int v = c < p.n_chunks ? p.chunk_cnt[(size_t)c * p.E_local + e] : 0;
+      int incl = wave_incl_scan(v, lane);
+      if (c < p.n_chunks) p.chunk_cnt[(size_t)c * p.E_local + e] = running + incl - v;
+      running += __shfl(incl, kWave - 1, kWave);
+    }
+    if (lane == 0) s_cnt[e] = running;
+  }
+  __syncthreads();
+  if (wave == 0) {
+    int row_run = 0, tile_run = 0;
+    for (int e0 = 0; e0 < p.E_local; e0 += kWave) {
+      int e = e0 + lane;
+      int c = e < p.E_local ? s_cnt[e] : 0;
+      int nt = (c + p.BM - 1) / p.BM;
+      int row_incl = wave_incl_scan(c, lane);
+      int tile_incl = wave_incl_scan(nt, lane);
+      int off = row_run + row_incl - c;
+      int tbase = tile_run + tile_incl - nt;
+      if (e < p.E_local) {
+        p.counts[e] = c;
+        p.offsets[e] = off;
+        for (int i = 0; i < nt; ++i) {
+          p.tiles.expert[tbase + i] = e;
+          p.tiles.row0[tbase + i] = off + i * p.BM;
+          p.tiles.rows[tbase + i] = min(p.BM, c - i * p.BM);
+        }
+      }
+      row_run += __shfl(row_incl, kWave - 1, kWave);
+      tile_run += __shfl(tile_incl, kWave - 1, kWave);
+    }
+    if (lane == 0) {
+      p.offsets[p.E_local] = row_run;
+      p.tiles.meta[kMetaMTiles] = tile_run;
+      p.tiles.meta[kMetaRows] = row_run;
+      p.tiles.meta[kMetaStatus] = 0;
+    }
+  }
+}
+
+// Rows of the local slots of one chunk, by one wave (lane = token):
+// row = offsets[e] + (tokens of earlier chunks selecting e) + (earlier lanes selecting e).
+__device__ __forceinline__ void rank_chunk(const RouteParams& p, int chunk) {
+  const int lane = lane_id();
+  const int t = chunk * kChunk + lane;
+  const bool live = t < p.T;
+  int32_t idx[kMaxK], row[kMaxK];
+#pragma unroll
+  for (int j = 0; j < kMaxK; ++j) {
+    idx[j] = (live && j < p.k) ? p.topk_idx[(size_t)t * p.k + j] : -1;
+    row[j] = -1;
+  }
+  uint64_t mask[kMaskWords];
+#pragma unroll
+  for (int w = 0; w < kMaskWords; ++w) mask[w] = 0;
+#pragma unroll
+  for (int j = 0; j < kMaxK; ++j) {
+    int le = idx[j] - p.expert_base;
+    if (idx[j] >= 0 && le >= 0 && le < p.E_local) {
+#pragma unroll
+      for (int w = 0; w < kMaskWords; ++w)
+        if ((le >> 6) == w) mask[w] |= 1ull << (le & 63);
+    }
+  }
+  const int32_t* coff = p.chunk_cnt + (size_t)chunk * p.E_local;
+  const uint64_t lt = (1ull << lane) - 1ull;
+#pragma unroll
+  for (int w = 0; w < kMaskWords; ++w) {
+    if (w * 64 >= p.E_local) break;
+    int n = min(64, p.E_local - w * 64);
+    for (int b = 0; b < n; ++b) {
+      bool sel = (mask[w] >> b) & 1;
+      uint64_t bal = __ballot(sel);
+      if (bal == 0) continue;
+      int e = w * 64 + b;
+      int base_row = p.offsets[e] + coff[e];
+      if (sel) {
+        int r = base_row + __popcll(bal & lt);
+        int ge = e + p.expert_base;
+        int slot = 0;
+#pragma unroll
+        for (int j = 0; j < kMaxK; ++j)
+          if (idx[j] == ge) { row[j] = r; slot = j; }
+        p.token_of[r] = t;
+        p.slot_of[r] = slot;
+      }
+    }
+  }
+  if (live) {
+#pragma unroll
+    for (int j = 0; j < kMaxK; ++j)
+      if (j < p.k) p.row_of[(size_t)t * p.k + j] = row[j];
+  }
+}
+
+__global__ __launch_bounds__(512) void route_kernel(RouteParams p) {
+  __shared__ int32_t s_idx[kChunk * kMaxK];
+  route_chunk(p, blockIdx.x, s_idx);
+}
+
+__global__ __launch_bounds__(1024) void scan_kernel(RouteParams p) {
+  __shared__ int32_t s_cnt[kMaxE + 2];
+  scan_all(p, s_cnt);
+}
+
+__global__ __launch_bounds__(256) void rank_kernel(RouteParams p) {
+  int chunk = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  if (chunk < p.n_chunks) rank_chunk(p, chunk);
+}
+
+}  // namespace moe
