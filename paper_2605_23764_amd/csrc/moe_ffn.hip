@@ -99,6 +99,7 @@ int make_ctx(Ctx& c, const MoeShape* shape, const MoeSaved* saved, void* ws, siz
   if (st != MOE_OK) return st;
   c.s = *shape;
   c.L = make_layout(c.s);
+  if (c.s.T == 0) return MOE_OK;   // nothing to do: callers return before touching any pointer
   if (!ws || !aligned16(ws)) return MOE_ERR_INVALID_ARG;
   if (ws_bytes < c.L.fwd_total) return MOE_ERR_WORKSPACE_TOO_SMALL;
   c.ws = static_cast<char*>(ws);
@@ -264,9 +265,8 @@ int moe_route(const MoeShape* shape, const float* d_logits, const MoeSaved* save
               size_t workspace_bytes, void* stream) {
   Ctx c;
   int st = make_ctx(c, shape, saved, d_workspace, workspace_bytes, stream);
-  if (st != MOE_OK) return st;
+  if (st != MOE_OK || c.s.T == 0) return st;
   if (!d_logits || !saved) return MOE_ERR_INVALID_ARG;
-  if (c.s.T == 0) return MOE_OK;
   return run_route(c, d_logits);
 }
 
@@ -274,9 +274,8 @@ int moe_permute(const MoeShape* shape, const void* d_x, const MoeSaved* saved, v
                 size_t workspace_bytes, void* stream) {
   Ctx c;
   int st = make_ctx(c, shape, saved, d_workspace, workspace_bytes, stream);
-  if (st != MOE_OK) return st;
+  if (st != MOE_OK || c.s.T == 0) return st;
   if (!d_x || !aligned16(d_x) || !saved) return MOE_ERR_INVALID_ARG;
-  if (c.s.T == 0) return MOE_OK;
   return run_permute(c, d_x);
 }
 
@@ -284,9 +283,8 @@ int moe_grouped_gemm_swiglu(const MoeShape* shape, const void* d_w_gate_up, cons
                             void* d_workspace, size_t workspace_bytes, void* stream) {
   Ctx c;
   int st = make_ctx(c, shape, saved, d_workspace, workspace_bytes, stream);
-  if (st != MOE_OK) return st;
+  if (st != MOE_OK || c.s.T == 0) return st;
   if (!d_w_gate_up || !aligned16(d_w_gate_up) || !saved) return MOE_ERR_INVALID_ARG;
-  if (c.s.T == 0) return MOE_OK;
   return run_gemm1(c, d_w_gate_up);
 }
 
@@ -294,9 +292,8 @@ int moe_grouped_gemm(const MoeShape* shape, const void* d_w_down, const MoeSaved
                      size_t workspace_bytes, void* stream) {
   Ctx c;
   int st = make_ctx(c, shape, saved, d_workspace, workspace_bytes, stream);
-  if (st != MOE_OK) return st;
+  if (st != MOE_OK || c.s.T == 0) return st;
   if (!d_w_down || !aligned16(d_w_down) || !saved) return MOE_ERR_INVALID_ARG;
-  if (c.s.T == 0) return MOE_OK;
   return run_gemm2(c, d_w_down);
 }
 
@@ -304,9 +301,8 @@ int moe_combine(const MoeShape* shape, const MoeSaved* saved, void* d_out, void*
                 size_t workspace_bytes, void* stream) {
   Ctx c;
   int st = make_ctx(c, shape, saved, d_workspace, workspace_bytes, stream);
-  if (st != MOE_OK) return st;
+  if (st != MOE_OK || c.s.T == 0) return st;
   if (!d_out || !aligned16(d_out) || !saved) return MOE_ERR_INVALID_ARG;
-  if (c.s.T == 0) return MOE_OK;
   return run_combine(c, d_out);
 }
 
@@ -316,11 +312,11 @@ int moe_ffn_forward(const MoeShape* shape, const void* d_x, const float* d_logit
   Ctx c;
   int st = make_ctx(c, shape, saved, d_workspace, workspace_bytes, stream);
   if (st != MOE_OK) return st;
+  if (mode != MOE_MODE_SERIALIZED && mode != MOE_MODE_PERSISTENT) return MOE_ERR_INVALID_ARG;
+  if (c.s.T == 0) return MOE_OK;
   const void* ptrs[] = {d_x, d_logits, d_w_gate_up, d_w_down, d_out};
   for (const void* q : ptrs)
     if (!q || !aligned16(q)) return MOE_ERR_INVALID_ARG;
-  if (mode != MOE_MODE_SERIALIZED && mode != MOE_MODE_PERSISTENT) return MOE_ERR_INVALID_ARG;
-  if (c.s.T == 0) return MOE_OK;
   if (mode == MOE_MODE_PERSISTENT) return MOE_ERR_INVALID_ARG;  // not built yet
   if ((st = run_route(c, d_logits)) != MOE_OK) return st;
   if ((st = run_permute(c, d_x)) != MOE_OK) return st;
