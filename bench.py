@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of the Dispatch-to-Combine MoE-FFN layer on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3] [--no-cpu-baseline]
+
+A step is one pass of the whole forward hot path (routing, dispatch permute,
+grouped GEMM-1 + SwiGLU, grouped GEMM-2, weighted combine) over one batch of
+seeded synthetic input already resident in HBM.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs one GPU's expert-parallel share on ONE GPU; "
+              "--gpus N with N > 1 is not supported (no inter-GPU path exists).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2605_23764_amd as moe
+    from workloads import CONFIGS, make_inputs
+
+    cfg = CONFIGS[args.workload]
+    torch.cuda.set_device(0)
+    moe.load_library()   # fails loudly if the HIP library is missing
+    inp = make_inputs(cfg)
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    eb = 2 if cfg.dtype == "bf16" else 4
+    shape = moe.make_shape(cfg.T, cfg.H, cfg.I, cfg.E, cfg.E_local, cfg.expert_base, cfg.k, tdt)
+    dev = {n: torch.from_numpy(inp[n]).cuda() for n in ("x", "logits", "w_gate_up", "w_down")}
+    for n in ("x", "w_gate_up", "w_down"):
+        dev[n] = dev[n].to(tdt)
+    saved = moe.alloc_saved(shape)
+    ws = moe.alloc_workspace(shape)
+    out = torch.empty(cfg.T, cfg.H, dtype=tdt, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step(mode):
+        moe.moe_ffn_forward(shape, dev["x"], dev["logits"], dev["w_gate_up"], dev["w_down"], out, saved, ws, mode)
+
+    def timed(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps * 1e3   # ms per step
+
+    modes = {"serialized": moe.MODE_SERIALIZED}
+    if os.environ.get("MOE_BENCH_PERSISTENT", "1") == "1":
+        modes["persistent"] = moe.MODE_PERSISTENT
+    ms = {}
+    for name, mode in modes.items():
+        try:
+            ms[name] = timed(lambda: step(mode), args.steps, args.warmup)
+            st = moe.moe_ffn_last_status(shape, ws)
+            if st != 0:
+                raise moe.MoeError(st, name)
+        except moe.MoeError as e:
+            print(f"bench.py: mode {name} unavailable: {e}", file=sys.stderr)
+    best = min(ms, key=ms.get)
+    R = int(saved.offsets.cpu()[-1])
+
+    # ---- per-operator durations: the serialized sequence with HIP events between launches
+    stages = [
+        ("route", lambda: moe.moe_route(shape, dev["logits"], saved, ws)),
+        ("permute", lambda: moe.moe_permute(shape, dev["x"], saved, ws)),
+        ("gemm1_swiglu", lambda: moe.moe_grouped_gemm_swiglu(shape, dev["w_gate_up"], saved, ws)),
+        ("gemm2", lambda: moe.moe_grouped_gemm(shape, dev["w_down"], saved, ws)),
+        ("combine", lambda: moe.moe_combine(shape, saved, out, ws)),
+    ]
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(stages) + 1)] for _ in range(args.steps)]
+    for _ in range(args.warmup):
+        for _, fn in stages:
+            fn()
+    torch.cuda.synchronize()
+    for it in range(args.steps):
+        ev[it][0].record(stream)
+        for i, (_, fn) in enumerate(stages):
+            fn()
+            ev[it][i + 1].record(stream)
+    torch.cuda.synchronize()
+    stage_us = {}
+    for i, (name, _) in enumerate(stages):
+        stage_us[name] = float(np.mean([ev[it][i].elapsed_time(ev[it][i + 1]) for it in range(args.steps)]) * 1e3)
+
+    T, H, I, El = cfg.T, cfg.H, cfg.I, cfg.E_local
+    active = int((saved.counts.cpu() > 0).sum())
+    flops1, flops2 = 2.0 * R * H * 2 * I, 2.0 * R * I * H
+    # algorithmic bytes: each operand read once, each result written once
+    bytes1 = (active * H * 2 * I + R * H + R * I) * eb
+    bytes2 = (active * I * H + R * I + R * H) * eb
+    bytes_perm = 2.0 * R * H * eb
+    bytes_comb = (R + T) * H * eb
+    g1 = stage_us["gemm1_swiglu"] * 1e-6
+    g2 = stage_us["gemm2"] * 1e-6
+    gemm_tflops = (flops1 + flops2) / (g1 + g2) / 1e12
+    ridge = MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)
+    hbm_bound = (flops1 / bytes1) < ridge
+    if hbm_bound:
+        roof = {"bound": "hbm", "kernel": "grouped_gemm_bf16_kernel<swiglu>", "achieved": bytes1 / g1 / 1e9,
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bytes1 / g1 / 1e9 / HBM_PEAK_GBS, "traffic": None}
+    else:
+        roof = {"bound": "mfma", "kernel": "grouped_gemm_bf16_kernel<swiglu>", "achieved": flops1 / g1 / 1e12,
+                "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": flops1 / g1 / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                "traffic": None}
+
+    res = {
+        "metric": "Dispatch-to-Combine MoE-FFN us/layer (forward, routing included)",
+        "value": ms[best] * 1e3,
+        "unit": "us/layer",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms[best],
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: T={T} H={H} I={I} E={cfg.E} E_local={El} k={cfg.k} R={R}",
+                   "mode": best, "active_experts": active},
+        "roofline": roof,
+        "detail": {
+            "us_per_layer": {k: v * 1e3 for k, v in ms.items()},
+            "stage_us": stage_us,
+            "dispatch_to_combine_us_serialized": sum(v for k, v in stage_us.items() if k != "route"),
+            "grouped_gemm_tflops": gemm_tflops,
+            "grouped_gemm_frac_of_bf16_mfma_peak": gemm_tflops / MFMA_BF16_PEAK_TFLOPS,
+            "gemm1_tflops": flops1 / g1 / 1e12, "gemm2_tflops": flops2 / g2 / 1e12,
+            "gemm1_algorithmic_GBs": bytes1 / g1 / 1e9, "gemm2_algorithmic_GBs": bytes2 / g2 / 1e9,
+            "permute_GBs": bytes_perm / (stage_us["permute"] * 1e-6) / 1e9,
+            "combine_GBs": bytes_comb / (stage_us["combine"] * 1e-6) / 1e9,
+            "hbm_peak_GBs": HBM_PEAK_GBS, "mfma_bf16_peak_tflops": MFMA_BF16_PEAK_TFLOPS,
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        from threadpoolctl import threadpool_info
+        t0 = time.perf_counter()
+        ref = oracle.forward(inp["x"], inp["logits"], inp["w_gate_up"], inp["w_down"], cfg.k, cfg.expert_base, El)
+        dt = time.perf_counter() - t0
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        got = out.float().cpu().numpy().astype(np.float64)
+        res["cpu_baseline"] = {
+            "value": dt * 1e6, "unit": "us/layer", "cores": threads, "kind": "oracle",
+            "sample": f"one full forward of workload {cfg.name} (fp64 numpy oracle, 1 pass, not scaled)",
+            "gpu_vs_oracle_max_err_over_max_ref": float(np.abs(got - ref["out"]).max() / np.abs(ref["out"]).max()),
+        }
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()
