@@ -33,10 +33,16 @@ namespace moe {
 
 enum GemmEpilogue { kEpiStore = 0, kEpiSwiglu = 1 };
 
-constexpr int kBM = 512;            // tile row capacity (one M tile of the tile map)
+#ifndef MOE_GEMM_BM
+#define MOE_GEMM_BM 512
+#endif
+#ifndef MOE_GEMM_STAGES
+#define MOE_GEMM_STAGES 3
+#endif
+constexpr int kBM = MOE_GEMM_BM;    // tile row capacity (one M tile of the tile map)
 constexpr int kBN = 128;            // weight columns staged per tile
 constexpr int kBK = 32;             // K step
-constexpr int kStages = 3;
+constexpr int kStages = MOE_GEMM_STAGES;
 constexpr int kGemmThreads = 256;
 constexpr int kLine = 1024;                          // bytes moved by one wave-wide 16-byte load
 constexpr int kALines = kBM / 16;                    // 16 rows x 32 k per line
@@ -61,14 +67,19 @@ typedef __attribute__((address_space(3))) void* lds_void_ptr;
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
 
-// s_waitcnt vmcnt(n) only (expcnt/lgkmcnt left at "don't wait"); n is wave-uniform, 0..10.
+// s_waitcnt vmcnt(n) only (expcnt/lgkmcnt left at "don't wait"); n is wave-uniform, 0..63.
+// The count is an instruction immediate, so a runtime n goes through a jump table.
 __device__ __forceinline__ void wait_vmcnt(int n) {
-#define MOE_WAIT_CASE(i) case i: __builtin_amdgcn_s_waitcnt(0x0F70 | (i)); break;
+#define MOE_WAIT_CASE(i) case i: __builtin_amdgcn_s_waitcnt(0x0F70 | ((i) & 15) | (((i) >> 4) << 14)); break;
+#define MOE_WAIT_CASE8(b) MOE_WAIT_CASE(b) MOE_WAIT_CASE(b + 1) MOE_WAIT_CASE(b + 2) MOE_WAIT_CASE(b + 3) \
+                          MOE_WAIT_CASE(b + 4) MOE_WAIT_CASE(b + 5) MOE_WAIT_CASE(b + 6) MOE_WAIT_CASE(b + 7)
   switch (n) {
-    MOE_WAIT_CASE(1) MOE_WAIT_CASE(2) MOE_WAIT_CASE(3) MOE_WAIT_CASE(4) MOE_WAIT_CASE(5)
-    MOE_WAIT_CASE(6) MOE_WAIT_CASE(7) MOE_WAIT_CASE(8) MOE_WAIT_CASE(9) MOE_WAIT_CASE(10)
+    MOE_WAIT_CASE(1) MOE_WAIT_CASE(2) MOE_WAIT_CASE(3) MOE_WAIT_CASE(4) MOE_WAIT_CASE(5) MOE_WAIT_CASE(6) MOE_WAIT_CASE(7)
+    MOE_WAIT_CASE8(8) MOE_WAIT_CASE8(16) MOE_WAIT_CASE8(24) MOE_WAIT_CASE8(32) MOE_WAIT_CASE8(40) MOE_WAIT_CASE8(48)
+    MOE_WAIT_CASE8(56)
     default: __builtin_amdgcn_s_waitcnt(0x0F70); break;   // vmcnt(0)
   }
+#undef MOE_WAIT_CASE8
 #undef MOE_WAIT_CASE
 }
 
@@ -124,22 +135,25 @@ __device__ __forceinline__ void gemm_compute_stage(f32x16 (&acc)[kMaxMT][2], con
   }
 }
 
-// K loop of one tile for a wave with NMT active row sub-tiles.  Three stages:
-// at the top of step s the loads of steps s and s+1 are outstanding; after the
+// K loop of one tile for a wave with NMT active row sub-tiles.  With S stages, at
+// the top of step s the loads of steps s .. s+S-2 are outstanding; after the
 // wait + barrier every wave's step-s data is in LDS and every wave has left
-// compute(s-1), whose stage is then refilled with step s+2.
+// compute(s-1), whose stage is then refilled with step s+S-1.
 template <int NMT>
 __device__ __forceinline__ void gemm_k_loop(f32x16 (&acc)[kMaxMT][2], const GemmTileCtx& t, char* smem, int n_steps,
                                             uint32_t a_rd, const uint32_t (&b_rd)[2]) {
   const int per_step = t.nA + 2;
-  gemm_issue_loads(t, smem, 0, 0);
-  if (n_steps > 1) gemm_issue_loads(t, smem, 1, 1);
+#pragma unroll
+  for (int i = 0; i < kStages - 1; ++i)
+    if (i < n_steps) gemm_issue_loads(t, smem, i, i);
   int stage = 0;
   for (int s = 0; s < n_steps; ++s) {
-    wait_vmcnt(s + 1 < n_steps ? per_step : 0);
+    wait_vmcnt(min(kStages - 2, n_steps - 1 - s) * per_step);   // younger steps may stay in flight
     __builtin_amdgcn_s_barrier();
-    if (s + 2 < n_steps) gemm_issue_loads(t, smem, stage == 0 ? 2 : stage - 1, s + 2);
+    if (s + kStages - 1 < n_steps) gemm_issue_loads(t, smem, stage == 0 ? kStages - 1 : stage - 1, s + kStages - 1);
+#if !defined(MOE_DBG_NOCOMPUTE)
     gemm_compute_stage<NMT>(acc, smem + stage * kStageBytes, a_rd, b_rd);
+#endif
     stage = stage == kStages - 1 ? 0 : stage + 1;
   }
   __builtin_amdgcn_s_barrier();   // all stages free before the next tile's first loads
