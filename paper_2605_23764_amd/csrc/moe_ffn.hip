@@ -149,6 +149,7 @@ RouteParams route_params(const Ctx& c, const float* logits) {
   p.T = c.s.T; p.E = c.s.E; p.E_local = c.s.E_local; p.expert_base = c.s.expert_base; p.k = c.s.k;
   p.n_chunks = n_chunks(c.s);
   p.BM = tile_bm(c.s);
+  p.granule = c.s.dtype == MOE_BF16 ? kRowGranule : kFBM;
   return p;
 }
 

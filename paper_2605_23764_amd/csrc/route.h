@@ -25,7 +25,9 @@ struct RouteParams {
   int32_t* slot_of;      // [R_max]
   int32_t* chunk_cnt;    // [n_chunks, E_local]  histogram, then exclusive offsets
   TileMap tiles;
-  int T, E, E_local, expert_base, k, n_chunks, BM;
+  int T, E, E_local, expert_base, k, n_chunks;
+  int BM;        // M-tile row capacity
+  int granule;   // an expert's tiles are equal multiples of this (last one takes the remainder)
 };
 
 // Monotone map float -> uint32 (larger float = larger key); -0.0 and NaN are
@@ -181,10 +183,13 @@ __device__ __forceinline__ void scan_all(const RouteParams& p, int32_t* s_cnt) {
       if (e < p.E_local) {
         p.counts[e] = c;
         p.offsets[e] = off;
+        // equal split: sibling tiles of an expert take the same time, so they
+        // stream the expert's weights in step and share them through L2
+        const int per = nt ? (((c + nt - 1) / nt + p.granule - 1) / p.granule) * p.granule : 0;
         for (int i = 0; i < nt; ++i) {
           p.tiles.expert[tbase + i] = e;
-          p.tiles.row0[tbase + i] = off + i * p.BM;
-          p.tiles.rows[tbase + i] = min(p.BM, c - i * p.BM);
+          p.tiles.row0[tbase + i] = off + i * per;
+          p.tiles.rows[tbase + i] = min(per, c - i * per);
         }
       }
       row_run += __shfl(row_incl, kWave - 1, kWave);
