@@ -67,9 +67,13 @@ struct GemmParams {
   TileMap tiles;
 };
 
-typedef __attribute__((address_space(3))) void* lds_void_ptr;
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+// LDS is addressed through explicit address-space-3 pointers: a generic pointer
+// would turn the operand reads into FLAT loads, which count on vmcnt and would
+// drain the global -> LDS pipeline at every read.
+typedef __attribute__((address_space(3))) const char* lds_cptr;
 typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
+typedef __attribute__((address_space(3))) const bf16x8* lds_bf16x8_cptr;
 
 // s_waitcnt vmcnt(n) only (expcnt/lgkmcnt left at "don't wait").
 template <int N>
@@ -78,127 +82,197 @@ __device__ __forceinline__ void wait_vmcnt() {
 }
 
 // One wave-wide global -> LDS copy: lane l moves 16 bytes from sbase + voff to LDS
-// byte address lds_addr + 16*l.  Issued as inline assembly so that the compiler's
-// own wait-count pass does not see an LDS write and force vmcnt(0) before every
-// operand read (which would serialise the pipeline); ordering is done by hand with
-// wait_vmcnt + s_barrier.  The "memory" clobber keeps LDS reads from moving across.
-__device__ __forceinline__ void lds_dma16(const void* sbase, uint32_t voff, uint32_t lds_addr) {
+// byte address lds_addr + 16*l.  sbase and lds_addr must be wave-uniform values held
+// in scalar registers (see uniform_ptr / uniform_u32).  Issued as inline assembly so
+// that the compiler's own wait-count pass does not see an LDS write and force
+// vmcnt(0) before every operand read (which would serialise the pipeline); ordering
+// is done by hand with wait_vmcnt + s_barrier.  The "memory" clobber keeps LDS reads
+// from moving across.
+__device__ __forceinline__ void lds_dma16(const char* sbase, uint32_t voff, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                :
                : "s"(lds_addr), "v"(voff), "s"(sbase)
                : "memory", "m0");
 }
 
+// Pin a wave-uniform value into scalar registers (readfirstlane returns a signed
+// int: widen through uint32_t, or the low half sign-extends into the high half).
+__device__ __forceinline__ uint32_t uniform_u32(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+__device__ __forceinline__ const char* uniform_ptr(const char* p) {
+  const uint64_t b = reinterpret_cast<uint64_t>(p);
+  return reinterpret_cast<const char*>((uint64_t)uniform_u32((uint32_t)b) | ((uint64_t)uniform_u32((uint32_t)(b >> 32)) << 32));
+}
+
 __device__ __forceinline__ uint32_t lds_addr_of(const char* p) {
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
 }
 
-// Per-tile, per-lane addressing state shared by the load and compute phases.
+__device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
+
+// Per-tile addressing state shared by the load and compute phases.
 struct GemmTileCtx {
   const char* a_base;          // uniform: first row of the tile, byte address
   const char* b_base;          // uniform: expert's weights, byte address
   uint32_t a_off[8];           // per lane: byte offset of the chunk this lane fetches for its i-th A line
   uint32_t b_off[2];           // per lane: byte offset inside a 4-row weight line, column halves 0 / 1
+  uint32_t a_rd[4];            // per lane: operand read offset inside an A stage, per 16-wide k slice
+  uint32_t b_rd[4];            // per lane: operand read offset inside a B stage, per 32-column block
+  uint32_t lds0;               // LDS byte address of the staging area
   int nA;                      // A lines per wave per step (1..8)
   int ldb_bytes;
   int wave;
 };
 
-// Quarter `part` (0..3) of the loads a K step issues: parts 0-1 fetch the
-// activation lines of step `a_step` into A stage `a_stage` (nA wave-wide loads in
-// all), parts 2-3 the weight lines of step `b_step` into B stage `b_stage` (8
-// loads: this wave's 16 k-rows x both 128-column halves).  A negative step skips.
+// The 16 wave-wide loads issued between two barriers: the activation lines of one
+// K step (indices 0..7, only nA of them real) followed by the weight lines of a
+// later K step (indices 8..15: this wave's 16 k-rows x both 128-column halves).
 // Activation loads always precede weight loads, which the vmcnt waits rely on.
-__device__ __forceinline__ void gemm_issue_part(const GemmTileCtx& t, uint32_t lds0, int part, int a_stage, int a_step,
-                                                int b_stage, int b_step) {
-  if (part < 2) {
-    if (a_step < 0) return;
-    const uint32_t st = lds0 + a_stage * kAStageBytes + t.wave * kLine;
-    const char* a_k = t.a_base + (size_t)a_step * (kBK * 2);
-#pragma unroll
-    for (int i = part * 4; i < part * 4 + 4; ++i)
-      if (i < t.nA) lds_dma16(a_k, t.a_off[i], st + 4 * i * kLine);
+struct GemmLoadGroup {
+  const char* a_k;   // uniform source of the activation lines, nullptr = none
+  const char* b_k;   // uniform source of the weight lines, nullptr = none
+  uint32_t a_st;     // uniform LDS address of this wave's first activation line
+  uint32_t b_st;     // uniform LDS address of this wave's first weight line
+};
+
+__device__ __forceinline__ GemmLoadGroup gemm_load_group(const GemmTileCtx& t, int a_step, int a_stage, int b_step,
+                                                         int b_stage) {
+  GemmLoadGroup g;
+  g.a_k = a_step >= 0 ? uniform_ptr(t.a_base + (size_t)a_step * (kBK * 2)) : nullptr;
+  g.b_k = b_step >= 0 ? uniform_ptr(t.b_base + (size_t)(b_step * kBK + t.wave * 16) * t.ldb_bytes) : nullptr;
+  g.a_st = uniform_u32(t.lds0 + a_stage * kAStageBytes + t.wave * kLine);
+  g.b_st = uniform_u32(t.lds0 + kBRegion + b_stage * kBStageBytes + t.wave * kBLinesPerWave * kLine);
+  return g;
+}
+
+__device__ __forceinline__ void gemm_issue_one(const GemmTileCtx& t, const GemmLoadGroup& g, int idx) {
+  if (idx < 8) {
+    if (g.a_k != nullptr && idx < t.nA) lds_dma16(g.a_k, t.a_off[idx], g.a_st + 4 * idx * kLine);
   } else {
-    if (b_step < 0) return;
-    const uint32_t st = lds0 + kBRegion + b_stage * kBStageBytes + t.wave * kBLinesPerWave * kLine;
-    const char* b_k = t.b_base + (size_t)(b_step * kBK + t.wave * 16) * t.ldb_bytes;
-#pragma unroll
-    for (int i = (part - 2) * 4; i < (part - 2) * 4 + 4; ++i)
-      lds_dma16(b_k + (size_t)((i >> 1) * 4) * t.ldb_bytes, t.b_off[i & 1], st + i * kLine);
+    const int i = idx - 8;
+    if (g.b_k != nullptr) lds_dma16(g.b_k + (size_t)((i >> 1) * 4) * t.ldb_bytes, t.b_off[i & 1], g.b_st + i * kLine);
   }
 }
 
-// MFMA operands of one 16-wide k slice: 4 weight fragments (transpose reads) and
-// NMT activation fragments.
+// MFMA operands of one 16-wide k slice: 4 weight fragments (two transpose reads
+// each) and NMT activation fragments.
 template <int NMT>
 struct GemmFrags {
-  bf16x8 wf[4];
+  s16x4 w[4][2];
   bf16x8 xf[NMT > 0 ? NMT : 1];
 };
 
+// One 16-wide k slice for a wave: NMT x 4 MFMAs on `cur`.  Behind the MFMAs, one
+// per slot, go the 8 + NMT operand reads that fill `nxt` (slice ks_n of the stages
+// as_n / bs_n) and four of the load group's global -> LDS copies, so LDS latency
+// and load issue hide under MFMA time.  sched_barrier pins that order.
 template <int NMT>
-__device__ __forceinline__ void gemm_load_frags(GemmFrags<NMT>& f, const char* as, const char* bs, int ks,
-                                                const uint32_t (&a_rd)[4], const uint32_t (&b_rd)[4]) {
+__device__ __forceinline__ void gemm_slice(f32x16 (&acc)[kMaxMT][4], const GemmFrags<NMT>& cur, GemmFrags<NMT>& nxt,
+                                           bool read_next, lds_cptr as_n, lds_cptr bs_n, int ks_n,
+                                           const GemmTileCtx& t, const GemmLoadGroup& g, int load0) {
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  constexpr int n_mfma = NMT * 4, n_act = 8 + NMT + 4;
+  bf16x8 wf[4];
 #pragma unroll
   for (int nt = 0; nt < 4; ++nt) {
-    const char* bp = bs + b_rd[nt] + ks * 8 * kLine;
-    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(bp));
-    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(bp + 2 * kLine));
-    typedef short s16x8 __attribute__((ext_vector_type(8)));
-    s16x8 both = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-    f.wf[nt] = __builtin_bit_cast(bf16x8, both);
+    const s16x4 lo = cur.w[nt][0], hi = cur.w[nt][1];
+    wf[nt] = __builtin_bit_cast(bf16x8, (s16x8){lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w});
   }
 #pragma unroll
-  for (int mt = 0; mt < NMT; ++mt)
-    f.xf[mt] = *reinterpret_cast<const bf16x8*>(as + a_rd[ks] + mt * 4 * kLine);
+  for (int j = 0; j < n_mfma; ++j) {
+    acc[j >> 2][j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j & 3], cur.xf[j >> 2], acc[j >> 2][j & 3], 0, 0, 0);
+#pragma unroll
+    for (int a = 0; a < n_act; ++a) {
+      if ((a * n_mfma) / n_act != j) continue;
+      if (a < 8) {
+        if (read_next)
+          nxt.w[a >> 1][a & 1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (lds_s16x4_ptr)(bs_n + t.b_rd[a >> 1] + ks_n * 8 * kLine + (a & 1) * 2 * kLine));
+      } else if (a < 8 + NMT) {
+        if (read_next) nxt.xf[a - 8] = *(lds_bf16x8_cptr)(as_n + t.a_rd[ks_n] + (a - 8) * 4 * kLine);
+      } else {
+        gemm_issue_one(t, g, load0 + (a - 8 - NMT));
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
 }
 
-// One K step (64) for a wave: NMT x 4 MFMAs per 16-wide k slice.  The operand
-// reads of slice ks+1 and a quarter of the step's global->LDS loads are issued
-// before the MFMAs of slice ks, so LDS latency and load issue hide under MFMA time.
 template <int NMT>
-__device__ __forceinline__ void gemm_step(f32x16 (&acc)[kMaxMT][4], const GemmTileCtx& t, uint32_t lds0, const char* as,
-                                          const char* bs, const uint32_t (&a_rd)[4], const uint32_t (&b_rd)[4],
-                                          int a_stage, int a_step, int b_stage, int b_step) {
-  GemmFrags<NMT> cur, nxt;
-  if (NMT > 0) gemm_load_frags<NMT>(cur, as, bs, 0, a_rd, b_rd);
+__device__ __forceinline__ void gemm_read_frags(GemmFrags<NMT>& f, lds_cptr as, lds_cptr bs, int ks,
+                                                const GemmTileCtx& t) {
 #pragma unroll
-  for (int ks = 0; ks < kBK / 16; ++ks) {
-    if (NMT > 0 && ks + 1 < kBK / 16) gemm_load_frags<NMT>(nxt, as, bs, ks + 1, a_rd, b_rd);
-    gemm_issue_part(t, lds0, ks, a_stage, a_step, b_stage, b_step);
-    __builtin_amdgcn_sched_barrier(0);
+  for (int a = 0; a < 8; ++a)
+    f.w[a >> 1][a & 1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (lds_s16x4_ptr)(bs + t.b_rd[a >> 1] + ks * 8 * kLine + (a & 1) * 2 * kLine));
 #pragma unroll
-    for (int mt = 0; mt < NMT; ++mt)
-#pragma unroll
-      for (int nt = 0; nt < 4; ++nt)
-        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.wf[nt], cur.xf[mt], acc[mt][nt], 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    if (ks + 1 < kBK / 16) cur = nxt;
-  }
+  for (int mt = 0; mt < NMT; ++mt) f.xf[mt] = *(lds_bf16x8_cptr)(as + t.a_rd[ks] + mt * 4 * kLine);
 }
 
 // K loop of one tile for a wave with NMT active row sub-tiles.
-// Issue order is A(s+1) then B(s+2) during step s, so at the top of step s+1 the
-// only loads allowed to be outstanding are the 8 of B(s+2).  After the wait +
-// barrier every wave's A(s) and B(s) are in LDS and every wave has left step s-1,
-// whose A stage and B stage are refilled during step s.
+//
+// Step s computes from A stage s%2 and B stage s%3.  Its barrier sits in front of
+// the LAST k slice: by then this wave has fetched all of step s's operands
+// (lgkmcnt 0), and the wait allows only the 8 weight loads of B(s+2) to be
+// outstanding, so A(s+1) and B(s+1) are in LDS.  After the barrier that holds for
+// every wave: the stages of step s are free and are refilled by the next load
+// group, A(s+2) then B(s+3), issued four at a time behind the MFMAs of the
+// following four slices, while the first operands of step s+1 are already being
+// read under the last slice of step s.
 template <int NMT>
-__device__ __forceinline__ void gemm_k_loop(f32x16 (&acc)[kMaxMT][4], const GemmTileCtx& t, char* smem, int n_steps,
-                                            const uint32_t (&a_rd)[4], const uint32_t (&b_rd)[4]) {
-  const uint32_t lds0 = lds_addr_of(smem);
+__device__ __forceinline__ void gemm_k_loop(f32x16 (&acc)[kMaxMT][4], const GemmTileCtx& t, char* smem, int n_steps) {
+  const lds_cptr lds = (lds_cptr)smem;
+  {
+    const GemmLoadGroup g0 = gemm_load_group(t, 0, 0, 0, 0);                       // A(0), B(0)
 #pragma unroll
-  for (int part = 0; part < 4; ++part) gemm_issue_part(t, lds0, part, 0, 0, 0, 0);            // A(0), B(0)
-  if (n_steps > 1) {
-    gemm_issue_part(t, lds0, 2, 0, -1, 1, 1);                                                  // B(1)
-    gemm_issue_part(t, lds0, 3, 0, -1, 1, 1);
-  }
-  int bstage = 0;
-  for (int s = 0; s < n_steps; ++s) {
-    if (s + 1 < n_steps) wait_vmcnt<kBLinesPerWave>(); else wait_vmcnt<0>();
+    for (int i = 0; i < 16; ++i) gemm_issue_one(t, g0, i);
+    if (n_steps > 1) {
+      const GemmLoadGroup g1 = gemm_load_group(t, -1, 0, 1, 1);                    // B(1)
+#pragma unroll
+      for (int i = 8; i < 16; ++i) gemm_issue_one(t, g1, i);
+      wait_vmcnt<kBLinesPerWave>();
+    } else {
+      wait_vmcnt<0>();
+    }
     __builtin_amdgcn_s_barrier();
-    gemm_step<NMT>(acc, t, lds0, smem + (s & 1) * kAStageBytes, smem + kBRegion + bstage * kBStageBytes, a_rd, b_rd,
-                   (s + 1) & 1, s + 1 < n_steps ? s + 1 : -1, bstage == 0 ? 2 : bstage - 1, s + 2 < n_steps ? s + 2 : -1);
-    bstage = bstage == kBStages - 1 ? 0 : bstage + 1;
+  }
+  GemmLoadGroup g = gemm_load_group(t, n_steps > 1 ? 1 : -1, 1, n_steps > 2 ? 2 : -1, 2);   // A(1), B(2)
+#pragma unroll
+  for (int i = 0; i < 4; ++i) gemm_issue_one(t, g, i);
+  GemmFrags<NMT> cur, nxt;
+  if (NMT > 0) gemm_read_frags<NMT>(cur, lds, lds + kBRegion, 0, t);
+
+  int bs_i = 0;
+  for (int s = 0; s < n_steps; ++s) {
+    const lds_cptr as = lds + (s & 1) * kAStageBytes;
+    const lds_cptr bs = lds + kBRegion + bs_i * kBStageBytes;
+    const int bs_next = bs_i == kBStages - 1 ? 0 : bs_i + 1;
+#pragma unroll
+    for (int ks = 0; ks < 3; ++ks) {
+      if (NMT > 0) {
+        gemm_slice<NMT>(acc, cur, nxt, true, as, bs, ks + 1, t, g, 4 + 4 * ks);
+        cur = nxt;
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) gemm_issue_one(t, g, 4 + 4 * ks + i);
+      }
+    }
+    const bool more = s + 1 < n_steps;
+    if (more) {
+      wait_lgkmcnt0();
+      if (s + 2 < n_steps) wait_vmcnt<kBLinesPerWave>(); else wait_vmcnt<0>();
+      __builtin_amdgcn_s_barrier();
+      g = gemm_load_group(t, s + 2 < n_steps ? s + 2 : -1, s & 1, s + 3 < n_steps ? s + 3 : -1, bs_i);
+    }
+    if (NMT > 0) {
+      // `more` false: no loads left (both sources null) and nothing further to read
+      gemm_slice<NMT>(acc, cur, nxt, more, lds + ((s + 1) & 1) * kAStageBytes, lds + kBRegion + bs_next * kBStageBytes, 0, t,
+                      g, 0);
+      if (more) cur = nxt;
+    } else if (more) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) gemm_issue_one(t, g, i);
+    }
+    bs_i = bs_next;
   }
   __builtin_amdgcn_s_barrier();   // all stages free before the next tile's first loads
 }
@@ -222,8 +296,8 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int mtile, i
   t.wave = wave;
   t.nA = (rows + 31) >> 5;            // (8-row lines any operand read touches = 4*ceil(rows/32)) / 4 waves
   t.ldb_bytes = p.ldb * 2;
-  t.a_base = reinterpret_cast<const char*>(p.A + (size_t)row0 * p.lda);
-  t.b_base = reinterpret_cast<const char*>(p.B + (size_t)e * p.strideB);
+  t.a_base = uniform_ptr(reinterpret_cast<const char*>(p.A + (size_t)row0 * p.lda));
+  t.b_base = uniform_ptr(reinterpret_cast<const char*>(p.B + (size_t)e * p.strideB));
   {
     // A line L = wave + 4*i holds rows 8L..8L+7; lane -> (row r = lane/8, LDS chunk position pos = lane%8),
     // which holds k chunk pos ^ ((row/2)%8)
@@ -247,7 +321,9 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int mtile, i
   }
 
   // operand read offsets inside a stage
-  uint32_t a_rd[4], b_rd[4];
+  t.lds0 = lds_addr_of(smem);
+  uint32_t (&a_rd)[4] = t.a_rd;
+  uint32_t (&b_rd)[4] = t.b_rd;
   {
     const uint32_t a0 = (uint32_t)(((wm * half) >> 3) * kLine + (l32 >> 3) * kLine + (l32 & 7) * 128);
     const int f = (l32 >> 1) & 7;
@@ -274,11 +350,11 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int mtile, i
 
   const int n_steps = p.K / kBK;
   switch (n_mt) {
-    case 0: gemm_k_loop<0>(acc, t, smem, n_steps, a_rd, b_rd); break;
-    case 1: gemm_k_loop<1>(acc, t, smem, n_steps, a_rd, b_rd); break;
-    case 2: gemm_k_loop<2>(acc, t, smem, n_steps, a_rd, b_rd); break;
-    case 3: gemm_k_loop<3>(acc, t, smem, n_steps, a_rd, b_rd); break;
-    default: gemm_k_loop<4>(acc, t, smem, n_steps, a_rd, b_rd); break;
+    case 0: gemm_k_loop<0>(acc, t, smem, n_steps); break;
+    case 1: gemm_k_loop<1>(acc, t, smem, n_steps); break;
+    case 2: gemm_k_loop<2>(acc, t, smem, n_steps); break;
+    case 3: gemm_k_loop<3>(acc, t, smem, n_steps); break;
+    default: gemm_k_loop<4>(acc, t, smem, n_steps); break;
   }
 
   // ---- epilogue: lane holds row l32 of each 32 x 32 block and, per register group q,
@@ -341,7 +417,10 @@ void grouped_gemm_bf16_kernel(GemmParams p) {
   for (int it = 0; it * G < total; ++it) {
     const int tile = xcd_tile_id(it, blockIdx.x, G);
     if (tile >= total) continue;
-    gemm_tile_bf16<EPI>(p, tile / p.n_ntiles, tile % p.n_ntiles, smem);
+    // the division runs on the vector ALU; pin the (uniform) results back into scalar registers
+    const int mtile = __builtin_amdgcn_readfirstlane(tile / p.n_ntiles);
+    const int ntile = tile - mtile * p.n_ntiles;
+    gemm_tile_bf16<EPI>(p, mtile, ntile, smem);
   }
 }
 
