@@ -156,6 +156,16 @@ int moe_ffn_backward(const MoeShape* shape, const void* d_dy, const void* d_x,
  */
 int moe_ffn_last_status(const MoeShape* shape, const void* d_workspace);
 
+/*
+ * Test hook for the persistent scheduler's failure path (paper Section 4.3: a
+ * task starts only once its dependent event has reached the threshold).  Sets
+ * how many polls a wait may spend before it gives up; the default is about
+ * one million (about a second).  With a tiny limit waits expire, the affected tasks
+ * are skipped, every workgroup still drains its queues and exits, and
+ * moe_ffn_last_status() reports MOE_ERR_SCHED_TIMEOUT.  Host-only, process-wide.
+ */
+int moe_ffn_debug_set_spin_limit(uint32_t polls);
+
 /* ---- Stage entry points (the serialized path's operators, one launch each;
  *      used by the unit tests and the benchmark).  Same buffers as above. ---- */
 

@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     make_shape,
     moe_combine,
     moe_ffn_backward,
+    moe_ffn_debug_set_spin_limit,
     moe_ffn_forward,
     moe_ffn_last_status,
     moe_ffn_workspace_bytes,

@@ -36,7 +36,7 @@ class _MoeSaved(ctypes.Structure):
 
 EXPORTS = (
     "moe_status_string", "moe_ffn_workspace_bytes", "moe_ffn_forward", "moe_ffn_backward",
-    "moe_ffn_last_status", "moe_route", "moe_permute", "moe_grouped_gemm_swiglu", "moe_grouped_gemm",
+    "moe_ffn_last_status", "moe_ffn_debug_set_spin_limit", "moe_route", "moe_permute", "moe_grouped_gemm_swiglu", "moe_grouped_gemm",
     "moe_combine",
 )
 
@@ -175,6 +175,10 @@ def moe_ffn_backward(shape, dy, x, w_gate_up, w_down, saved: Saved, dx, dw_gate_
 
 def moe_ffn_last_status(shape, workspace) -> int:
     return load_library().moe_ffn_last_status(ctypes.byref(shape), _ptr(workspace))
+
+
+def moe_ffn_debug_set_spin_limit(polls: int) -> None:
+    _check(load_library().moe_ffn_debug_set_spin_limit(ctypes.c_uint32(polls)), "moe_ffn_debug_set_spin_limit")
 
 
 def moe_route(shape, logits, saved: Saved, workspace, stream=None) -> None:

@@ -9,6 +9,7 @@
 #include "gemm_bf16.h"
 #include "gemm_f32.h"
 #include "permute_combine.h"
+#include "persistent.h"
 #include "route.h"
 
 using namespace moe;
@@ -23,6 +24,13 @@ inline int tile_bm(const MoeShape& s) { return s.dtype == MOE_BF16 ? kBM : kFBM;
 inline long r_max(const MoeShape& s) { return (long)s.T * (s.k < s.E_local ? s.k : s.E_local); }
 inline int n_chunks(const MoeShape& s) { return (s.T + kChunk - 1) / kChunk; }
 inline long max_mtiles(const MoeShape& s) { return r_max(s) / tile_bm(s) + s.E_local + 1; }
+inline int gemm1_ntiles(const MoeShape& s) { return s.dtype == MOE_BF16 ? (s.I + kBN / 2 - 1) / (kBN / 2) : s.I / kFBN; }
+inline int gemm2_ntiles(const MoeShape& s) { return s.dtype == MOE_BF16 ? (s.H + kBN - 1) / kBN : s.H / kFBN; }
+inline long n_events(const MoeShape& s) { return kEvPerTile + 2 * max_mtiles(s); }
+inline long max_tasks_per_queue(const MoeShape& s) {
+  const long mq = (max_mtiles(s) + kNumXcd - 1) / kNumXcd;
+  return mq * ((tile_bm(s) + kPermRows - 1) / kPermRows + gemm1_ntiles(s) + gemm2_ntiles(s));
+}
 
 int check_shape(const MoeShape* s) {
   if (!s) return MOE_ERR_INVALID_ARG;
@@ -40,7 +48,7 @@ int check_shape(const MoeShape* s) {
 
 // Device workspace carved from one base pointer.
 struct Layout {
-  size_t meta, chunk_cnt, tile_expert, tile_row0, tile_rows, counters;
+  size_t meta, chunk_cnt, tile_expert, tile_row0, tile_rows, events, qhead, tasks;
   // fallback storage when the caller passes saved == NULL
   size_t topk_idx, topk_w, counts, offsets, row_of, token_of, slot_of, Xp, A, Yp;
   size_t fwd_total;
@@ -56,7 +64,9 @@ Layout make_layout(const MoeShape& s) {
   L.tile_expert = take((size_t)max_mtiles(s) * 4);
   L.tile_row0 = take((size_t)max_mtiles(s) * 4);
   L.tile_rows = take((size_t)max_mtiles(s) * 4);
-  L.counters = take(4);
+  L.events = take((size_t)n_events(s) * 4);
+  L.qhead = take(kNumQueues * 4);
+  L.tasks = take((size_t)kNumXcd * max_tasks_per_queue(s) * sizeof(TaskDesc));
   L.topk_idx = take((size_t)s.T * s.k * 4);
   L.topk_w = take((size_t)s.T * s.k * 4);
   L.counts = take((size_t)s.E_local * 4);
@@ -157,17 +167,16 @@ int launch_status() { return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_
 
 int run_route(const Ctx& c, const float* logits) {
   RouteParams p = route_params(c, logits);
-  hipLaunchKernelGGL(route_kernel, dim3(p.n_chunks), dim3(512), 0, c.stream, p);
+  hipLaunchKernelGGL(route_kernel, dim3(p.n_chunks), dim3(1024), 0, c.stream, p);
   hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, c.stream, p);
   hipLaunchKernelGGL(rank_kernel, dim3((p.n_chunks + 3) / 4), dim3(256), 0, c.stream, p);
   return launch_status();
 }
 
+PermuteParams permute_params(const Ctx& c, const void* x);
+
 int run_permute(const Ctx& c, const void* x) {
-  PermuteParams p;
-  p.x = x; p.Xp = c.sv.Xp; p.token_of = c.sv.token_of;
-  p.meta = reinterpret_cast<int32_t*>(c.ws + c.L.meta);
-  p.H = c.s.H; p.elem_bytes = elem_bytes(c.s);
+  PermuteParams p = permute_params(c, x);
   long want = (r_max(c.s) + 3) / 4;
   int grid = (int)(want < (long)c.n_cu * 8 ? (want > 0 ? want : 1) : (long)c.n_cu * 8);
   hipLaunchKernelGGL(permute_kernel, dim3(grid), dim3(256), 0, c.stream, p);
@@ -176,58 +185,100 @@ int run_permute(const Ctx& c, const void* x) {
 
 int gemm_grid(const Ctx& c) { return (c.n_cu + 7) / 8 * 8; }
 
-int run_gemm1(const Ctx& c, const void* w_gate_up) {
+template <typename P, typename T>
+P gemm1_params(const Ctx& c, const void* w_gate_up) {
   const MoeShape& s = c.s;
-  if (s.dtype == MOE_BF16) {
-    GemmParams p;
-    p.A = static_cast<const __bf16*>(c.sv.Xp); p.B = static_cast<const __bf16*>(w_gate_up);
-    p.C = static_cast<__bf16*>(c.sv.A); p.C2 = static_cast<__bf16*>(c.sv.H1);
-    p.strideB = (long)s.H * 2 * s.I; p.K = s.H; p.N = s.I;
-    p.lda = s.H; p.ldb = 2 * s.I; p.ldc = s.I;
-    p.n_ntiles = (s.I + kBN / 2 - 1) / (kBN / 2);
-    p.tiles = tile_map(c);
-    hipLaunchKernelGGL(grouped_gemm_bf16_kernel<kEpiSwiglu>, dim3(gemm_grid(c)), dim3(kGemmThreads), 0, c.stream, p);
-  } else {
-    GemmParamsF32 p;
-    p.A = static_cast<const float*>(c.sv.Xp); p.B = static_cast<const float*>(w_gate_up);
-    p.C = static_cast<float*>(c.sv.A); p.C2 = static_cast<float*>(c.sv.H1);
-    p.strideB = (long)s.H * 2 * s.I; p.K = s.H; p.N = s.I;
-    p.lda = s.H; p.ldb = 2 * s.I; p.ldc = s.I;
-    p.n_ntiles = s.I / kFBN;
-    p.tiles = tile_map(c);
-    hipLaunchKernelGGL(grouped_gemm_f32_kernel<kEpiSwiglu>, dim3(gemm_grid(c) * 4), dim3(256), 0, c.stream, p);
-  }
+  P p;
+  p.A = static_cast<const T*>(c.sv.Xp); p.B = static_cast<const T*>(w_gate_up);
+  p.C = static_cast<T*>(c.sv.A); p.C2 = static_cast<T*>(c.sv.H1);
+  p.strideB = (long)s.H * 2 * s.I; p.K = s.H; p.N = s.I;
+  p.lda = s.H; p.ldb = 2 * s.I; p.ldc = s.I;
+  p.n_ntiles = gemm1_ntiles(s);
+  p.tiles = tile_map(c);
+  return p;
+}
+
+template <typename P, typename T>
+P gemm2_params(const Ctx& c, const void* w_down) {
+  const MoeShape& s = c.s;
+  P p;
+  p.A = static_cast<const T*>(c.sv.A); p.B = static_cast<const T*>(w_down);
+  p.C = static_cast<T*>(c.sv.Yp); p.C2 = nullptr;
+  p.strideB = (long)s.I * s.H; p.K = s.I; p.N = s.H;
+  p.lda = s.I; p.ldb = s.H; p.ldc = s.H;
+  p.n_ntiles = gemm2_ntiles(s);
+  p.tiles = tile_map(c);
+  return p;
+}
+
+int run_gemm1(const Ctx& c, const void* w_gate_up) {
+  if (c.s.dtype == MOE_BF16)
+    hipLaunchKernelGGL(grouped_gemm_bf16_kernel<kEpiSwiglu>, dim3(gemm_grid(c)), dim3(kGemmThreads), 0, c.stream,
+                       gemm1_params<GemmParams, __bf16>(c, w_gate_up));
+  else
+    hipLaunchKernelGGL(grouped_gemm_f32_kernel<kEpiSwiglu>, dim3(gemm_grid(c) * 4), dim3(256), 0, c.stream,
+                       gemm1_params<GemmParamsF32, float>(c, w_gate_up));
   return launch_status();
 }
 
 int run_gemm2(const Ctx& c, const void* w_down) {
-  const MoeShape& s = c.s;
-  if (s.dtype == MOE_BF16) {
-    GemmParams p;
-    p.A = static_cast<const __bf16*>(c.sv.A); p.B = static_cast<const __bf16*>(w_down);
-    p.C = static_cast<__bf16*>(c.sv.Yp); p.C2 = nullptr;
-    p.strideB = (long)s.I * s.H; p.K = s.I; p.N = s.H;
-    p.lda = s.I; p.ldb = s.H; p.ldc = s.H;
-    p.n_ntiles = (s.H + kBN - 1) / kBN;
-    p.tiles = tile_map(c);
-    hipLaunchKernelGGL(grouped_gemm_bf16_kernel<kEpiStore>, dim3(gemm_grid(c)), dim3(kGemmThreads), 0, c.stream, p);
-  } else {
-    GemmParamsF32 p;
-    p.A = static_cast<const float*>(c.sv.A); p.B = static_cast<const float*>(w_down);
-    p.C = static_cast<float*>(c.sv.Yp); p.C2 = nullptr;
-    p.strideB = (long)s.I * s.H; p.K = s.I; p.N = s.H;
-    p.lda = s.I; p.ldb = s.H; p.ldc = s.H;
-    p.n_ntiles = s.H / kFBN;
-    p.tiles = tile_map(c);
-    hipLaunchKernelGGL(grouped_gemm_f32_kernel<kEpiStore>, dim3(gemm_grid(c) * 4), dim3(256), 0, c.stream, p);
-  }
+  if (c.s.dtype == MOE_BF16)
+    hipLaunchKernelGGL(grouped_gemm_bf16_kernel<kEpiStore>, dim3(gemm_grid(c)), dim3(kGemmThreads), 0, c.stream,
+                       gemm2_params<GemmParams, __bf16>(c, w_down));
+  else
+    hipLaunchKernelGGL(grouped_gemm_f32_kernel<kEpiStore>, dim3(gemm_grid(c) * 4), dim3(256), 0, c.stream,
+                       gemm2_params<GemmParamsF32, float>(c, w_down));
+  return launch_status();
+}
+
+CombineParams combine_params(const Ctx& c, void* out) {
+  CombineParams p;
+  p.Yp = c.sv.Yp; p.out = out; p.row_of = c.sv.row_of; p.topk_w = c.sv.topk_w;
+  p.T = c.s.T; p.H = c.s.H; p.k = c.s.k;
+  return p;
+}
+
+PermuteParams permute_params(const Ctx& c, const void* x) {
+  PermuteParams p;
+  p.x = x; p.Xp = c.sv.Xp; p.token_of = c.sv.token_of;
+  p.meta = reinterpret_cast<int32_t*>(c.ws + c.L.meta);
+  p.H = c.s.H; p.elem_bytes = elem_bytes(c.s);
+  return p;
+}
+
+// Polls a scheduler wait may spend before it gives up (each poll is an L2 round
+// trip plus a short sleep: the default is several seconds).
+uint32_t g_spin_limit = 1u << 20;
+
+template <bool BF16>
+int run_persistent(const Ctx& c, const void* x, const float* logits, const void* w_gate_up, const void* w_down,
+                   void* out) {
+  using P = typename std::conditional<BF16, GemmParams, GemmParamsF32>::type;
+  using T = typename std::conditional<BF16, __bf16, float>::type;
+  SchedParams<BF16> sp;
+  sp.route = route_params(c, logits);
+  sp.perm = permute_params(c, x);
+  sp.g1 = gemm1_params<P, T>(c, w_gate_up);
+  sp.g2 = gemm2_params<P, T>(c, w_down);
+  sp.comb = combine_params(c, out);
+  sp.events = reinterpret_cast<uint32_t*>(c.ws + c.L.events);
+  sp.qhead = reinterpret_cast<uint32_t*>(c.ws + c.L.qhead);
+  sp.tasks = reinterpret_cast<TaskDesc*>(c.ws + c.L.tasks);
+  sp.meta = reinterpret_cast<int32_t*>(c.ws + c.L.meta);
+  sp.max_mtiles = (int)max_mtiles(c.s);
+  sp.max_tasks_per_q = (int)max_tasks_per_queue(c.s);
+  sp.n_rank_tasks = (sp.route.n_chunks + kRankChunksPerTask - 1) / kRankChunksPerTask;
+  sp.n_comb_tasks = (c.s.T + kCombineTokens - 1) / kCombineTokens;
+  sp.spin_limit = g_spin_limit;
+  sp.timeout_status = MOE_ERR_SCHED_TIMEOUT;
+  hipLaunchKernelGGL(sched_clear_kernel, dim3(1), dim3(256), 0, c.stream, sp.events, (int)n_events(c.s), sp.qhead,
+                     sp.meta);
+  hipLaunchKernelGGL(persistent_forward_kernel<BF16>, dim3(gemm_grid(c)), dim3(kGemmThreads), 0, c.stream, sp);
   return launch_status();
 }
 
 int run_combine(const Ctx& c, void* out) {
-  CombineParams p;
-  p.Yp = c.sv.Yp; p.out = out; p.row_of = c.sv.row_of; p.topk_w = c.sv.topk_w;
-  p.T = c.s.T; p.H = c.s.H; p.k = c.s.k;
+  CombineParams p = combine_params(c, out);
   long want = ((long)c.s.T + 3) / 4;
   int grid = (int)(want < (long)c.n_cu * 8 ? want : (long)c.n_cu * 8);
   if (c.s.dtype == MOE_BF16)
@@ -318,7 +369,9 @@ int moe_ffn_forward(const MoeShape* shape, const void* d_x, const float* d_logit
   const void* ptrs[] = {d_x, d_logits, d_w_gate_up, d_w_down, d_out};
   for (const void* q : ptrs)
     if (!q || !aligned16(q)) return MOE_ERR_INVALID_ARG;
-  if (mode == MOE_MODE_PERSISTENT) return MOE_ERR_INVALID_ARG;  // not built yet
+  if (mode == MOE_MODE_PERSISTENT)
+    return c.s.dtype == MOE_BF16 ? run_persistent<true>(c, d_x, d_logits, d_w_gate_up, d_w_down, d_out)
+                                 : run_persistent<false>(c, d_x, d_logits, d_w_gate_up, d_w_down, d_out);
   if ((st = run_route(c, d_logits)) != MOE_OK) return st;
   if ((st = run_permute(c, d_x)) != MOE_OK) return st;
   if ((st = run_gemm1(c, d_w_gate_up)) != MOE_OK) return st;
@@ -334,6 +387,11 @@ int moe_ffn_backward(const MoeShape* shape, const void* d_dy, const void* d_x, c
   (void)d_dw_gate_up; (void)d_dw_down; (void)d_dtopk_w; (void)d_workspace; (void)workspace_bytes;
   (void)mode; (void)stream;
   return MOE_ERR_INVALID_ARG;  // not built yet
+}
+
+int moe_ffn_debug_set_spin_limit(uint32_t polls) {
+  g_spin_limit = polls;
+  return MOE_OK;
 }
 
 int moe_ffn_last_status(const MoeShape* shape, const void* d_workspace) {

@@ -1,0 +1,267 @@
+// Single-launch persistent tile scheduler (paper Sections 4.3-4.4, the unified
+// runtime; this is its one-GPU analogue on homogeneous CUs).
+//
+// Every workgroup is a worker: it takes the next task index of a queue with one
+// atomic ticket, loads the task descriptor (TD, the paper's Table 1 in spirit:
+// task type, tile coordinates, dependent event + threshold; the trigger event
+// follows from type and tile), spins until the dependent event counter has reached
+// its threshold, runs the handler, makes its outputs visible device-wide and bumps
+// the trigger counter.  Queue order is a topological order of the layer's DAG and
+// tickets are consumed in order, so every wait is on work that an earlier ticket
+// holder is already running: no cycles, no scheduler state besides the counters
+// (Section 4.3's progress argument).  Handlers are the same device functions the
+// serialized launches run, so results are bit-identical for any legal order.
+//
+// Queues
+//   G  (global)   ROUTE x chunks, SCAN, RANK x groups           - static, host-known
+//   X0..X7        one per XCD: PERMUTE parts, GEMM-1 tiles, GEMM-2 tiles of the M
+//                 tiles dealt to that XCD (m % 8), so tiles sharing an activation
+//                 panel sit behind one L2.  These TDs depend on the routing result
+//                 (Section 5.1: "routing-derived offsets") and are materialised on
+//                 the device by the SCAN task.  GEMM-2 tiles of M tile j are queued
+//                 behind the GEMM-1 tiles of M tile j+2: a consumer is issued about
+//                 one sweep after its producers, close enough for L2 reuse, far
+//                 enough not to stall the queue.
+//   C  (global)   COMBINE x token groups, after every GEMM-2 tile
+// A worker whose own XCD queue is empty steals from the other XCD queues.
+#pragma once
+#include <type_traits>
+
+#include "common.h"
+#include "gemm_bf16.h"
+#include "gemm_f32.h"
+#include "permute_combine.h"
+#include "route.h"
+
+namespace moe {
+
+constexpr int kNumXcd = 8;
+constexpr int kPermRows = 32;            // rows per PERMUTE task
+constexpr int kCombineTokens = 32;       // tokens per COMBINE task
+constexpr int kRankChunksPerTask = 4;    // one chunk per wave
+constexpr int kGemm2Lag = 2;             // GEMM-2 of M tile j is queued behind GEMM-1 of M tile j + lag
+
+enum TaskType { kTaskPermute = 0, kTaskGemm1 = 1, kTaskGemm2 = 2 };
+
+// Event counters (uint32, zero at kernel start).
+enum EventId { kEvRoute = 0, kEvScan = 1, kEvRank = 2, kEvGemm2 = 3, kEvPerTile = 4 };
+//   kEvPerTile + m               rows of M tile m are in Xp      (PERMUTE parts of m)
+//   kEvPerTile + max_mtiles + m  A rows of M tile m are complete (GEMM-1 tiles of m)
+
+enum QueueId { kQGlobal = 0, kQXcd0 = 1, kQCombine = 1 + kNumXcd, kNumQueues = 16 };
+
+enum SchedMetaWord { kMetaQueueCount0 = 4, kMetaGemm2Total = 12 };   // after MetaWord
+
+struct TaskDesc {
+  int32_t type_n;      // TaskType | (N tile or part index << 8)
+  int32_t m;           // M tile
+  int32_t dep_event;   // counter that must reach `threshold` before the task may start
+  int32_t threshold;
+};
+
+template <bool BF16>
+struct SchedParams {
+  RouteParams route;
+  PermuteParams perm;
+  typename std::conditional<BF16, GemmParams, GemmParamsF32>::type g1, g2;
+  CombineParams comb;
+  uint32_t* events;
+  uint32_t* qhead;         // [kNumQueues]
+  TaskDesc* tasks;         // [kNumXcd][max_tasks_per_q]
+  int32_t* meta;
+  int max_mtiles, max_tasks_per_q;
+  int n_rank_tasks, n_comb_tasks;
+  uint32_t spin_limit;     // polls before a wait gives up (MOE_ERR_SCHED_TIMEOUT)
+  int32_t timeout_status;
+};
+
+// The scheduler's control flow is kept wave-uniform on purpose.  A lane-divergent
+// `if (threadIdx.x == 0) { atomic }` at the head of a loop that also contains
+// barriers was restructured by the compiler into nested loops in which lanes 1..63
+// never left the inner (barrier + ticket read) loop, so no new ticket was ever drawn
+// and the kernel spun forever.  Here wave 0 acts as a whole: single-lane atomics are
+// issued with the execution mask narrowed inside one assembly statement, polls are
+// uniform loads, and every branch below is scalar.
+
+// One atomic add of `inc` at p, issued by lane 0 only; returns the old value to all lanes.
+__device__ __forceinline__ uint32_t wave_atomic_add(uint32_t* p, uint32_t inc) {
+  uint32_t old;
+  uint64_t saved_exec;
+  asm volatile(
+      "s_mov_b64 %1, exec\n\t"
+      "s_mov_b64 exec, 1\n\t"
+      "global_atomic_add %0, %2, %3, %4 sc0\n\t"
+      "s_waitcnt vmcnt(0)\n\t"
+      "s_mov_b64 exec, %1"
+      : "=&v"(old), "=&s"(saved_exec)
+      : "v"(0u), "v"(inc), "s"(p)
+      : "memory");
+  return (uint32_t)__builtin_amdgcn_readfirstlane((int)old);
+}
+
+__device__ __forceinline__ uint32_t ev_load(const uint32_t* p) {
+  return (uint32_t)__builtin_amdgcn_readfirstlane((int)__hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+
+// One ticket of queue `q` for the whole workgroup (wave 0 draws, LDS broadcasts).
+__device__ __forceinline__ int sched_fetch(uint32_t* qhead, int q, volatile int* s_box, int wave) {
+  if (wave == 0) s_box[0] = (int)wave_atomic_add(&qhead[q], 1u);   // every lane stores the same value
+  __syncthreads();
+  const int t = __builtin_amdgcn_readfirstlane(s_box[0]);
+  __syncthreads();
+  return t;
+}
+
+// Wait until events[ev] >= threshold (bounded).  Returns false on timeout after
+// recording the status word; the caller then skips the task without triggering.
+template <bool BF16>
+__device__ __forceinline__ bool sched_wait(const SchedParams<BF16>& sp, int ev, uint32_t threshold, volatile int* s_box,
+                                           int wave) {
+  if (wave == 0) {
+    uint32_t polls = 0;
+    int ok = 1;
+    for (;;) {
+      if (ev_load(&sp.events[ev]) >= threshold) break;
+      if (++polls > sp.spin_limit) { ok = 0; break; }
+      __builtin_amdgcn_s_sleep(1);
+    }
+    if (!ok) __hip_atomic_store(&sp.meta[kMetaStatus], sp.timeout_status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    s_box[1] = ok;
+  }
+  __syncthreads();
+  const int ok = __builtin_amdgcn_readfirstlane(s_box[1]);
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // producers' data, not only the counter
+  __syncthreads();
+  return ok != 0;
+}
+
+// Outputs of this workgroup become visible device-wide, then the counter moves.
+template <bool BF16>
+__device__ __forceinline__ void sched_trigger(const SchedParams<BF16>& sp, int ev, int wave) {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+  __syncthreads();
+  if (wave == 0) wave_atomic_add(&sp.events[ev], 1u);
+}
+
+// SCAN task tail: materialise the per-XCD task tables from the fresh tile map.
+template <bool BF16>
+__device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
+  const int q = threadIdx.x;
+  if (q >= kNumXcd) return;
+  const int n_mtiles = sp.meta[kMetaMTiles];
+  const int nN1 = sp.g1.n_ntiles, nN2 = sp.g2.n_ntiles;
+  const int Mq = n_mtiles > q ? (n_mtiles - q + kNumXcd - 1) / kNumXcd : 0;
+  TaskDesc* tq = sp.tasks + (size_t)q * sp.max_tasks_per_q;
+  int n = 0;
+  for (int j = 0; j < Mq; ++j) {
+    const int m = q + kNumXcd * j;
+    const int parts = (sp.route.tiles.rows[m] + kPermRows - 1) / kPermRows;
+    for (int part = 0; part < parts; ++part) tq[n++] = TaskDesc{kTaskPermute | (part << 8), m, kEvRank, sp.n_rank_tasks};
+  }
+  for (int j = 0; j < Mq + kGemm2Lag; ++j) {
+    if (j < Mq) {
+      const int m = q + kNumXcd * j;
+      const int parts = (sp.route.tiles.rows[m] + kPermRows - 1) / kPermRows;
+      for (int nt = 0; nt < nN1; ++nt) tq[n++] = TaskDesc{kTaskGemm1 | (nt << 8), m, kEvPerTile + m, parts};
+    }
+    if (j >= kGemm2Lag) {
+      const int m = q + kNumXcd * (j - kGemm2Lag);
+      for (int nt = 0; nt < nN2; ++nt) tq[n++] = TaskDesc{kTaskGemm2 | (nt << 8), m, kEvPerTile + sp.max_mtiles + m, nN1};
+    }
+  }
+  sp.meta[kMetaQueueCount0 + q] = n;
+  if (q == 0) sp.meta[kMetaGemm2Total] = n_mtiles * nN2;
+}
+
+template <bool BF16>
+__device__ __forceinline__ void run_tile_task(const SchedParams<BF16>& sp, const TaskDesc& td, char* smem, volatile int* s_box,
+                                              int wave) {
+  const int type_n = __builtin_amdgcn_readfirstlane(td.type_n);
+  const int type = type_n & 0xFF, idx = type_n >> 8, m = __builtin_amdgcn_readfirstlane(td.m);
+  if (!sched_wait(sp, __builtin_amdgcn_readfirstlane(td.dep_event), (uint32_t)__builtin_amdgcn_readfirstlane(td.threshold), s_box, wave))
+    return;
+  if (type == kTaskPermute) {
+    const int row0 = sp.route.tiles.row0[m], rows = sp.route.tiles.rows[m];
+    const int r0 = row0 + idx * kPermRows;
+    permute_rows(sp.perm, r0, min(r0 + kPermRows, row0 + rows), wave, blockDim.x / kWave);
+    sched_trigger(sp, kEvPerTile + m, wave);
+  } else if (type == kTaskGemm1) {
+    if constexpr (BF16) gemm_tile_bf16<kEpiSwiglu>(sp.g1, m, idx, smem);
+    else gemm_tile_f32<kEpiSwiglu>(sp.g1, m, idx, reinterpret_cast<float*>(smem));
+    sched_trigger(sp, kEvPerTile + sp.max_mtiles + m, wave);
+  } else {
+    if constexpr (BF16) gemm_tile_bf16<kEpiStore>(sp.g2, m, idx, smem);
+    else gemm_tile_f32<kEpiStore>(sp.g2, m, idx, reinterpret_cast<float*>(smem));
+    sched_trigger(sp, kEvGemm2, wave);
+  }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void persistent_forward_kernel(SchedParams<BF16> sp) {
+  __shared__ __attribute__((aligned(1024))) char smem[kGemmLdsBytes];
+  // between tasks the staging area is idle: its first words carry the ticket and the wait result
+  volatile int* s_box = reinterpret_cast<volatile int*>(smem);
+  int32_t* s_scratch = reinterpret_cast<int32_t*>(smem + 64);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+
+  // ---- queue G: routing ----
+  const int n_chunks = sp.route.n_chunks;
+  const int n_g = n_chunks + 1 + sp.n_rank_tasks;
+  for (;;) {
+    const int t = sched_fetch(sp.qhead, kQGlobal, s_box, wave);
+    if (t >= n_g) break;
+    if (t < n_chunks) {
+      route_chunk(sp.route, t, s_scratch);
+      sched_trigger(sp, kEvRoute, wave);
+    } else if (t == n_chunks) {
+      if (!sched_wait(sp, kEvRoute, (uint32_t)n_chunks, s_box, wave)) continue;
+      scan_all(sp.route, s_scratch);
+      __syncthreads();
+      build_task_tables(sp);
+      sched_trigger(sp, kEvScan, wave);
+    } else {
+      if (!sched_wait(sp, kEvScan, 1u, s_box, wave)) continue;
+      const int chunk = (t - n_chunks - 1) * kRankChunksPerTask + wave;
+      if (wave < kRankChunksPerTask && chunk < n_chunks) rank_chunk(sp.route, chunk);
+      sched_trigger(sp, kEvRank, wave);
+    }
+  }
+
+  // ---- queues X: dispatch + grouped GEMMs, own XCD first, then steal ----
+  if (sched_wait(sp, kEvScan, 1u, s_box, wave)) {
+    const int home = blockIdx.x % kNumXcd;
+    for (int dq = 0; dq < kNumXcd; ++dq) {
+      const int q = (home + dq) % kNumXcd;
+      const int count = __builtin_amdgcn_readfirstlane(sp.meta[kMetaQueueCount0 + q]);
+      for (;;) {
+        const int t = sched_fetch(sp.qhead, kQXcd0 + q, s_box, wave);
+        if (t >= count) break;
+        const TaskDesc td = sp.tasks[(size_t)q * sp.max_tasks_per_q + t];
+        run_tile_task(sp, td, smem, s_box, wave);
+      }
+    }
+
+    // ---- queue C: combine ----
+    const uint32_t g2_total = (uint32_t)__builtin_amdgcn_readfirstlane(sp.meta[kMetaGemm2Total]);
+    for (;;) {
+      const int t = sched_fetch(sp.qhead, kQCombine, s_box, wave);
+      if (t >= sp.n_comb_tasks) break;
+      if (!sched_wait(sp, kEvGemm2, g2_total, s_box, wave)) continue;
+      const int t0 = t * kCombineTokens;
+      for (int i = wave; i < kCombineTokens; i += blockDim.x / kWave)
+        if (t0 + i < sp.comb.T) combine_token<BF16>(sp.comb, t0 + i);
+    }
+  }
+}
+
+// Zeroes the scheduler's counters, queue heads and status word (one small launch
+// ahead of the persistent kernel; a fill kernel rather than a memset node so the
+// pair can be captured in a graph).
+__global__ void sched_clear_kernel(uint32_t* events, int n_events, uint32_t* qhead, int32_t* meta) {
+  for (int i = threadIdx.x; i < n_events; i += blockDim.x) events[i] = 0;
+  if (threadIdx.x < kNumQueues) qhead[threadIdx.x] = 0;
+  if (threadIdx.x == 0) meta[kMetaStatus] = 0;
+}
+
+}  // namespace moe

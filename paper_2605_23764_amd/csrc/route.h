@@ -52,45 +52,72 @@ __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
   return v;
 }
 
-// Top-k of one token by one wave.  Key = (ordered logit << 32) | ~expert id, so
-// the wave maximum is the largest logit and, among equal logits, the lowest id.
-// Lane j < k ends up holding slot j.
-__device__ __forceinline__ void route_token(const RouteParams& p, int t, int lane, int32_t* s_idx) {
-  const float* row = p.logits + (size_t)t * p.E;
-  uint64_t key[kMaxE / kWave];
+constexpr int kRouteTokensPerWave = 4;   // tokens a wave routes at once (independent shuffle chains overlap)
+
+// Top-k of kRouteTokensPerWave tokens by one wave.  Key = (ordered logit << 32) |
+// ~expert id, so the wave maximum is the largest logit and, among equal logits, the
+// lowest id.  The tokens' reduction chains are independent and interleaved, which
+// hides the cross-lane shuffle latency.  Lane j < k ends up holding slot j.
+__device__ __forceinline__ void route_tokens(const RouteParams& p, int t_first, int lane, int32_t* s_idx_first) {
+  constexpr int Q = kRouteTokensPerWave, PL = kMaxE / kWave;
+  uint64_t key[Q][PL];
 #pragma unroll
-  for (int i = 0; i < kMaxE / kWave; ++i) {
-    int e = lane + i * kWave;
-    key[i] = 0;
-    if (e < p.E) key[i] = ((uint64_t)float_order_key(row[e]) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)e);
+  for (int q = 0; q < Q; ++q) {
+    const int t = min(t_first + q, p.T - 1);   // tokens past the end repeat the last one; results are not stored
+    const float* row = p.logits + (size_t)t * p.E;
+#pragma unroll
+    for (int i = 0; i < PL; ++i) {
+      const int e = lane + i * kWave;
+      key[q][i] = 0;
+      if (e < p.E) key[q][i] = ((uint64_t)float_order_key(row[e]) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)e);
+    }
   }
-  float my_val = 0.f;
-  int my_idx = 0;
+  float my_val[Q];
+  int my_idx[Q];
+#pragma unroll
+  for (int q = 0; q < Q; ++q) { my_val[q] = 0.f; my_idx[q] = 0; }
   for (int j = 0; j < p.k; ++j) {
-    uint64_t best = key[0];
+    uint64_t best[Q];
 #pragma unroll
-    for (int i = 1; i < kMaxE / kWave; ++i) best = key[i] > best ? key[i] : best;
-    best = wave_max_u64(best);
-    int e = (int)(0xFFFFFFFFu - (uint32_t)best);
+    for (int q = 0; q < Q; ++q) {
+      best[q] = key[q][0];
 #pragma unroll
-    for (int i = 0; i < kMaxE / kWave; ++i)
-      if (key[i] == best) key[i] = 0;   // keys are unique (they embed the id)
-    if (lane == j) {
-      my_val = float_from_order_key((uint32_t)(best >> 32));
-      my_idx = e;
+      for (int i = 1; i < PL; ++i) best[q] = key[q][i] > best[q] ? key[q][i] : best[q];
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+#pragma unroll
+      for (int q = 0; q < Q; ++q) {
+        const uint64_t o = __shfl_xor(best[q], off, kWave);
+        best[q] = o > best[q] ? o : best[q];
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+#pragma unroll
+      for (int i = 0; i < PL; ++i)
+        if (key[q][i] == best[q]) key[q][i] = 0;   // keys are unique (they embed the id)
+      if (lane == j) {
+        my_val[q] = float_from_order_key((uint32_t)(best[q] >> 32));
+        my_idx[q] = (int)(0xFFFFFFFFu - (uint32_t)best[q]);
+      }
     }
   }
   // softmax over the k selected logits; slot 0 holds the maximum
-  float m = __shfl(my_val, 0, kWave);
-  float pj = lane < p.k ? expf(my_val - m) : 0.f;
-  float sum = pj;
 #pragma unroll
-  for (int off = 8; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, kWave);  // k <= 16 lanes hold mass
-  sum = __shfl(sum, 0, kWave);
-  if (lane < p.k) {
-    p.topk_idx[(size_t)t * p.k + lane] = my_idx;
-    p.topk_w[(size_t)t * p.k + lane] = pj / sum;
-    s_idx[lane] = my_idx;
+  for (int q = 0; q < Q; ++q) {
+    const int t = t_first + q;
+    const float m = __shfl(my_val[q], 0, kWave);
+    const float pj = lane < p.k ? expf(my_val[q] - m) : 0.f;
+    float sum = pj;
+#pragma unroll
+    for (int off = 8; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, kWave);   // k <= 16 lanes hold mass
+    sum = __shfl(sum, 0, kWave);
+    if (t < p.T && lane < p.k) {
+      p.topk_idx[(size_t)t * p.k + lane] = my_idx[q];
+      p.topk_w[(size_t)t * p.k + lane] = pj / sum;
+      s_idx_first[q * kMaxK + lane] = my_idx[q];
+    }
   }
 }
 
@@ -110,7 +137,7 @@ __device__ __forceinline__ void local_mask(const int32_t* idx, int k, int base, 
   }
 }
 
-// One chunk of kChunk tokens by a workgroup of 512 threads (8 waves x 8 tokens),
+// One chunk of kChunk tokens by a workgroup (16 waves x 4 tokens at 1024 threads),
 // then wave 0 (lane = token) builds the chunk's histogram with ballots.
 // s_idx: kChunk*kMaxK int32 of LDS.
 __device__ __forceinline__ void route_chunk(const RouteParams& p, int chunk, int32_t* s_idx) {
@@ -118,10 +145,8 @@ __device__ __forceinline__ void route_chunk(const RouteParams& p, int chunk, int
   const int wave = threadIdx.x / kWave;
   const int n_waves = blockDim.x / kWave;
   const int t0 = chunk * kChunk;
-  for (int i = wave; i < kChunk; i += n_waves) {
-    int t = t0 + i;
-    if (t < p.T) route_token(p, t, lane, s_idx + i * kMaxK);
-  }
+  for (int i = wave * kRouteTokensPerWave; i < kChunk; i += n_waves * kRouteTokensPerWave)
+    if (t0 + i < p.T) route_tokens(p, t0 + i, lane, s_idx + i * kMaxK);
   __syncthreads();
   if (wave == 0) {
     uint64_t mask[kMaskWords];
@@ -259,7 +284,7 @@ __device__ __forceinline__ void rank_chunk(const RouteParams& p, int chunk) {
   }
 }
 
-__global__ __launch_bounds__(512) void route_kernel(RouteParams p) {
+__global__ __launch_bounds__(1024) void route_kernel(RouteParams p) {
   __shared__ int32_t s_idx[kChunk * kMaxK];
   route_chunk(p, blockIdx.x, s_idx);
 }
