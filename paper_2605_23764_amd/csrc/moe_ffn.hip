@@ -17,6 +17,11 @@ using namespace moe;
 namespace {
 
 constexpr size_t kAlign = 256;
+#if defined(MOE_SCHED_TRACE)
+constexpr size_t kSchedTraceBytes = 8192 * 48;   // task time stamps behind the task tables
+#else
+constexpr size_t kSchedTraceBytes = 0;
+#endif
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 inline int elem_bytes(const MoeShape& s) { return s.dtype == MOE_BF16 ? 2 : 4; }
@@ -66,7 +71,7 @@ Layout make_layout(const MoeShape& s) {
   L.tile_rows = take((size_t)max_mtiles(s) * 4);
   L.events = take((size_t)n_events(s) * 4);
   L.qhead = take(kNumQueues * 4);
-  L.tasks = take((size_t)kNumXcd * max_tasks_per_queue(s) * sizeof(TaskDesc));
+  L.tasks = take((size_t)kNumXcd * max_tasks_per_queue(s) * sizeof(TaskDesc) + kSchedTraceBytes);
   L.topk_idx = take((size_t)s.T * s.k * 4);
   L.topk_w = take((size_t)s.T * s.k * 4);
   L.counts = take((size_t)s.E_local * 4);

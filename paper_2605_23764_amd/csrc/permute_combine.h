@@ -26,7 +26,16 @@ __device__ __forceinline__ void permute_rows(const PermuteParams& p, int r_begin
     const int t = p.token_of[r];
     const uint4* src = reinterpret_cast<const uint4*>(static_cast<const char*>(p.x) + (size_t)t * p.H * p.elem_bytes);
     uint4* dst = reinterpret_cast<uint4*>(static_cast<char*>(p.Xp) + (size_t)r * p.H * p.elem_bytes);
+    // eight 16-byte loads in flight per lane: a persistent worker has only four waves
+    // on its CU, so memory-level parallelism has to come from within the wave
     int v = lane;
+    for (; v + 7 * kWave < vec_per_row; v += 8 * kWave) {
+      uint4 r[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) r[u] = src[v + u * kWave];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) dst[v + u * kWave] = r[u];
+    }
     for (; v + 3 * kWave < vec_per_row; v += 4 * kWave) {
       uint4 a = src[v], b = src[v + kWave], c = src[v + 2 * kWave], d = src[v + 3 * kWave];
       dst[v] = a; dst[v + kWave] = b; dst[v + 2 * kWave] = c; dst[v + 3 * kWave] = d;
@@ -67,21 +76,39 @@ __device__ __forceinline__ void combine_token(const CombineParams& p, int t) {
   if (BF16) {
     const int vec_per_row = p.H / 8;
     uint4* dst = reinterpret_cast<uint4*>(static_cast<__bf16*>(p.out) + (size_t)t * p.H);
-    for (int v = lane; v < vec_per_row; v += kWave) {
-      float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    // four column chunks per lane per pass: the loads of one slot are issued together
+    // (memory-level parallelism inside the wave); each element still accumulates its
+    // slots in order j = 0..k-1
+    constexpr int U = 4;
+    for (int v0 = lane; v0 < vec_per_row; v0 += U * kWave) {
+      float acc[U][8];
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int x = 0; x < 8; ++x) acc[u][x] = 0.f;
 #pragma unroll
       for (int i = 0; i < kMaxK; ++i) {
         if (rows[i] < 0) continue;
-        uint4 y = reinterpret_cast<const uint4*>(static_cast<const __bf16*>(p.Yp) + (size_t)rows[i] * p.H)[v];
-        acc[0] += w[i] * bf16_lo(y.x); acc[1] += w[i] * bf16_hi(y.x);
-        acc[2] += w[i] * bf16_lo(y.y); acc[3] += w[i] * bf16_hi(y.y);
-        acc[4] += w[i] * bf16_lo(y.z); acc[5] += w[i] * bf16_hi(y.z);
-        acc[6] += w[i] * bf16_lo(y.w); acc[7] += w[i] * bf16_hi(y.w);
+        const uint4* yrow = reinterpret_cast<const uint4*>(static_cast<const __bf16*>(p.Yp) + (size_t)rows[i] * p.H);
+        uint4 y[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) y[u] = (v0 + u * kWave < vec_per_row) ? yrow[v0 + u * kWave] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          acc[u][0] += w[i] * bf16_lo(y[u].x); acc[u][1] += w[i] * bf16_hi(y[u].x);
+          acc[u][2] += w[i] * bf16_lo(y[u].y); acc[u][3] += w[i] * bf16_hi(y[u].y);
+          acc[u][4] += w[i] * bf16_lo(y[u].z); acc[u][5] += w[i] * bf16_hi(y[u].z);
+          acc[u][6] += w[i] * bf16_lo(y[u].w); acc[u][7] += w[i] * bf16_hi(y[u].w);
+        }
       }
-      uint4 o;
-      o.x = pack_bf16(acc[0], acc[1]); o.y = pack_bf16(acc[2], acc[3]);
-      o.z = pack_bf16(acc[4], acc[5]); o.w = pack_bf16(acc[6], acc[7]);
-      dst[v] = o;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (v0 + u * kWave >= vec_per_row) break;
+        uint4 o;
+        o.x = pack_bf16(acc[u][0], acc[u][1]); o.y = pack_bf16(acc[u][2], acc[u][3]);
+        o.z = pack_bf16(acc[u][4], acc[u][5]); o.w = pack_bf16(acc[u][6], acc[u][7]);
+        dst[v0 + u * kWave] = o;
+      }
     }
   } else {
     const int vec_per_row = p.H / 4;

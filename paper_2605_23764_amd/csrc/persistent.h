@@ -23,7 +23,16 @@
 //                 one sweep after its producers, close enough for L2 reuse, far
 //                 enough not to stall the queue.
 //   C  (global)   COMBINE x token groups, after every GEMM-2 tile
-// A worker whose own XCD queue is empty steals from the other XCD queues.
+// XCD queues are private to the workers of that XCD (no stealing), so the PERMUTE ->
+// GEMM-1 -> GEMM-2 chain of an M tile is produced and consumed behind one L2.  That
+// lets those events skip the device-scope cache maintenance: a device-scope release
+// (buffer_wbl2) stalls for a write-back of everything dirty in the XCD's L2 (about
+// 30 us per task when all CUs do it) and a device-scope acquire (buffer_inv) drops
+// the L2 contents the sibling tiles are sharing.  Inside an XCD it is enough that the
+// producer's stores have been acknowledged by the L2 before the counter moves; every
+// address is written once before its first read within a launch, so there is no
+// stale line to invalidate on the consumer side.  Events that cross XCDs (routing,
+// and GEMM-2 -> COMBINE) keep the full device-scope fences.
 #pragma once
 #include <type_traits>
 
@@ -75,6 +84,29 @@ struct SchedParams {
   int32_t timeout_status;
 };
 
+// Optional per-task time stamps (100 MHz wall clock) for a tile-level timeline;
+// compiled in only with -DMOE_SCHED_TRACE, the buffer then sits behind the task tables.
+#if defined(MOE_SCHED_TRACE)
+struct TraceRec { int32_t wg, kind, a, b; long long t_fetch, t_start, t_end; };
+#define MOE_TRACE_DECL TraceRec tr_; tr_.wg = blockIdx.x;
+#define MOE_TRACE_FETCH(kind_, a_, b_) { tr_.kind = (kind_); tr_.a = (a_); tr_.b = (b_); tr_.t_fetch = wall_clock64(); }
+#define MOE_TRACE_START tr_.t_start = wall_clock64();
+#define MOE_TRACE_END(sp_)                                                                                   \
+  {                                                                                                          \
+    tr_.t_end = wall_clock64();                                                                              \
+    if (threadIdx.x == 0) {                                                                                  \
+      TraceRec* base_ = reinterpret_cast<TraceRec*>((sp_).tasks + (size_t)kNumXcd * (sp_).max_tasks_per_q);  \
+      int slot_ = atomicAdd(reinterpret_cast<int*>(&(sp_).qhead[kNumQueues - 1]), 1);                        \
+      if (slot_ < 8192) base_[slot_] = tr_;                                                                  \
+    }                                                                                                        \
+  }
+#else
+#define MOE_TRACE_DECL
+#define MOE_TRACE_FETCH(kind_, a_, b_)
+#define MOE_TRACE_START
+#define MOE_TRACE_END(sp_)
+#endif
+
 // The scheduler's control flow is kept wave-uniform on purpose.  A lane-divergent
 // `if (threadIdx.x == 0) { atomic }` at the head of a loop that also contains
 // barriers was restructured by the compiler into nested loops in which lanes 1..63
@@ -114,9 +146,11 @@ __device__ __forceinline__ int sched_fetch(uint32_t* qhead, int q, volatile int*
 
 // Wait until events[ev] >= threshold (bounded).  Returns false on timeout after
 // recording the status word; the caller then skips the task without triggering.
+enum EventScope { kScopeDevice = 0, kScopeXcd = 1 };
+
 template <bool BF16>
 __device__ __forceinline__ bool sched_wait(const SchedParams<BF16>& sp, int ev, uint32_t threshold, volatile int* s_box,
-                                           int wave) {
+                                           int wave, int scope = kScopeDevice) {
   if (wave == 0) {
     uint32_t polls = 0;
     int ok = 1;
@@ -130,15 +164,17 @@ __device__ __forceinline__ bool sched_wait(const SchedParams<BF16>& sp, int ev, 
   }
   __syncthreads();
   const int ok = __builtin_amdgcn_readfirstlane(s_box[1]);
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // producers' data, not only the counter
+  if (scope == kScopeDevice) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // producers' data, not only the counter
+  else __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
   __syncthreads();
   return ok != 0;
 }
 
 // Outputs of this workgroup become visible device-wide, then the counter moves.
 template <bool BF16>
-__device__ __forceinline__ void sched_trigger(const SchedParams<BF16>& sp, int ev, int wave) {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+__device__ __forceinline__ void sched_trigger(const SchedParams<BF16>& sp, int ev, int wave, int scope = kScopeDevice) {
+  if (scope == kScopeDevice) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+  else __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // stores acknowledged by the XCD's L2
   __syncthreads();
   if (wave == 0) wave_atomic_add(&sp.events[ev], 1u);
 }
@@ -175,20 +211,27 @@ __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
 
 template <bool BF16>
 __device__ __forceinline__ void run_tile_task(const SchedParams<BF16>& sp, const TaskDesc& td, char* smem, volatile int* s_box,
-                                              int wave) {
+                                              int wave, long long& t_start) {
   const int type_n = __builtin_amdgcn_readfirstlane(td.type_n);
   const int type = type_n & 0xFF, idx = type_n >> 8, m = __builtin_amdgcn_readfirstlane(td.m);
-  if (!sched_wait(sp, __builtin_amdgcn_readfirstlane(td.dep_event), (uint32_t)__builtin_amdgcn_readfirstlane(td.threshold), s_box, wave))
+  // PERMUTE waits on the routing tasks of every XCD; the GEMM tiles wait on tasks of their own XCD queue
+  if (!sched_wait(sp, __builtin_amdgcn_readfirstlane(td.dep_event), (uint32_t)__builtin_amdgcn_readfirstlane(td.threshold), s_box, wave,
+                  type == kTaskPermute ? kScopeDevice : kScopeXcd))
     return;
+#if defined(MOE_SCHED_TRACE)
+  t_start = wall_clock64();
+#else
+  (void)t_start;
+#endif
   if (type == kTaskPermute) {
     const int row0 = sp.route.tiles.row0[m], rows = sp.route.tiles.rows[m];
     const int r0 = row0 + idx * kPermRows;
     permute_rows(sp.perm, r0, min(r0 + kPermRows, row0 + rows), wave, blockDim.x / kWave);
-    sched_trigger(sp, kEvPerTile + m, wave);
+    sched_trigger(sp, kEvPerTile + m, wave, kScopeXcd);
   } else if (type == kTaskGemm1) {
     if constexpr (BF16) gemm_tile_bf16<kEpiSwiglu>(sp.g1, m, idx, smem);
     else gemm_tile_f32<kEpiSwiglu>(sp.g1, m, idx, reinterpret_cast<float*>(smem));
-    sched_trigger(sp, kEvPerTile + sp.max_mtiles + m, wave);
+    sched_trigger(sp, kEvPerTile + sp.max_mtiles + m, wave, kScopeXcd);
   } else {
     if constexpr (BF16) gemm_tile_bf16<kEpiStore>(sp.g2, m, idx, smem);
     else gemm_tile_f32<kEpiStore>(sp.g2, m, idx, reinterpret_cast<float*>(smem));
@@ -204,6 +247,7 @@ void persistent_forward_kernel(SchedParams<BF16> sp) {
   volatile int* s_box = reinterpret_cast<volatile int*>(smem);
   int32_t* s_scratch = reinterpret_cast<int32_t*>(smem + 64);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  MOE_TRACE_DECL
 
   // ---- queue G: routing ----
   const int n_chunks = sp.route.n_chunks;
@@ -212,33 +256,46 @@ void persistent_forward_kernel(SchedParams<BF16> sp) {
     const int t = sched_fetch(sp.qhead, kQGlobal, s_box, wave);
     if (t >= n_g) break;
     if (t < n_chunks) {
+      MOE_TRACE_FETCH(10, t, 0) MOE_TRACE_START
       route_chunk(sp.route, t, s_scratch);
       sched_trigger(sp, kEvRoute, wave);
+      MOE_TRACE_END(sp)
     } else if (t == n_chunks) {
+      MOE_TRACE_FETCH(11, t, 0)
       if (!sched_wait(sp, kEvRoute, (uint32_t)n_chunks, s_box, wave)) continue;
+      MOE_TRACE_START
       scan_all(sp.route, s_scratch);
       __syncthreads();
       build_task_tables(sp);
       sched_trigger(sp, kEvScan, wave);
+      MOE_TRACE_END(sp)
     } else {
+      MOE_TRACE_FETCH(12, t, 0)
       if (!sched_wait(sp, kEvScan, 1u, s_box, wave)) continue;
+      MOE_TRACE_START
       const int chunk = (t - n_chunks - 1) * kRankChunksPerTask + wave;
       if (wave < kRankChunksPerTask && chunk < n_chunks) rank_chunk(sp.route, chunk);
       sched_trigger(sp, kEvRank, wave);
+      MOE_TRACE_END(sp)
     }
   }
 
-  // ---- queues X: dispatch + grouped GEMMs, own XCD first, then steal ----
+  // ---- queue X of this workgroup's XCD: dispatch + grouped GEMMs ----
   if (sched_wait(sp, kEvScan, 1u, s_box, wave)) {
-    const int home = blockIdx.x % kNumXcd;
-    for (int dq = 0; dq < kNumXcd; ++dq) {
-      const int q = (home + dq) % kNumXcd;
+    {
+      const int q = blockIdx.x % kNumXcd;   // workgroups are dealt to XCDs round-robin by id
       const int count = __builtin_amdgcn_readfirstlane(sp.meta[kMetaQueueCount0 + q]);
       for (;;) {
         const int t = sched_fetch(sp.qhead, kQXcd0 + q, s_box, wave);
         if (t >= count) break;
         const TaskDesc td = sp.tasks[(size_t)q * sp.max_tasks_per_q + t];
-        run_tile_task(sp, td, smem, s_box, wave);
+        MOE_TRACE_FETCH(td.type_n & 0xFF, td.m, td.type_n >> 8)
+        long long t_start = 0;
+        run_tile_task(sp, td, smem, s_box, wave, t_start);
+#if defined(MOE_SCHED_TRACE)
+        tr_.t_start = t_start;
+#endif
+        MOE_TRACE_END(sp)
       }
     }
 
@@ -247,10 +304,13 @@ void persistent_forward_kernel(SchedParams<BF16> sp) {
     for (;;) {
       const int t = sched_fetch(sp.qhead, kQCombine, s_box, wave);
       if (t >= sp.n_comb_tasks) break;
+      MOE_TRACE_FETCH(3, t, 0)
       if (!sched_wait(sp, kEvGemm2, g2_total, s_box, wave)) continue;
+      MOE_TRACE_START
       const int t0 = t * kCombineTokens;
       for (int i = wave; i < kCombineTokens; i += blockDim.x / kWave)
         if (t0 + i < sp.comb.T) combine_token<BF16>(sp.comb, t0 + i);
+      MOE_TRACE_END(sp)
     }
   }
 }

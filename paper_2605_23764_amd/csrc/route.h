@@ -43,24 +43,36 @@ __device__ __forceinline__ float float_from_order_key(uint32_t k) {
   return __builtin_bit_cast(float, u);
 }
 
-__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    uint64_t o = __shfl_xor(v, off, kWave);
-    v = o > v ? o : v;
+// Wave-wide unsigned maximum through DPP row operations (no LDS traffic): row_shr
+// 1/2/4/8 leave each 16-lane row's maximum in its last lane, row_bcast 15 and 31
+// carry it across rows, lane 63 ends up with the wave maximum.  0 is the identity.
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+#define MOE_DPP_MAX(ctrl, row_mask)                                                                          \
+  {                                                                                                          \
+    const uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, ctrl, row_mask, 0xf, false);         \
+    v = o > v ? o : v;                                                                                       \
   }
-  return v;
+  MOE_DPP_MAX(0x111, 0xf)   // row_shr:1
+  MOE_DPP_MAX(0x112, 0xf)   // row_shr:2
+  MOE_DPP_MAX(0x114, 0xf)   // row_shr:4
+  MOE_DPP_MAX(0x118, 0xf)   // row_shr:8
+  MOE_DPP_MAX(0x142, 0xa)   // row_bcast:15 into rows 1 and 3
+  MOE_DPP_MAX(0x143, 0xc)   // row_bcast:31 into rows 2 and 3
+#undef MOE_DPP_MAX
+  return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
-constexpr int kRouteTokensPerWave = 4;   // tokens a wave routes at once (independent shuffle chains overlap)
+constexpr int kRouteTokensPerWave = 4;   // tokens a wave routes at once (independent reduction chains overlap)
 
-// Top-k of kRouteTokensPerWave tokens by one wave.  Key = (ordered logit << 32) |
-// ~expert id, so the wave maximum is the largest logit and, among equal logits, the
-// lowest id.  The tokens' reduction chains are independent and interleaved, which
-// hides the cross-lane shuffle latency.  Lane j < k ends up holding slot j.
+// Top-k of kRouteTokensPerWave tokens by one wave.  Lane l holds the logits of
+// experts l, l+64, l+128, l+192 as order-preserving 32-bit keys (0 = taken or
+// absent).  Each round takes the wave maximum and, among the lanes that hold it,
+// the lowest expert id: ids grow with the register index first, then with the
+// lane, so the first register whose ballot is non-empty and its lowest set lane
+// win.  Lane j < k ends up holding slot j.
 __device__ __forceinline__ void route_tokens(const RouteParams& p, int t_first, int lane, int32_t* s_idx_first) {
   constexpr int Q = kRouteTokensPerWave, PL = kMaxE / kWave;
-  uint64_t key[Q][PL];
+  uint32_t key[Q][PL];
 #pragma unroll
   for (int q = 0; q < Q; ++q) {
     const int t = min(t_first + q, p.T - 1);   // tokens past the end repeat the last one; results are not stored
@@ -68,8 +80,7 @@ __device__ __forceinline__ void route_tokens(const RouteParams& p, int t_first, 
 #pragma unroll
     for (int i = 0; i < PL; ++i) {
       const int e = lane + i * kWave;
-      key[q][i] = 0;
-      if (e < p.E) key[q][i] = ((uint64_t)float_order_key(row[e]) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)e);
+      key[q][i] = e < p.E ? float_order_key(row[e]) : 0u;
     }
   }
   float my_val[Q];
@@ -77,29 +88,24 @@ __device__ __forceinline__ void route_tokens(const RouteParams& p, int t_first, 
 #pragma unroll
   for (int q = 0; q < Q; ++q) { my_val[q] = 0.f; my_idx[q] = 0; }
   for (int j = 0; j < p.k; ++j) {
-    uint64_t best[Q];
 #pragma unroll
     for (int q = 0; q < Q; ++q) {
-      best[q] = key[q][0];
+      uint32_t local = key[q][0];
 #pragma unroll
-      for (int i = 1; i < PL; ++i) best[q] = key[q][i] > best[q] ? key[q][i] : best[q];
-    }
+      for (int i = 1; i < PL; ++i) local = key[q][i] > local ? key[q][i] : local;
+      const uint32_t best = wave_max_u32(local);
+      int win_i = -1, win_lane = 0;
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-#pragma unroll
-      for (int q = 0; q < Q; ++q) {
-        const uint64_t o = __shfl_xor(best[q], off, kWave);
-        best[q] = o > best[q] ? o : best[q];
+      for (int i = PL - 1; i >= 0; --i) {
+        const uint64_t b = __ballot(key[q][i] == best);
+        if (b != 0) { win_i = i; win_lane = __builtin_ctzll(b); }
       }
-    }
-#pragma unroll
-    for (int q = 0; q < Q; ++q) {
 #pragma unroll
       for (int i = 0; i < PL; ++i)
-        if (key[q][i] == best[q]) key[q][i] = 0;   // keys are unique (they embed the id)
+        if (i == win_i && lane == win_lane) key[q][i] = 0;
       if (lane == j) {
-        my_val[q] = float_from_order_key((uint32_t)(best[q] >> 32));
-        my_idx[q] = (int)(0xFFFFFFFFu - (uint32_t)best[q]);
+        my_val[q] = float_from_order_key(best);
+        my_idx[q] = win_lane + win_i * kWave;
       }
     }
   }
@@ -258,16 +264,18 @@ __device__ __forceinline__ void rank_chunk(const RouteParams& p, int chunk) {
 #pragma unroll
   for (int w = 0; w < kMaskWords; ++w) {
     if (w * 64 >= p.E_local) break;
-    int n = min(64, p.E_local - w * 64);
+    const int n = min(64, p.E_local - w * 64);
+    // first row of expert w*64+lane for this chunk, fetched once (one coalesced load
+    // instead of a dependent load per expert inside the loop)
+    const int my_base = lane < n ? p.offsets[w * 64 + lane] + coff[w * 64 + lane] : 0;
     for (int b = 0; b < n; ++b) {
-      bool sel = (mask[w] >> b) & 1;
-      uint64_t bal = __ballot(sel);
+      const bool sel = (mask[w] >> b) & 1;
+      const uint64_t bal = __ballot(sel);
       if (bal == 0) continue;
-      int e = w * 64 + b;
-      int base_row = p.offsets[e] + coff[e];
+      const int base_row = __builtin_amdgcn_readlane(my_base, b);
       if (sel) {
-        int r = base_row + __popcll(bal & lt);
-        int ge = e + p.expert_base;
+        const int r = base_row + __popcll(bal & lt);
+        const int ge = w * 64 + b + p.expert_base;
         int slot = 0;
 #pragma unroll
         for (int j = 0; j < kMaxK; ++j)
