@@ -36,7 +36,18 @@
 
 namespace moe {
 
-enum GemmEpilogue { kEpiStore = 0, kEpiSwiglu = 1 };
+// Operand layouts.  The forward GEMMs are "NN": activations [rows, K] k-contiguous,
+// weights [K, N] n-contiguous.  The backward graph (Section 2.2, Figure 2b) adds
+//   NT  act_grad / gate_grad: C[rows, N] = A[rows, K] * W_e[N, K]^T -- both operands
+//       k-contiguous, so the weight tile is staged like an activation tile (8 rows x
+//       64 k per line, XOR swizzle, plain 16-byte operand reads);
+//   TN  w2_grad / w1_grad: C_e[M, N] = A_e[rows_e, M]^T * B_e[rows_e, N] -- the
+//       reduction runs over the expert's rows, both operands are k-rows of
+//       contiguous m / n, so both are staged like a weight tile and fetched with
+//       transpose reads.  rows_e is ragged: k-rows past the segment are clamped at
+//       load time and zeroed in LDS before the last K step.
+enum GemmLayout { kLayNN = 0, kLayNT = 1, kLayTN = 2 };
+enum GemmEpilogue { kEpiStore = 0, kEpiSwiglu = 1, kEpiSwigluGrad = 2 };
 
 constexpr int kBM = 256;            // tile row capacity (one M tile of the tile map)
 constexpr int kBN = 256;            // weight columns staged per tile
@@ -60,11 +71,17 @@ struct GemmParams {
   const __bf16* B;    // per expert [K, ldb] row-major weights
   __bf16* C;          // [rows, ldc]
   __bf16* C2;         // SwiGLU only: optional pre-activation [rows, 2N] (gate|up), else null
-  long strideB;       // elements between consecutive experts' weights
-  int K, N;           // N = output columns (SwiGLU: I, weights have 2N columns)
+  const __bf16* G;    // SwiGLU-grad only: pre-activations saved by the forward [rows, 2N]
+  long strideB;       // elements between consecutive experts' weights (NN, NT)
+  long strideC;       // TN: elements between consecutive experts' outputs
+  int K, N;           // N = output columns (SwiGLU: I, weights have 2N columns); TN: K unused (rows of the expert)
+  int M;              // TN: output rows
   int lda, ldb, ldc;
   int n_ntiles;       // ceil(N / 256) (SwiGLU: ceil(N / 128))
-  TileMap tiles;
+  int n_mtiles;       // TN: ceil(M / 256)
+  int E_local;        // TN
+  const int32_t* offsets;   // TN: [E_local + 1] segment boundaries
+  TileMap tiles;      // NN, NT
 };
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -111,135 +128,214 @@ __device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xC
 
 // Per-tile addressing state shared by the load and compute phases.
 struct GemmTileCtx {
-  const char* a_base;          // uniform: first row of the tile, byte address
-  const char* b_base;          // uniform: expert's weights, byte address
-  uint32_t a_off[8];           // per lane: byte offset of the chunk this lane fetches for its i-th A line
-  uint32_t b_off[2];           // per lane: byte offset inside a 4-row weight line, column halves 0 / 1
-  uint32_t a_rd[4];            // per lane: operand read offset inside an A stage, per 16-wide k slice
-  uint32_t b_rd[4];            // per lane: operand read offset inside a B stage, per 32-column block
+  const char* a_base;          // uniform: first row of the tile (TN: of the expert's segment), byte address
+  const char* b_base;          // uniform: expert's weights (TN: first row of the segment), byte address
+  uint32_t a_off[8];           // NN/NT: per lane byte offset of the chunk fetched for the i-th A line; TN: [0..1] column halves
+  uint32_t b_off[8];           // NN/TN: [0..1] per lane byte offset inside a 4-row line, column halves; NT: like a_off
+  uint32_t a_rd[4];            // operand read offset inside an A stage (NN/NT: per k slice; TN: per 32-row block)
+  uint32_t b_rd[4];            // operand read offset inside a B stage (NN/TN: per 32-column block; NT: per k slice)
   uint32_t lds0;               // LDS byte address of the staging area
   int nA;                      // A lines per wave per step (1..8)
-  int ldb_bytes;
+  int lda_bytes, ldb_bytes;
   int wave;
+  int kk;                      // TN: k-row of this lane inside a 4-row line (lane / 16)
+  int k_rows;                  // TN: rows of the expert's segment (the reduction length)
 };
 
-// The 16 wave-wide loads issued between two barriers: the activation lines of one
-// K step (indices 0..7, only nA of them real) followed by the weight lines of a
-// later K step (indices 8..15: this wave's 16 k-rows x both 128-column halves).
-// Activation loads always precede weight loads, which the vmcnt waits rely on.
+// The 16 wave-wide loads issued between two barriers: the A lines of one K step
+// (indices 0..7, NN/NT: only nA of them real) followed by the B lines of a later
+// K step (indices 8..15).  A loads always precede B loads, which the vmcnt waits
+// rely on.
 struct GemmLoadGroup {
-  const char* a_k;   // uniform source of the activation lines, nullptr = none
-  const char* b_k;   // uniform source of the weight lines, nullptr = none
-  uint32_t a_st;     // uniform LDS address of this wave's first activation line
-  uint32_t b_st;     // uniform LDS address of this wave's first weight line
+  const char* a_k;   // uniform source of the A lines, nullptr = none
+  const char* b_k;   // uniform source of the B lines, nullptr = none
+  uint32_t a_st;     // uniform LDS address of this wave's first A line
+  uint32_t b_st;     // uniform LDS address of this wave's first B line
+  int a_row0;        // TN: first k-row this wave loads for A / B
+  int b_row0;
 };
 
+template <int LAY>
 __device__ __forceinline__ GemmLoadGroup gemm_load_group(const GemmTileCtx& t, int a_step, int a_stage, int b_step,
                                                          int b_stage) {
   GemmLoadGroup g;
-  g.a_k = a_step >= 0 ? uniform_ptr(t.a_base + (size_t)a_step * (kBK * 2)) : nullptr;
-  g.b_k = b_step >= 0 ? uniform_ptr(t.b_base + (size_t)(b_step * kBK + t.wave * 16) * t.ldb_bytes) : nullptr;
-  g.a_st = uniform_u32(t.lds0 + a_stage * kAStageBytes + t.wave * kLine);
-  g.b_st = uniform_u32(t.lds0 + kBRegion + b_stage * kBStageBytes + t.wave * kBLinesPerWave * kLine);
+  g.a_row0 = 0; g.b_row0 = 0;
+  if (LAY == kLayTN) {
+    g.a_k = a_step >= 0 ? t.a_base : nullptr;
+    g.b_k = b_step >= 0 ? t.b_base : nullptr;
+    g.a_row0 = __builtin_amdgcn_readfirstlane(a_step * kBK + t.wave * 16);
+    g.b_row0 = __builtin_amdgcn_readfirstlane(b_step * kBK + t.wave * 16);
+    g.a_st = uniform_u32(t.lds0 + a_stage * kAStageBytes + t.wave * kBLinesPerWave * kLine);
+  } else {
+    g.a_k = a_step >= 0 ? uniform_ptr(t.a_base + (size_t)a_step * (kBK * 2)) : nullptr;
+    g.a_st = uniform_u32(t.lds0 + a_stage * kAStageBytes + t.wave * kLine);
+    if (LAY == kLayNT) g.b_k = b_step >= 0 ? uniform_ptr(t.b_base + (size_t)b_step * (kBK * 2)) : nullptr;
+    else g.b_k = b_step >= 0 ? uniform_ptr(t.b_base + (size_t)(b_step * kBK + t.wave * 16) * t.ldb_bytes) : nullptr;
+  }
+  if (LAY == kLayNT) g.b_st = uniform_u32(t.lds0 + kBRegion + b_stage * kBStageBytes + t.wave * kLine);
+  else g.b_st = uniform_u32(t.lds0 + kBRegion + b_stage * kBStageBytes + t.wave * kBLinesPerWave * kLine);
   return g;
 }
 
+template <int LAY>
 __device__ __forceinline__ void gemm_issue_one(const GemmTileCtx& t, const GemmLoadGroup& g, int idx) {
   if (idx < 8) {
-    if (g.a_k != nullptr && idx < t.nA) lds_dma16(g.a_k, t.a_off[idx], g.a_st + 4 * idx * kLine);
+    if (LAY == kLayTN) {
+      if (g.a_k != nullptr) {
+        const int krow = min(g.a_row0 + (idx >> 1) * 4 + t.kk, t.k_rows - 1);   // rows past the segment: re-read, zeroed later
+        lds_dma16(g.a_k, (uint32_t)(krow * t.lda_bytes) + t.a_off[idx & 1], g.a_st + idx * kLine);
+      }
+    } else {
+      if (g.a_k != nullptr && idx < t.nA) lds_dma16(g.a_k, t.a_off[idx], g.a_st + 4 * idx * kLine);
+    }
   } else {
     const int i = idx - 8;
-    if (g.b_k != nullptr) lds_dma16(g.b_k + (size_t)((i >> 1) * 4) * t.ldb_bytes, t.b_off[i & 1], g.b_st + i * kLine);
+    if (g.b_k == nullptr) return;
+    if (LAY == kLayNN) {
+      lds_dma16(g.b_k + (size_t)((i >> 1) * 4) * t.ldb_bytes, t.b_off[i & 1], g.b_st + i * kLine);
+    } else if (LAY == kLayNT) {
+      lds_dma16(g.b_k, t.b_off[i], g.b_st + 4 * i * kLine);
+    } else {
+      const int krow = min(g.b_row0 + (i >> 1) * 4 + t.kk, t.k_rows - 1);
+      lds_dma16(g.b_k, (uint32_t)(krow * t.ldb_bytes) + t.b_off[i & 1], g.b_st + i * kLine);
+    }
   }
 }
 
-// MFMA operands of one 16-wide k slice: 4 weight fragments (two transpose reads
-// each) and NMT activation fragments.
-template <int NMT>
+// MFMA operands of one 16-wide k slice: 4 weight-side fragments and NMT
+// activation-side fragments.  An operand staged n-/m-contiguous takes two
+// transpose reads per fragment, a k-contiguous one a single 16-byte read.
+template <int LAY, int NMT>
 struct GemmFrags {
-  s16x4 w[4][2];
-  bf16x8 xf[NMT > 0 ? NMT : 1];
+  s16x4 w[4][2];                       // NN, TN
+  bf16x8 wk[4];                        // NT
+  bf16x8 xf[NMT > 0 ? NMT : 1];        // NN, NT
+  s16x4 xt[NMT > 0 ? NMT : 1][2];      // TN
 };
 
+template <int LAY, int NMT>
+struct GemmSliceShape {
+  static constexpr int n_wreads = LAY == kLayNT ? 4 : 8;
+  static constexpr int n_xreads = LAY == kLayTN ? 2 * NMT : NMT;
+  static constexpr int n_reads = n_wreads + n_xreads;
+};
+
+// Operand read number `a` of slice ks from the stages as / bs into f.
+template <int LAY, int NMT>
+__device__ __forceinline__ void gemm_read_one(GemmFrags<LAY, NMT>& f, int a, lds_cptr as, lds_cptr bs, int ks,
+                                              const GemmTileCtx& t) {
+  typedef GemmSliceShape<LAY, NMT> S;
+  if (a < S::n_wreads) {
+    if (LAY == kLayNT) f.wk[a] = *(lds_bf16x8_cptr)(bs + t.b_rd[ks] + a * 4 * kLine);
+    else
+      f.w[a >> 1][a & 1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (lds_s16x4_ptr)(bs + t.b_rd[a >> 1] + ks * 8 * kLine + (a & 1) * 2 * kLine));
+  } else {
+    const int i = a - S::n_wreads;
+    if (LAY == kLayTN)
+      f.xt[i >> 1][i & 1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (lds_s16x4_ptr)(as + t.a_rd[i >> 1] + ks * 8 * kLine + (i & 1) * 2 * kLine));
+    else f.xf[i] = *(lds_bf16x8_cptr)(as + t.a_rd[ks] + i * 4 * kLine);
+  }
+}
+
+__device__ __forceinline__ bf16x8 join_tr(s16x4 lo, s16x4 hi) {
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  return __builtin_bit_cast(bf16x8, (s16x8){lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w});
+}
+
 // One 16-wide k slice for a wave: NMT x 4 MFMAs on `cur`.  Behind the MFMAs, one
-// per slot, go the 8 + NMT operand reads that fill `nxt` (slice ks_n of the stages
+// per slot, go the operand reads that fill `nxt` (slice ks_n of the stages
 // as_n / bs_n) and four of the load group's global -> LDS copies, so LDS latency
 // and load issue hide under MFMA time.  sched_barrier pins that order.
-template <int NMT>
-__device__ __forceinline__ void gemm_slice(f32x16 (&acc)[kMaxMT][4], const GemmFrags<NMT>& cur, GemmFrags<NMT>& nxt,
-                                           bool read_next, lds_cptr as_n, lds_cptr bs_n, int ks_n,
-                                           const GemmTileCtx& t, const GemmLoadGroup& g, int load0) {
-  typedef short s16x8 __attribute__((ext_vector_type(8)));
-  constexpr int n_mfma = NMT * 4, n_act = 8 + NMT + 4;
-  bf16x8 wf[4];
+template <int LAY, int NMT>
+__device__ __forceinline__ void gemm_slice(f32x16 (&acc)[kMaxMT][4], const GemmFrags<LAY, NMT>& cur,
+                                           GemmFrags<LAY, NMT>& nxt, bool read_next, lds_cptr as_n, lds_cptr bs_n,
+                                           int ks_n, const GemmTileCtx& t, const GemmLoadGroup& g, int load0) {
+  typedef GemmSliceShape<LAY, NMT> S;
+  constexpr int n_mfma = NMT * 4, n_act = S::n_reads + 4;
+  bf16x8 wf[4], xf[NMT > 0 ? NMT : 1];
 #pragma unroll
-  for (int nt = 0; nt < 4; ++nt) {
-    const s16x4 lo = cur.w[nt][0], hi = cur.w[nt][1];
-    wf[nt] = __builtin_bit_cast(bf16x8, (s16x8){lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w});
-  }
+  for (int nt = 0; nt < 4; ++nt) wf[nt] = LAY == kLayNT ? cur.wk[nt] : join_tr(cur.w[nt][0], cur.w[nt][1]);
+#pragma unroll
+  for (int mt = 0; mt < NMT; ++mt) xf[mt] = LAY == kLayTN ? join_tr(cur.xt[mt][0], cur.xt[mt][1]) : cur.xf[mt];
 #pragma unroll
   for (int j = 0; j < n_mfma; ++j) {
-    acc[j >> 2][j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j & 3], cur.xf[j >> 2], acc[j >> 2][j & 3], 0, 0, 0);
+    acc[j >> 2][j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j & 3], xf[j >> 2], acc[j >> 2][j & 3], 0, 0, 0);
 #pragma unroll
     for (int a = 0; a < n_act; ++a) {
       if ((a * n_mfma) / n_act != j) continue;
-      if (a < 8) {
-        if (read_next)
-          nxt.w[a >> 1][a & 1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (lds_s16x4_ptr)(bs_n + t.b_rd[a >> 1] + ks_n * 8 * kLine + (a & 1) * 2 * kLine));
-      } else if (a < 8 + NMT) {
-        if (read_next) nxt.xf[a - 8] = *(lds_bf16x8_cptr)(as_n + t.a_rd[ks_n] + (a - 8) * 4 * kLine);
+      if (a < S::n_reads) {
+        if (read_next) gemm_read_one<LAY, NMT>(nxt, a, as_n, bs_n, ks_n, t);
       } else {
-        gemm_issue_one(t, g, load0 + (a - 8 - NMT));
+        gemm_issue_one<LAY>(t, g, load0 + (a - S::n_reads));
       }
     }
     __builtin_amdgcn_sched_barrier(0);
   }
 }
 
-template <int NMT>
-__device__ __forceinline__ void gemm_read_frags(GemmFrags<NMT>& f, lds_cptr as, lds_cptr bs, int ks,
+template <int LAY, int NMT>
+__device__ __forceinline__ void gemm_read_frags(GemmFrags<LAY, NMT>& f, lds_cptr as, lds_cptr bs, int ks,
                                                 const GemmTileCtx& t) {
 #pragma unroll
-  for (int a = 0; a < 8; ++a)
-    f.w[a >> 1][a & 1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-        (lds_s16x4_ptr)(bs + t.b_rd[a >> 1] + ks * 8 * kLine + (a & 1) * 2 * kLine));
-#pragma unroll
-  for (int mt = 0; mt < NMT; ++mt) f.xf[mt] = *(lds_bf16x8_cptr)(as + t.a_rd[ks] + mt * 4 * kLine);
+  for (int a = 0; a < GemmSliceShape<LAY, NMT>::n_reads; ++a) gemm_read_one<LAY, NMT>(f, a, as, bs, ks, t);
+}
+
+// TN only: zero the k-rows >= k_valid of one A stage and one B stage (both hold
+// 64 k-rows x 256 contiguous elements as lines of 4 k-rows x 128), so that rows
+// past the expert's segment contribute nothing.  Whole workgroup; the caller
+// brackets it with barriers.
+__device__ __forceinline__ void gemm_zero_k_tail(char* smem, int a_stage, int b_stage, int k_valid) {
+  typedef __attribute__((address_space(3))) u32x4* lds_u32x4_ptr;
+  const lds_cptr lds = (lds_cptr)smem;
+  const u32x4 z = {0u, 0u, 0u, 0u};
+  for (int idx = threadIdx.x; idx < (kBK - k_valid) * 32; idx += kGemmThreads) {
+    const int kr = k_valid + (idx >> 5), c = idx & 31;
+    const int off = ((kr >> 4) * 8 + ((kr & 15) >> 2) * 2 + (c >> 4)) * kLine + (kr & 3) * 256 + (c & 15) * 16;
+    *(lds_u32x4_ptr)(lds + a_stage * kAStageBytes + off) = z;
+    *(lds_u32x4_ptr)(lds + kBRegion + b_stage * kBStageBytes + off) = z;
+  }
+  wait_lgkmcnt0();
+  __builtin_amdgcn_s_barrier();
 }
 
 // K loop of one tile for a wave with NMT active row sub-tiles.
 //
 // Step s computes from A stage s%2 and B stage s%3.  Its barrier sits in front of
 // the LAST k slice: by then this wave has fetched all of step s's operands
-// (lgkmcnt 0), and the wait allows only the 8 weight loads of B(s+2) to be
+// (lgkmcnt 0), and the wait allows only the 8 B loads of B(s+2) to be
 // outstanding, so A(s+1) and B(s+1) are in LDS.  After the barrier that holds for
 // every wave: the stages of step s are free and are refilled by the next load
 // group, A(s+2) then B(s+3), issued four at a time behind the MFMAs of the
 // following four slices, while the first operands of step s+1 are already being
 // read under the last slice of step s.
-template <int NMT>
-__device__ __forceinline__ void gemm_k_loop(f32x16 (&acc)[kMaxMT][4], const GemmTileCtx& t, char* smem, int n_steps) {
+// k_tail (TN): valid k-rows of the last step if it is partial, else 0.
+template <int LAY, int NMT>
+__device__ __forceinline__ void gemm_k_loop(f32x16 (&acc)[kMaxMT][4], const GemmTileCtx& t, char* smem, int n_steps,
+                                            int k_tail) {
   const lds_cptr lds = (lds_cptr)smem;
+  if (n_steps <= 0) return;
   {
-    const GemmLoadGroup g0 = gemm_load_group(t, 0, 0, 0, 0);                       // A(0), B(0)
+    const GemmLoadGroup g0 = gemm_load_group<LAY>(t, 0, 0, 0, 0);                       // A(0), B(0)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) gemm_issue_one(t, g0, i);
+    for (int i = 0; i < 16; ++i) gemm_issue_one<LAY>(t, g0, i);
     if (n_steps > 1) {
-      const GemmLoadGroup g1 = gemm_load_group(t, -1, 0, 1, 1);                    // B(1)
+      const GemmLoadGroup g1 = gemm_load_group<LAY>(t, -1, 0, 1, 1);                    // B(1)
 #pragma unroll
-      for (int i = 8; i < 16; ++i) gemm_issue_one(t, g1, i);
+      for (int i = 8; i < 16; ++i) gemm_issue_one<LAY>(t, g1, i);
       wait_vmcnt<kBLinesPerWave>();
     } else {
       wait_vmcnt<0>();
     }
     __builtin_amdgcn_s_barrier();
+    if (LAY == kLayTN && n_steps == 1 && k_tail) gemm_zero_k_tail(smem, 0, 0, k_tail);
   }
-  GemmLoadGroup g = gemm_load_group(t, n_steps > 1 ? 1 : -1, 1, n_steps > 2 ? 2 : -1, 2);   // A(1), B(2)
+  GemmLoadGroup g = gemm_load_group<LAY>(t, n_steps > 1 ? 1 : -1, 1, n_steps > 2 ? 2 : -1, 2);   // A(1), B(2)
 #pragma unroll
-  for (int i = 0; i < 4; ++i) gemm_issue_one(t, g, i);
-  GemmFrags<NMT> cur, nxt;
-  if (NMT > 0) gemm_read_frags<NMT>(cur, lds, lds + kBRegion, 0, t);
+  for (int i = 0; i < 4; ++i) gemm_issue_one<LAY>(t, g, i);
+  GemmFrags<LAY, NMT> cur, nxt;
+  if (NMT > 0) gemm_read_frags<LAY, NMT>(cur, lds, lds + kBRegion, 0, t);
 
   int bs_i = 0;
   for (int s = 0; s < n_steps; ++s) {
@@ -249,11 +345,11 @@ __device__ __forceinline__ void gemm_k_loop(f32x16 (&acc)[kMaxMT][4], const Gemm
 #pragma unroll
     for (int ks = 0; ks < 3; ++ks) {
       if (NMT > 0) {
-        gemm_slice<NMT>(acc, cur, nxt, true, as, bs, ks + 1, t, g, 4 + 4 * ks);
+        gemm_slice<LAY, NMT>(acc, cur, nxt, true, as, bs, ks + 1, t, g, 4 + 4 * ks);
         cur = nxt;
       } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) gemm_issue_one(t, g, 4 + 4 * ks + i);
+        for (int i = 0; i < 4; ++i) gemm_issue_one<LAY>(t, g, 4 + 4 * ks + i);
       }
     }
     const bool more = s + 1 < n_steps;
@@ -261,82 +357,124 @@ __device__ __forceinline__ void gemm_k_loop(f32x16 (&acc)[kMaxMT][4], const Gemm
       wait_lgkmcnt0();
       if (s + 2 < n_steps) wait_vmcnt<kBLinesPerWave>(); else wait_vmcnt<0>();
       __builtin_amdgcn_s_barrier();
-      g = gemm_load_group(t, s + 2 < n_steps ? s + 2 : -1, s & 1, s + 3 < n_steps ? s + 3 : -1, bs_i);
+      // the last step's operands have landed (nothing is in flight any more): blank its k-rows past the segment
+      if (LAY == kLayTN && s + 2 == n_steps && k_tail) gemm_zero_k_tail(smem, (s + 1) & 1, bs_next, k_tail);
+      g = gemm_load_group<LAY>(t, s + 2 < n_steps ? s + 2 : -1, s & 1, s + 3 < n_steps ? s + 3 : -1, bs_i);
     }
     if (NMT > 0) {
       // `more` false: no loads left (both sources null) and nothing further to read
-      gemm_slice<NMT>(acc, cur, nxt, more, lds + ((s + 1) & 1) * kAStageBytes, lds + kBRegion + bs_next * kBStageBytes, 0, t,
-                      g, 0);
+      gemm_slice<LAY, NMT>(acc, cur, nxt, more, lds + ((s + 1) & 1) * kAStageBytes,
+                           lds + kBRegion + bs_next * kBStageBytes, 0, t, g, 0);
       if (more) cur = nxt;
     } else if (more) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) gemm_issue_one(t, g, i);
+      for (int i = 0; i < 4; ++i) gemm_issue_one<LAY>(t, g, i);
     }
     bs_i = bs_next;
   }
   __builtin_amdgcn_s_barrier();   // all stages free before the next tile's first loads
 }
 
-template <int EPI>
-__device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int mtile, int ntile, char* smem) {
+// One output tile.  NN / NT: (t0, t1) = (M tile of the tile map, N tile).
+// TN: (t0, t1, t2) = (expert, M tile, N tile) of that expert's [M, N] gradient.
+template <int LAY, int EPI>
+__device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int t1, int t2, char* smem) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps branches and LDS bases scalar
   const int wm = wave >> 1, wn = wave & 1;
   const int l32 = lane & 31, lh = lane >> 5;
 
-  const int e = p.tiles.expert[mtile];
-  const int row0 = p.tiles.row0[mtile];
-  const int rows = p.tiles.rows[mtile];
-  const int half = ((rows + 63) >> 6) << 5;                 // rows per wave row, multiple of 32
-  const int my_rows = wm == 0 ? min(rows, half) : max(0, rows - half);
-  const int n_mt = (my_rows + 31) >> 5;
+  int e, row0, rows, ntile, half, n_mt, n_steps, k_tail = 0;
+  if (LAY == kLayTN) {
+    e = t0;
+    ntile = t2;
+    row0 = t1 * kBM;                                          // first output row (of M)
+    rows = min(kBM, p.M - row0);
+    half = 128;                                               // wave rows split the staged 256 columns of A^T
+    n_mt = min(kMaxMT, max(0, (rows - wm * 128 + 31) >> 5));
+    const int seg0 = p.offsets[e], cnt = p.offsets[e + 1] - seg0;
+    n_steps = (cnt + kBK - 1) / kBK;
+    k_tail = cnt % kBK;
+  } else {
+    e = p.tiles.expert[t0];
+    row0 = p.tiles.row0[t0];
+    rows = p.tiles.rows[t0];
+    ntile = t1;
+    half = ((rows + 63) >> 6) << 5;                           // rows per wave row, multiple of 32
+    const int my_rows = wm == 0 ? min(rows, half) : max(0, rows - half);
+    n_mt = (my_rows + 31) >> 5;
+    n_steps = p.K / kBK;
+  }
 
   GemmTileCtx t;
   t.wave = wave;
+  t.kk = lane >> 4;
   t.nA = (rows + 31) >> 5;            // (8-row lines any operand read touches = 4*ceil(rows/32)) / 4 waves
+  t.lda_bytes = p.lda * 2;
   t.ldb_bytes = p.ldb * 2;
-  t.a_base = uniform_ptr(reinterpret_cast<const char*>(p.A + (size_t)row0 * p.lda));
-  t.b_base = uniform_ptr(reinterpret_cast<const char*>(p.B + (size_t)e * p.strideB));
-  {
-    // A line L = wave + 4*i holds rows 8L..8L+7; lane -> (row r = lane/8, LDS chunk position pos = lane%8),
-    // which holds k chunk pos ^ ((row/2)%8)
-    const int r = lane >> 3, pos = lane & 7;
-    const int c = pos ^ ((4 * (wave & 1) + (r >> 1)) & 7);
+  t.k_rows = 0;
+  // chunk position -> k chunk of an 8-row x 64-k line: lane -> (row r = lane/8, position pos = lane%8) holds
+  // k chunk pos ^ ((row/2)%8); line L = wave + 4*i, so (row/2)%8 = 4*(wave&1) + r/2
+  const int kc_r = lane >> 3;
+  const int kc_c = (lane & 7) ^ ((4 * (wave & 1) + (kc_r >> 1)) & 7);
+  // 4-k-row x 128-column line: lane -> (k-row kk = lane/16, position pos = lane%16) holds column chunk pos - 4*kk
+  const int tr_nl = (((lane & 15) - 4 * t.kk) & 15) * 8;
+  if (LAY == kLayTN) {
+    const int seg0 = p.offsets[e];
+    t.k_rows = p.offsets[e + 1] - seg0;
+    t.a_base = uniform_ptr(reinterpret_cast<const char*>(p.A + (size_t)seg0 * p.lda));
+    t.b_base = uniform_ptr(reinterpret_cast<const char*>(p.B + (size_t)seg0 * p.ldb));
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      t.a_off[h] = (uint32_t)(min(row0 + h * 128 + tr_nl, p.M - 8) * 2);
+      t.b_off[h] = (uint32_t)(min(ntile * kBN + h * 128 + tr_nl, p.N - 8) * 2);
+    }
+  } else {
+    t.a_base = uniform_ptr(reinterpret_cast<const char*>(p.A + (size_t)row0 * p.lda));
+    t.b_base = uniform_ptr(reinterpret_cast<const char*>(p.B + (size_t)e * p.strideB));
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      int row = min((wave + 4 * i) * 8 + r, rows - 1);      // rows past the end re-read the last row; never stored
-      t.a_off[i] = (uint32_t)((row * p.lda + c * 8) * 2);
+      const int row = min((wave + 4 * i) * 8 + kc_r, rows - 1);      // rows past the end re-read the last row; never stored
+      t.a_off[i] = (uint32_t)((row * p.lda + kc_c * 8) * 2);
     }
-    // B line: lane -> (k-row kk = lane/16, LDS chunk position pos = lane%16) holds weight chunk j = pos - 4*kk
-    const int kk = lane >> 4, bpos = lane & 15;
-    const int nl = ((bpos - 4 * kk) & 15) * 8;              // column inside a 128-column half
+    if (LAY == kLayNT) {
 #pragma unroll
-    for (int nh = 0; nh < 2; ++nh) {
-      int gcol;
-      if (EPI == kEpiSwiglu) gcol = nh * p.N + min(ntile * (kBN / 2) + nl, p.N - 8);   // half 0 = gate, 1 = up
-      else gcol = min(ntile * kBN + nh * 128 + nl, p.N - 8);
-      t.b_off[nh] = (uint32_t)((kk * p.ldb + gcol) * 2);
+      for (int i = 0; i < 8; ++i) {
+        const int n = min(ntile * kBN + (wave + 4 * i) * 8 + kc_r, p.N - 1);   // weight row = output column
+        t.b_off[i] = (uint32_t)(((size_t)n * p.ldb + kc_c * 8) * 2);
+      }
+    } else {
+#pragma unroll
+      for (int nh = 0; nh < 2; ++nh) {
+        int gcol;
+        if (EPI == kEpiSwiglu) gcol = nh * p.N + min(ntile * (kBN / 2) + tr_nl, p.N - 8);   // half 0 = gate, 1 = up
+        else gcol = min(ntile * kBN + nh * 128 + tr_nl, p.N - 8);
+        t.b_off[nh] = (uint32_t)((t.kk * p.ldb + gcol) * 2);
+      }
     }
   }
 
   // operand read offsets inside a stage
   t.lds0 = lds_addr_of(smem);
-  uint32_t (&a_rd)[4] = t.a_rd;
-  uint32_t (&b_rd)[4] = t.b_rd;
   {
-    const uint32_t a0 = (uint32_t)(((wm * half) >> 3) * kLine + (l32 >> 3) * kLine + (l32 & 7) * 128);
+    // k-contiguous stage: row m -> line m/8, 128 bytes per row, chunk swizzle by (m/2)%8
     const int f = (l32 >> 1) & 7;
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) a_rd[ks] = a0 + (uint32_t)((((ks * 2 + lh) ^ f) & 7) << 4);
+    const uint32_t a0 = (uint32_t)(((wm * half) >> 3) * kLine + (l32 >> 3) * kLine + (l32 & 7) * 128);
+    const uint32_t w0 = (uint32_t)(((wn * 128) >> 3) * kLine + (l32 >> 3) * kLine + (l32 & 7) * 128);
+    // transposing stage: 32-column block nb of the staged 256 columns
     const int g = lane >> 4, i = lane & 15;
     const int kk = i >> 2;
-#pragma unroll
-    for (int nt = 0; nt < 4; ++nt) {
-      // column block of 32 inside the tile's 256 staged columns
-      const int nb = (EPI == kEpiSwiglu) ? (nt >> 1) * 128 + wn * 64 + (nt & 1) * 32 : wn * 128 + nt * 32;
+    auto tr_off = [&](int nb) {
       const int j = ((nb & 127) >> 3) + (g & 1) * 2 + ((i & 3) >> 1);
-      b_rd[nt] = (uint32_t)((g >> 1) * 4 * kLine + (nb >> 7) * kLine + kk * 256 + ((j + 4 * kk) & 15) * 16 + (i & 1) * 8);
+      return (uint32_t)((g >> 1) * 4 * kLine + (nb >> 7) * kLine + kk * 256 + ((j + 4 * kk) & 15) * 16 + (i & 1) * 8);
+    };
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      if (LAY == kLayTN) t.a_rd[q] = tr_off(wm * 128 + q * 32);
+      else t.a_rd[q] = a0 + (uint32_t)((((q * 2 + lh) ^ f) & 7) << 4);
+      if (LAY == kLayNT) t.b_rd[q] = w0 + (uint32_t)((((q * 2 + lh) ^ f) & 7) << 4);
+      else t.b_rd[q] = tr_off((EPI == kEpiSwiglu) ? (q >> 1) * 128 + wn * 64 + (q & 1) * 32 : wn * 128 + q * 32);
     }
   }
 
@@ -348,17 +486,17 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int mtile, i
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int n_steps = p.K / kBK;
   switch (n_mt) {
-    case 0: gemm_k_loop<0>(acc, t, smem, n_steps); break;
-    case 1: gemm_k_loop<1>(acc, t, smem, n_steps); break;
-    case 2: gemm_k_loop<2>(acc, t, smem, n_steps); break;
-    case 3: gemm_k_loop<3>(acc, t, smem, n_steps); break;
-    default: gemm_k_loop<4>(acc, t, smem, n_steps); break;
+    case 0: gemm_k_loop<LAY, 0>(acc, t, smem, n_steps, k_tail); break;
+    case 1: gemm_k_loop<LAY, 1>(acc, t, smem, n_steps, k_tail); break;
+    case 2: gemm_k_loop<LAY, 2>(acc, t, smem, n_steps, k_tail); break;
+    case 3: gemm_k_loop<LAY, 3>(acc, t, smem, n_steps, k_tail); break;
+    default: gemm_k_loop<LAY, 4>(acc, t, smem, n_steps, k_tail); break;
   }
 
   // ---- epilogue: lane holds row l32 of each 32 x 32 block and, per register group q,
   // the 4 consecutive columns q*8 + lh*4 .. +3 ----
+  __bf16* c_base = LAY == kLayTN ? p.C + (size_t)e * p.strideC : p.C;
 #pragma unroll
   for (int mt = 0; mt < kMaxMT; ++mt) {
     const int m = wm * half + mt * 32 + l32;
@@ -385,6 +523,32 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int mtile, i
             *reinterpret_cast<u32x2*>(h + p.N + c) = u32x2{pack_bf16(u[0], u[1]), pack_bf16(u[2], u[3])};
           }
         }
+    } else if (EPI == kEpiSwigluGrad) {
+      // SwiGLU_grad on the act_grad tile (Section 2.2, Figure 2b): the accumulators hold dA; with the saved
+      // pre-activations (g, u): d_gate = dA*u*s*(1 + g*(1 - s)), d_up = dA*g*s, s = sigmoid(g)
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int c = ntile * kBN + wn * 128 + nt * 32 + q * 8 + lh * 4;
+          if (c >= p.N) continue;
+          const __bf16* h = p.G + grow * (size_t)(2 * p.N);
+          const u32x2 gv = *reinterpret_cast<const u32x2*>(h + c);
+          const u32x2 uv = *reinterpret_cast<const u32x2*>(h + p.N + c);
+          const float g[4] = {bf16_lo(gv.x), bf16_hi(gv.x), bf16_lo(gv.y), bf16_hi(gv.y)};
+          const float u[4] = {bf16_lo(uv.x), bf16_hi(uv.x), bf16_lo(uv.y), bf16_hi(uv.y)};
+          float dg[4], du[4];
+#pragma unroll
+          for (int x = 0; x < 4; ++x) {
+            const float da = acc[mt][nt][q * 4 + x];
+            const float s = sigmoidf_(g[x]);
+            dg[x] = da * u[x] * s * (1.f + g[x] * (1.f - s));
+            du[x] = da * g[x] * s;
+          }
+          __bf16* o = p.C + grow * p.ldc;
+          *reinterpret_cast<u32x2*>(o + c) = u32x2{pack_bf16(dg[0], dg[1]), pack_bf16(dg[2], dg[3])};
+          *reinterpret_cast<u32x2*>(o + p.N + c) = u32x2{pack_bf16(du[0], du[1]), pack_bf16(du[2], du[3])};
+        }
     } else {
 #pragma unroll
       for (int nt = 0; nt < 4; ++nt)
@@ -392,12 +556,19 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int mtile, i
         for (int q = 0; q < 4; ++q) {
           const int c = ntile * kBN + wn * 128 + nt * 32 + q * 8 + lh * 4;
           if (c >= p.N) continue;
-          *reinterpret_cast<u32x2*>(p.C + grow * p.ldc + c) =
+          *reinterpret_cast<u32x2*>(c_base + grow * p.ldc + c) =
               u32x2{pack_bf16(acc[mt][nt][q * 4 + 0], acc[mt][nt][q * 4 + 1]),
                     pack_bf16(acc[mt][nt][q * 4 + 2], acc[mt][nt][q * 4 + 3])};
         }
     }
   }
+}
+
+// Forward tile (activations x weights), as used by the serialized kernels and the
+// persistent scheduler.
+template <int EPI>
+__device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int mtile, int ntile, char* smem) {
+  gemm_tile_bf16<kLayNN, EPI>(p, mtile, ntile, 0, smem);
 }
 
 // Tile id for workgroup b in sweep `it` of a grid of G workgroups (G % 8 == 0).
@@ -408,7 +579,7 @@ __device__ __forceinline__ int xcd_tile_id(int it, int b, int G) {
   return it * G + (b & 7) * (G >> 3) + (b >> 3);
 }
 
-template <int EPI>
+template <int LAY, int EPI>
 __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void grouped_gemm_bf16_kernel(GemmParams p) {
   __shared__ __attribute__((aligned(1024))) char smem[kGemmLdsBytes];
@@ -420,7 +591,25 @@ void grouped_gemm_bf16_kernel(GemmParams p) {
     // the division runs on the vector ALU; pin the (uniform) results back into scalar registers
     const int mtile = __builtin_amdgcn_readfirstlane(tile / p.n_ntiles);
     const int ntile = tile - mtile * p.n_ntiles;
-    gemm_tile_bf16<EPI>(p, mtile, ntile, smem);
+    gemm_tile_bf16<LAY, EPI>(p, mtile, ntile, 0, smem);
+  }
+}
+
+// Weight gradients: one [M, N] output per expert, reduction over the expert's rows
+// (w2_grad, w1_grad of Section 2.2).  Experts without rows get zeros.
+__global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void grouped_wgrad_bf16_kernel(GemmParams p) {
+  __shared__ __attribute__((aligned(1024))) char smem[kGemmLdsBytes];
+  const int per_e = p.n_mtiles * p.n_ntiles;
+  const int total = p.E_local * per_e;
+  const int G = gridDim.x;
+  for (int it = 0; it * G < total; ++it) {
+    const int tile = xcd_tile_id(it, blockIdx.x, G);
+    if (tile >= total) continue;
+    const int e = __builtin_amdgcn_readfirstlane(tile / per_e);
+    const int rem = tile - e * per_e;
+    const int mt = __builtin_amdgcn_readfirstlane(rem / p.n_ntiles);
+    gemm_tile_bf16<kLayTN, kEpiStore>(p, e, mt, rem - mt * p.n_ntiles, smem);
   }
 }
 

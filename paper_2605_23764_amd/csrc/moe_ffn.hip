@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include "backward.h"
 #include "common.h"
 #include "gemm_bf16.h"
 #include "gemm_f32.h"
@@ -193,7 +194,7 @@ int gemm_grid(const Ctx& c) { return (c.n_cu + 7) / 8 * 8; }
 template <typename P, typename T>
 P gemm1_params(const Ctx& c, const void* w_gate_up) {
   const MoeShape& s = c.s;
-  P p;
+  P p{};
   p.A = static_cast<const T*>(c.sv.Xp); p.B = static_cast<const T*>(w_gate_up);
   p.C = static_cast<T*>(c.sv.A); p.C2 = static_cast<T*>(c.sv.H1);
   p.strideB = (long)s.H * 2 * s.I; p.K = s.H; p.N = s.I;
@@ -206,7 +207,7 @@ P gemm1_params(const Ctx& c, const void* w_gate_up) {
 template <typename P, typename T>
 P gemm2_params(const Ctx& c, const void* w_down) {
   const MoeShape& s = c.s;
-  P p;
+  P p{};
   p.A = static_cast<const T*>(c.sv.A); p.B = static_cast<const T*>(w_down);
   p.C = static_cast<T*>(c.sv.Yp); p.C2 = nullptr;
   p.strideB = (long)s.I * s.H; p.K = s.I; p.N = s.H;
@@ -218,7 +219,7 @@ P gemm2_params(const Ctx& c, const void* w_down) {
 
 int run_gemm1(const Ctx& c, const void* w_gate_up) {
   if (c.s.dtype == MOE_BF16)
-    hipLaunchKernelGGL(grouped_gemm_bf16_kernel<kEpiSwiglu>, dim3(gemm_grid(c)), dim3(kGemmThreads), 0, c.stream,
+    hipLaunchKernelGGL((grouped_gemm_bf16_kernel<kLayNN, kEpiSwiglu>), dim3(gemm_grid(c)), dim3(kGemmThreads), 0, c.stream,
                        gemm1_params<GemmParams, __bf16>(c, w_gate_up));
   else
     hipLaunchKernelGGL(grouped_gemm_f32_kernel<kEpiSwiglu>, dim3(gemm_grid(c) * 4), dim3(256), 0, c.stream,
@@ -228,7 +229,7 @@ int run_gemm1(const Ctx& c, const void* w_gate_up) {
 
 int run_gemm2(const Ctx& c, const void* w_down) {
   if (c.s.dtype == MOE_BF16)
-    hipLaunchKernelGGL(grouped_gemm_bf16_kernel<kEpiStore>, dim3(gemm_grid(c)), dim3(kGemmThreads), 0, c.stream,
+    hipLaunchKernelGGL((grouped_gemm_bf16_kernel<kLayNN, kEpiStore>), dim3(gemm_grid(c)), dim3(kGemmThreads), 0, c.stream,
                        gemm2_params<GemmParams, __bf16>(c, w_down));
   else
     hipLaunchKernelGGL(grouped_gemm_f32_kernel<kEpiStore>, dim3(gemm_grid(c) * 4), dim3(256), 0, c.stream,
@@ -293,6 +294,125 @@ int run_combine(const Ctx& c, void* out) {
   return launch_status();
 }
 
+// ---- backward ----
+struct BwdLayout {
+  size_t meta, tile_expert, tile_row0, tile_rows, dYp, dH1, dXp, total;
+};
+
+BwdLayout make_bwd_layout(const MoeShape& s) {
+  BwdLayout L{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+  const size_t Rm = (size_t)r_max(s), eb = (size_t)elem_bytes(s);
+  L.meta = take(kMetaWords * 4);
+  L.tile_expert = take((size_t)max_mtiles(s) * 4);
+  L.tile_row0 = take((size_t)max_mtiles(s) * 4);
+  L.tile_rows = take((size_t)max_mtiles(s) * 4);
+  L.dYp = take(Rm * s.H * eb);
+  L.dH1 = take(Rm * 2 * s.I * eb);
+  L.dXp = take(Rm * s.H * eb);
+  L.total = off;
+  return L;
+}
+
+struct BwdCtx {
+  MoeShape s;
+  BwdLayout L;
+  char* ws;
+  MoeSaved sv;
+  hipStream_t stream;
+  int n_cu;
+  TileMap tiles;
+};
+
+template <typename T>
+int run_backward(const BwdCtx& c, const void* dy, const void* w_gate_up, const void* w_down, void* dx,
+                 void* dw_gate_up, void* dw_down, float* d_topk_w) {
+  constexpr bool BF16 = std::is_same<T, __bf16>::value;
+  const MoeShape& s = c.s;
+  T* dYp = reinterpret_cast<T*>(c.ws + c.L.dYp);
+  T* dH1 = reinterpret_cast<T*>(c.ws + c.L.dH1);
+  T* dXp = reinterpret_cast<T*>(c.ws + c.L.dXp);
+  const int bm = tile_bm(s);
+  const int tn = BF16 ? kBN : kFBN;
+  auto ceil_div = [](int a, int b) { return (a + b - 1) / b; };
+  const int grid = BF16 ? (c.n_cu + 7) / 8 * 8 : c.n_cu * 4;
+
+  hipLaunchKernelGGL(tile_map_kernel, dim3(1), dim3(kWave), 0, c.stream, c.sv.counts, s.E_local, bm,
+                     BF16 ? kRowGranule : kFBM, c.tiles);
+
+  // backward Dispatch
+  BwdDispatchParams bd;
+  bd.dY = dy; bd.Yp = c.sv.Yp; bd.dYp = dYp; bd.row_of = c.sv.row_of; bd.topk_w = c.sv.topk_w;
+  bd.d_topk_w = d_topk_w; bd.T = s.T; bd.H = s.H; bd.k = s.k;
+  {
+    long want = ((long)s.T + 3) / 4;
+    int g = (int)(want < (long)c.n_cu * 8 ? want : (long)c.n_cu * 8);
+    hipLaunchKernelGGL(bwd_dispatch_kernel<BF16>, dim3(g), dim3(256), 0, c.stream, bd);
+  }
+
+  using P = typename std::conditional<BF16, GemmParams, GemmBwdParamsF32>::type;
+  // act_grad + SwiGLU_grad: dH1 = swiglu'(dYp W_down^T ; H1)
+  {
+    P p{};
+    p.A = dYp; p.B = static_cast<const T*>(w_down); p.C = dH1; p.G = static_cast<const T*>(c.sv.H1);
+    p.strideB = (long)s.I * s.H; p.K = s.H; p.N = s.I;
+    p.lda = s.H; p.ldb = s.H; p.ldc = 2 * s.I;
+    p.n_ntiles = ceil_div(s.I, tn);
+    p.tiles = c.tiles;
+    if constexpr (BF16)
+      hipLaunchKernelGGL((grouped_gemm_bf16_kernel<kLayNT, kEpiSwigluGrad>), dim3(grid), dim3(kGemmThreads), 0,
+                         c.stream, p);
+    else
+      hipLaunchKernelGGL(grouped_dgrad_f32_kernel<kEpiSwigluGrad>, dim3(grid), dim3(256), 0, c.stream, p);
+  }
+  // w2_grad: dW_down[e] = A_e^T dYp_e
+  {
+    P p{};
+    p.A = static_cast<const T*>(c.sv.A); p.B = dYp; p.C = static_cast<T*>(dw_down);
+    p.strideC = (long)s.I * s.H; p.M = s.I; p.N = s.H;
+    p.lda = s.I; p.ldb = s.H; p.ldc = s.H;
+    p.n_mtiles = ceil_div(s.I, bm); p.n_ntiles = ceil_div(s.H, tn);
+    p.E_local = s.E_local; p.offsets = c.sv.offsets;
+    if constexpr (BF16) hipLaunchKernelGGL(grouped_wgrad_bf16_kernel, dim3(grid), dim3(kGemmThreads), 0, c.stream, p);
+    else hipLaunchKernelGGL(grouped_wgrad_f32_kernel, dim3(grid), dim3(256), 0, c.stream, p);
+  }
+  // gate_grad: dXp = dH1 W_gate_up^T
+  {
+    P p{};
+    p.A = dH1; p.B = static_cast<const T*>(w_gate_up); p.C = dXp;
+    p.strideB = (long)s.H * 2 * s.I; p.K = 2 * s.I; p.N = s.H;
+    p.lda = 2 * s.I; p.ldb = 2 * s.I; p.ldc = s.H;
+    p.n_ntiles = ceil_div(s.H, tn);
+    p.tiles = c.tiles;
+    if constexpr (BF16)
+      hipLaunchKernelGGL((grouped_gemm_bf16_kernel<kLayNT, kEpiStore>), dim3(grid), dim3(kGemmThreads), 0, c.stream, p);
+    else
+      hipLaunchKernelGGL(grouped_dgrad_f32_kernel<kEpiStore>, dim3(grid), dim3(256), 0, c.stream, p);
+  }
+  // w1_grad: dW_gate_up[e] = Xp_e^T dH1_e
+  {
+    P p{};
+    p.A = static_cast<const T*>(c.sv.Xp); p.B = dH1; p.C = static_cast<T*>(dw_gate_up);
+    p.strideC = (long)s.H * 2 * s.I; p.M = s.H; p.N = 2 * s.I;
+    p.lda = s.H; p.ldb = 2 * s.I; p.ldc = 2 * s.I;
+    p.n_mtiles = ceil_div(s.H, bm); p.n_ntiles = ceil_div(2 * s.I, tn);
+    p.E_local = s.E_local; p.offsets = c.sv.offsets;
+    if constexpr (BF16) hipLaunchKernelGGL(grouped_wgrad_bf16_kernel, dim3(grid), dim3(kGemmThreads), 0, c.stream, p);
+    else hipLaunchKernelGGL(grouped_wgrad_f32_kernel, dim3(grid), dim3(256), 0, c.stream, p);
+  }
+  // backward Combine: dX[t] = sum over local slots of dXp[row_of[t,j]]
+  {
+    CombineParams p;
+    p.Yp = dXp; p.out = dx; p.row_of = c.sv.row_of; p.topk_w = nullptr;
+    p.T = s.T; p.H = s.H; p.k = s.k;
+    long want = ((long)s.T + 3) / 4;
+    int g = (int)(want < (long)c.n_cu * 8 ? want : (long)c.n_cu * 8);
+    hipLaunchKernelGGL(combine_kernel<BF16>, dim3(g), dim3(256), 0, c.stream, p);
+  }
+  return launch_status();
+}
+
 }  // namespace
 
 extern "C" {
@@ -314,7 +434,7 @@ int moe_ffn_workspace_bytes(const MoeShape* shape, size_t* fwd_bytes, size_t* bw
   if (st != MOE_OK) return st;
   Layout L = make_layout(*shape);
   if (fwd_bytes) *fwd_bytes = L.fwd_total;
-  if (bwd_bytes) *bwd_bytes = L.fwd_total;
+  if (bwd_bytes) *bwd_bytes = make_bwd_layout(*shape).total;
   return MOE_OK;
 }
 
@@ -388,10 +508,35 @@ int moe_ffn_backward(const MoeShape* shape, const void* d_dy, const void* d_x, c
                      const void* d_w_down, const MoeSaved* saved, void* d_dx, void* d_dw_gate_up,
                      void* d_dw_down, float* d_dtopk_w, void* d_workspace, size_t workspace_bytes, int mode,
                      void* stream) {
-  (void)shape; (void)d_dy; (void)d_x; (void)d_w_gate_up; (void)d_w_down; (void)saved; (void)d_dx;
-  (void)d_dw_gate_up; (void)d_dw_down; (void)d_dtopk_w; (void)d_workspace; (void)workspace_bytes;
-  (void)mode; (void)stream;
-  return MOE_ERR_INVALID_ARG;  // not built yet
+  int st = check_shape(shape);
+  if (st != MOE_OK) return st;
+  if (mode != MOE_MODE_SERIALIZED) return MOE_ERR_INVALID_ARG;   // the backward graph runs as one launch per operator
+  if (shape->T == 0) return MOE_OK;
+  // 32-bit byte offsets of segment rows inside the weight-gradient loads
+  if ((double)shape->T * (2 * shape->I > shape->H ? 2 * shape->I : shape->H) * elem_bytes(*shape) >= 4.0e9)
+    return MOE_ERR_UNSUPPORTED_SHAPE;
+  BwdCtx c;
+  c.s = *shape;
+  c.L = make_bwd_layout(c.s);
+  if (!d_workspace || !aligned16(d_workspace) || !saved) return MOE_ERR_INVALID_ARG;
+  if (workspace_bytes < c.L.total) return MOE_ERR_WORKSPACE_TOO_SMALL;
+  const void* must[] = {d_dy, d_w_gate_up, d_w_down, d_dx, d_dw_gate_up, d_dw_down, d_dtopk_w,
+                        saved->topk_w, saved->counts, saved->offsets, saved->row_of,
+                        saved->Xp, saved->H1, saved->A, saved->Yp};
+  for (const void* q : must)
+    if (!q || !aligned16(q)) return MOE_ERR_INVALID_ARG;
+  (void)d_x;   // the dispatched copy saved->Xp is used instead
+  c.ws = static_cast<char*>(d_workspace);
+  c.sv = *saved;
+  c.stream = static_cast<hipStream_t>(stream);
+  c.n_cu = device_cus();
+  c.tiles.expert = reinterpret_cast<int32_t*>(c.ws + c.L.tile_expert);
+  c.tiles.row0 = reinterpret_cast<int32_t*>(c.ws + c.L.tile_row0);
+  c.tiles.rows = reinterpret_cast<int32_t*>(c.ws + c.L.tile_rows);
+  c.tiles.meta = reinterpret_cast<int32_t*>(c.ws + c.L.meta);
+  return c.s.dtype == MOE_BF16
+             ? run_backward<__bf16>(c, d_dy, d_w_gate_up, d_w_down, d_dx, d_dw_gate_up, d_dw_down, d_dtopk_w)
+             : run_backward<float>(c, d_dy, d_w_gate_up, d_w_down, d_dx, d_dw_gate_up, d_dw_down, d_dtopk_w);
 }
 
 int moe_ffn_debug_set_spin_limit(uint32_t polls) {

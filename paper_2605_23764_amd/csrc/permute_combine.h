@@ -57,7 +57,7 @@ struct CombineParams {
   const void* Yp;          // [R_max,H]
   void* out;               // [T,H]
   const int32_t* row_of;   // [T,k]
-  const float* topk_w;     // [T,k]
+  const float* topk_w;     // [T,k]; nullptr = unit weights (backward Combine)
   int T, H, k;
 };
 
@@ -71,7 +71,7 @@ __device__ __forceinline__ void combine_token(const CombineParams& p, int t) {
 #pragma unroll
   for (int j = 0; j < kMaxK; ++j) {
     rows[j] = j < p.k ? p.row_of[(size_t)t * p.k + j] : -1;
-    w[j] = j < p.k ? p.topk_w[(size_t)t * p.k + j] : 0.f;
+    w[j] = j < p.k ? (p.topk_w ? p.topk_w[(size_t)t * p.k + j] : 1.f) : 0.f;
   }
   if (BF16) {
     const int vec_per_row = p.H / 8;

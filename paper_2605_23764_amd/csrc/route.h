@@ -183,6 +183,43 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
   return v;
 }
 
+// Rows per expert -> counts, offsets (both optional outputs) and the M-tile map, by
+// ONE wave.  cnt may live in LDS or in global memory.
+__device__ __forceinline__ void build_tile_map(int E_local, const int32_t* cnt, int BM, int granule,
+                                               int32_t* counts, int32_t* offsets, const TileMap& tiles) {
+  const int lane = lane_id();
+  int row_run = 0, tile_run = 0;
+  for (int e0 = 0; e0 < E_local; e0 += kWave) {
+    int e = e0 + lane;
+    int c = e < E_local ? cnt[e] : 0;
+    int nt = (c + BM - 1) / BM;
+    int row_incl = wave_incl_scan(c, lane);
+    int tile_incl = wave_incl_scan(nt, lane);
+    int off = row_run + row_incl - c;
+    int tbase = tile_run + tile_incl - nt;
+    if (e < E_local) {
+      if (counts) counts[e] = c;
+      if (offsets) offsets[e] = off;
+      // equal split: sibling tiles of an expert take the same time, so they
+      // stream the expert's weights in step and share them through L2
+      const int per = nt ? (((c + nt - 1) / nt + granule - 1) / granule) * granule : 0;
+      for (int i = 0; i < nt; ++i) {
+        tiles.expert[tbase + i] = e;
+        tiles.row0[tbase + i] = off + i * per;
+        tiles.rows[tbase + i] = min(per, c - i * per);
+      }
+    }
+    row_run += __shfl(row_incl, kWave - 1, kWave);
+    tile_run += __shfl(tile_incl, kWave - 1, kWave);
+  }
+  if (lane == 0) {
+    if (offsets) offsets[E_local] = row_run;
+    tiles.meta[kMetaMTiles] = tile_run;
+    tiles.meta[kMetaRows] = row_run;
+    tiles.meta[kMetaStatus] = 0;
+  }
+}
+
 // Whole-problem scan by ONE workgroup: chunk histograms -> exclusive chunk
 // offsets (in place), counts, offsets, M-tile map.  s_cnt: (kMaxE + 2) int32 of LDS.
 __device__ __forceinline__ void scan_all(const RouteParams& p, int32_t* s_cnt) {
@@ -201,38 +238,7 @@ __device__ __forceinline__ void scan_all(const RouteParams& p, int32_t* s_cnt) {
     if (lane == 0) s_cnt[e] = running;
   }
   __syncthreads();
-  if (wave == 0) {
-    int row_run = 0, tile_run = 0;
-    for (int e0 = 0; e0 < p.E_local; e0 += kWave) {
-      int e = e0 + lane;
-      int c = e < p.E_local ? s_cnt[e] : 0;
-      int nt = (c + p.BM - 1) / p.BM;
-      int row_incl = wave_incl_scan(c, lane);
-      int tile_incl = wave_incl_scan(nt, lane);
-      int off = row_run + row_incl - c;
-      int tbase = tile_run + tile_incl - nt;
-      if (e < p.E_local) {
-        p.counts[e] = c;
-        p.offsets[e] = off;
-        // equal split: sibling tiles of an expert take the same time, so they
-        // stream the expert's weights in step and share them through L2
-        const int per = nt ? (((c + nt - 1) / nt + p.granule - 1) / p.granule) * p.granule : 0;
-        for (int i = 0; i < nt; ++i) {
-          p.tiles.expert[tbase + i] = e;
-          p.tiles.row0[tbase + i] = off + i * per;
-          p.tiles.rows[tbase + i] = min(per, c - i * per);
-        }
-      }
-      row_run += __shfl(row_incl, kWave - 1, kWave);
-      tile_run += __shfl(tile_incl, kWave - 1, kWave);
-    }
-    if (lane == 0) {
-      p.offsets[p.E_local] = row_run;
-      p.tiles.meta[kMetaMTiles] = tile_run;
-      p.tiles.meta[kMetaRows] = row_run;
-      p.tiles.meta[kMetaStatus] = 0;
-    }
-  }
+  if (wave == 0) build_tile_map(p.E_local, s_cnt, p.BM, p.granule, p.counts, p.offsets, p.tiles);
 }
 
 // Rows of the local slots of one chunk, by one wave (lane = token):
@@ -305,6 +311,13 @@ __global__ __launch_bounds__(1024) void scan_kernel(RouteParams p) {
 __global__ __launch_bounds__(256) void rank_kernel(RouteParams p) {
   int chunk = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
   if (chunk < p.n_chunks) rank_chunk(p, chunk);
+}
+
+// M-tile map from the rows per expert alone (the backward rebuilds it from the
+// saved counts instead of keeping the forward's workspace alive).
+__global__ __launch_bounds__(kWave) void tile_map_kernel(const int32_t* counts, int E_local, int BM, int granule,
+                                                         TileMap tiles) {
+  build_tile_map(E_local, counts, BM, granule, nullptr, nullptr, tiles);
 }
 
 }  // namespace moe

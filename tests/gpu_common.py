@@ -86,3 +86,48 @@ def check_forward(run: GpuRun, ref: dict, dtype: str, store_h1=False):
         assert e <= tol, f"{name}: max|err|/max|ref| = {e:.3e} > {tol}"
     assert not torch.isnan(run.out.float()).any()
     return errs
+
+
+@dataclasses.dataclass
+class GpuBackward:
+    dx: torch.Tensor
+    dw_gate_up: torch.Tensor
+    dw_down: torch.Tensor
+    dtopk_w: torch.Tensor
+
+
+def run_backward(cfg: MoeConfig, inp: dict, run: GpuRun) -> GpuBackward:
+    """Backward through the C ABI on the buffers a forward with H1 stored has filled."""
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    dy = to_device(inp["dy"], cfg.dtype)
+    nan = float("nan")
+    dx = torch.full((cfg.T, cfg.H), nan, dtype=tdt, device="cuda")
+    dw1 = torch.full((cfg.E_local, cfg.H, 2 * cfg.I), nan, dtype=tdt, device="cuda")
+    dw2 = torch.full((cfg.E_local, cfg.I, cfg.H), nan, dtype=tdt, device="cuda")
+    dtw = torch.full((cfg.T, cfg.k), nan, dtype=torch.float32, device="cuda")
+    ws = moe.alloc_workspace(run.shape, backward=True)
+    moe.moe_ffn_backward(run.shape, dy, run.dev["x"], run.dev["w_gate_up"], run.dev["w_down"], run.saved,
+                         dx, dw1, dw2, dtw, ws)
+    torch.cuda.synchronize()
+    return GpuBackward(dx, dw1, dw2, dtw)
+
+
+def check_backward(bwd: GpuBackward, ref_b: dict, counts: np.ndarray, dtype: str):
+    """dX and d_topk_w against the whole tensor's scale; each expert's weight gradients
+    against that expert's own scale (so a mistake confined to a small expert shows);
+    experts without rows must hold exact zeros."""
+    tol = TOL[dtype]
+    errs = {"dX": rel_err(to_f64(bwd.dx), ref_b["dX"]),
+            "d_topk_w": rel_err(bwd.dtopk_w.cpu().numpy().astype(np.float64), ref_b["d_topk_w"])}
+    worst1 = worst2 = 0.0
+    for e in range(len(counts)):
+        g1, g2 = to_f64(bwd.dw_gate_up[e]), to_f64(bwd.dw_down[e])
+        if counts[e] == 0:
+            assert not g1.any() and not g2.any(), f"expert {e} has no rows: gradients must be zero"
+            continue
+        worst1 = max(worst1, rel_err(g1, ref_b["dW_gate_up"][e]))
+        worst2 = max(worst2, rel_err(g2, ref_b["dW_down"][e]))
+    errs["dW_gate_up"], errs["dW_down"] = worst1, worst2
+    for name, e in errs.items():
+        assert np.isfinite(e) and e <= tol, f"{name}: max|err|/max|ref| = {e:.3e} > {tol}"
+    return errs

@@ -1,0 +1,100 @@
+"""GPU parity of the backward graph (backward Dispatch, act_grad, w2_grad,
+SwiGLU_grad, gate_grad, w1_grad, backward Combine, gradient of the routing weights)
+against the fp64 oracle, through the C ABI.  Tolerance: max|err|/max|ref| <= 1e-2
+for bf16 storage (the intermediate gradients dYp, dH1, dXp are rounded to bf16, sums
+are fp32) and 1e-5 for fp32."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from workloads import CONFIGS, make_inputs
+
+pytestmark = pytest.mark.gpu
+
+SMALL = [
+    # name, T, H, I, E, E_local, base, k, dtype, seed
+    ("b_f32_a", 300, 128, 64, 8, 8, 0, 2, "f32", 31),
+    ("b_f32_shard", 257, 192, 128, 16, 5, 9, 3, "f32", 32),
+    ("b_f32_one_token", 1, 64, 64, 2, 2, 0, 1, "f32", 33),
+    ("b_bf16_a", 700, 256, 192, 8, 8, 0, 2, "bf16", 34),         # ~175 rows/expert: reduction tail, N edge
+    ("b_bf16_multi", 1500, 128, 128, 4, 4, 0, 2, "bf16", 35),     # ~750 rows/expert: 12 reduction steps, 3 M tiles
+    ("b_bf16_shard", 513, 320, 64, 64, 7, 50, 8, "bf16", 36),     # H = 1.25 tiles, I = 0.25 tile, tiny segments
+    ("b_bf16_k1", 65, 64, 64, 3, 3, 0, 1, "bf16", 37),
+    ("b_bf16_kE", 130, 64, 128, 4, 4, 0, 4, "bf16", 38),          # 130 rows per expert: 2 full steps + 2 rows
+    ("b_bf16_exact64", 64, 576, 320, 2, 2, 0, 2, "bf16", 39),     # 64 rows per expert: no reduction tail
+]
+
+
+def _run_case(cfg, never_selected=()):
+    from gpu_common import check_backward, check_forward, check_routing, run_backward, run_forward
+    inp = make_inputs(cfg, with_dy=True)
+    for e in never_selected:
+        inp["logits"][:, e] = -50.0
+    ref = oracle.forward(inp["x"], inp["logits"], inp["w_gate_up"], inp["w_down"], cfg.k, cfg.expert_base, cfg.E_local)
+    ref_b = oracle.backward(inp["dy"], ref, inp["w_gate_up"], inp["w_down"])
+    run = run_forward(cfg, inp, store_h1=True)
+    check_routing(run, ref)
+    check_forward(run, ref, cfg.dtype, store_h1=True)
+    bwd = run_backward(cfg, inp, run)
+    errs = check_backward(bwd, ref_b, ref["counts"], cfg.dtype)
+    print(cfg.name, "R=%d" % int(ref["offsets"][-1]), "counts", ref["counts"][:8].tolist(),
+          {k: "%.2e" % v for k, v in errs.items()}, flush=True)
+    return run, bwd, ref, ref_b
+
+
+@pytest.mark.parametrize("case", SMALL, ids=[c[0] for c in SMALL])
+def test_small_shapes(case):
+    from gpu_common import small_config
+    _run_case(small_config(*case))
+
+
+def test_experts_without_rows_get_zero_gradients():
+    from gpu_common import small_config
+    cfg = small_config("b_empty", 200, 64, 64, 32, 6, 20, 2, "bf16", 41)
+    run, bwd, ref, ref_b = _run_case(cfg, never_selected=(20, 23))
+    assert ref["counts"][0] == 0 and ref["counts"][3] == 0 and ref["counts"].sum() > 0
+    none_local = np.all(ref["row_of"] < 0, axis=1)
+    assert none_local.any()
+    sel = torch.from_numpy(none_local).cuda()
+    assert torch.all(bwd.dx[sel] == 0) and torch.all(bwd.dtopk_w[sel] == 0)
+
+
+@pytest.mark.parametrize("name", ["c1", "c2"])
+def test_mid_configs(name):
+    import dataclasses
+    cfg = dataclasses.replace(CONFIGS[name], name=name + "_bwd")
+    _run_case(cfg)
+
+
+def test_config_c5_full():
+    """The full-size training configuration, compared element by element."""
+    _run_case(CONFIGS["c5"])
+
+
+def test_backward_argument_errors():
+    import paper_2605_23764_amd as moe
+    from gpu_common import run_forward, small_config
+    cfg = small_config("b_err", 64, 64, 64, 4, 4, 0, 2, "f32", 42)
+    inp = make_inputs(cfg, with_dy=True)
+    run = run_forward(cfg, inp, store_h1=True)
+    dy = torch.from_numpy(inp["dy"]).cuda()
+    dx = torch.empty_like(dy)
+    dw1 = torch.empty_like(run.dev["w_gate_up"])
+    dw2 = torch.empty_like(run.dev["w_down"])
+    dtw = torch.empty(cfg.T, cfg.k, device="cuda")
+    ws = moe.alloc_workspace(run.shape, backward=True)
+    args = (run.shape, dy, run.dev["x"], run.dev["w_gate_up"], run.dev["w_down"], run.saved, dx, dw1, dw2, dtw)
+    with pytest.raises(moe.MoeError) as ei:      # the backward graph has no single-launch mode
+        moe.moe_ffn_backward(*args, ws, moe.MODE_PERSISTENT)
+    assert ei.value.status == -1
+    with pytest.raises(moe.MoeError) as ei:
+        moe.moe_ffn_backward(*args, ws[:1024])
+    assert ei.value.status == -3
+    no_h1 = moe.alloc_saved(run.shape, store_h1=False)
+    with pytest.raises(moe.MoeError) as ei:      # saved without the GEMM-1 pre-activations
+        moe.moe_ffn_backward(run.shape, dy, run.dev["x"], run.dev["w_gate_up"], run.dev["w_down"], no_h1,
+                             dx, dw1, dw2, dtw, ws)
+    assert ei.value.status == -1
+    moe.moe_ffn_backward(*args, ws)
+    torch.cuda.synchronize()
