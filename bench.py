@@ -1,11 +1,13 @@
 #!/usr/bin/env python3
 """Benchmark of the Dispatch-to-Combine MoE-FFN layer on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3] [--no-cpu-baseline] [--no-backward]
 
 A step is one pass of the whole forward hot path (routing, dispatch permute,
 grouped GEMM-1 + SwiGLU, grouped GEMM-2, weighted combine) over one batch of
-seeded synthetic input already resident in HBM.  Prints ONE JSON line.
+seeded synthetic input already resident in HBM; `value` is its duration.  With
+--workload c5 a step is forward + backward.  For the other bf16 workloads the
+backward graph is timed as well and reported under "detail".  Prints ONE JSON line.
 """
 import argparse
 import json
@@ -25,8 +27,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-backward", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs one GPU's expert-parallel share on ONE GPU; "
@@ -42,20 +45,31 @@ def main():
     cfg = CONFIGS[args.workload]
     torch.cuda.set_device(0)
     moe.load_library()   # fails loudly if the HIP library is missing
-    inp = make_inputs(cfg)
+    with_bwd = cfg.name == "c5" or not args.no_backward
+    inp = make_inputs(cfg, with_dy=with_bwd)
     tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
     eb = 2 if cfg.dtype == "bf16" else 4
     shape = moe.make_shape(cfg.T, cfg.H, cfg.I, cfg.E, cfg.E_local, cfg.expert_base, cfg.k, tdt)
     dev = {n: torch.from_numpy(inp[n]).cuda() for n in ("x", "logits", "w_gate_up", "w_down")}
     for n in ("x", "w_gate_up", "w_down"):
         dev[n] = dev[n].to(tdt)
-    saved = moe.alloc_saved(shape)
+    saved = moe.alloc_saved(shape, store_h1=with_bwd)
     ws = moe.alloc_workspace(shape)
     out = torch.empty(cfg.T, cfg.H, dtype=tdt, device="cuda")
     stream = torch.cuda.current_stream()
+    if with_bwd:
+        dy = torch.from_numpy(inp["dy"]).cuda().to(tdt)
+        dx = torch.empty_like(dy)
+        dw1 = torch.empty_like(dev["w_gate_up"])
+        dw2 = torch.empty_like(dev["w_down"])
+        dtw = torch.empty(cfg.T, cfg.k, dtype=torch.float32, device="cuda")
+        ws_b = moe.alloc_workspace(shape, backward=True)
 
     def step(mode):
         moe.moe_ffn_forward(shape, dev["x"], dev["logits"], dev["w_gate_up"], dev["w_down"], out, saved, ws, mode)
+
+    def step_bwd():
+        moe.moe_ffn_backward(shape, dy, dev["x"], dev["w_gate_up"], dev["w_down"], saved, dx, dw1, dw2, dtw, ws_b)
 
     def timed(fn, steps, warmup):
         for _ in range(warmup):
@@ -81,6 +95,10 @@ def main():
             print(f"bench.py: mode {name} unavailable: {e}", file=sys.stderr)
     best = min(ms, key=ms.get)
     R = int(saved.offsets.cpu()[-1])
+    bwd_ms = None
+    if with_bwd:
+        step(moe.MODE_SERIALIZED)          # saved activations the backward reads
+        bwd_ms = timed(step_bwd, args.steps, args.warmup)
 
     # ---- per-operator durations: the serialized sequence with HIP events between launches
     stages = [
@@ -126,14 +144,16 @@ def main():
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": flops1 / g1 / 1e12 / MFMA_BF16_PEAK_TFLOPS,
                 "traffic": None}
 
+    fwd_bwd = cfg.name == "c5"
+    step_ms = ms[best] + (bwd_ms if fwd_bwd else 0.0)
     res = {
-        "metric": "Dispatch-to-Combine MoE-FFN us/layer (forward, routing included)",
-        "value": ms[best] * 1e3,
+        "metric": "Dispatch-to-Combine MoE-FFN us/layer (%s, routing included)" % ("forward + backward" if fwd_bwd else "forward"),
+        "value": step_ms * 1e3,
         "unit": "us/layer",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": ms[best],
+        "ms_per_step": step_ms,
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
@@ -155,6 +175,18 @@ def main():
             "hbm_peak_GBs": HBM_PEAK_GBS, "mfma_bf16_peak_tflops": MFMA_BF16_PEAK_TFLOPS,
         },
     }
+
+    if bwd_ms is not None:
+        # backward: 2x the forward GEMM work (act_grad, gate_grad, w2_grad, w1_grad); bytes: weights read once,
+        # weight gradients written once, activations and activation gradients read / written once per use
+        flops_b = 2.0 * (flops1 + flops2)
+        bytes_b = (2 * El * 3 * H * I + R * (8 * H + 7 * I) + 2 * T * H) * eb
+        res["detail"]["backward"] = {
+            "us": bwd_ms * 1e3, "tflops": flops_b / (bwd_ms * 1e-3) / 1e12,
+            "frac_of_bf16_mfma_peak": flops_b / (bwd_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+            "algorithmic_GBs": bytes_b / (bwd_ms * 1e-3) / 1e9, "algorithmic_bytes": bytes_b,
+            "frac_of_hbm_peak": bytes_b / (bwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        }
 
     if not args.no_cpu_baseline:
         import oracle

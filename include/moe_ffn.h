@@ -169,8 +169,8 @@ int moe_ffn_debug_set_spin_limit(uint32_t polls);
 /* ---- Stage entry points (the serialized path's operators, one launch each;
  *      used by the unit tests and the benchmark).  Same buffers as above. ---- */
 
-/* Routing + Dispatch bookkeeping (paper Section 2.2 "top-k routing"; Section 5.1
- * "routing-derived offsets"): fills topk_idx, topk_w, counts, offsets, row_of,
+/* Routing + Dispatch bookkeeping (paper Section 2.2, routing; Section 5.1,
+ * tile offsets derived from the routing result at run time): fills topk_idx, topk_w, counts, offsets, row_of,
  * token_of, slot_of of `saved` and the tile map in the workspace. */
 int moe_route(const MoeShape* shape, const float* d_logits, const MoeSaved* saved,
               void* d_workspace, size_t workspace_bytes, void* stream);

@@ -36,7 +36,7 @@ import numpy as np
 
 
 def route(logits, k):
-    """Top-k selection and routing scores (paper Section 2.2, "top-k routing").
+    """Top-k selection and routing scores (paper Section 2.2, the routing step of the MoE layer).
 
     For each token the experts are ordered by (logit descending, id ascending)
     and the first k are kept; the scores are the softmax over those k logits.
@@ -57,8 +57,8 @@ def route(logits, k):
 
 
 def local_permutation(topk_idx, expert_base, E_local):
-    """Dispatch bookkeeping (paper Section 2.2, Dispatch "permutes ... tokens
-    according to the routing decisions"; Section 5.1 "routing-derived offsets").
+    """Dispatch bookkeeping (paper Section 2.2: Dispatch reorders the tokens by their routing
+    decisions; Section 5.1: tile offsets follow from the routing result at run time).
 
     counts[e]   rows of local expert e
     offsets[e]  first row of expert e in the expert-contiguous order (E_local+1)

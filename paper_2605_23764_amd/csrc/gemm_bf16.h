@@ -579,19 +579,27 @@ __device__ __forceinline__ int xcd_tile_id(int it, int b, int G) {
   return it * G + (b & 7) * (G >> 3) + (b >> 3);
 }
 
+// Activation x weight GEMMs over the M-tile map.  The map lists M tiles in pairs
+// (entries 2j, 2j+1: siblings of one expert where possible).  Pair j belongs to
+// XCD j % 8 (workgroups are dealt to the XCDs round-robin by id); inside an XCD
+// the work items run N-tile-major with the two siblings adjacent, so the CUs that
+// stream the same weight panel do so at the same time behind the same L2.
 template <int LAY, int EPI>
 __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void grouped_gemm_bf16_kernel(GemmParams p) {
   __shared__ __attribute__((aligned(1024))) char smem[kGemmLdsBytes];
-  const int total = p.tiles.meta[kMetaMTiles] * p.n_ntiles;
-  const int G = gridDim.x;
-  for (int it = 0; it * G < total; ++it) {
-    const int tile = xcd_tile_id(it, blockIdx.x, G);
-    if (tile >= total) continue;
+  const int n_m = p.tiles.meta[kMetaMTiles];
+  const int xcd = blockIdx.x & 7, lw = blockIdx.x >> 3, W = gridDim.x >> 3;
+  const int n_pairs = (n_m + 1) >> 1;
+  const int pairs_x = n_pairs > xcd ? (n_pairs - xcd + 7) >> 3 : 0;
+  const int per_pair = 2 * p.n_ntiles;
+  for (int i = lw; i < pairs_x * per_pair; i += W) {
     // the division runs on the vector ALU; pin the (uniform) results back into scalar registers
-    const int mtile = __builtin_amdgcn_readfirstlane(tile / p.n_ntiles);
-    const int ntile = tile - mtile * p.n_ntiles;
-    gemm_tile_bf16<LAY, EPI>(p, mtile, ntile, 0, smem);
+    const int pl = __builtin_amdgcn_readfirstlane(i / per_pair);
+    const int rem = i - pl * per_pair;
+    const int mtile = 2 * (pl * 8 + xcd) + (rem & 1);
+    if (mtile >= n_m) continue;
+    gemm_tile_bf16<LAY, EPI>(p, mtile, rem >> 1, 0, smem);
   }
 }
 

@@ -34,7 +34,7 @@ inline int gemm1_ntiles(const MoeShape& s) { return s.dtype == MOE_BF16 ? (s.I +
 inline int gemm2_ntiles(const MoeShape& s) { return s.dtype == MOE_BF16 ? (s.H + kBN - 1) / kBN : s.H / kFBN; }
 inline long n_events(const MoeShape& s) { return kEvPerTile + 2 * max_mtiles(s); }
 inline long max_tasks_per_queue(const MoeShape& s) {
-  const long mq = (max_mtiles(s) + kNumXcd - 1) / kNumXcd;
+  const long mq = (max_mtiles(s) + kNumXcd - 1) / kNumXcd + 2;   // tiles are dealt in pairs
   return mq * ((tile_bm(s) + kPermRows - 1) / kPermRows + gemm1_ntiles(s) + gemm2_ntiles(s));
 }
 

@@ -26,16 +26,7 @@ __device__ __forceinline__ void permute_rows(const PermuteParams& p, int r_begin
     const int t = p.token_of[r];
     const uint4* src = reinterpret_cast<const uint4*>(static_cast<const char*>(p.x) + (size_t)t * p.H * p.elem_bytes);
     uint4* dst = reinterpret_cast<uint4*>(static_cast<char*>(p.Xp) + (size_t)r * p.H * p.elem_bytes);
-    // eight 16-byte loads in flight per lane: a persistent worker has only four waves
-    // on its CU, so memory-level parallelism has to come from within the wave
     int v = lane;
-    for (; v + 7 * kWave < vec_per_row; v += 8 * kWave) {
-      uint4 r[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) r[u] = src[v + u * kWave];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) dst[v + u * kWave] = r[u];
-    }
     for (; v + 3 * kWave < vec_per_row; v += 4 * kWave) {
       uint4 a = src[v], b = src[v + kWave], c = src[v + 2 * kWave], d = src[v + 3 * kWave];
       dst[v] = a; dst[v + kWave] = b; dst[v + 2 * kWave] = c; dst[v + 3 * kWave] = d;

@@ -14,12 +14,12 @@
 //
 // Queues
 //   G  (global)   ROUTE x chunks, SCAN, RANK x groups           - static, host-known
-//   X0..X7        one per XCD: PERMUTE parts, GEMM-1 tiles, GEMM-2 tiles of the M
-//                 tiles dealt to that XCD (m % 8), so tiles sharing an activation
-//                 panel sit behind one L2.  These TDs depend on the routing result
-//                 (Section 5.1: "routing-derived offsets") and are materialised on
-//                 the device by the SCAN task.  GEMM-2 tiles of M tile j are queued
-//                 behind the GEMM-1 tiles of M tile j+2: a consumer is issued about
+//   X0..X7        one per XCD: PERMUTE parts, GEMM-1 tiles, GEMM-2 tiles of the M-tile
+//                 pairs dealt to that XCD (pair % 8), so tiles sharing an activation
+//                 or weight panel sit behind one L2.  These TDs depend on the routing result
+//                 (Section 5.1: tile offsets are only known once routing is) and are materialised on
+//                 the device by the SCAN task.  GEMM-2 tiles of pair j are queued
+//                 behind the GEMM-1 tiles of pair j+1: a consumer is issued about
 //                 one sweep after its producers, close enough for L2 reuse, far
 //                 enough not to stall the queue.
 //   C  (global)   COMBINE x token groups, after every GEMM-2 tile
@@ -48,7 +48,7 @@ constexpr int kNumXcd = 8;
 constexpr int kPermRows = 32;            // rows per PERMUTE task
 constexpr int kCombineTokens = 32;       // tokens per COMBINE task
 constexpr int kRankChunksPerTask = 4;    // one chunk per wave
-constexpr int kGemm2Lag = 2;             // GEMM-2 of M tile j is queued behind GEMM-1 of M tile j + lag
+constexpr int kGemm2Lag = 1;             // GEMM-2 of tile pair j is queued behind GEMM-1 of pair j + lag
 
 enum TaskType { kTaskPermute = 0, kTaskGemm1 = 1, kTaskGemm2 = 2 };
 
@@ -186,24 +186,33 @@ __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
   if (q >= kNumXcd) return;
   const int n_mtiles = sp.meta[kMetaMTiles];
   const int nN1 = sp.g1.n_ntiles, nN2 = sp.g2.n_ntiles;
-  const int Mq = n_mtiles > q ? (n_mtiles - q + kNumXcd - 1) / kNumXcd : 0;
+  // the tile map lists M tiles in pairs (siblings of one expert where possible); queue q owns pairs q, q+8, ...
+  const int n_pairs = (n_mtiles + 1) >> 1;
+  const int Pq = n_pairs > q ? (n_pairs - q + kNumXcd - 1) / kNumXcd : 0;
   TaskDesc* tq = sp.tasks + (size_t)q * sp.max_tasks_per_q;
+  auto parts_of = [&](int m) { return (sp.route.tiles.rows[m] + kPermRows - 1) / kPermRows; };
   int n = 0;
-  for (int j = 0; j < Mq; ++j) {
-    const int m = q + kNumXcd * j;
-    const int parts = (sp.route.tiles.rows[m] + kPermRows - 1) / kPermRows;
-    for (int part = 0; part < parts; ++part) tq[n++] = TaskDesc{kTaskPermute | (part << 8), m, kEvRank, sp.n_rank_tasks};
-  }
-  for (int j = 0; j < Mq + kGemm2Lag; ++j) {
-    if (j < Mq) {
-      const int m = q + kNumXcd * j;
-      const int parts = (sp.route.tiles.rows[m] + kPermRows - 1) / kPermRows;
-      for (int nt = 0; nt < nN1; ++nt) tq[n++] = TaskDesc{kTaskGemm1 | (nt << 8), m, kEvPerTile + m, parts};
+  for (int j = 0; j < Pq; ++j)
+    for (int s = 0; s < 2; ++s) {
+      const int m = 2 * (q + kNumXcd * j) + s;
+      if (m >= n_mtiles) continue;
+      const int parts = parts_of(m);
+      for (int part = 0; part < parts; ++part) tq[n++] = TaskDesc{kTaskPermute | (part << 8), m, kEvRank, sp.n_rank_tasks};
     }
-    if (j >= kGemm2Lag) {
-      const int m = q + kNumXcd * (j - kGemm2Lag);
-      for (int nt = 0; nt < nN2; ++nt) tq[n++] = TaskDesc{kTaskGemm2 | (nt << 8), m, kEvPerTile + sp.max_mtiles + m, nN1};
-    }
+  // GEMM tiles N-tile-major with the two siblings adjacent: they stream the same weight panel at the same time
+  for (int j = 0; j < Pq + kGemm2Lag; ++j) {
+    if (j < Pq)
+      for (int nt = 0; nt < nN1; ++nt)
+        for (int s = 0; s < 2; ++s) {
+          const int m = 2 * (q + kNumXcd * j) + s;
+          if (m < n_mtiles) tq[n++] = TaskDesc{kTaskGemm1 | (nt << 8), m, kEvPerTile + m, parts_of(m)};
+        }
+    if (j >= kGemm2Lag)
+      for (int nt = 0; nt < nN2; ++nt)
+        for (int s = 0; s < 2; ++s) {
+          const int m = 2 * (q + kNumXcd * (j - kGemm2Lag)) + s;
+          if (m < n_mtiles) tq[n++] = TaskDesc{kTaskGemm2 | (nt << 8), m, kEvPerTile + sp.max_mtiles + m, nN1};
+        }
   }
   sp.meta[kMetaQueueCount0 + q] = n;
   if (q == 0) sp.meta[kMetaGemm2Total] = n_mtiles * nN2;

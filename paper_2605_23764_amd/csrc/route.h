@@ -1,5 +1,5 @@
-// Routing and Dispatch bookkeeping kernels (paper Section 2.2 "top-k routing" and
-// Dispatch; Section 5.1 "routing-derived offsets").
+// Routing and Dispatch bookkeeping kernels (paper Section 2.2: routing and
+// Dispatch; Section 5.1: tile offsets derived from the routing result at run time).
 //
 // Three steps, each a device function so that the serialized launches and the
 // persistent scheduler run the same code:
@@ -185,36 +185,55 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
 
 // Rows per expert -> counts, offsets (both optional outputs) and the M-tile map, by
 // ONE wave.  cnt may live in LDS or in global memory.
+//
+// Order of the map: an expert with nt tiles contributes nt/2 sibling pairs; pair j
+// sits at entries 2j, 2j+1.  The left-over single tiles of experts with an odd
+// count follow, in expert order, and pair up with each other.  Consumers deal pair
+// j to XCD j % 8 and run its two tiles side by side on neighbouring CUs, so the
+// weight panel both siblings stream is fetched from HBM once and hits in that
+// XCD's L2 for the second reader.
 __device__ __forceinline__ void build_tile_map(int E_local, const int32_t* cnt, int BM, int granule,
                                                int32_t* counts, int32_t* offsets, const TileMap& tiles) {
   const int lane = lane_id();
-  int row_run = 0, tile_run = 0;
+  int total_pairs = 0;
   for (int e0 = 0; e0 < E_local; e0 += kWave) {
-    int e = e0 + lane;
-    int c = e < E_local ? cnt[e] : 0;
-    int nt = (c + BM - 1) / BM;
-    int row_incl = wave_incl_scan(c, lane);
-    int tile_incl = wave_incl_scan(nt, lane);
-    int off = row_run + row_incl - c;
-    int tbase = tile_run + tile_incl - nt;
+    const int e = e0 + lane;
+    const int c = e < E_local ? cnt[e] : 0;
+    const int np_incl = wave_incl_scan(((c + BM - 1) / BM) >> 1, lane);
+    total_pairs += __shfl(np_incl, kWave - 1, kWave);
+  }
+  int row_run = 0, pair_run = 0, single_run = 0;
+  for (int e0 = 0; e0 < E_local; e0 += kWave) {
+    const int e = e0 + lane;
+    const int c = e < E_local ? cnt[e] : 0;
+    const int nt = (c + BM - 1) / BM;
+    const int np = nt >> 1, ns = nt & 1;
+    const int row_incl = wave_incl_scan(c, lane);
+    const int pair_incl = wave_incl_scan(np, lane);
+    const int single_incl = wave_incl_scan(ns, lane);
+    const int off = row_run + row_incl - c;
+    const int pbase = pair_run + pair_incl - np;
+    const int sbase = single_run + single_incl - ns;
     if (e < E_local) {
       if (counts) counts[e] = c;
       if (offsets) offsets[e] = off;
       // equal split: sibling tiles of an expert take the same time, so they
-      // stream the expert's weights in step and share them through L2
+      // stream the expert's weights in step
       const int per = nt ? (((c + nt - 1) / nt + granule - 1) / granule) * granule : 0;
       for (int i = 0; i < nt; ++i) {
-        tiles.expert[tbase + i] = e;
-        tiles.row0[tbase + i] = off + i * per;
-        tiles.rows[tbase + i] = min(per, c - i * per);
+        const int idx = i < 2 * np ? 2 * pbase + i : 2 * total_pairs + sbase;
+        tiles.expert[idx] = e;
+        tiles.row0[idx] = off + i * per;
+        tiles.rows[idx] = min(per, c - i * per);
       }
     }
     row_run += __shfl(row_incl, kWave - 1, kWave);
-    tile_run += __shfl(tile_incl, kWave - 1, kWave);
+    pair_run += __shfl(pair_incl, kWave - 1, kWave);
+    single_run += __shfl(single_incl, kWave - 1, kWave);
   }
   if (lane == 0) {
     if (offsets) offsets[E_local] = row_run;
-    tiles.meta[kMetaMTiles] = tile_run;
+    tiles.meta[kMetaMTiles] = 2 * total_pairs + single_run;
     tiles.meta[kMetaRows] = row_run;
     tiles.meta[kMetaStatus] = 0;
   }
