@@ -21,6 +21,13 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 
+# HBM bytes per launch of the dominant kernel (grouped GEMM-1 + SwiGLU), from separate
+# `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` runs of this command: counter KiB per
+# dispatch, FETCH_SIZE scaled by 2.024 and WRITE_SIZE by 1.000 (what the same counters read
+# for the permute kernel, a plain copy of known size).  Counters cannot be read inside a
+# timed run, so the figure of the last profiled build is carried here.
+MEASURED_TRAFFIC_BYTES = {"c3": (1283112.1 * 2.024 + 102026.8) * 1024}
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -144,6 +151,7 @@ def main():
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": flops1 / g1 / 1e12 / MFMA_BF16_PEAK_TFLOPS,
                 "traffic": None}
 
+    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(cfg.name) if with_bwd else None   # profiled with H1 stored
     fwd_bwd = cfg.name == "c5"
     step_ms = ms[best] + (bwd_ms if fwd_bwd else 0.0)
     res = {
