@@ -32,7 +32,8 @@
 // producer's stores have been acknowledged by the L2 before the counter moves; every
 // address is written once before its first read within a launch, so there is no
 // stale line to invalidate on the consumer side.  Events that cross XCDs (routing,
-// and GEMM-2 -> COMBINE) keep the full device-scope fences.
+// and GEMM-2 -> COMBINE) keep the full device-scope fences; since COMBINE needs every
+// GEMM-2 tile, a worker publishes its GEMM-2 completions once, after its queue has drained.
 #pragma once
 #include <type_traits>
 
@@ -172,11 +173,12 @@ __device__ __forceinline__ bool sched_wait(const SchedParams<BF16>& sp, int ev, 
 
 // Outputs of this workgroup become visible device-wide, then the counter moves.
 template <bool BF16>
-__device__ __forceinline__ void sched_trigger(const SchedParams<BF16>& sp, int ev, int wave, int scope = kScopeDevice) {
+__device__ __forceinline__ void sched_trigger(const SchedParams<BF16>& sp, int ev, int wave, int scope = kScopeDevice,
+                                              uint32_t inc = 1u) {
   if (scope == kScopeDevice) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
   else __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // stores acknowledged by the XCD's L2
   __syncthreads();
-  if (wave == 0) wave_atomic_add(&sp.events[ev], 1u);
+  if (wave == 0) wave_atomic_add(&sp.events[ev], inc);
 }
 
 // SCAN task tail: materialise the per-XCD task tables from the fresh tile map.
@@ -201,18 +203,21 @@ __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
     }
   // GEMM tiles N-tile-major with the two siblings adjacent: they stream the same weight panel at the same time
   for (int j = 0; j < Pq + kGemm2Lag; ++j) {
-    if (j < Pq)
+    if (j < Pq) {
+      const int m0 = 2 * (q + kNumXcd * j);
+      const int n_sib = min(2, n_mtiles - m0);
+      int parts[2] = {0, 0};
+      for (int s = 0; s < n_sib; ++s) parts[s] = parts_of(m0 + s);   // loaded once, not once per N tile
       for (int nt = 0; nt < nN1; ++nt)
-        for (int s = 0; s < 2; ++s) {
-          const int m = 2 * (q + kNumXcd * j) + s;
-          if (m < n_mtiles) tq[n++] = TaskDesc{kTaskGemm1 | (nt << 8), m, kEvPerTile + m, parts_of(m)};
-        }
-    if (j >= kGemm2Lag)
+        for (int s = 0; s < n_sib; ++s) tq[n++] = TaskDesc{kTaskGemm1 | (nt << 8), m0 + s, kEvPerTile + m0 + s, parts[s]};
+    }
+    if (j >= kGemm2Lag) {
+      const int m0 = 2 * (q + kNumXcd * (j - kGemm2Lag));
+      const int n_sib = min(2, n_mtiles - m0);
       for (int nt = 0; nt < nN2; ++nt)
-        for (int s = 0; s < 2; ++s) {
-          const int m = 2 * (q + kNumXcd * (j - kGemm2Lag)) + s;
-          if (m < n_mtiles) tq[n++] = TaskDesc{kTaskGemm2 | (nt << 8), m, kEvPerTile + sp.max_mtiles + m, nN1};
-        }
+        for (int s = 0; s < n_sib; ++s)
+          tq[n++] = TaskDesc{kTaskGemm2 | (nt << 8), m0 + s, kEvPerTile + sp.max_mtiles + m0 + s, nN1};
+    }
   }
   sp.meta[kMetaQueueCount0 + q] = n;
   if (q == 0) sp.meta[kMetaGemm2Total] = n_mtiles * nN2;
@@ -220,7 +225,7 @@ __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
 
 template <bool BF16>
 __device__ __forceinline__ void run_tile_task(const SchedParams<BF16>& sp, const TaskDesc& td, char* smem, volatile int* s_box,
-                                              int wave, long long& t_start) {
+                                              int wave, long long& t_start, uint32_t& gemm2_done) {
   const int type_n = __builtin_amdgcn_readfirstlane(td.type_n);
   const int type = type_n & 0xFF, idx = type_n >> 8, m = __builtin_amdgcn_readfirstlane(td.m);
   // PERMUTE waits on the routing tasks of every XCD; the GEMM tiles wait on tasks of their own XCD queue
@@ -244,7 +249,10 @@ __device__ __forceinline__ void run_tile_task(const SchedParams<BF16>& sp, const
   } else {
     if constexpr (BF16) gemm_tile_bf16<kEpiStore>(sp.g2, m, idx, smem);
     else gemm_tile_f32<kEpiStore>(sp.g2, m, idx, reinterpret_cast<float*>(smem));
-    sched_trigger(sp, kEvGemm2, wave);
+    // COMBINE waits for every GEMM-2 tile, so completions are counted here and published once per
+    // worker after its queue has drained: a device-scope release per tile would write back the
+    // XCD's whole L2 each time (about 30 us per tile in a trace)
+    ++gemm2_done;
   }
 }
 
@@ -294,18 +302,20 @@ void persistent_forward_kernel(SchedParams<BF16> sp) {
     {
       const int q = blockIdx.x % kNumXcd;   // workgroups are dealt to XCDs round-robin by id
       const int count = __builtin_amdgcn_readfirstlane(sp.meta[kMetaQueueCount0 + q]);
+      uint32_t gemm2_done = 0;
       for (;;) {
         const int t = sched_fetch(sp.qhead, kQXcd0 + q, s_box, wave);
         if (t >= count) break;
         const TaskDesc td = sp.tasks[(size_t)q * sp.max_tasks_per_q + t];
         MOE_TRACE_FETCH(td.type_n & 0xFF, td.m, td.type_n >> 8)
         long long t_start = 0;
-        run_tile_task(sp, td, smem, s_box, wave, t_start);
+        run_tile_task(sp, td, smem, s_box, wave, t_start, gemm2_done);
 #if defined(MOE_SCHED_TRACE)
         tr_.t_start = t_start;
 #endif
         MOE_TRACE_END(sp)
       }
+      if (gemm2_done) sched_trigger(sp, kEvGemm2, wave, kScopeDevice, gemm2_done);
     }
 
     // ---- queue C: combine ----
