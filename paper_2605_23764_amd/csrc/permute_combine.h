@@ -17,7 +17,11 @@ struct PermuteParams {
 };
 
 // Copy rows [r_begin, r_end) of the expert-contiguous order: Xp[r] = x[token_of[r]].
-// Called by every wave of the workgroup; waves split the rows.
+// Called by every wave of the workgroup; waves split the rows.  U = 16-byte loads a
+// lane keeps in flight: 4 is enough when a CU holds dozens of waves; a worker of the
+// persistent kernel has four waves on its CU and needs the memory-level parallelism
+// inside the wave (a whole row in flight).
+template <int U>
 __device__ __forceinline__ void permute_rows(const PermuteParams& p, int r_begin, int r_end,
                                              int wave, int n_waves) {
   const int lane = lane_id();
@@ -27,9 +31,12 @@ __device__ __forceinline__ void permute_rows(const PermuteParams& p, int r_begin
     const uint4* src = reinterpret_cast<const uint4*>(static_cast<const char*>(p.x) + (size_t)t * p.H * p.elem_bytes);
     uint4* dst = reinterpret_cast<uint4*>(static_cast<char*>(p.Xp) + (size_t)r * p.H * p.elem_bytes);
     int v = lane;
-    for (; v + 3 * kWave < vec_per_row; v += 4 * kWave) {
-      uint4 a = src[v], b = src[v + kWave], c = src[v + 2 * kWave], d = src[v + 3 * kWave];
-      dst[v] = a; dst[v + kWave] = b; dst[v + 2 * kWave] = c; dst[v + 3 * kWave] = d;
+    for (; v + (U - 1) * kWave < vec_per_row; v += U * kWave) {
+      uint4 q[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) q[u] = src[v + u * kWave];
+#pragma unroll
+      for (int u = 0; u < U; ++u) dst[v + u * kWave] = q[u];
     }
     for (; v < vec_per_row; v += kWave) dst[v] = src[v];
   }
@@ -41,7 +48,7 @@ __global__ __launch_bounds__(256) void permute_kernel(PermuteParams p) {
   const int wave = threadIdx.x / kWave;
   // workgroup b takes rows b*n_waves .. in a grid-stride loop, one row per wave
   for (int r0 = blockIdx.x * n_waves; r0 < R; r0 += gridDim.x * n_waves)
-    permute_rows(p, r0, min(R, r0 + n_waves), wave, n_waves);
+    permute_rows<4>(p, r0, min(R, r0 + n_waves), wave, n_waves);
 }
 
 struct CombineParams {
@@ -52,67 +59,90 @@ struct CombineParams {
   int T, H, k;
 };
 
+// acc[0..EPV) += w * (the elements of one 16-byte vector)
+template <bool BF16>
+__device__ __forceinline__ void accumulate(float (&acc)[BF16 ? 8 : 4], float w, const uint4& y) {
+  if constexpr (BF16) {
+    acc[0] += w * bf16_lo(y.x); acc[1] += w * bf16_hi(y.x);
+    acc[2] += w * bf16_lo(y.y); acc[3] += w * bf16_hi(y.y);
+    acc[4] += w * bf16_lo(y.z); acc[5] += w * bf16_hi(y.z);
+    acc[6] += w * bf16_lo(y.w); acc[7] += w * bf16_hi(y.w);
+  } else {
+    acc[0] += w * __builtin_bit_cast(float, y.x); acc[1] += w * __builtin_bit_cast(float, y.y);
+    acc[2] += w * __builtin_bit_cast(float, y.z); acc[3] += w * __builtin_bit_cast(float, y.w);
+  }
+}
+
 // out[t,:] = sum_j w[t,j] * Yp[row_of[t,j],:] (local slots only), one wave per token.
+// Lane j < k holds slot j; the local slots are walked in ascending j through the
+// ballot of "row >= 0", two at a time, rows and weights as wave-uniform scalars, so
+// the loads of both rows are in flight together and no per-slot branch breaks up the
+// load batches.  Each element still accumulates its slots in order j = 0..k-1.
 template <bool BF16>
 __device__ __forceinline__ void combine_token(const CombineParams& p, int t) {
   const int lane = lane_id();
-  // statically indexed slot arrays (stay in registers); row < 0 = slot not local
-  int rows[kMaxK];
-  float w[kMaxK];
-#pragma unroll
-  for (int j = 0; j < kMaxK; ++j) {
-    rows[j] = j < p.k ? p.row_of[(size_t)t * p.k + j] : -1;
-    w[j] = j < p.k ? (p.topk_w ? p.topk_w[(size_t)t * p.k + j] : 1.f) : 0.f;
+  int rowv = -1;
+  float wv = 0.f;
+  if (lane < p.k) {
+    rowv = p.row_of[(size_t)t * p.k + lane];
+    wv = p.topk_w ? p.topk_w[(size_t)t * p.k + lane] : 1.f;
   }
-  if (BF16) {
-    const int vec_per_row = p.H / 8;
-    uint4* dst = reinterpret_cast<uint4*>(static_cast<__bf16*>(p.out) + (size_t)t * p.H);
-    // four column chunks per lane per pass: the loads of one slot are issued together
-    // (memory-level parallelism inside the wave); each element still accumulates its
-    // slots in order j = 0..k-1
-    constexpr int U = 4;
-    for (int v0 = lane; v0 < vec_per_row; v0 += U * kWave) {
-      float acc[U][8];
+  const uint64_t local = __ballot(rowv >= 0);
+  constexpr int EPV = BF16 ? 8 : 4;                 // elements per 16-byte vector
+  constexpr int U = BF16 ? 7 : 4;                   // vectors per lane per pass
+  const int vec_per_row = p.H / EPV;
+  const size_t row_bytes = (size_t)p.H * (BF16 ? 2 : 4);
+  uint4* dst = reinterpret_cast<uint4*>(static_cast<char*>(p.out) + (size_t)t * row_bytes);
+  for (int v0 = lane; v0 < vec_per_row; v0 += U * kWave) {
+    float acc[U][EPV];
 #pragma unroll
-      for (int u = 0; u < U; ++u)
+    for (int u = 0; u < U; ++u)
 #pragma unroll
-        for (int x = 0; x < 8; ++x) acc[u][x] = 0.f;
+      for (int x = 0; x < EPV; ++x) acc[u][x] = 0.f;
+    uint64_t m = local;
+    while (m != 0) {
+      const int j0 = __builtin_amdgcn_readfirstlane(__builtin_ctzll(m));
+      m &= m - 1;
+      const bool two = m != 0;
+      const int j1 = two ? __builtin_amdgcn_readfirstlane(__builtin_ctzll(m)) : j0;
+      m &= m - 1;   // no-op when m is already 0
+      const int r0 = __builtin_amdgcn_readlane(rowv, j0), r1 = __builtin_amdgcn_readlane(rowv, j1);
+      const float w0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wv), j0));
+      const float w1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wv), j1));
+      const uint4* y0p = reinterpret_cast<const uint4*>(static_cast<const char*>(p.Yp) + (size_t)r0 * row_bytes);
+      const uint4* y1p = reinterpret_cast<const uint4*>(static_cast<const char*>(p.Yp) + (size_t)r1 * row_bytes);
+      uint4 y0[U], y1[U];
 #pragma unroll
-      for (int i = 0; i < kMaxK; ++i) {
-        if (rows[i] < 0) continue;
-        const uint4* yrow = reinterpret_cast<const uint4*>(static_cast<const __bf16*>(p.Yp) + (size_t)rows[i] * p.H);
-        uint4 y[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) y[u] = (v0 + u * kWave < vec_per_row) ? yrow[v0 + u * kWave] : make_uint4(0, 0, 0, 0);
+      for (int u = 0; u < U; ++u) {
+        const bool ok = v0 + u * kWave < vec_per_row;
+        y0[u] = ok ? y0p[v0 + u * kWave] : make_uint4(0, 0, 0, 0);
+      }
+      if (two) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-          acc[u][0] += w[i] * bf16_lo(y[u].x); acc[u][1] += w[i] * bf16_hi(y[u].x);
-          acc[u][2] += w[i] * bf16_lo(y[u].y); acc[u][3] += w[i] * bf16_hi(y[u].y);
-          acc[u][4] += w[i] * bf16_lo(y[u].z); acc[u][5] += w[i] * bf16_hi(y[u].z);
-          acc[u][6] += w[i] * bf16_lo(y[u].w); acc[u][7] += w[i] * bf16_hi(y[u].w);
+          const bool ok = v0 + u * kWave < vec_per_row;
+          y1[u] = ok ? y1p[v0 + u * kWave] : make_uint4(0, 0, 0, 0);
         }
       }
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        if (v0 + u * kWave >= vec_per_row) break;
-        uint4 o;
-        o.x = pack_bf16(acc[u][0], acc[u][1]); o.y = pack_bf16(acc[u][2], acc[u][3]);
-        o.z = pack_bf16(acc[u][4], acc[u][5]); o.w = pack_bf16(acc[u][6], acc[u][7]);
-        dst[v0 + u * kWave] = o;
+      for (int u = 0; u < U; ++u) accumulate<BF16>(acc[u], w0, y0[u]);
+      if (two) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) accumulate<BF16>(acc[u], w1, y1[u]);
       }
     }
-  } else {
-    const int vec_per_row = p.H / 4;
-    float4* dst = reinterpret_cast<float4*>(static_cast<float*>(p.out) + (size_t)t * p.H);
-    for (int v = lane; v < vec_per_row; v += kWave) {
-      float4 acc = {0, 0, 0, 0};
 #pragma unroll
-      for (int i = 0; i < kMaxK; ++i) {
-        if (rows[i] < 0) continue;
-        float4 y = reinterpret_cast<const float4*>(static_cast<const float*>(p.Yp) + (size_t)rows[i] * p.H)[v];
-        acc.x += w[i] * y.x; acc.y += w[i] * y.y; acc.z += w[i] * y.z; acc.w += w[i] * y.w;
+    for (int u = 0; u < U; ++u) {
+      if (v0 + u * kWave >= vec_per_row) break;
+      uint4 o;
+      if constexpr (BF16) {
+        o.x = pack_bf16(acc[u][0], acc[u][1]); o.y = pack_bf16(acc[u][2], acc[u][3]);
+        o.z = pack_bf16(acc[u][4], acc[u][5]); o.w = pack_bf16(acc[u][6], acc[u][7]);
+      } else {
+        o.x = __builtin_bit_cast(uint32_t, acc[u][0]); o.y = __builtin_bit_cast(uint32_t, acc[u][1]);
+        o.z = __builtin_bit_cast(uint32_t, acc[u][2]); o.w = __builtin_bit_cast(uint32_t, acc[u][3]);
       }
-      dst[v] = acc;
+      dst[v0 + u * kWave] = o;
     }
   }
 }

@@ -182,45 +182,55 @@ __device__ __forceinline__ void sched_trigger(const SchedParams<BF16>& sp, int e
 }
 
 // SCAN task tail: materialise the per-XCD task tables from the fresh tile map.
+// Whole workgroup: a wave per queue, the lanes of the wave fill a block of
+// descriptors in parallel (block offsets are wave-uniform running sums).
 template <bool BF16>
 __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
-  const int q = threadIdx.x;
-  if (q >= kNumXcd) return;
+  const int lane = lane_id();
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), n_waves = blockDim.x / kWave;
   const int n_mtiles = sp.meta[kMetaMTiles];
   const int nN1 = sp.g1.n_ntiles, nN2 = sp.g2.n_ntiles;
   // the tile map lists M tiles in pairs (siblings of one expert where possible); queue q owns pairs q, q+8, ...
   const int n_pairs = (n_mtiles + 1) >> 1;
-  const int Pq = n_pairs > q ? (n_pairs - q + kNumXcd - 1) / kNumXcd : 0;
-  TaskDesc* tq = sp.tasks + (size_t)q * sp.max_tasks_per_q;
   auto parts_of = [&](int m) { return (sp.route.tiles.rows[m] + kPermRows - 1) / kPermRows; };
-  int n = 0;
-  for (int j = 0; j < Pq; ++j)
-    for (int s = 0; s < 2; ++s) {
-      const int m = 2 * (q + kNumXcd * j) + s;
-      if (m >= n_mtiles) continue;
-      const int parts = parts_of(m);
-      for (int part = 0; part < parts; ++part) tq[n++] = TaskDesc{kTaskPermute | (part << 8), m, kEvRank, sp.n_rank_tasks};
+  for (int q = wave; q < kNumXcd; q += n_waves) {
+    const int Pq = n_pairs > q ? (n_pairs - q + kNumXcd - 1) / kNumXcd : 0;
+    TaskDesc* tq = sp.tasks + (size_t)q * sp.max_tasks_per_q;
+    int n = 0;
+    for (int j = 0; j < Pq; ++j)
+      for (int s = 0; s < 2; ++s) {
+        const int m = 2 * (q + kNumXcd * j) + s;
+        if (m >= n_mtiles) continue;
+        const int parts = parts_of(m);
+        for (int part = lane; part < parts; part += kWave)
+          tq[n + part] = TaskDesc{kTaskPermute | (part << 8), m, kEvRank, sp.n_rank_tasks};
+        n += parts;
+      }
+    // GEMM tiles N-tile-major with the two siblings adjacent: they stream the same weight panel at the same time
+    for (int j = 0; j < Pq + kGemm2Lag; ++j) {
+      if (j < Pq) {
+        const int m0 = 2 * (q + kNumXcd * j);
+        const int n_sib = min(2, n_mtiles - m0);
+        const int parts0 = parts_of(m0), parts1 = n_sib > 1 ? parts_of(m0 + 1) : 0;
+        for (int i = lane; i < nN1 * n_sib; i += kWave) {
+          const int nt = i / n_sib, sib = i - nt * n_sib;
+          tq[n + i] = TaskDesc{kTaskGemm1 | (nt << 8), m0 + sib, kEvPerTile + m0 + sib, sib ? parts1 : parts0};
+        }
+        n += nN1 * n_sib;
+      }
+      if (j >= kGemm2Lag) {
+        const int m0 = 2 * (q + kNumXcd * (j - kGemm2Lag));
+        const int n_sib = min(2, n_mtiles - m0);
+        for (int i = lane; i < nN2 * n_sib; i += kWave) {
+          const int nt = i / n_sib, sib = i - nt * n_sib;
+          tq[n + i] = TaskDesc{kTaskGemm2 | (nt << 8), m0 + sib, kEvPerTile + sp.max_mtiles + m0 + sib, nN1};
+        }
+        n += nN2 * n_sib;
+      }
     }
-  // GEMM tiles N-tile-major with the two siblings adjacent: they stream the same weight panel at the same time
-  for (int j = 0; j < Pq + kGemm2Lag; ++j) {
-    if (j < Pq) {
-      const int m0 = 2 * (q + kNumXcd * j);
-      const int n_sib = min(2, n_mtiles - m0);
-      int parts[2] = {0, 0};
-      for (int s = 0; s < n_sib; ++s) parts[s] = parts_of(m0 + s);   // loaded once, not once per N tile
-      for (int nt = 0; nt < nN1; ++nt)
-        for (int s = 0; s < n_sib; ++s) tq[n++] = TaskDesc{kTaskGemm1 | (nt << 8), m0 + s, kEvPerTile + m0 + s, parts[s]};
-    }
-    if (j >= kGemm2Lag) {
-      const int m0 = 2 * (q + kNumXcd * (j - kGemm2Lag));
-      const int n_sib = min(2, n_mtiles - m0);
-      for (int nt = 0; nt < nN2; ++nt)
-        for (int s = 0; s < n_sib; ++s)
-          tq[n++] = TaskDesc{kTaskGemm2 | (nt << 8), m0 + s, kEvPerTile + sp.max_mtiles + m0 + s, nN1};
-    }
+    if (lane == 0) sp.meta[kMetaQueueCount0 + q] = n;
   }
-  sp.meta[kMetaQueueCount0 + q] = n;
-  if (q == 0) sp.meta[kMetaGemm2Total] = n_mtiles * nN2;
+  if (threadIdx.x == 0) sp.meta[kMetaGemm2Total] = n_mtiles * nN2;
 }
 
 template <bool BF16>
@@ -240,7 +250,7 @@ __device__ __forceinline__ void run_tile_task(const SchedParams<BF16>& sp, const
   if (type == kTaskPermute) {
     const int row0 = sp.route.tiles.row0[m], rows = sp.route.tiles.rows[m];
     const int r0 = row0 + idx * kPermRows;
-    permute_rows(sp.perm, r0, min(r0 + kPermRows, row0 + rows), wave, blockDim.x / kWave);
+    permute_rows<4>(sp.perm, r0, min(r0 + kPermRows, row0 + rows), wave, blockDim.x / kWave);
     sched_trigger(sp, kEvPerTile + m, wave, kScopeXcd);
   } else if (type == kTaskGemm1) {
     if constexpr (BF16) gemm_tile_bf16<kEpiSwiglu>(sp.g1, m, idx, smem);
@@ -274,15 +284,15 @@ void persistent_forward_kernel(SchedParams<BF16> sp) {
     if (t >= n_g) break;
     if (t < n_chunks) {
       MOE_TRACE_FETCH(10, t, 0) MOE_TRACE_START
-      route_chunk(sp.route, t, s_scratch);
+      route_chunk(sp.route, t, s_scratch, reinterpret_cast<float*>(s_scratch + kChunk * kMaxK));
       sched_trigger(sp, kEvRoute, wave);
       MOE_TRACE_END(sp)
     } else if (t == n_chunks) {
       MOE_TRACE_FETCH(11, t, 0)
       if (!sched_wait(sp, kEvRoute, (uint32_t)n_chunks, s_box, wave)) continue;
       MOE_TRACE_START
-      scan_all(sp.route, s_scratch);
-      __syncthreads();
+      scan_all(sp.route, s_scratch, s_scratch + kMaxE + 64, (kGemmLdsBytes - 64) / 4 - kMaxE - 64);
+      __syncthreads();   // tile map (written by wave 0) complete before every wave reads it
       build_task_tables(sp);
       sched_trigger(sp, kEvScan, wave);
       MOE_TRACE_END(sp)
@@ -291,7 +301,7 @@ void persistent_forward_kernel(SchedParams<BF16> sp) {
       if (!sched_wait(sp, kEvScan, 1u, s_box, wave)) continue;
       MOE_TRACE_START
       const int chunk = (t - n_chunks - 1) * kRankChunksPerTask + wave;
-      if (wave < kRankChunksPerTask && chunk < n_chunks) rank_chunk(sp.route, chunk);
+      if (wave < kRankChunksPerTask && chunk < n_chunks) rank_chunk(sp.route, chunk, s_scratch + wave * kRankLdsWords);
       sched_trigger(sp, kEvRank, wave);
       MOE_TRACE_END(sp)
     }

@@ -43,87 +43,97 @@ __device__ __forceinline__ float float_from_order_key(uint32_t k) {
   return __builtin_bit_cast(float, u);
 }
 
-// Wave-wide unsigned maximum through DPP row operations (no LDS traffic): row_shr
-// 1/2/4/8 leave each 16-lane row's maximum in its last lane, row_bcast 15 and 31
-// carry it across rows, lane 63 ends up with the wave maximum.  0 is the identity.
-__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
-#define MOE_DPP_MAX(ctrl, row_mask)                                                                          \
-  {                                                                                                          \
-    const uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, ctrl, row_mask, 0xf, false);         \
-    v = o > v ? o : v;                                                                                       \
+// Reductions over the 16 lanes of a DPP row (butterfly: every lane ends up with the
+// result): quad_perm [1,0,3,2] and [2,3,0,1], then the 8-lane and 16-lane mirrors.
+#define MOE_DPP_ROW_STEPS(OP)  \
+  OP(0xB1) OP(0x4E) OP(0x141) OP(0x140)
+__device__ __forceinline__ uint32_t row_max_u32(uint32_t v) {
+#define MOE_STEP(ctrl)                                                                               \
+  {                                                                                                  \
+    const uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, ctrl, 0xf, 0xf, false);      \
+    v = o > v ? o : v;                                                                               \
   }
-  MOE_DPP_MAX(0x111, 0xf)   // row_shr:1
-  MOE_DPP_MAX(0x112, 0xf)   // row_shr:2
-  MOE_DPP_MAX(0x114, 0xf)   // row_shr:4
-  MOE_DPP_MAX(0x118, 0xf)   // row_shr:8
-  MOE_DPP_MAX(0x142, 0xa)   // row_bcast:15 into rows 1 and 3
-  MOE_DPP_MAX(0x143, 0xc)   // row_bcast:31 into rows 2 and 3
-#undef MOE_DPP_MAX
-  return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+  MOE_DPP_ROW_STEPS(MOE_STEP)
+#undef MOE_STEP
+  return v;
+}
+__device__ __forceinline__ float row_sum_f32(float v) {
+#define MOE_STEP(ctrl) v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, 0xf, 0xf, false));
+  MOE_DPP_ROW_STEPS(MOE_STEP)
+#undef MOE_STEP
+  return v;
+}
+#undef MOE_DPP_ROW_STEPS
+
+constexpr int kScanStageWords = 12288;    // LDS words the scan kernel can stage (48 KB)
+constexpr int kRouteTokensPerWave = 4;    // one token per 16-lane row
+constexpr int kRouteKeys = kMaxE / 16;    // experts per lane
+
+// Logits of the wave's four tokens as order-preserving keys: lane s of row r holds
+// experts 16s .. 16s+15 of token t_first + r (0 = absent).
+__device__ __forceinline__ void route_load(const RouteParams& p, int t_first, int lane, uint32_t (&key)[kRouteKeys]) {
+  const int t = min(t_first + (lane >> 4), p.T - 1);   // tokens past the end repeat the last one; results are not stored
+  const float* row = p.logits + (size_t)t * p.E;
+  const int e0 = (lane & 15) * kRouteKeys;
+  if ((p.E & 3) == 0) {
+#pragma unroll
+    for (int i = 0; i < kRouteKeys; i += 4) {
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      const bool in = e0 + i < p.E;
+      if (in) v = *reinterpret_cast<const float4*>(row + e0 + i);
+      key[i + 0] = in ? float_order_key(v.x) : 0u;
+      key[i + 1] = in ? float_order_key(v.y) : 0u;
+      key[i + 2] = in ? float_order_key(v.z) : 0u;
+      key[i + 3] = in ? float_order_key(v.w) : 0u;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < kRouteKeys; ++i) key[i] = e0 + i < p.E ? float_order_key(row[e0 + i]) : 0u;
+  }
 }
 
-constexpr int kRouteTokensPerWave = 4;   // tokens a wave routes at once (independent reduction chains overlap)
-
-// Top-k of kRouteTokensPerWave tokens by one wave.  Lane l holds the logits of
-// experts l, l+64, l+128, l+192 as order-preserving 32-bit keys (0 = taken or
-// absent).  Each round takes the wave maximum and, among the lanes that hold it,
-// the lowest expert id: ids grow with the register index first, then with the
-// lane, so the first register whose ballot is non-empty and its lowest set lane
-// win.  Lane j < k ends up holding slot j.
-__device__ __forceinline__ void route_tokens(const RouteParams& p, int t_first, int lane, int32_t* s_idx_first) {
-  constexpr int Q = kRouteTokensPerWave, PL = kMaxE / kWave;
-  uint32_t key[Q][PL];
-#pragma unroll
-  for (int q = 0; q < Q; ++q) {
-    const int t = min(t_first + q, p.T - 1);   // tokens past the end repeat the last one; results are not stored
-    const float* row = p.logits + (size_t)t * p.E;
-#pragma unroll
-    for (int i = 0; i < PL; ++i) {
-      const int e = lane + i * kWave;
-      key[q][i] = e < p.E ? float_order_key(row[e]) : 0u;
-    }
-  }
-  float my_val[Q];
-  int my_idx[Q];
-#pragma unroll
-  for (int q = 0; q < Q; ++q) { my_val[q] = 0.f; my_idx[q] = 0; }
+// Top-k of four tokens by one wave, one token per 16-lane row, so every reduction
+// step serves four tokens.  Each round: a lane's best remaining key (lowest
+// position among equals), the row maximum, the lowest lane of the row that holds
+// it (expert ids grow with the lane, then with the position), and that lane
+// retires the key and files (id, logit) as slot j in LDS.  Afterwards lane s < k of
+// a row picks up slot s and the row computes the softmax over the k selected logits.
+// s_idx / s_val: [4][kMaxK] words of LDS for this wave.
+__device__ __forceinline__ void route_select(const RouteParams& p, int t_first, int lane, uint32_t (&key)[kRouteKeys],
+                                             int32_t* s_idx, float* s_val) {
+  const int row = lane >> 4, s = lane & 15;
   for (int j = 0; j < p.k; ++j) {
+    uint32_t local = key[0];
+    int li = 0;
 #pragma unroll
-    for (int q = 0; q < Q; ++q) {
-      uint32_t local = key[q][0];
+    for (int i = 1; i < kRouteKeys; ++i)
+      if (key[i] > local) { local = key[i]; li = i; }
+    const uint32_t best = row_max_u32(local);
+    const uint64_t bal = __ballot(local == best);
+    const uint32_t in_row = (uint32_t)(bal >> (row * 16)) & 0xFFFFu;
+    const bool winner = s == __builtin_ctz(in_row);   // in_row != 0: the row maximum is some lane's local maximum
 #pragma unroll
-      for (int i = 1; i < PL; ++i) local = key[q][i] > local ? key[q][i] : local;
-      const uint32_t best = wave_max_u32(local);
-      int win_i = -1, win_lane = 0;
-#pragma unroll
-      for (int i = PL - 1; i >= 0; --i) {
-        const uint64_t b = __ballot(key[q][i] == best);
-        if (b != 0) { win_i = i; win_lane = __builtin_ctzll(b); }
-      }
-#pragma unroll
-      for (int i = 0; i < PL; ++i)
-        if (i == win_i && lane == win_lane) key[q][i] = 0;
-      if (lane == j) {
-        my_val[q] = float_from_order_key(best);
-        my_idx[q] = win_lane + win_i * kWave;
-      }
+    for (int i = 0; i < kRouteKeys; ++i)
+      if (winner && i == li) key[i] = 0u;
+    if (winner) {
+      s_idx[row * kMaxK + j] = s * kRouteKeys + li;
+      s_val[row * kMaxK + j] = float_from_order_key(best);
     }
   }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   // softmax over the k selected logits; slot 0 holds the maximum
-#pragma unroll
-  for (int q = 0; q < Q; ++q) {
-    const int t = t_first + q;
-    const float m = __shfl(my_val[q], 0, kWave);
-    const float pj = lane < p.k ? expf(my_val[q] - m) : 0.f;
-    float sum = pj;
-#pragma unroll
-    for (int off = 8; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, kWave);   // k <= 16 lanes hold mass
-    sum = __shfl(sum, 0, kWave);
-    if (t < p.T && lane < p.k) {
-      p.topk_idx[(size_t)t * p.k + lane] = my_idx[q];
-      p.topk_w[(size_t)t * p.k + lane] = pj / sum;
-      s_idx_first[q * kMaxK + lane] = my_idx[q];
-    }
+  const int t = t_first + row;
+  const bool slot = s < p.k;
+  const float val = slot ? s_val[row * kMaxK + s] : 0.f;
+  const int idx = slot ? s_idx[row * kMaxK + s] : 0;
+  const float m = s_val[row * kMaxK];
+  const float pj = slot ? expf(val - m) : 0.f;
+  const float sum = row_sum_f32(pj);
+  if (t < p.T && slot) {
+    p.topk_idx[(size_t)t * p.k + s] = idx;
+    p.topk_w[(size_t)t * p.k + s] = pj / sum;
   }
 }
 
@@ -143,16 +153,26 @@ __device__ __forceinline__ void local_mask(const int32_t* idx, int k, int base, 
   }
 }
 
-// One chunk of kChunk tokens by a workgroup (16 waves x 4 tokens at 1024 threads),
-// then wave 0 (lane = token) builds the chunk's histogram with ballots.
-// s_idx: kChunk*kMaxK int32 of LDS.
-__device__ __forceinline__ void route_chunk(const RouteParams& p, int chunk, int32_t* s_idx) {
+// One chunk of kChunk tokens by a workgroup (a wave routes four tokens per pass; the
+// logits of the next pass are fetched while the current one is selected), then
+// wave 0 (lane = token) builds the chunk's histogram with ballots.
+// s_idx, s_val: kChunk*kMaxK words of LDS each.
+__device__ __forceinline__ void route_chunk(const RouteParams& p, int chunk, int32_t* s_idx, float* s_val) {
   const int lane = lane_id();
   const int wave = threadIdx.x / kWave;
   const int n_waves = blockDim.x / kWave;
   const int t0 = chunk * kChunk;
-  for (int i = wave * kRouteTokensPerWave; i < kChunk; i += n_waves * kRouteTokensPerWave)
-    if (t0 + i < p.T) route_tokens(p, t0 + i, lane, s_idx + i * kMaxK);
+  const int step = n_waves * kRouteTokensPerWave;
+  uint32_t key[kRouteKeys], key_next[kRouteKeys];
+  int i = wave * kRouteTokensPerWave;
+  if (i < kChunk && t0 + i < p.T) route_load(p, t0 + i, lane, key);
+  for (; i < kChunk && t0 + i < p.T; i += step) {
+    const bool more = i + step < kChunk && t0 + i + step < p.T;
+    if (more) route_load(p, t0 + i + step, lane, key_next);
+    route_select(p, t0 + i, lane, key, s_idx + i * kMaxK, s_val + i * kMaxK);
+#pragma unroll
+    for (int q = 0; q < kRouteKeys; ++q) key[q] = key_next[q];
+  }
   __syncthreads();
   if (wave == 0) {
     uint64_t mask[kMaskWords];
@@ -241,95 +261,100 @@ __device__ __forceinline__ void build_tile_map(int E_local, const int32_t* cnt, 
 
 // Whole-problem scan by ONE workgroup: chunk histograms -> exclusive chunk
 // offsets (in place), counts, offsets, M-tile map.  s_cnt: (kMaxE + 2) int32 of LDS.
-__device__ __forceinline__ void scan_all(const RouteParams& p, int32_t* s_cnt) {
+// s_stage: optional LDS staging area of stage_words int32.  When the histogram
+// table fits, it is pulled into LDS with coalesced loads, scanned there and written
+// back, so the per-expert scans do not pay a global round trip per 64 chunks.
+__device__ __forceinline__ void scan_all(const RouteParams& p, int32_t* s_cnt, int32_t* s_stage, int stage_words) {
   const int lane = lane_id();
   const int wave = threadIdx.x / kWave;
   const int n_waves = blockDim.x / kWave;
+  const int n = p.n_chunks * p.E_local;
+  const bool staged = s_stage != nullptr && n <= stage_words;
+  if (staged) {
+    for (int i = threadIdx.x; i < n; i += blockDim.x) s_stage[i] = p.chunk_cnt[i];
+    __syncthreads();
+  }
+  int32_t* tab = staged ? s_stage : p.chunk_cnt;
   for (int e = wave; e < p.E_local; e += n_waves) {
     int running = 0;
     for (int c0 = 0; c0 < p.n_chunks; c0 += kWave) {
       int c = c0 + lane;
-      int v = c < p.n_chunks ? p.chunk_cnt[(size_t)c * p.E_local + e] : 0;
+      int v = c < p.n_chunks ? tab[(size_t)c * p.E_local + e] : 0;
       int incl = wave_incl_scan(v, lane);
-      if (c < p.n_chunks) p.chunk_cnt[(size_t)c * p.E_local + e] = running + incl - v;
+      if (c < p.n_chunks) tab[(size_t)c * p.E_local + e] = running + incl - v;
       running += __shfl(incl, kWave - 1, kWave);
     }
     if (lane == 0) s_cnt[e] = running;
   }
   __syncthreads();
+  if (staged)
+    for (int i = threadIdx.x; i < n; i += blockDim.x) p.chunk_cnt[i] = s_stage[i];
   if (wave == 0) build_tile_map(p.E_local, s_cnt, p.BM, p.granule, p.counts, p.offsets, p.tiles);
 }
 
+constexpr int kRankLdsWords = 3 * kMaxE;   // LDS words rank_chunk needs per wave
+
 // Rows of the local slots of one chunk, by one wave (lane = token):
 // row = offsets[e] + (tokens of earlier chunks selecting e) + (earlier lanes selecting e).
-__device__ __forceinline__ void rank_chunk(const RouteParams& p, int chunk) {
+// The lanes that selected expert e are collected as a 64-bit mask per expert in LDS
+// (an OR, so the result does not depend on the order of the updates); a slot's rank
+// inside the chunk is the number of lower lanes in its expert's mask.
+// s_lds: kRankLdsWords int32 of LDS owned by this wave.
+__device__ __forceinline__ void rank_chunk(const RouteParams& p, int chunk, int32_t* s_lds) {
   const int lane = lane_id();
   const int t = chunk * kChunk + lane;
   const bool live = t < p.T;
-  int32_t idx[kMaxK], row[kMaxK];
-#pragma unroll
-  for (int j = 0; j < kMaxK; ++j) {
-    idx[j] = (live && j < p.k) ? p.topk_idx[(size_t)t * p.k + j] : -1;
-    row[j] = -1;
-  }
-  uint64_t mask[kMaskWords];
-#pragma unroll
-  for (int w = 0; w < kMaskWords; ++w) mask[w] = 0;
-#pragma unroll
-  for (int j = 0; j < kMaxK; ++j) {
-    int le = idx[j] - p.expert_base;
-    if (idx[j] >= 0 && le >= 0 && le < p.E_local) {
-#pragma unroll
-      for (int w = 0; w < kMaskWords; ++w)
-        if ((le >> 6) == w) mask[w] |= 1ull << (le & 63);
-    }
-  }
+  unsigned long long* s_mask = reinterpret_cast<unsigned long long*>(s_lds);   // [E_local]
+  int32_t* s_base = s_lds + 2 * kMaxE;                                           // [E_local]
   const int32_t* coff = p.chunk_cnt + (size_t)chunk * p.E_local;
-  const uint64_t lt = (1ull << lane) - 1ull;
-#pragma unroll
-  for (int w = 0; w < kMaskWords; ++w) {
-    if (w * 64 >= p.E_local) break;
-    const int n = min(64, p.E_local - w * 64);
-    // first row of expert w*64+lane for this chunk, fetched once (one coalesced load
-    // instead of a dependent load per expert inside the loop)
-    const int my_base = lane < n ? p.offsets[w * 64 + lane] + coff[w * 64 + lane] : 0;
-    for (int b = 0; b < n; ++b) {
-      const bool sel = (mask[w] >> b) & 1;
-      const uint64_t bal = __ballot(sel);
-      if (bal == 0) continue;
-      const int base_row = __builtin_amdgcn_readlane(my_base, b);
-      if (sel) {
-        const int r = base_row + __popcll(bal & lt);
-        const int ge = w * 64 + b + p.expert_base;
-        int slot = 0;
-#pragma unroll
-        for (int j = 0; j < kMaxK; ++j)
-          if (idx[j] == ge) { row[j] = r; slot = j; }
-        p.token_of[r] = t;
-        p.slot_of[r] = slot;
-      }
-    }
+  for (int e = lane; e < p.E_local; e += kWave) {
+    s_mask[e] = 0ull;
+    s_base[e] = p.offsets[e] + coff[e];   // first row of expert e for this chunk
   }
-  if (live) {
+  int32_t le[kMaxK];
 #pragma unroll
-    for (int j = 0; j < kMaxK; ++j)
-      if (j < p.k) p.row_of[(size_t)t * p.k + j] = row[j];
+  for (int j = 0; j < kMaxK; ++j) {
+    const int idx = (live && j < p.k) ? p.topk_idx[(size_t)t * p.k + j] : -1;
+    const int l = idx - p.expert_base;
+    le[j] = (idx >= 0 && l >= 0 && l < p.E_local) ? l : -1;
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+#pragma unroll
+  for (int j = 0; j < kMaxK; ++j)
+    if (le[j] >= 0) atomicOr(&s_mask[le[j]], 1ull << lane);
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  const unsigned long long lt = (1ull << lane) - 1ull;
+#pragma unroll
+  for (int j = 0; j < kMaxK; ++j) {
+    if (j >= p.k) break;
+    int r = -1;
+    if (le[j] >= 0) {
+      r = s_base[le[j]] + __popcll(s_mask[le[j]] & lt);
+      p.token_of[r] = t;
+      p.slot_of[r] = j;
+    }
+    if (live) p.row_of[(size_t)t * p.k + j] = r;
   }
 }
 
 __global__ __launch_bounds__(1024) void route_kernel(RouteParams p) {
   __shared__ int32_t s_idx[kChunk * kMaxK];
-  route_chunk(p, blockIdx.x, s_idx);
+  __shared__ float s_val[kChunk * kMaxK];
+  route_chunk(p, blockIdx.x, s_idx, s_val);
 }
 
 __global__ __launch_bounds__(1024) void scan_kernel(RouteParams p) {
   __shared__ int32_t s_cnt[kMaxE + 2];
-  scan_all(p, s_cnt);
+  __shared__ int32_t s_stage[kScanStageWords];
+  scan_all(p, s_cnt, s_stage, kScanStageWords);
 }
 
 __global__ __launch_bounds__(256) void rank_kernel(RouteParams p) {
+  __shared__ int32_t s_lds[4 * kRankLdsWords];
   int chunk = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
-  if (chunk < p.n_chunks) rank_chunk(p, chunk);
+  if (chunk < p.n_chunks) rank_chunk(p, chunk, s_lds + (threadIdx.x / kWave) * kRankLdsWords);
 }
 
 // M-tile map from the rows per expert alone (the backward rebuilds it from the
