@@ -6,7 +6,8 @@
 namespace moe {
 
 constexpr int kWave = 64;        // CDNA wavefront width
-constexpr int kChunk = 64;       // tokens per routing chunk (one wave, lane = token)
+constexpr int kChunk = 64;       // tokens per rank group (one wave, lane = token)
+constexpr int kSub = 32;         // tokens per routing sub-chunk (one histogram row); two per rank group
 constexpr int kMaxK = 16;        // max experts per token
 constexpr int kMaxE = 256;       // max global experts (4 logits per lane)
 constexpr int kMaskWords = 4;    // 64-bit words of a local-expert bitmask (E_local <= 256)

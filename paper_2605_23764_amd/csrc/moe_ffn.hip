@@ -28,7 +28,8 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 inline int elem_bytes(const MoeShape& s) { return s.dtype == MOE_BF16 ? 2 : 4; }
 inline int tile_bm(const MoeShape& s) { return s.dtype == MOE_BF16 ? kBM : kFBM; }
 inline long r_max(const MoeShape& s) { return (long)s.T * (s.k < s.E_local ? s.k : s.E_local); }
-inline int n_chunks(const MoeShape& s) { return (s.T + kChunk - 1) / kChunk; }
+inline int n_sub(const MoeShape& s) { return (s.T + kSub - 1) / kSub; }
+inline int n_groups(const MoeShape& s) { return (s.T + kChunk - 1) / kChunk; }
 inline long max_mtiles(const MoeShape& s) { return r_max(s) / tile_bm(s) + s.E_local + 1; }
 inline int gemm1_ntiles(const MoeShape& s) { return s.dtype == MOE_BF16 ? (s.I + kBN / 2 - 1) / (kBN / 2) : s.I / kFBN; }
 inline int gemm2_ntiles(const MoeShape& s) { return s.dtype == MOE_BF16 ? (s.H + kBN - 1) / kBN : s.H / kFBN; }
@@ -66,7 +67,7 @@ Layout make_layout(const MoeShape& s) {
   auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
   const size_t Rm = (size_t)r_max(s), eb = (size_t)elem_bytes(s);
   L.meta = take(kMetaWords * 4);
-  L.chunk_cnt = take((size_t)n_chunks(s) * s.E_local * 4);
+  L.chunk_cnt = take((size_t)n_sub(s) * s.E_local * 4);
   L.tile_expert = take((size_t)max_mtiles(s) * 4);
   L.tile_row0 = take((size_t)max_mtiles(s) * 4);
   L.tile_rows = take((size_t)max_mtiles(s) * 4);
@@ -163,7 +164,8 @@ RouteParams route_params(const Ctx& c, const float* logits) {
   p.chunk_cnt = reinterpret_cast<int32_t*>(c.ws + c.L.chunk_cnt);
   p.tiles = tile_map(c);
   p.T = c.s.T; p.E = c.s.E; p.E_local = c.s.E_local; p.expert_base = c.s.expert_base; p.k = c.s.k;
-  p.n_chunks = n_chunks(c.s);
+  p.n_sub = n_sub(c.s);
+  p.n_groups = n_groups(c.s);
   p.BM = tile_bm(c.s);
   p.granule = c.s.dtype == MOE_BF16 ? kRowGranule : kFBM;
   return p;
@@ -173,9 +175,9 @@ int launch_status() { return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_
 
 int run_route(const Ctx& c, const float* logits) {
   RouteParams p = route_params(c, logits);
-  hipLaunchKernelGGL(route_kernel, dim3(p.n_chunks), dim3(1024), 0, c.stream, p);
+  hipLaunchKernelGGL(route_kernel, dim3(p.n_sub), dim3(512), 0, c.stream, p);
   hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, c.stream, p);
-  hipLaunchKernelGGL(rank_kernel, dim3((p.n_chunks + 3) / 4), dim3(256), 0, c.stream, p);
+  hipLaunchKernelGGL(rank_kernel, dim3((p.n_groups + 3) / 4), dim3(256), 0, c.stream, p);
   return launch_status();
 }
 
@@ -273,7 +275,7 @@ int run_persistent(const Ctx& c, const void* x, const float* logits, const void*
   sp.meta = reinterpret_cast<int32_t*>(c.ws + c.L.meta);
   sp.max_mtiles = (int)max_mtiles(c.s);
   sp.max_tasks_per_q = (int)max_tasks_per_queue(c.s);
-  sp.n_rank_tasks = (sp.route.n_chunks + kRankChunksPerTask - 1) / kRankChunksPerTask;
+  sp.n_rank_tasks = (sp.route.n_groups + kRankChunksPerTask - 1) / kRankChunksPerTask;
   sp.n_comb_tasks = (c.s.T + kCombineTokens - 1) / kCombineTokens;
   sp.spin_limit = g_spin_limit;
   sp.timeout_status = MOE_ERR_SCHED_TIMEOUT;

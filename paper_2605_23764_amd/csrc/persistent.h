@@ -13,7 +13,8 @@
 // serialized launches run, so results are bit-identical for any legal order.
 //
 // Queues
-//   G  (global)   ROUTE x chunks, SCAN, RANK x groups           - static, host-known
+//   G  (global)   ROUTE x sub-chunks, SCAN, RANK x groups (SCAN and RANK both wait
+//                 only for the ROUTE tasks)                     - static, host-known
 //   X0..X7        one per XCD: PERMUTE parts, GEMM-1 tiles, GEMM-2 tiles of the M-tile
 //                 pairs dealt to that XCD (pair % 8), so tiles sharing an activation
 //                 or weight panel sit behind one L2.  These TDs depend on the routing result
@@ -276,32 +277,33 @@ void persistent_forward_kernel(SchedParams<BF16> sp) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   MOE_TRACE_DECL
 
-  // ---- queue G: routing ----
-  const int n_chunks = sp.route.n_chunks;
-  const int n_g = n_chunks + 1 + sp.n_rank_tasks;
+  // ---- queue G: routing.  SCAN (tile map, task tables) and the RANK tasks both need only the
+  // finished histogram table, so they run side by side ----
+  const int n_sub = sp.route.n_sub;
+  const int n_g = n_sub + 1 + sp.n_rank_tasks;
   for (;;) {
     const int t = sched_fetch(sp.qhead, kQGlobal, s_box, wave);
     if (t >= n_g) break;
-    if (t < n_chunks) {
+    if (t < n_sub) {
       MOE_TRACE_FETCH(10, t, 0) MOE_TRACE_START
-      route_chunk(sp.route, t, s_scratch, reinterpret_cast<float*>(s_scratch + kChunk * kMaxK));
+      route_chunk(sp.route, t, s_scratch, reinterpret_cast<float*>(s_scratch + kSub * kMaxK));
       sched_trigger(sp, kEvRoute, wave);
       MOE_TRACE_END(sp)
-    } else if (t == n_chunks) {
+    } else if (t == n_sub) {
       MOE_TRACE_FETCH(11, t, 0)
-      if (!sched_wait(sp, kEvRoute, (uint32_t)n_chunks, s_box, wave)) continue;
+      if (!sched_wait(sp, kEvRoute, (uint32_t)n_sub, s_box, wave)) continue;
       MOE_TRACE_START
-      scan_all(sp.route, s_scratch, s_scratch + kMaxE + 64, (kGemmLdsBytes - 64) / 4 - kMaxE - 64);
+      scan_all(sp.route, s_scratch, s_scratch + kMaxE + 64);
       __syncthreads();   // tile map (written by wave 0) complete before every wave reads it
       build_task_tables(sp);
       sched_trigger(sp, kEvScan, wave);
       MOE_TRACE_END(sp)
     } else {
       MOE_TRACE_FETCH(12, t, 0)
-      if (!sched_wait(sp, kEvScan, 1u, s_box, wave)) continue;
+      if (!sched_wait(sp, kEvRoute, (uint32_t)n_sub, s_box, wave)) continue;
       MOE_TRACE_START
-      const int chunk = (t - n_chunks - 1) * kRankChunksPerTask + wave;
-      if (wave < kRankChunksPerTask && chunk < n_chunks) rank_chunk(sp.route, chunk, s_scratch + wave * kRankLdsWords);
+      const int group = (t - n_sub - 1) * kRankChunksPerTask + wave;
+      if (wave < kRankChunksPerTask && group < sp.route.n_groups) rank_chunk(sp.route, group, s_scratch + wave * kRankLdsWords);
       sched_trigger(sp, kEvRank, wave);
       MOE_TRACE_END(sp)
     }

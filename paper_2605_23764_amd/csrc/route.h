@@ -23,9 +23,11 @@ struct RouteParams {
   int32_t* row_of;       // [T,k]
   int32_t* token_of;     // [R_max]
   int32_t* slot_of;      // [R_max]
-  int32_t* chunk_cnt;    // [n_chunks, E_local]  histogram, then exclusive offsets
+  int32_t* chunk_cnt;    // [n_sub, E_local]  histogram of every 32-token sub-chunk
   TileMap tiles;
-  int T, E, E_local, expert_base, k, n_chunks;
+  int T, E, E_local, expert_base, k;
+  int n_sub;     // ceil(T / kSub) histogram rows
+  int n_groups;  // ceil(T / kChunk) rank groups
   int BM;        // M-tile row capacity
   int granule;   // an expert's tiles are equal multiples of this (last one takes the remainder)
 };
@@ -65,7 +67,7 @@ __device__ __forceinline__ float row_sum_f32(float v) {
 }
 #undef MOE_DPP_ROW_STEPS
 
-constexpr int kScanStageWords = 12288;    // LDS words the scan kernel can stage (48 KB)
+constexpr int kHistBatch = 16;             // histogram rows fetched per round trip
 constexpr int kRouteTokensPerWave = 4;    // one token per 16-lane row
 constexpr int kRouteKeys = kMaxE / 16;    // experts per lane
 
@@ -153,21 +155,21 @@ __device__ __forceinline__ void local_mask(const int32_t* idx, int k, int base, 
   }
 }
 
-// One chunk of kChunk tokens by a workgroup (a wave routes four tokens per pass; the
-// logits of the next pass are fetched while the current one is selected), then
-// wave 0 (lane = token) builds the chunk's histogram with ballots.
-// s_idx, s_val: kChunk*kMaxK words of LDS each.
-__device__ __forceinline__ void route_chunk(const RouteParams& p, int chunk, int32_t* s_idx, float* s_val) {
+// One sub-chunk of kSub tokens by a workgroup (a wave routes four tokens per pass;
+// the logits of the next pass are fetched while the current one is selected), then
+// wave 0 (lane = token) builds the sub-chunk's histogram row with ballots.
+// s_idx, s_val: kSub*kMaxK words of LDS each.
+__device__ __forceinline__ void route_chunk(const RouteParams& p, int sub, int32_t* s_idx, float* s_val) {
   const int lane = lane_id();
   const int wave = threadIdx.x / kWave;
   const int n_waves = blockDim.x / kWave;
-  const int t0 = chunk * kChunk;
+  const int t0 = sub * kSub;
   const int step = n_waves * kRouteTokensPerWave;
   uint32_t key[kRouteKeys], key_next[kRouteKeys];
   int i = wave * kRouteTokensPerWave;
-  if (i < kChunk && t0 + i < p.T) route_load(p, t0 + i, lane, key);
-  for (; i < kChunk && t0 + i < p.T; i += step) {
-    const bool more = i + step < kChunk && t0 + i + step < p.T;
+  if (i < kSub && t0 + i < p.T) route_load(p, t0 + i, lane, key);
+  for (; i < kSub && t0 + i < p.T; i += step) {
+    const bool more = i + step < kSub && t0 + i + step < p.T;
     if (more) route_load(p, t0 + i + step, lane, key_next);
     route_select(p, t0 + i, lane, key, s_idx + i * kMaxK, s_val + i * kMaxK);
 #pragma unroll
@@ -176,9 +178,9 @@ __device__ __forceinline__ void route_chunk(const RouteParams& p, int chunk, int
   __syncthreads();
   if (wave == 0) {
     uint64_t mask[kMaskWords];
-    int t = t0 + lane;
-    local_mask(s_idx + lane * kMaxK, t < p.T ? p.k : 0, p.expert_base, p.E_local, mask);
-    int32_t* out = p.chunk_cnt + (size_t)chunk * p.E_local;
+    const int t = t0 + lane;
+    local_mask(s_idx + (lane & (kSub - 1)) * kMaxK, (lane < kSub && t < p.T) ? p.k : 0, p.expert_base, p.E_local, mask);
+    int32_t* out = p.chunk_cnt + (size_t)sub * p.E_local;
 #pragma unroll
     for (int w = 0; w < kMaskWords; ++w) {
       if (w * 64 >= p.E_local) break;
@@ -194,6 +196,7 @@ __device__ __forceinline__ void route_chunk(const RouteParams& p, int chunk, int
   __syncthreads();
 }
 
+// Inclusive scan across a wave.
 __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
 #pragma unroll
   for (int off = 1; off < kWave; off <<= 1) {
@@ -259,57 +262,87 @@ __device__ __forceinline__ void build_tile_map(int E_local, const int32_t* cnt, 
   }
 }
 
-// Whole-problem scan by ONE workgroup: chunk histograms -> exclusive chunk
-// offsets (in place), counts, offsets, M-tile map.  s_cnt: (kMaxE + 2) int32 of LDS.
-// s_stage: optional LDS staging area of stage_words int32.  When the histogram
-// table fits, it is pulled into LDS with coalesced loads, scanned there and written
-// back, so the per-expert scans do not pay a global round trip per 64 chunks.
-__device__ __forceinline__ void scan_all(const RouteParams& p, int32_t* s_cnt, int32_t* s_stage, int stage_words) {
+// Whole-problem step by ONE workgroup: rows per expert (column sums of the
+// histogram table) -> counts, offsets, M-tile map.  The table itself is left as it
+// is: every rank group derives its own prefix from it.
+// s_cnt: (kMaxE + 2) int32 of LDS; s_part: n_waves * kMaxE int32 of LDS.
+__device__ __forceinline__ void scan_all(const RouteParams& p, int32_t* s_cnt, int32_t* s_part) {
   const int lane = lane_id();
   const int wave = threadIdx.x / kWave;
   const int n_waves = blockDim.x / kWave;
-  const int n = p.n_chunks * p.E_local;
-  const bool staged = s_stage != nullptr && n <= stage_words;
-  if (staged) {
-    for (int i = threadIdx.x; i < n; i += blockDim.x) s_stage[i] = p.chunk_cnt[i];
-    __syncthreads();
-  }
-  int32_t* tab = staged ? s_stage : p.chunk_cnt;
-  for (int e = wave; e < p.E_local; e += n_waves) {
-    int running = 0;
-    for (int c0 = 0; c0 < p.n_chunks; c0 += kWave) {
-      int c = c0 + lane;
-      int v = c < p.n_chunks ? tab[(size_t)c * p.E_local + e] : 0;
-      int incl = wave_incl_scan(v, lane);
-      if (c < p.n_chunks) tab[(size_t)c * p.E_local + e] = running + incl - v;
-      running += __shfl(incl, kWave - 1, kWave);
+  for (int e0 = 0; e0 < p.E_local; e0 += kWave) {
+    const int e = e0 + lane;
+    int sum = 0;
+    if (e < p.E_local) {
+      // batches of independent loads: the table comes from L2, one round trip per batch
+      for (int c0 = wave; c0 < p.n_sub; c0 += kHistBatch * n_waves) {
+        int v[kHistBatch];
+#pragma unroll
+        for (int u = 0; u < kHistBatch; ++u) {
+          const int c = c0 + u * n_waves;
+          v[u] = c < p.n_sub ? p.chunk_cnt[(size_t)c * p.E_local + e] : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < kHistBatch; ++u) sum += v[u];
+      }
+      s_part[wave * kMaxE + e] = sum;
     }
-    if (lane == 0) s_cnt[e] = running;
   }
   __syncthreads();
-  if (staged)
-    for (int i = threadIdx.x; i < n; i += blockDim.x) p.chunk_cnt[i] = s_stage[i];
+  for (int e = threadIdx.x; e < p.E_local; e += blockDim.x) {
+    int sum = 0;
+    for (int w = 0; w < n_waves; ++w) sum += s_part[w * kMaxE + e];
+    s_cnt[e] = sum;
+  }
+  __syncthreads();
   if (wave == 0) build_tile_map(p.E_local, s_cnt, p.BM, p.granule, p.counts, p.offsets, p.tiles);
 }
 
-constexpr int kRankLdsWords = 3 * kMaxE;   // LDS words rank_chunk needs per wave
+constexpr int kRankLdsWords = 4 * kMaxE;   // LDS words rank_chunk needs per wave
 
-// Rows of the local slots of one chunk, by one wave (lane = token):
-// row = offsets[e] + (tokens of earlier chunks selecting e) + (earlier lanes selecting e).
-// The lanes that selected expert e are collected as a 64-bit mask per expert in LDS
-// (an OR, so the result does not depend on the order of the updates); a slot's rank
-// inside the chunk is the number of lower lanes in its expert's mask.
+// Rows of the local slots of one group of kChunk tokens, by one wave (lane = token):
+// row = (rows of lower experts) + (tokens of earlier sub-chunks selecting e) + (earlier lanes of the
+// token's own sub-chunk selecting e).
+// The first two terms come straight from the histogram table (lane = expert: one
+// pass over its rows gives every expert's total and its count in earlier sub-chunks;
+// a wave scan of the totals gives the expert offsets), so a group needs nothing but
+// the finished table.  The lanes that selected expert e are collected as a 64-bit
+// mask per expert in LDS (an OR, so the result does not depend on the order of the
+// updates); a slot's rank inside its sub-chunk is the number of lower lanes of that
+// sub-chunk in its expert's mask.
 // s_lds: kRankLdsWords int32 of LDS owned by this wave.
-__device__ __forceinline__ void rank_chunk(const RouteParams& p, int chunk, int32_t* s_lds) {
+__device__ __forceinline__ void rank_chunk(const RouteParams& p, int group, int32_t* s_lds) {
   const int lane = lane_id();
-  const int t = chunk * kChunk + lane;
+  const int t = group * kChunk + lane;
   const bool live = t < p.T;
   unsigned long long* s_mask = reinterpret_cast<unsigned long long*>(s_lds);   // [E_local]
-  int32_t* s_base = s_lds + 2 * kMaxE;                                           // [E_local]
-  const int32_t* coff = p.chunk_cnt + (size_t)chunk * p.E_local;
-  for (int e = lane; e < p.E_local; e += kWave) {
-    s_mask[e] = 0ull;
-    s_base[e] = p.offsets[e] + coff[e];   // first row of expert e for this chunk
+  int32_t* s_base = s_lds + 2 * kMaxE;                                           // [2][E_local] first row per half
+  const int sub0 = group * (kChunk / kSub);
+  int run = 0;   // rows of the experts before this block of 64
+  for (int e0 = 0; e0 < p.E_local; e0 += kWave) {
+    const int e = e0 + lane;
+    int total = 0, before = 0, own0 = 0;
+    if (e < p.E_local) {
+      for (int c0 = 0; c0 < p.n_sub; c0 += kHistBatch) {
+        int v[kHistBatch];
+#pragma unroll
+        for (int u = 0; u < kHistBatch; ++u) v[u] = c0 + u < p.n_sub ? p.chunk_cnt[(size_t)(c0 + u) * p.E_local + e] : 0;
+#pragma unroll
+        for (int u = 0; u < kHistBatch; ++u) {
+          total += v[u];
+          before += c0 + u < sub0 ? v[u] : 0;
+          own0 = c0 + u == sub0 ? v[u] : own0;
+        }
+      }
+    }
+    const int incl = wave_incl_scan(total, lane);
+    if (e < p.E_local) {
+      const int first = run + incl - total + before;
+      s_mask[e] = 0ull;
+      s_base[e] = first;
+      s_base[kMaxE + e] = first + own0;
+    }
+    run += __shfl(incl, kWave - 1, kWave);
   }
   int32_t le[kMaxK];
 #pragma unroll
@@ -325,13 +358,15 @@ __device__ __forceinline__ void rank_chunk(const RouteParams& p, int chunk, int3
     if (le[j] >= 0) atomicOr(&s_mask[le[j]], 1ull << lane);
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
   __builtin_amdgcn_wave_barrier();
-  const unsigned long long lt = (1ull << lane) - 1ull;
+  const int half = lane / kSub;
+  // lower lanes of this lane's own sub-chunk
+  const unsigned long long lt = ((1ull << lane) - 1ull) & (half ? ~((1ull << kSub) - 1ull) : ~0ull);
 #pragma unroll
   for (int j = 0; j < kMaxK; ++j) {
     if (j >= p.k) break;
     int r = -1;
     if (le[j] >= 0) {
-      r = s_base[le[j]] + __popcll(s_mask[le[j]] & lt);
+      r = s_base[half * kMaxE + le[j]] + __popcll(s_mask[le[j]] & lt);
       p.token_of[r] = t;
       p.slot_of[r] = j;
     }
@@ -339,22 +374,22 @@ __device__ __forceinline__ void rank_chunk(const RouteParams& p, int chunk, int3
   }
 }
 
-__global__ __launch_bounds__(1024) void route_kernel(RouteParams p) {
-  __shared__ int32_t s_idx[kChunk * kMaxK];
-  __shared__ float s_val[kChunk * kMaxK];
+__global__ __launch_bounds__(512) void route_kernel(RouteParams p) {
+  __shared__ int32_t s_idx[kSub * kMaxK];
+  __shared__ float s_val[kSub * kMaxK];
   route_chunk(p, blockIdx.x, s_idx, s_val);
 }
 
 __global__ __launch_bounds__(1024) void scan_kernel(RouteParams p) {
   __shared__ int32_t s_cnt[kMaxE + 2];
-  __shared__ int32_t s_stage[kScanStageWords];
-  scan_all(p, s_cnt, s_stage, kScanStageWords);
+  __shared__ int32_t s_part[16 * kMaxE];
+  scan_all(p, s_cnt, s_part);
 }
 
 __global__ __launch_bounds__(256) void rank_kernel(RouteParams p) {
   __shared__ int32_t s_lds[4 * kRankLdsWords];
-  int chunk = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
-  if (chunk < p.n_chunks) rank_chunk(p, chunk, s_lds + (threadIdx.x / kWave) * kRankLdsWords);
+  int group = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  if (group < p.n_groups) rank_chunk(p, group, s_lds + (threadIdx.x / kWave) * kRankLdsWords);
 }
 
 // M-tile map from the rows per expert alone (the backward rebuilds it from the
