@@ -375,12 +375,69 @@ __device__ __forceinline__ void gemm_k_loop(f32x16 (&acc)[kMaxMT][4], const Gemm
   __builtin_amdgcn_s_barrier();   // all stages free before the next tile's first loads
 }
 
+// Epilogue staging.  The MFMA result layout gives a lane 4 consecutive columns of
+// one row, so a direct store writes 16-byte pieces of 32 different rows: partial
+// lines, which the L2 completes by fetching the rest of each line from HBM (seen as
+// ~0.9 GB of extra fetches on a 1.4 GB weight-gradient write).  Instead each wave
+// parks a 32-row block in its own LDS region and writes it back out row-contiguous,
+// 16 bytes per lane, whole 128-byte lines.  No cross-wave synchronisation: a wave
+// only touches its own region, and LDS operations of one wave complete in order.
+// The regions lie in the activation stage 1 and weight stage 2, which the next
+// tile's first loads (stages 0, 0 and 1) do not touch before its first barrier.
+constexpr int kEpiRowBytes = 256 + 16;                 // 128 columns + padding against bank alignment of the rows
+constexpr int kEpiWaveBytes = 32 * kEpiRowBytes;       // 8704
+
+__device__ __forceinline__ char* epilogue_region(char* smem, int wave) {
+  return wave < 2 ? smem + kAStageBytes + wave * kEpiWaveBytes
+                  : smem + kBRegion + 2 * kBStageBytes + (wave - 2) * kEpiWaveBytes;
+}
+
+// pk[nt][q]: this lane's 4 packed columns nt*32 + q*8 + (lane/32)*4 .. +3 of row lane%32.
+// Writes rows [0, rows_valid) x columns [0, cols_valid) of the block to gdst (row stride ld elements).
+template <int NB>
+__device__ __forceinline__ void store_block_via_lds(char* region, const u32x2 (&pk)[NB][4], __bf16* gdst, long ld,
+                                                    int rows_valid, int cols_valid) {
+  typedef __attribute__((address_space(3))) char* lds_ptr;
+  typedef __attribute__((address_space(3))) u32x2* lds_u32x2_ptr;
+  typedef __attribute__((address_space(3))) const u32x4* lds_u32x4_cptr;
+  constexpr int LPR = NB * 4;                           // lanes per row at 16 bytes each
+  // The lane id passes through an empty asm so that nothing derived from it here counts as
+  // loop-invariant: hoisted out of the tile loop, the per-row addresses and bounds were spilled
+  // and every reload (s_waitcnt vmcnt(0)) waited for all earlier global stores as well.
+  int lane = lane_id();
+  asm volatile("" : "+v"(lane));
+  const int l32 = lane & 31, lh = lane >> 5;
+  const lds_ptr base = (lds_ptr)region;
+#pragma unroll
+  for (int nt = 0; nt < NB; ++nt)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) *(lds_u32x2_ptr)(base + l32 * kEpiRowBytes + (nt * 32 + q * 8 + lh * 4) * 2) = pk[nt][q];
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  const int row_l = lane / LPR, ch = lane % LPR;
+  const bool col_ok = ch * 8 < cols_valid;
+  __bf16* gp = gdst + (size_t)row_l * ld + ch * 8;
+  const lds_ptr lp = base + row_l * kEpiRowBytes + ch * 16;
+#pragma unroll
+  for (int it = 0; it < 32 * LPR / kWave; ++it) {
+    const int row = it * (kWave / LPR) + row_l;
+    const u32x4 v = *(lds_u32x4_cptr)(lp + it * (kWave / LPR) * kEpiRowBytes);
+    if (row < rows_valid && col_ok) *reinterpret_cast<u32x4*>(gp + (size_t)(it * (kWave / LPR)) * ld) = v;
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
 // One output tile.  NN / NT: (t0, t1) = (M tile of the tile map, N tile).
 // TN: (t0, t1, t2) = (expert, M tile, N tile) of that expert's [M, N] gradient.
 template <int LAY, int EPI>
 __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int t1, int t2, char* smem) {
   const int tid = threadIdx.x;
-  const int lane = tid & 63;
+  // opaque to the optimiser: per-lane setup is recomputed per tile instead of being hoisted out of
+  // the tile loop and held (or spilled) across every K loop
+  int lane = tid & 63;
+  asm volatile("" : "+v"(lane));
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps branches and LDS bases scalar
   const int wm = wave >> 1, wn = wave & 1;
   const int l32 = lane & 31, lh = lane >> 5;
@@ -495,20 +552,23 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
   }
 
   // ---- epilogue: lane holds row l32 of each 32 x 32 block and, per register group q,
-  // the 4 consecutive columns q*8 + lh*4 .. +3 ----
+  // the 4 consecutive columns q*8 + lh*4 .. +3; blocks leave through the wave's LDS region ----
   __bf16* c_base = LAY == kLayTN ? p.C + (size_t)e * p.strideC : p.C;
+  char* region = epilogue_region(smem, wave);
 #pragma unroll
   for (int mt = 0; mt < kMaxMT; ++mt) {
-    const int m = wm * half + mt * 32 + l32;
-    if (mt >= n_mt || m >= rows) continue;
-    const size_t grow = (size_t)(row0 + m);
+    const int m0 = wm * half + mt * 32;               // first row of the block inside the tile
+    const int rows_valid = min(32, rows - m0);
+    if (mt >= n_mt || rows_valid <= 0) continue;      // wave-uniform
+    const size_t grow0 = (size_t)(row0 + m0);
+    const size_t grow = grow0 + l32;                  // this lane's row (may be past the end: never stored)
     if (EPI == kEpiSwiglu) {
+      const int c0 = ntile * (kBN / 2) + wn * 64;     // this wave's 64 gate columns and the 64 matching up columns
+      u32x2 pa[2][4], pg[2][4], pu[2][4];
 #pragma unroll
       for (int ng = 0; ng < 2; ++ng)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const int c = ntile * (kBN / 2) + wn * 64 + ng * 32 + q * 8 + lh * 4;
-          if (c >= p.N) continue;
           float g[4], u[4], a[4];
 #pragma unroll
           for (int x = 0; x < 4; ++x) {
@@ -516,50 +576,59 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
             u[x] = acc[mt][ng + 2][q * 4 + x];
             a[x] = g[x] * sigmoidf_(g[x]) * u[x];
           }
-          *reinterpret_cast<u32x2*>(p.C + grow * p.ldc + c) = u32x2{pack_bf16(a[0], a[1]), pack_bf16(a[2], a[3])};
-          if (p.C2) {
-            __bf16* h = p.C2 + grow * (size_t)(2 * p.N);
-            *reinterpret_cast<u32x2*>(h + c) = u32x2{pack_bf16(g[0], g[1]), pack_bf16(g[2], g[3])};
-            *reinterpret_cast<u32x2*>(h + p.N + c) = u32x2{pack_bf16(u[0], u[1]), pack_bf16(u[2], u[3])};
-          }
+          pa[ng][q] = u32x2{pack_bf16(a[0], a[1]), pack_bf16(a[2], a[3])};
+          pg[ng][q] = u32x2{pack_bf16(g[0], g[1]), pack_bf16(g[2], g[3])};
+          pu[ng][q] = u32x2{pack_bf16(u[0], u[1]), pack_bf16(u[2], u[3])};
         }
+      store_block_via_lds<2>(region, pa, p.C + grow0 * p.ldc + c0, p.ldc, rows_valid, p.N - c0);
+      if (p.C2) {
+        __bf16* h = p.C2 + grow0 * (size_t)(2 * p.N) + c0;
+        store_block_via_lds<2>(region, pg, h, 2 * p.N, rows_valid, p.N - c0);
+        store_block_via_lds<2>(region, pu, h + p.N, 2 * p.N, rows_valid, p.N - c0);
+      }
     } else if (EPI == kEpiSwigluGrad) {
       // SwiGLU_grad on the act_grad tile (Section 2.2, Figure 2b): the accumulators hold dA; with the saved
       // pre-activations (g, u): d_gate = dA*u*s*(1 + g*(1 - s)), d_up = dA*g*s, s = sigmoid(g)
+      const int c0 = ntile * kBN + wn * 128;
+      u32x2 pdg[4][4], pdu[4][4];
+      const bool row_ok = l32 < rows_valid;
+      const __bf16* h = p.G + grow * (size_t)(2 * p.N);
 #pragma unroll
       for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const int c = ntile * kBN + wn * 128 + nt * 32 + q * 8 + lh * 4;
-          if (c >= p.N) continue;
-          const __bf16* h = p.G + grow * (size_t)(2 * p.N);
-          const u32x2 gv = *reinterpret_cast<const u32x2*>(h + c);
-          const u32x2 uv = *reinterpret_cast<const u32x2*>(h + p.N + c);
+          const int c = c0 + nt * 32 + q * 8 + lh * 4;
+          u32x2 gv = {0u, 0u}, uv = {0u, 0u};
+          if (row_ok && c < p.N) {
+            gv = *reinterpret_cast<const u32x2*>(h + c);
+            uv = *reinterpret_cast<const u32x2*>(h + p.N + c);
+          }
           const float g[4] = {bf16_lo(gv.x), bf16_hi(gv.x), bf16_lo(gv.y), bf16_hi(gv.y)};
           const float u[4] = {bf16_lo(uv.x), bf16_hi(uv.x), bf16_lo(uv.y), bf16_hi(uv.y)};
           float dg[4], du[4];
 #pragma unroll
           for (int x = 0; x < 4; ++x) {
             const float da = acc[mt][nt][q * 4 + x];
-            const float s = sigmoidf_(g[x]);
-            dg[x] = da * u[x] * s * (1.f + g[x] * (1.f - s));
-            du[x] = da * g[x] * s;
+            const float sg = sigmoidf_(g[x]);
+            dg[x] = da * u[x] * sg * (1.f + g[x] * (1.f - sg));
+            du[x] = da * g[x] * sg;
           }
-          __bf16* o = p.C + grow * p.ldc;
-          *reinterpret_cast<u32x2*>(o + c) = u32x2{pack_bf16(dg[0], dg[1]), pack_bf16(dg[2], dg[3])};
-          *reinterpret_cast<u32x2*>(o + p.N + c) = u32x2{pack_bf16(du[0], du[1]), pack_bf16(du[2], du[3])};
+          pdg[nt][q] = u32x2{pack_bf16(dg[0], dg[1]), pack_bf16(dg[2], dg[3])};
+          pdu[nt][q] = u32x2{pack_bf16(du[0], du[1]), pack_bf16(du[2], du[3])};
         }
+      __bf16* o = p.C + grow0 * p.ldc + c0;
+      store_block_via_lds<4>(region, pdg, o, p.ldc, rows_valid, p.N - c0);
+      store_block_via_lds<4>(region, pdu, o + p.N, p.ldc, rows_valid, p.N - c0);
     } else {
+      const int c0 = ntile * kBN + wn * 128;
+      u32x2 pk[4][4];
 #pragma unroll
       for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int c = ntile * kBN + wn * 128 + nt * 32 + q * 8 + lh * 4;
-          if (c >= p.N) continue;
-          *reinterpret_cast<u32x2*>(c_base + grow * p.ldc + c) =
-              u32x2{pack_bf16(acc[mt][nt][q * 4 + 0], acc[mt][nt][q * 4 + 1]),
-                    pack_bf16(acc[mt][nt][q * 4 + 2], acc[mt][nt][q * 4 + 3])};
-        }
+        for (int q = 0; q < 4; ++q)
+          pk[nt][q] = u32x2{pack_bf16(acc[mt][nt][q * 4 + 0], acc[mt][nt][q * 4 + 1]),
+                            pack_bf16(acc[mt][nt][q * 4 + 2], acc[mt][nt][q * 4 + 3])};
+      store_block_via_lds<4>(region, pk, c_base + grow0 * p.ldc + c0, p.ldc, rows_valid, p.N - c0);
     }
   }
 }
