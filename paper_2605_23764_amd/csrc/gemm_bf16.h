@@ -126,16 +126,37 @@ __device__ __forceinline__ uint32_t lds_addr_of(const char* p) {
 
 __device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 
+// Tile shapes.  "Wide" is the default 256 rows x 256 staged weight columns (waves
+// 2 x 2).  "Tall" is 384 rows x 128 columns (waves 4 x 1, up to 96 rows each): an
+// expert with 257..384 rows is covered by ONE tall M tile, so its weights stream
+// from HBM once instead of once per 256-row tile (two sibling tiles on neighbouring
+// CUs do not share through the L2: the in-flight footprint of 32 CUs is most of its
+// 4 MB).  Both shapes issue 16 wave-wide loads per wave per K step (8 + 8 or
+// 12 + 4), so the pipeline and its wait counts are the same.
+template <bool TALL>
+struct TileShape {
+  static constexpr int kRows = TALL ? 384 : 256;
+  static constexpr int kCols = TALL ? 128 : 256;
+  static constexpr int kALoads = TALL ? 12 : 8;             // A lines per wave per K step
+  static constexpr int kBLoads = TALL ? 4 : 8;              // B lines per wave per K step
+  static constexpr int kAStage = kALoads * 4 * kLine;       // 48 KB : 32 KB
+  static constexpr int kBStage = kBLoads * 4 * kLine;       // 16 KB : 32 KB
+  static constexpr int kBReg = kAStages * kAStage;          // weight stages start here
+  static constexpr int kHalves = TALL ? 1 : 2;              // 128-column halves per 4-k-row group
+  static_assert(kBReg + kBStages * kBStage <= kGemmLdsBytes, "LDS budget");
+};
+constexpr int kTallRows = TileShape<true>::kRows;
+
 // Per-tile addressing state shared by the load and compute phases.
 struct GemmTileCtx {
   const char* a_base;          // uniform: first row of the tile (TN: of the expert's segment), byte address
   const char* b_base;          // uniform: expert's weights (TN: first row of the segment), byte address
-  uint32_t a_off[8];           // NN/NT: per lane byte offset of the chunk fetched for the i-th A line; TN: [0..1] column halves
-  uint32_t b_off[8];           // NN/TN: [0..1] per lane byte offset inside a 4-row line, column halves; NT: like a_off
+  uint32_t a_off[12];          // NN/NT: per lane byte offset of the chunk fetched for the i-th A line; TN: [0..1] column halves
+  uint32_t b_off[8];           // NN/TN: per lane byte offset inside a 4-row line per column half; NT: like a_off
   uint32_t a_rd[4];            // operand read offset inside an A stage (NN/NT: per k slice; TN: per 32-row block)
   uint32_t b_rd[4];            // operand read offset inside a B stage (NN/TN: per 32-column block; NT: per k slice)
   uint32_t lds0;               // LDS byte address of the staging area
-  int nA;                      // A lines per wave per step (1..8)
+  int nA;                      // A lines per wave per step
   int lda_bytes, ldb_bytes;
   int wave;
   int kk;                      // TN: k-row of this lane inside a 4-row line (lane / 16)
@@ -143,9 +164,8 @@ struct GemmTileCtx {
 };
 
 // The 16 wave-wide loads issued between two barriers: the A lines of one K step
-// (indices 0..7, NN/NT: only nA of them real) followed by the B lines of a later
-// K step (indices 8..15).  A loads always precede B loads, which the vmcnt waits
-// rely on.
+// (indices 0..kALoads-1, NN/NT: only nA of them real) followed by the B lines of a
+// later K step.  A loads always precede B loads, which the vmcnt waits rely on.
 struct GemmLoadGroup {
   const char* a_k;   // uniform source of the A lines, nullptr = none
   const char* b_k;   // uniform source of the B lines, nullptr = none
@@ -155,9 +175,10 @@ struct GemmLoadGroup {
   int b_row0;
 };
 
-template <int LAY>
+template <int LAY, bool TALL>
 __device__ __forceinline__ GemmLoadGroup gemm_load_group(const GemmTileCtx& t, int a_step, int a_stage, int b_step,
                                                          int b_stage) {
+  typedef TileShape<TALL> S;
   GemmLoadGroup g;
   g.a_row0 = 0; g.b_row0 = 0;
   if (LAY == kLayTN) {
@@ -165,21 +186,22 @@ __device__ __forceinline__ GemmLoadGroup gemm_load_group(const GemmTileCtx& t, i
     g.b_k = b_step >= 0 ? t.b_base : nullptr;
     g.a_row0 = __builtin_amdgcn_readfirstlane(a_step * kBK + t.wave * 16);
     g.b_row0 = __builtin_amdgcn_readfirstlane(b_step * kBK + t.wave * 16);
-    g.a_st = uniform_u32(t.lds0 + a_stage * kAStageBytes + t.wave * kBLinesPerWave * kLine);
+    g.a_st = uniform_u32(t.lds0 + a_stage * S::kAStage + t.wave * 8 * kLine);
   } else {
     g.a_k = a_step >= 0 ? uniform_ptr(t.a_base + (size_t)a_step * (kBK * 2)) : nullptr;
-    g.a_st = uniform_u32(t.lds0 + a_stage * kAStageBytes + t.wave * kLine);
+    g.a_st = uniform_u32(t.lds0 + a_stage * S::kAStage + t.wave * kLine);
     if (LAY == kLayNT) g.b_k = b_step >= 0 ? uniform_ptr(t.b_base + (size_t)b_step * (kBK * 2)) : nullptr;
     else g.b_k = b_step >= 0 ? uniform_ptr(t.b_base + (size_t)(b_step * kBK + t.wave * 16) * t.ldb_bytes) : nullptr;
   }
-  if (LAY == kLayNT) g.b_st = uniform_u32(t.lds0 + kBRegion + b_stage * kBStageBytes + t.wave * kLine);
-  else g.b_st = uniform_u32(t.lds0 + kBRegion + b_stage * kBStageBytes + t.wave * kBLinesPerWave * kLine);
+  if (LAY == kLayNT) g.b_st = uniform_u32(t.lds0 + S::kBReg + b_stage * S::kBStage + t.wave * kLine);
+  else g.b_st = uniform_u32(t.lds0 + S::kBReg + b_stage * S::kBStage + t.wave * S::kBLoads * kLine);
   return g;
 }
 
-template <int LAY>
+template <int LAY, bool TALL>
 __device__ __forceinline__ void gemm_issue_one(const GemmTileCtx& t, const GemmLoadGroup& g, int idx) {
-  if (idx < 8) {
+  typedef TileShape<TALL> S;
+  if (idx < S::kALoads) {
     if (LAY == kLayTN) {
       if (g.a_k != nullptr) {
         const int krow = min(g.a_row0 + (idx >> 1) * 4 + t.kk, t.k_rows - 1);   // rows past the segment: re-read, zeroed later
@@ -189,10 +211,11 @@ __device__ __forceinline__ void gemm_issue_one(const GemmTileCtx& t, const GemmL
       if (g.a_k != nullptr && idx < t.nA) lds_dma16(g.a_k, t.a_off[idx], g.a_st + 4 * idx * kLine);
     }
   } else {
-    const int i = idx - 8;
+    const int i = idx - S::kALoads;
     if (g.b_k == nullptr) return;
     if (LAY == kLayNN) {
-      lds_dma16(g.b_k + (size_t)((i >> 1) * 4) * t.ldb_bytes, t.b_off[i & 1], g.b_st + i * kLine);
+      // line i of this wave: k-row group i / halves, column half i % halves
+      lds_dma16(g.b_k + (size_t)((i / S::kHalves) * 4) * t.ldb_bytes, t.b_off[i % S::kHalves], g.b_st + i * kLine);
     } else if (LAY == kLayNT) {
       lds_dma16(g.b_k, t.b_off[i], g.b_st + 4 * i * kLine);
     } else {
@@ -221,15 +244,16 @@ struct GemmSliceShape {
 };
 
 // Operand read number `a` of slice ks from the stages as / bs into f.
-template <int LAY, int NMT>
+template <int LAY, int NMT, bool TALL>
 __device__ __forceinline__ void gemm_read_one(GemmFrags<LAY, NMT>& f, int a, lds_cptr as, lds_cptr bs, int ks,
                                               const GemmTileCtx& t) {
   typedef GemmSliceShape<LAY, NMT> S;
+  constexpr int H = TileShape<TALL>::kHalves;   // lines per 4-k-row group of the weight stage
   if (a < S::n_wreads) {
     if (LAY == kLayNT) f.wk[a] = *(lds_bf16x8_cptr)(bs + t.b_rd[ks] + a * 4 * kLine);
     else
       f.w[a >> 1][a & 1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-          (lds_s16x4_ptr)(bs + t.b_rd[a >> 1] + ks * 8 * kLine + (a & 1) * 2 * kLine));
+          (lds_s16x4_ptr)(bs + t.b_rd[a >> 1] + ks * 4 * H * kLine + (a & 1) * H * kLine));
   } else {
     const int i = a - S::n_wreads;
     if (LAY == kLayTN)
@@ -248,7 +272,7 @@ __device__ __forceinline__ bf16x8 join_tr(s16x4 lo, s16x4 hi) {
 // per slot, go the operand reads that fill `nxt` (slice ks_n of the stages
 // as_n / bs_n) and four of the load group's global -> LDS copies, so LDS latency
 // and load issue hide under MFMA time.  sched_barrier pins that order.
-template <int LAY, int NMT>
+template <int LAY, int NMT, bool TALL>
 __device__ __forceinline__ void gemm_slice(f32x16 (&acc)[kMaxMT][4], const GemmFrags<LAY, NMT>& cur,
                                            GemmFrags<LAY, NMT>& nxt, bool read_next, lds_cptr as_n, lds_cptr bs_n,
                                            int ks_n, const GemmTileCtx& t, const GemmLoadGroup& g, int load0) {
@@ -266,20 +290,20 @@ __device__ __forceinline__ void gemm_slice(f32x16 (&acc)[kMaxMT][4], const GemmF
     for (int a = 0; a < n_act; ++a) {
       if ((a * n_mfma) / n_act != j) continue;
       if (a < S::n_reads) {
-        if (read_next) gemm_read_one<LAY, NMT>(nxt, a, as_n, bs_n, ks_n, t);
+        if (read_next) gemm_read_one<LAY, NMT, TALL>(nxt, a, as_n, bs_n, ks_n, t);
       } else {
-        gemm_issue_one<LAY>(t, g, load0 + (a - S::n_reads));
+        gemm_issue_one<LAY, TALL>(t, g, load0 + (a - S::n_reads));
       }
     }
     __builtin_amdgcn_sched_barrier(0);
   }
 }
 
-template <int LAY, int NMT>
+template <int LAY, int NMT, bool TALL>
 __device__ __forceinline__ void gemm_read_frags(GemmFrags<LAY, NMT>& f, lds_cptr as, lds_cptr bs, int ks,
                                                 const GemmTileCtx& t) {
 #pragma unroll
-  for (int a = 0; a < GemmSliceShape<LAY, NMT>::n_reads; ++a) gemm_read_one<LAY, NMT>(f, a, as, bs, ks, t);
+  for (int a = 0; a < GemmSliceShape<LAY, NMT>::n_reads; ++a) gemm_read_one<LAY, NMT, TALL>(f, a, as, bs, ks, t);
 }
 
 // TN only: zero the k-rows >= k_valid of one A stage and one B stage (both hold
@@ -304,71 +328,72 @@ __device__ __forceinline__ void gemm_zero_k_tail(char* smem, int a_stage, int b_
 //
 // Step s computes from A stage s%2 and B stage s%3.  Its barrier sits in front of
 // the LAST k slice: by then this wave has fetched all of step s's operands
-// (lgkmcnt 0), and the wait allows only the 8 B loads of B(s+2) to be
-// outstanding, so A(s+1) and B(s+1) are in LDS.  After the barrier that holds for
-// every wave: the stages of step s are free and are refilled by the next load
-// group, A(s+2) then B(s+3), issued four at a time behind the MFMAs of the
-// following four slices, while the first operands of step s+1 are already being
-// read under the last slice of step s.
+// (lgkmcnt 0), and the wait allows only the B loads of B(s+2) to be outstanding,
+// so A(s+1) and B(s+1) are in LDS.  After the barrier that holds for every wave:
+// the stages of step s are free and are refilled by the next load group, A(s+2)
+// then B(s+3), issued four at a time behind the MFMAs of the following four
+// slices, while the first operands of step s+1 are already being read under the
+// last slice of step s.
 // k_tail (TN): valid k-rows of the last step if it is partial, else 0.
-template <int LAY, int NMT>
+template <int LAY, int NMT, bool TALL>
 __device__ __forceinline__ void gemm_k_loop(f32x16 (&acc)[kMaxMT][4], const GemmTileCtx& t, char* smem, int n_steps,
                                             int k_tail) {
+  typedef TileShape<TALL> S;
   const lds_cptr lds = (lds_cptr)smem;
   if (n_steps <= 0) return;
   {
-    const GemmLoadGroup g0 = gemm_load_group<LAY>(t, 0, 0, 0, 0);                       // A(0), B(0)
+    const GemmLoadGroup g0 = gemm_load_group<LAY, TALL>(t, 0, 0, 0, 0);                       // A(0), B(0)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) gemm_issue_one<LAY>(t, g0, i);
+    for (int i = 0; i < 16; ++i) gemm_issue_one<LAY, TALL>(t, g0, i);
     if (n_steps > 1) {
-      const GemmLoadGroup g1 = gemm_load_group<LAY>(t, -1, 0, 1, 1);                    // B(1)
+      const GemmLoadGroup g1 = gemm_load_group<LAY, TALL>(t, -1, 0, 1, 1);                    // B(1)
 #pragma unroll
-      for (int i = 8; i < 16; ++i) gemm_issue_one<LAY>(t, g1, i);
-      wait_vmcnt<kBLinesPerWave>();
+      for (int i = S::kALoads; i < 16; ++i) gemm_issue_one<LAY, TALL>(t, g1, i);
+      wait_vmcnt<S::kBLoads>();
     } else {
       wait_vmcnt<0>();
     }
     __builtin_amdgcn_s_barrier();
     if (LAY == kLayTN && n_steps == 1 && k_tail) gemm_zero_k_tail(smem, 0, 0, k_tail);
   }
-  GemmLoadGroup g = gemm_load_group<LAY>(t, n_steps > 1 ? 1 : -1, 1, n_steps > 2 ? 2 : -1, 2);   // A(1), B(2)
+  GemmLoadGroup g = gemm_load_group<LAY, TALL>(t, n_steps > 1 ? 1 : -1, 1, n_steps > 2 ? 2 : -1, 2);   // A(1), B(2)
 #pragma unroll
-  for (int i = 0; i < 4; ++i) gemm_issue_one<LAY>(t, g, i);
+  for (int i = 0; i < 4; ++i) gemm_issue_one<LAY, TALL>(t, g, i);
   GemmFrags<LAY, NMT> cur, nxt;
-  if (NMT > 0) gemm_read_frags<LAY, NMT>(cur, lds, lds + kBRegion, 0, t);
+  if (NMT > 0) gemm_read_frags<LAY, NMT, TALL>(cur, lds, lds + S::kBReg, 0, t);
 
   int bs_i = 0;
   for (int s = 0; s < n_steps; ++s) {
-    const lds_cptr as = lds + (s & 1) * kAStageBytes;
-    const lds_cptr bs = lds + kBRegion + bs_i * kBStageBytes;
+    const lds_cptr as = lds + (s & 1) * S::kAStage;
+    const lds_cptr bs = lds + S::kBReg + bs_i * S::kBStage;
     const int bs_next = bs_i == kBStages - 1 ? 0 : bs_i + 1;
 #pragma unroll
     for (int ks = 0; ks < 3; ++ks) {
       if (NMT > 0) {
-        gemm_slice<LAY, NMT>(acc, cur, nxt, true, as, bs, ks + 1, t, g, 4 + 4 * ks);
+        gemm_slice<LAY, NMT, TALL>(acc, cur, nxt, true, as, bs, ks + 1, t, g, 4 + 4 * ks);
         cur = nxt;
       } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) gemm_issue_one<LAY>(t, g, 4 + 4 * ks + i);
+        for (int i = 0; i < 4; ++i) gemm_issue_one<LAY, TALL>(t, g, 4 + 4 * ks + i);
       }
     }
     const bool more = s + 1 < n_steps;
     if (more) {
       wait_lgkmcnt0();
-      if (s + 2 < n_steps) wait_vmcnt<kBLinesPerWave>(); else wait_vmcnt<0>();
+      if (s + 2 < n_steps) wait_vmcnt<S::kBLoads>(); else wait_vmcnt<0>();
       __builtin_amdgcn_s_barrier();
       // the last step's operands have landed (nothing is in flight any more): blank its k-rows past the segment
       if (LAY == kLayTN && s + 2 == n_steps && k_tail) gemm_zero_k_tail(smem, (s + 1) & 1, bs_next, k_tail);
-      g = gemm_load_group<LAY>(t, s + 2 < n_steps ? s + 2 : -1, s & 1, s + 3 < n_steps ? s + 3 : -1, bs_i);
+      g = gemm_load_group<LAY, TALL>(t, s + 2 < n_steps ? s + 2 : -1, s & 1, s + 3 < n_steps ? s + 3 : -1, bs_i);
     }
     if (NMT > 0) {
       // `more` false: no loads left (both sources null) and nothing further to read
-      gemm_slice<LAY, NMT>(acc, cur, nxt, more, lds + ((s + 1) & 1) * kAStageBytes,
-                           lds + kBRegion + bs_next * kBStageBytes, 0, t, g, 0);
+      gemm_slice<LAY, NMT, TALL>(acc, cur, nxt, more, lds + ((s + 1) & 1) * S::kAStage,
+                                 lds + S::kBReg + bs_next * S::kBStage, 0, t, g, 0);
       if (more) cur = nxt;
     } else if (more) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) gemm_issue_one<LAY>(t, g, i);
+      for (int i = 0; i < 4; ++i) gemm_issue_one<LAY, TALL>(t, g, i);
     }
     bs_i = bs_next;
   }
@@ -382,14 +407,15 @@ __device__ __forceinline__ void gemm_k_loop(f32x16 (&acc)[kMaxMT][4], const Gemm
 // parks a 32-row block in its own LDS region and writes it back out row-contiguous,
 // 16 bytes per lane, whole 128-byte lines.  No cross-wave synchronisation: a wave
 // only touches its own region, and LDS operations of one wave complete in order.
-// The regions lie in the activation stage 1 and weight stage 2, which the next
-// tile's first loads (stages 0, 0 and 1) do not touch before its first barrier.
+// The regions lie at 128..154 KB and 48..57 KB of the staging area: the next tile's
+// first loads (activation stage 0, weight stages 0 and 1: wide 0..32 KB and
+// 64..128 KB, tall 0..48 KB and 96..128 KB) do not touch them before its first
+// barrier, whichever shape it has.
 constexpr int kEpiRowBytes = 256 + 16;                 // 128 columns + padding against bank alignment of the rows
 constexpr int kEpiWaveBytes = 32 * kEpiRowBytes;       // 8704
 
 __device__ __forceinline__ char* epilogue_region(char* smem, int wave) {
-  return wave < 2 ? smem + kAStageBytes + wave * kEpiWaveBytes
-                  : smem + kBRegion + 2 * kBStageBytes + (wave - 2) * kEpiWaveBytes;
+  return wave < 3 ? smem + 128 * 1024 + wave * kEpiWaveBytes : smem + 48 * 1024;
 }
 
 // pk[nt][q]: this lane's 4 packed columns nt*32 + q*8 + (lane/32)*4 .. +3 of row lane%32.
@@ -429,27 +455,31 @@ __device__ __forceinline__ void store_block_via_lds(char* region, const u32x2 (&
   __builtin_amdgcn_wave_barrier();
 }
 
-// One output tile.  NN / NT: (t0, t1) = (M tile of the tile map, N tile).
-// TN: (t0, t1, t2) = (expert, M tile, N tile) of that expert's [M, N] gradient.
-template <int LAY, int EPI>
+// One output tile.  NN / NT: (t0, t1) = (M tile of the tile map, N tile of TileShape<TALL>::kCols
+// columns; SwiGLU: half as many output columns).  TN: (t0, t1, t2) = (expert, M tile, N tile) of that
+// expert's [M, N] gradient (wide shape only).
+template <int LAY, int EPI, bool TALL>
 __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int t1, int t2, char* smem) {
+  typedef TileShape<TALL> S;
+  static_assert(!(TALL && LAY == kLayTN), "weight gradients use the wide shape");
   const int tid = threadIdx.x;
   // opaque to the optimiser: per-lane setup is recomputed per tile instead of being hoisted out of
   // the tile loop and held (or spilled) across every K loop
   int lane = tid & 63;
   asm volatile("" : "+v"(lane));
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps branches and LDS bases scalar
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave >> 1, wn = TALL ? 0 : (wave & 1);
   const int l32 = lane & 31, lh = lane >> 5;
 
-  int e, row0, rows, ntile, half, n_mt, n_steps, k_tail = 0;
+  // row_base: first tile row of this wave; n_mt: its 32-row blocks
+  int e, row0, rows, ntile, row_base, n_mt, n_steps, k_tail = 0;
   if (LAY == kLayTN) {
     e = t0;
     ntile = t2;
     row0 = t1 * kBM;                                          // first output row (of M)
     rows = min(kBM, p.M - row0);
-    half = 128;                                               // wave rows split the staged 256 columns of A^T
-    n_mt = min(kMaxMT, max(0, (rows - wm * 128 + 31) >> 5));
+    row_base = wm * 128;                                      // wave rows split the staged 256 columns of A^T
+    n_mt = min(kMaxMT, max(0, (rows - row_base + 31) >> 5));
     const int seg0 = p.offsets[e], cnt = p.offsets[e + 1] - seg0;
     n_steps = (cnt + kBK - 1) / kBK;
     k_tail = cnt % kBK;
@@ -458,9 +488,10 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
     row0 = p.tiles.row0[t0];
     rows = p.tiles.rows[t0];
     ntile = t1;
-    half = ((rows + 63) >> 6) << 5;                           // rows per wave row, multiple of 32
-    const int my_rows = wm == 0 ? min(rows, half) : max(0, rows - half);
-    n_mt = (my_rows + 31) >> 5;
+    // rows per wave (row), a multiple of 32: tall = four wave rows, wide = two
+    const int per = TALL ? ((((rows + 31) >> 5) + 3) >> 2) << 5 : ((rows + 63) >> 6) << 5;
+    row_base = (TALL ? wave : wm) * per;
+    n_mt = (max(0, min(per, rows - row_base)) + 31) >> 5;
     n_steps = p.K / kBK;
   }
 
@@ -491,16 +522,22 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
     t.a_base = uniform_ptr(reinterpret_cast<const char*>(p.A + (size_t)row0 * p.lda));
     t.b_base = uniform_ptr(reinterpret_cast<const char*>(p.B + (size_t)e * p.strideB));
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < S::kALoads; ++i) {
       const int row = min((wave + 4 * i) * 8 + kc_r, rows - 1);      // rows past the end re-read the last row; never stored
       t.a_off[i] = (uint32_t)((row * p.lda + kc_c * 8) * 2);
     }
     if (LAY == kLayNT) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int n = min(ntile * kBN + (wave + 4 * i) * 8 + kc_r, p.N - 1);   // weight row = output column
+      for (int i = 0; i < S::kBLoads; ++i) {
+        const int n = min(ntile * S::kCols + (wave + 4 * i) * 8 + kc_r, p.N - 1);   // weight row = output column
         t.b_off[i] = (uint32_t)(((size_t)n * p.ldb + kc_c * 8) * 2);
       }
+    } else if (TALL) {
+      // one 128-column line per k-row group; SwiGLU: 64 gate columns then the 64 matching up columns
+      int gcol;
+      if (EPI == kEpiSwiglu) gcol = (tr_nl >> 6) * p.N + min(ntile * 64 + (tr_nl & 63), p.N - 8);
+      else gcol = min(ntile * 128 + tr_nl, p.N - 8);
+      t.b_off[0] = (uint32_t)((t.kk * p.ldb + gcol) * 2);
     } else {
 #pragma unroll
       for (int nh = 0; nh < 2; ++nh) {
@@ -517,21 +554,22 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
   {
     // k-contiguous stage: row m -> line m/8, 128 bytes per row, chunk swizzle by (m/2)%8
     const int f = (l32 >> 1) & 7;
-    const uint32_t a0 = (uint32_t)(((wm * half) >> 3) * kLine + (l32 >> 3) * kLine + (l32 & 7) * 128);
+    const uint32_t a0 = (uint32_t)((row_base >> 3) * kLine + (l32 >> 3) * kLine + (l32 & 7) * 128);
     const uint32_t w0 = (uint32_t)(((wn * 128) >> 3) * kLine + (l32 >> 3) * kLine + (l32 & 7) * 128);
-    // transposing stage: 32-column block nb of the staged 256 columns
+    // transposing stage: 32-column block nb of the staged columns; a 4-k-row group is kHalves lines
     const int g = lane >> 4, i = lane & 15;
     const int kk = i >> 2;
-    auto tr_off = [&](int nb) {
+    auto tr_off = [&](int nb, int halves) {
       const int j = ((nb & 127) >> 3) + (g & 1) * 2 + ((i & 3) >> 1);
-      return (uint32_t)((g >> 1) * 4 * kLine + (nb >> 7) * kLine + kk * 256 + ((j + 4 * kk) & 15) * 16 + (i & 1) * 8);
+      return (uint32_t)((g >> 1) * 2 * halves * kLine + (nb >> 7) * kLine + kk * 256 + ((j + 4 * kk) & 15) * 16 + (i & 1) * 8);
     };
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      if (LAY == kLayTN) t.a_rd[q] = tr_off(wm * 128 + q * 32);
+      if (LAY == kLayTN) t.a_rd[q] = tr_off(wm * 128 + q * 32, 2);
       else t.a_rd[q] = a0 + (uint32_t)((((q * 2 + lh) ^ f) & 7) << 4);
       if (LAY == kLayNT) t.b_rd[q] = w0 + (uint32_t)((((q * 2 + lh) ^ f) & 7) << 4);
-      else t.b_rd[q] = tr_off((EPI == kEpiSwiglu) ? (q >> 1) * 128 + wn * 64 + (q & 1) * 32 : wn * 128 + q * 32);
+      else if (TALL) t.b_rd[q] = tr_off(q * 32, 1);
+      else t.b_rd[q] = tr_off((EPI == kEpiSwiglu) ? (q >> 1) * 128 + wn * 64 + (q & 1) * 32 : wn * 128 + q * 32, 2);
     }
   }
 
@@ -544,11 +582,13 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   switch (n_mt) {
-    case 0: gemm_k_loop<LAY, 0>(acc, t, smem, n_steps, k_tail); break;
-    case 1: gemm_k_loop<LAY, 1>(acc, t, smem, n_steps, k_tail); break;
-    case 2: gemm_k_loop<LAY, 2>(acc, t, smem, n_steps, k_tail); break;
-    case 3: gemm_k_loop<LAY, 3>(acc, t, smem, n_steps, k_tail); break;
-    default: gemm_k_loop<LAY, 4>(acc, t, smem, n_steps, k_tail); break;
+    case 0: gemm_k_loop<LAY, 0, TALL>(acc, t, smem, n_steps, k_tail); break;
+    case 1: gemm_k_loop<LAY, 1, TALL>(acc, t, smem, n_steps, k_tail); break;
+    case 2: gemm_k_loop<LAY, 2, TALL>(acc, t, smem, n_steps, k_tail); break;
+    case 3: gemm_k_loop<LAY, 3, TALL>(acc, t, smem, n_steps, k_tail); break;
+    default:
+      if constexpr (!TALL) gemm_k_loop<LAY, 4, TALL>(acc, t, smem, n_steps, k_tail);   // a tall wave row has at most 96 rows
+      break;
   }
 
   // ---- epilogue: lane holds row l32 of each 32 x 32 block and, per register group q,
@@ -557,13 +597,13 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
   char* region = epilogue_region(smem, wave);
 #pragma unroll
   for (int mt = 0; mt < kMaxMT; ++mt) {
-    const int m0 = wm * half + mt * 32;               // first row of the block inside the tile
+    const int m0 = row_base + mt * 32;                // first row of the block inside the tile
     const int rows_valid = min(32, rows - m0);
     if (mt >= n_mt || rows_valid <= 0) continue;      // wave-uniform
     const size_t grow0 = (size_t)(row0 + m0);
     const size_t grow = grow0 + l32;                  // this lane's row (may be past the end: never stored)
     if (EPI == kEpiSwiglu) {
-      const int c0 = ntile * (kBN / 2) + wn * 64;     // this wave's 64 gate columns and the 64 matching up columns
+      const int c0 = ntile * (S::kCols / 2) + wn * 64;   // this wave's 64 gate columns and the 64 matching up columns
       u32x2 pa[2][4], pg[2][4], pu[2][4];
 #pragma unroll
       for (int ng = 0; ng < 2; ++ng)
@@ -589,7 +629,7 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
     } else if (EPI == kEpiSwigluGrad) {
       // SwiGLU_grad on the act_grad tile (Section 2.2, Figure 2b): the accumulators hold dA; with the saved
       // pre-activations (g, u): d_gate = dA*u*s*(1 + g*(1 - s)), d_up = dA*g*s, s = sigmoid(g)
-      const int c0 = ntile * kBN + wn * 128;
+      const int c0 = ntile * S::kCols + wn * 128;
       u32x2 pdg[4][4], pdu[4][4];
       const bool row_ok = l32 < rows_valid;
       const __bf16* h = p.G + grow * (size_t)(2 * p.N);
@@ -620,7 +660,7 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
       store_block_via_lds<4>(region, pdg, o, p.ldc, rows_valid, p.N - c0);
       store_block_via_lds<4>(region, pdu, o + p.N, p.ldc, rows_valid, p.N - c0);
     } else {
-      const int c0 = ntile * kBN + wn * 128;
+      const int c0 = ntile * S::kCols + wn * 128;
       u32x2 pk[4][4];
 #pragma unroll
       for (int nt = 0; nt < 4; ++nt)
@@ -633,11 +673,28 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
   }
 }
 
-// Forward tile (activations x weights), as used by the serialized kernels and the
-// persistent scheduler.
-template <int EPI>
-__device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int mtile, int ntile, char* smem) {
-  gemm_tile_bf16<kLayNN, EPI>(p, mtile, ntile, 0, smem);
+// A tile of the M-tile map runs in the tall shape iff it has more than 256 rows (the
+// map builder makes such tiles only with <= 384 rows and gives each a pair slot of its own).
+template <int LAY, int EPI>
+__device__ __forceinline__ void gemm_map_tile_bf16(const GemmParams& p, int mtile, int ntile, bool tall, char* smem) {
+  if (tall) gemm_tile_bf16<LAY, EPI, true>(p, mtile, ntile, 0, smem);
+  else gemm_tile_bf16<LAY, EPI, false>(p, mtile, ntile, 0, smem);
+}
+
+// Work item `rem` (0 .. 2*n_ntiles-1) of tile pair (m0, m0+1): a tall tile owns the whole slot as
+// 2*n_ntiles narrow N tiles; otherwise the items alternate between the two siblings, N-tile-major.
+// Returns false for an item that does not exist.
+__device__ __forceinline__ bool pair_work_item(const GemmParams& p, int m0, int rem, int n_m, int out_cols_per_ntile,
+                                               int& mtile, int& ntile, bool& tall) {
+  tall = __builtin_amdgcn_readfirstlane(p.tiles.rows[m0]) > kBM;   // scalar: the branch below contains barriers
+  if (tall) {
+    mtile = m0;
+    ntile = rem;
+    return ntile * (out_cols_per_ntile / 2) < p.N;
+  }
+  mtile = m0 + (rem & 1);
+  ntile = rem >> 1;
+  return mtile < n_m && __builtin_amdgcn_readfirstlane(p.tiles.rows[mtile]) > 0;
 }
 
 // Tile id for workgroup b in sweep `it` of a grid of G workgroups (G % 8 == 0).
@@ -666,9 +723,10 @@ void grouped_gemm_bf16_kernel(GemmParams p) {
     // the division runs on the vector ALU; pin the (uniform) results back into scalar registers
     const int pl = __builtin_amdgcn_readfirstlane(i / per_pair);
     const int rem = i - pl * per_pair;
-    const int mtile = 2 * (pl * 8 + xcd) + (rem & 1);
-    if (mtile >= n_m) continue;
-    gemm_tile_bf16<LAY, EPI>(p, mtile, rem >> 1, 0, smem);
+    int mtile, ntile;
+    bool tall;
+    if (!pair_work_item(p, 2 * (pl * 8 + xcd), rem, n_m, EPI == kEpiSwiglu ? kBN / 2 : kBN, mtile, ntile, tall)) continue;
+    gemm_map_tile_bf16<LAY, EPI>(p, mtile, ntile, tall, smem);
   }
 }
 
@@ -686,7 +744,7 @@ void grouped_wgrad_bf16_kernel(GemmParams p) {
     const int e = __builtin_amdgcn_readfirstlane(tile / per_e);
     const int rem = tile - e * per_e;
     const int mt = __builtin_amdgcn_readfirstlane(rem / p.n_ntiles);
-    gemm_tile_bf16<kLayTN, kEpiStore>(p, e, mt, rem - mt * p.n_ntiles, smem);
+    gemm_tile_bf16<kLayTN, kEpiStore, false>(p, e, mt, rem - mt * p.n_ntiles, smem);
   }
 }
 

@@ -30,13 +30,15 @@ inline int tile_bm(const MoeShape& s) { return s.dtype == MOE_BF16 ? kBM : kFBM;
 inline long r_max(const MoeShape& s) { return (long)s.T * (s.k < s.E_local ? s.k : s.E_local); }
 inline int n_sub(const MoeShape& s) { return (s.T + kSub - 1) / kSub; }
 inline int n_groups(const MoeShape& s) { return (s.T + kChunk - 1) / kChunk; }
-inline long max_mtiles(const MoeShape& s) { return r_max(s) / tile_bm(s) + s.E_local + 1; }
+// pair slots of the tile map: a tall tile (> BM rows) takes two entries, a wide tile of a split expert has > BM/2 rows
+inline long max_mtiles(const MoeShape& s) { return 2 * (r_max(s) / tile_bm(s)) + 2 * s.E_local + 2; }
+inline int tile_tall(const MoeShape& s) { return s.dtype == MOE_BF16 ? kTallRows : 0; }
 inline int gemm1_ntiles(const MoeShape& s) { return s.dtype == MOE_BF16 ? (s.I + kBN / 2 - 1) / (kBN / 2) : s.I / kFBN; }
 inline int gemm2_ntiles(const MoeShape& s) { return s.dtype == MOE_BF16 ? (s.H + kBN - 1) / kBN : s.H / kFBN; }
 inline long n_events(const MoeShape& s) { return kEvPerTile + 2 * max_mtiles(s); }
 inline long max_tasks_per_queue(const MoeShape& s) {
   const long mq = (max_mtiles(s) + kNumXcd - 1) / kNumXcd + 2;   // tiles are dealt in pairs
-  return mq * ((tile_bm(s) + kPermRows - 1) / kPermRows + gemm1_ntiles(s) + gemm2_ntiles(s));
+  return mq * ((tile_bm(s) + kPermRows - 1) / kPermRows + gemm1_ntiles(s) + gemm2_ntiles(s) + 2);
 }
 
 int check_shape(const MoeShape* s) {
@@ -168,6 +170,7 @@ RouteParams route_params(const Ctx& c, const float* logits) {
   p.n_groups = n_groups(c.s);
   p.BM = tile_bm(c.s);
   p.granule = c.s.dtype == MOE_BF16 ? kRowGranule : kFBM;
+  p.tall = tile_tall(c.s);
   return p;
 }
 
@@ -341,7 +344,7 @@ int run_backward(const BwdCtx& c, const void* dy, const void* w_gate_up, const v
   const int grid = BF16 ? (c.n_cu + 7) / 8 * 8 : c.n_cu * 4;
 
   hipLaunchKernelGGL(tile_map_kernel, dim3(1), dim3(kWave), 0, c.stream, c.sv.counts, s.E_local, bm,
-                     BF16 ? kRowGranule : kFBM, c.tiles);
+                     BF16 ? kRowGranule : kFBM, tile_tall(s), c.tiles);
 
   // backward Dispatch
   BwdDispatchParams bd;

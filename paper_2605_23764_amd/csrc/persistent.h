@@ -194,6 +194,7 @@ __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
   // the tile map lists M tiles in pairs (siblings of one expert where possible); queue q owns pairs q, q+8, ...
   const int n_pairs = (n_mtiles + 1) >> 1;
   auto parts_of = [&](int m) { return (sp.route.tiles.rows[m] + kPermRows - 1) / kPermRows; };
+  constexpr int kWideRows = BF16 ? kBM : (1 << 30);   // a bf16 tile with more rows runs in the tall shape
   for (int q = wave; q < kNumXcd; q += n_waves) {
     const int Pq = n_pairs > q ? (n_pairs - q + kNumXcd - 1) / kNumXcd : 0;
     TaskDesc* tq = sp.tasks + (size_t)q * sp.max_tasks_per_q;
@@ -202,36 +203,52 @@ __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
       for (int s = 0; s < 2; ++s) {
         const int m = 2 * (q + kNumXcd * j) + s;
         if (m >= n_mtiles) continue;
-        const int parts = parts_of(m);
+        const int parts = parts_of(m);   // 0 for the unused half of a tall tile's slot
         for (int part = lane; part < parts; part += kWave)
           tq[n + part] = TaskDesc{kTaskPermute | (part << 8), m, kEvRank, sp.n_rank_tasks};
         n += parts;
       }
-    // GEMM tiles N-tile-major with the two siblings adjacent: they stream the same weight panel at the same time
+    // GEMM tiles of a slot N-tile-major with the two siblings adjacent (they stream the same weight panel
+    // at the same time); a tall tile fills its slot with twice as many half-width N tiles
     for (int j = 0; j < Pq + kGemm2Lag; ++j) {
       if (j < Pq) {
         const int m0 = 2 * (q + kNumXcd * j);
-        const int n_sib = min(2, n_mtiles - m0);
+        const int rows0 = sp.route.tiles.rows[m0];
+        const bool tall = rows0 > kWideRows;
+        const int n_sib = tall ? 1 : ((m0 + 1 < n_mtiles && sp.route.tiles.rows[m0 + 1] > 0) ? 2 : 1);
+        const int n_nt = tall ? (sp.g1.N + 63) / 64 : nN1;
         const int parts0 = parts_of(m0), parts1 = n_sib > 1 ? parts_of(m0 + 1) : 0;
-        for (int i = lane; i < nN1 * n_sib; i += kWave) {
+        for (int i = lane; i < n_nt * n_sib; i += kWave) {
           const int nt = i / n_sib, sib = i - nt * n_sib;
           tq[n + i] = TaskDesc{kTaskGemm1 | (nt << 8), m0 + sib, kEvPerTile + m0 + sib, sib ? parts1 : parts0};
         }
-        n += nN1 * n_sib;
+        n += n_nt * n_sib;
       }
       if (j >= kGemm2Lag) {
         const int m0 = 2 * (q + kNumXcd * (j - kGemm2Lag));
-        const int n_sib = min(2, n_mtiles - m0);
-        for (int i = lane; i < nN2 * n_sib; i += kWave) {
+        const bool tall = sp.route.tiles.rows[m0] > kWideRows;
+        const int n_sib = tall ? 1 : ((m0 + 1 < n_mtiles && sp.route.tiles.rows[m0 + 1] > 0) ? 2 : 1);
+        const int n_nt = tall ? (sp.g2.N + 127) / 128 : nN2;
+        const int g1_tiles = tall ? (sp.g1.N + 63) / 64 : nN1;     // GEMM-1 tiles that complete a row block of A
+        for (int i = lane; i < n_nt * n_sib; i += kWave) {
           const int nt = i / n_sib, sib = i - nt * n_sib;
-          tq[n + i] = TaskDesc{kTaskGemm2 | (nt << 8), m0 + sib, kEvPerTile + sp.max_mtiles + m0 + sib, nN1};
+          tq[n + i] = TaskDesc{kTaskGemm2 | (nt << 8), m0 + sib, kEvPerTile + sp.max_mtiles + m0 + sib, g1_tiles};
         }
-        n += nN2 * n_sib;
+        n += n_nt * n_sib;
       }
     }
     if (lane == 0) sp.meta[kMetaQueueCount0 + q] = n;
   }
-  if (threadIdx.x == 0) sp.meta[kMetaGemm2Total] = n_mtiles * nN2;
+  // COMBINE waits for every GEMM-2 tile: count them
+  if (wave == 0) {
+    int total = 0;
+    for (int m = lane; m < n_mtiles; m += kWave) {
+      const int rows = sp.route.tiles.rows[m];
+      total += rows > kWideRows ? (sp.g2.N + 127) / 128 : (rows > 0 ? nN2 : 0);
+    }
+    total = wave_incl_scan(total, lane);
+    if (lane == kWave - 1) sp.meta[kMetaGemm2Total] = total;
+  }
 }
 
 template <bool BF16>
@@ -254,11 +271,11 @@ __device__ __forceinline__ void run_tile_task(const SchedParams<BF16>& sp, const
     permute_rows<4>(sp.perm, r0, min(r0 + kPermRows, row0 + rows), wave, blockDim.x / kWave);
     sched_trigger(sp, kEvPerTile + m, wave, kScopeXcd);
   } else if (type == kTaskGemm1) {
-    if constexpr (BF16) gemm_tile_bf16<kEpiSwiglu>(sp.g1, m, idx, smem);
+    if constexpr (BF16) gemm_map_tile_bf16<kLayNN, kEpiSwiglu>(sp.g1, m, idx, __builtin_amdgcn_readfirstlane(sp.route.tiles.rows[m]) > kBM, smem);
     else gemm_tile_f32<kEpiSwiglu>(sp.g1, m, idx, reinterpret_cast<float*>(smem));
     sched_trigger(sp, kEvPerTile + sp.max_mtiles + m, wave, kScopeXcd);
   } else {
-    if constexpr (BF16) gemm_tile_bf16<kEpiStore>(sp.g2, m, idx, smem);
+    if constexpr (BF16) gemm_map_tile_bf16<kLayNN, kEpiStore>(sp.g2, m, idx, __builtin_amdgcn_readfirstlane(sp.route.tiles.rows[m]) > kBM, smem);
     else gemm_tile_f32<kEpiStore>(sp.g2, m, idx, reinterpret_cast<float*>(smem));
     // COMBINE waits for every GEMM-2 tile, so completions are counted here and published once per
     // worker after its queue has drained: a device-scope release per tile would write back the

@@ -29,6 +29,7 @@ struct RouteParams {
   int n_sub;     // ceil(T / kSub) histogram rows
   int n_groups;  // ceil(T / kChunk) rank groups
   int BM;        // M-tile row capacity
+  int tall;      // row capacity of a tall M tile (0 = the kernels have no tall shape)
   int granule;   // an expert's tiles are equal multiples of this (last one takes the remainder)
 };
 
@@ -206,57 +207,75 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
   return v;
 }
 
+// Tiling of one expert with c rows: n tiles of `per` rows (the last takes the
+// remainder).  Wide tiles hold up to BM rows; an expert with BM < c <= tall rows
+// (tall = 0: never) is covered by ONE tall tile, so its weights are fetched once
+// instead of once per wide tile.  Larger experts stay with wide tiles: with many
+// rows the kernel is MFMA-bound and the wide shape moves fewer operand bytes per
+// MFMA (measured: tall tiles for 1000-row experts cost 15-20 %).
+struct ExpertTiling { int n, per; bool is_tall; };
+__device__ __forceinline__ ExpertTiling expert_tiling(int c, int BM, int granule, int tall) {
+  ExpertTiling t;
+  t.is_tall = c > BM && c <= tall;
+  t.n = t.is_tall ? 1 : (c + BM - 1) / BM;
+  t.per = t.n ? (((c + t.n - 1) / t.n + granule - 1) / granule) * granule : 0;
+  return t;
+}
+
 // Rows per expert -> counts, offsets (both optional outputs) and the M-tile map, by
 // ONE wave.  cnt may live in LDS or in global memory.
 //
-// Order of the map: an expert with nt tiles contributes nt/2 sibling pairs; pair j
-// sits at entries 2j, 2j+1.  The left-over single tiles of experts with an odd
-// count follow, in expert order, and pair up with each other.  Consumers deal pair
-// j to XCD j % 8 and run its two tiles side by side on neighbouring CUs, so the
-// weight panel both siblings stream is fetched from HBM once and hits in that
-// XCD's L2 for the second reader.
-__device__ __forceinline__ void build_tile_map(int E_local, const int32_t* cnt, int BM, int granule,
+// Order of the map: it is a list of pair slots, slot j = entries 2j, 2j+1.  A tall
+// tile owns a slot (its second entry has 0 rows); wide sibling tiles of one expert
+// share a slot; the left-over single wide tiles follow, in expert order, and pair
+// up with each other.  Consumers deal slot j to XCD j % 8 and run its two tiles side
+// by side on neighbouring CUs.
+__device__ __forceinline__ void build_tile_map(int E_local, const int32_t* cnt, int BM, int granule, int tall,
                                                int32_t* counts, int32_t* offsets, const TileMap& tiles) {
   const int lane = lane_id();
-  int total_pairs = 0;
+  int total_slots = 0;   // slots that are not made of left-over singles
   for (int e0 = 0; e0 < E_local; e0 += kWave) {
     const int e = e0 + lane;
-    const int c = e < E_local ? cnt[e] : 0;
-    const int np_incl = wave_incl_scan(((c + BM - 1) / BM) >> 1, lane);
-    total_pairs += __shfl(np_incl, kWave - 1, kWave);
+    const ExpertTiling t = expert_tiling(e < E_local ? cnt[e] : 0, BM, granule, tall);
+    const int incl = wave_incl_scan(t.is_tall ? t.n : (t.n >> 1), lane);
+    total_slots += __shfl(incl, kWave - 1, kWave);
   }
-  int row_run = 0, pair_run = 0, single_run = 0;
+  int row_run = 0, slot_run = 0, single_run = 0;
   for (int e0 = 0; e0 < E_local; e0 += kWave) {
     const int e = e0 + lane;
     const int c = e < E_local ? cnt[e] : 0;
-    const int nt = (c + BM - 1) / BM;
-    const int np = nt >> 1, ns = nt & 1;
+    const ExpertTiling t = expert_tiling(c, BM, granule, tall);
+    const int ns = t.is_tall ? t.n : (t.n >> 1);          // slots
+    const int n1 = t.is_tall ? 0 : (t.n & 1);             // left-over single
     const int row_incl = wave_incl_scan(c, lane);
-    const int pair_incl = wave_incl_scan(np, lane);
-    const int single_incl = wave_incl_scan(ns, lane);
+    const int slot_incl = wave_incl_scan(ns, lane);
+    const int single_incl = wave_incl_scan(n1, lane);
     const int off = row_run + row_incl - c;
-    const int pbase = pair_run + pair_incl - np;
-    const int sbase = single_run + single_incl - ns;
+    const int sbase = slot_run + slot_incl - ns;
+    const int obase = single_run + single_incl - n1;
     if (e < E_local) {
       if (counts) counts[e] = c;
       if (offsets) offsets[e] = off;
-      // equal split: sibling tiles of an expert take the same time, so they
-      // stream the expert's weights in step
-      const int per = nt ? (((c + nt - 1) / nt + granule - 1) / granule) * granule : 0;
-      for (int i = 0; i < nt; ++i) {
-        const int idx = i < 2 * np ? 2 * pbase + i : 2 * total_pairs + sbase;
+      for (int i = 0; i < t.n; ++i) {
+        int idx;
+        if (t.is_tall) {
+          idx = 2 * (sbase + i);
+          tiles.expert[idx + 1] = e; tiles.row0[idx + 1] = off; tiles.rows[idx + 1] = 0;   // the slot's unused half
+        } else {
+          idx = i < 2 * ns ? 2 * sbase + i : 2 * total_slots + obase;
+        }
         tiles.expert[idx] = e;
-        tiles.row0[idx] = off + i * per;
-        tiles.rows[idx] = min(per, c - i * per);
+        tiles.row0[idx] = off + i * t.per;
+        tiles.rows[idx] = min(t.per, c - i * t.per);
       }
     }
     row_run += __shfl(row_incl, kWave - 1, kWave);
-    pair_run += __shfl(pair_incl, kWave - 1, kWave);
+    slot_run += __shfl(slot_incl, kWave - 1, kWave);
     single_run += __shfl(single_incl, kWave - 1, kWave);
   }
   if (lane == 0) {
     if (offsets) offsets[E_local] = row_run;
-    tiles.meta[kMetaMTiles] = 2 * total_pairs + single_run;
+    tiles.meta[kMetaMTiles] = 2 * total_slots + single_run;
     tiles.meta[kMetaRows] = row_run;
     tiles.meta[kMetaStatus] = 0;
   }
@@ -295,7 +314,7 @@ __device__ __forceinline__ void scan_all(const RouteParams& p, int32_t* s_cnt, i
     s_cnt[e] = sum;
   }
   __syncthreads();
-  if (wave == 0) build_tile_map(p.E_local, s_cnt, p.BM, p.granule, p.counts, p.offsets, p.tiles);
+  if (wave == 0) build_tile_map(p.E_local, s_cnt, p.BM, p.granule, p.tall, p.counts, p.offsets, p.tiles);
 }
 
 constexpr int kRankLdsWords = 4 * kMaxE;   // LDS words rank_chunk needs per wave
@@ -395,8 +414,8 @@ __global__ __launch_bounds__(256) void rank_kernel(RouteParams p) {
 // M-tile map from the rows per expert alone (the backward rebuilds it from the
 // saved counts instead of keeping the forward's workspace alive).
 __global__ __launch_bounds__(kWave) void tile_map_kernel(const int32_t* counts, int E_local, int BM, int granule,
-                                                         TileMap tiles) {
-  build_tile_map(E_local, counts, BM, granule, nullptr, nullptr, tiles);
+                                                         int tall, TileMap tiles) {
+  build_tile_map(E_local, counts, BM, granule, tall, nullptr, nullptr, tiles);
 }
 
 }  // namespace moe
