@@ -23,6 +23,8 @@ SMALL = [
     ("b_bf16_k1", 65, 64, 64, 3, 3, 0, 1, "bf16", 37),
     ("b_bf16_kE", 130, 64, 128, 4, 4, 0, 4, "bf16", 38),          # 130 rows per expert: 2 full steps + 2 rows
     ("b_bf16_exact64", 64, 576, 320, 2, 2, 0, 2, "bf16", 39),     # 64 rows per expert: no reduction tail
+    ("b_bf16_limits", 97, 128, 64, 256, 256, 0, 16, "bf16", 43),   # maximum k, E and E_local; most experts 0..10 rows
+    ("b_bf16_tall", 1200, 192, 128, 4, 4, 0, 1, "bf16", 44),       # ~300 rows/expert: tall tiles in act_grad / gate_grad
 ]
 
 

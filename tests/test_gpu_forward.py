@@ -20,6 +20,9 @@ SMALL = [
     ("s_bf16_k1", 65, 64, 64, 3, 3, 0, 1, "bf16", 16),
     ("s_bf16_kE", 130, 64, 128, 4, 4, 0, 4, "bf16", 17),         # k = E: every expert gets every token
     ("s_f32_one_token", 1, 64, 64, 2, 2, 0, 1, "f32", 18),
+    ("s_bf16_limits", 97, 128, 64, 256, 256, 0, 16, "bf16", 19),   # maximum k, E and E_local; T not a multiple of 32
+    ("s_f32_limits", 33, 64, 64, 256, 200, 56, 16, "f32", 20),
+    ("s_bf16_tall", 1200, 192, 128, 4, 4, 0, 1, "bf16", 23),       # ~300 rows/expert: tall tiles (257..384 rows)
 ]
 
 

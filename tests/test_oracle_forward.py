@@ -107,3 +107,24 @@ def test_linear_in_w_down_and_intermediates():
     for r in range(len(e_of_row)):
         np.testing.assert_allclose(f1["H1"][r], f1["Xp"][r] @ d["w1"][e_of_row[r]].astype(np.float64), rtol=1e-13)
         np.testing.assert_allclose(f1["Yp"][r], f1["A"][r] @ d["w2"][e_of_row[r]].astype(np.float64), rtol=1e-13)
+
+
+def test_hand_worked_example_fixture():
+    """Forward and backward on the 2-token, 2-expert, k=2 example worked by hand in
+    tests/golden/hand_example_2tok_2exp.json (closed forms in ln 3; nothing in the
+    fixture comes from the oracle)."""
+    import json
+    import os
+    fx = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "hand_example_2tok_2exp.json")))
+    x, lg = np.array(fx["x"]), np.array(fx["logits"])
+    w1, w2 = np.array(fx["w_gate_up"]), np.array(fx["w_down"])
+    from oracle import backward
+    ref = forward(x, lg, w1, w2, fx["k"])
+    ex = fx["expect"]
+    for name in ("topk_idx", "counts", "offsets", "row_of", "token_of", "slot_of"):
+        np.testing.assert_array_equal(ref[name], np.array(ex[name]), err_msg=name)
+    for name in ("topk_w", "A", "Yp", "out"):
+        np.testing.assert_allclose(ref[name], np.array(ex[name]), rtol=1e-13, atol=1e-14, err_msg=name)
+    bwd = backward(np.array(fx["dy"]), ref, w1, w2)
+    for name in ("d_topk_w", "dW_down", "dXp", "dX", "dW_gate_up"):
+        np.testing.assert_allclose(bwd[name], np.array(ex[name]), rtol=1e-13, atol=1e-14, err_msg=name)
