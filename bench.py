@@ -26,7 +26,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 # dispatch, FETCH_SIZE scaled by 2.024 and WRITE_SIZE by 1.000 (what the same counters read
 # for the permute kernel, a plain copy of known size).  Counters cannot be read inside a
 # timed run, so the figure of the last profiled build is carried here.
-MEASURED_TRAFFIC_BYTES = {"c3": (1283112.1 * 2.024 + 102026.8) * 1024}
+MEASURED_TRAFFIC_BYTES = {"c3": (975434.6 * 2.024 + 98108.0) * 1024}
 
 
 def main():
@@ -201,14 +201,21 @@ def main():
         from threadpoolctl import threadpool_info
         t0 = time.perf_counter()
         ref = oracle.forward(inp["x"], inp["logits"], inp["w_gate_up"], inp["w_down"], cfg.k, cfg.expert_base, El)
+        if fwd_bwd:
+            ref_b = oracle.backward(inp["dy"], ref, inp["w_gate_up"], inp["w_down"])
         dt = time.perf_counter() - t0
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
         got = out.float().cpu().numpy().astype(np.float64)
         res["cpu_baseline"] = {
             "value": dt * 1e6, "unit": "us/layer", "cores": threads, "kind": "oracle",
-            "sample": f"one full forward of workload {cfg.name} (fp64 numpy oracle, 1 pass, not scaled)",
+            "sample": "one full %s of workload %s (fp64 numpy oracle, 1 pass, not scaled)"
+                      % ("forward + backward" if fwd_bwd else "forward", cfg.name),
             "gpu_vs_oracle_max_err_over_max_ref": float(np.abs(got - ref["out"]).max() / np.abs(ref["out"]).max()),
         }
+        if fwd_bwd:
+            gdx = dx.float().cpu().numpy().astype(np.float64)
+            res["cpu_baseline"]["gpu_vs_oracle_dx_max_err_over_max_ref"] = float(
+                np.abs(gdx - ref_b["dX"]).max() / np.abs(ref_b["dX"]).max())
     print(json.dumps(res))
 
 
