@@ -27,62 +27,77 @@ __device__ __forceinline__ float wave_sum(float v) {
 // One wave per token t: for every local slot j with row r = row_of[t,j]
 //   dYp[r,:] = topk_w[t,j] * dY[t,:],   d_topk_w[t,j] = <dY[t,:], Yp[r,:]>  (fp32),
 // and d_topk_w[t,j] = 0 for slots whose expert is not local.
+// Lane j < k holds slot j; the local slots are walked through the ballot of "row >= 0" with rows and
+// weights as wave-uniform scalars.  A pass covers 7 x 64 16-byte vectors of the row: dY[t] is fetched
+// once per pass and reused by every local slot, the Yp vectors of a slot are all in flight together.
 template <bool BF16>
 __device__ __forceinline__ void bwd_dispatch_token(const BwdDispatchParams& p, int t) {
   const int lane = lane_id();
+  int rowv = -1;
+  float wv = 0.f;
+  if (lane < p.k) {
+    rowv = p.row_of[(size_t)t * p.k + lane];
+    wv = p.topk_w[(size_t)t * p.k + lane];
+    if (rowv < 0) p.d_topk_w[(size_t)t * p.k + lane] = 0.f;
+  }
+  const uint64_t local = __ballot(rowv >= 0);
+  if (local == 0) return;
+  constexpr int EPV = BF16 ? 8 : 4;                 // elements per 16-byte vector
+  constexpr int U = BF16 ? 7 : 4;                   // vectors per lane per pass
+  const int vec = p.H / EPV;
+  const size_t row_bytes = (size_t)p.H * (BF16 ? 2 : 4);
+  const uint4* dy = reinterpret_cast<const uint4*>(static_cast<const char*>(p.dY) + (size_t)t * row_bytes);
+  float dot[kMaxK];
 #pragma unroll
-  for (int j = 0; j < kMaxK; ++j) {
-    if (j >= p.k) break;
-    const int r = p.row_of[(size_t)t * p.k + j];
-    if (r < 0) {
-      if (lane == 0) p.d_topk_w[(size_t)t * p.k + j] = 0.f;
-      continue;
-    }
-    const float w = p.topk_w[(size_t)t * p.k + j];
-    float dot = 0.f;
-    if (BF16) {
-      const int vec = p.H / 8;
-      const uint4* dy = reinterpret_cast<const uint4*>(static_cast<const __bf16*>(p.dY) + (size_t)t * p.H);
-      const uint4* yp = reinterpret_cast<const uint4*>(static_cast<const __bf16*>(p.Yp) + (size_t)r * p.H);
-      uint4* o = reinterpret_cast<uint4*>(static_cast<__bf16*>(p.dYp) + (size_t)r * p.H);
-      constexpr int U = 4;
-      for (int v0 = lane; v0 < vec; v0 += U * kWave) {
-        uint4 a[U], b[U];
+  for (int n = 0; n < kMaxK; ++n) dot[n] = 0.f;
+  for (int v0 = lane; v0 < vec; v0 += U * kWave) {
+    uint4 a[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const bool ok = v0 + u * kWave < vec;
-          a[u] = ok ? dy[v0 + u * kWave] : make_uint4(0, 0, 0, 0);
-          b[u] = ok ? yp[v0 + u * kWave] : make_uint4(0, 0, 0, 0);
-        }
+    for (int u = 0; u < U; ++u) a[u] = v0 + u * kWave < vec ? dy[v0 + u * kWave] : make_uint4(0, 0, 0, 0);
+    uint64_t m = local;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-          if (v0 + u * kWave >= vec) break;
-          const uint32_t aw[4] = {a[u].x, a[u].y, a[u].z, a[u].w};
-          const uint32_t bw[4] = {b[u].x, b[u].y, b[u].z, b[u].w};
-          uint32_t ow[4];
+    for (int n = 0; n < kMaxK; ++n) {
+      if (m == 0) break;
+      const int j = __builtin_amdgcn_readfirstlane(__builtin_ctzll(m));
+      m &= m - 1;
+      const int r = __builtin_amdgcn_readlane(rowv, j);
+      const float w = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wv), j));
+      const uint4* yp = reinterpret_cast<const uint4*>(static_cast<const char*>(p.Yp) + (size_t)r * row_bytes);
+      uint4* o = reinterpret_cast<uint4*>(static_cast<char*>(p.dYp) + (size_t)r * row_bytes);
+      uint4 b[U];
 #pragma unroll
-          for (int x = 0; x < 4; ++x) {
+      for (int u = 0; u < U; ++u) b[u] = v0 + u * kWave < vec ? yp[v0 + u * kWave] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (v0 + u * kWave >= vec) break;
+        const uint32_t aw[4] = {a[u].x, a[u].y, a[u].z, a[u].w};
+        const uint32_t bw[4] = {b[u].x, b[u].y, b[u].z, b[u].w};
+        uint32_t ow[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+          if constexpr (BF16) {
             const float lo = bf16_lo(aw[x]), hi = bf16_hi(aw[x]);
-            dot = fmaf(lo, bf16_lo(bw[x]), dot);
-            dot = fmaf(hi, bf16_hi(bw[x]), dot);
+            dot[n] = fmaf(lo, bf16_lo(bw[x]), dot[n]);
+            dot[n] = fmaf(hi, bf16_hi(bw[x]), dot[n]);
             ow[x] = pack_bf16(w * lo, w * hi);
+          } else {
+            const float av = __builtin_bit_cast(float, aw[x]);
+            dot[n] = fmaf(av, __builtin_bit_cast(float, bw[x]), dot[n]);
+            ow[x] = __builtin_bit_cast(uint32_t, w * av);
           }
-          o[v0 + u * kWave] = make_uint4(ow[0], ow[1], ow[2], ow[3]);
         }
-      }
-    } else {
-      const int vec = p.H / 4;
-      const float4* dy = reinterpret_cast<const float4*>(static_cast<const float*>(p.dY) + (size_t)t * p.H);
-      const float4* yp = reinterpret_cast<const float4*>(static_cast<const float*>(p.Yp) + (size_t)r * p.H);
-      float4* o = reinterpret_cast<float4*>(static_cast<float*>(p.dYp) + (size_t)r * p.H);
-      for (int v = lane; v < vec; v += kWave) {
-        const float4 a = dy[v], b = yp[v];
-        dot = fmaf(a.x, b.x, dot); dot = fmaf(a.y, b.y, dot); dot = fmaf(a.z, b.z, dot); dot = fmaf(a.w, b.w, dot);
-        o[v] = make_float4(w * a.x, w * a.y, w * a.z, w * a.w);
+        o[v0 + u * kWave] = make_uint4(ow[0], ow[1], ow[2], ow[3]);
       }
     }
-    dot = wave_sum(dot);
-    if (lane == 0) p.d_topk_w[(size_t)t * p.k + j] = dot;
+  }
+  uint64_t m = local;
+#pragma unroll
+  for (int n = 0; n < kMaxK; ++n) {
+    if (m == 0) break;
+    const int j = __builtin_amdgcn_readfirstlane(__builtin_ctzll(m));
+    m &= m - 1;
+    const float d = wave_sum(dot[n]);
+    if (lane == 0) p.d_topk_w[(size_t)t * p.k + j] = d;
   }
 }
 

@@ -45,3 +45,15 @@ def test_status_strings_and_workspace_query(lib):
             moe.moe_ffn_workspace_bytes(bad)
         assert ei.value.status == -2
     assert lib.moe_ffn_workspace_bytes(None, None, None) == -1
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU's share is all this build runs: bench.py --gpus 2 must exit with a message."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stderr + r.stdout) or "ONE GPU" in (r.stderr + r.stdout)
