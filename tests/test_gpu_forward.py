@@ -123,3 +123,29 @@ def test_argument_errors_are_reported_on_the_host():
     with pytest.raises(moe.MoeError) as ei:
         moe.moe_ffn_workspace_bytes(bad)
     assert ei.value.status == -2
+
+
+def test_stage_entry_points_reproduce_the_forward():
+    """moe_route, moe_permute, moe_grouped_gemm_swiglu, moe_grouped_gemm and moe_combine called one
+    after the other give bit-identical results to moe_ffn_forward (they are its serialized path)."""
+    import paper_2605_23764_amd as moe
+    from gpu_common import run_forward, small_config
+    cfg = small_config("s_stages", 900, 192, 128, 8, 6, 1, 2, "bf16", 24)
+    inp = make_inputs(cfg)
+    run = run_forward(cfg, inp, store_h1=True)
+    sv2 = moe.alloc_saved(run.shape, store_h1=True)
+    ws2 = moe.alloc_workspace(run.shape)
+    out2 = torch.full_like(run.out, float("nan"))
+    d = run.dev
+    moe.moe_route(run.shape, d["logits"], sv2, ws2)
+    moe.moe_permute(run.shape, d["x"], sv2, ws2)
+    moe.moe_grouped_gemm_swiglu(run.shape, d["w_gate_up"], sv2, ws2)
+    moe.moe_grouped_gemm(run.shape, d["w_down"], sv2, ws2)
+    moe.moe_combine(run.shape, sv2, out2, ws2)
+    torch.cuda.synchronize()
+    R = int(run.saved.offsets[-1])
+    assert torch.equal(out2, run.out)
+    for name in ("topk_idx", "topk_w", "counts", "offsets", "row_of"):
+        assert torch.equal(getattr(sv2, name), getattr(run.saved, name)), name
+    for name in ("token_of", "slot_of", "Xp", "H1", "A", "Yp"):
+        assert torch.equal(getattr(sv2, name)[:R], getattr(run.saved, name)[:R]), name
