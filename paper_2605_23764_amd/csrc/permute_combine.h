@@ -20,7 +20,9 @@ struct PermuteParams {
 // Called by every wave of the workgroup; waves split the rows.  U = 16-byte loads a
 // lane keeps in flight: 4 is enough when a CU holds dozens of waves; a worker of the
 // persistent kernel has four waves on its CU and needs the memory-level parallelism
-// inside the wave (a whole row in flight).
+// inside the wave (a whole row in flight).  The copies are non-temporal: every byte is
+// touched once, and with ordinary loads more than four in flight per lane made the
+// persistent tasks slower (53 / 82 / 117 us per task at 4 / 7 / 14), not faster.
 template <int U>
 __device__ __forceinline__ void permute_rows(const PermuteParams& p, int r_begin, int r_end,
                                              int wave, int n_waves) {
@@ -32,11 +34,11 @@ __device__ __forceinline__ void permute_rows(const PermuteParams& p, int r_begin
     uint4* dst = reinterpret_cast<uint4*>(static_cast<char*>(p.Xp) + (size_t)r * p.H * p.elem_bytes);
     int v = lane;
     for (; v + (U - 1) * kWave < vec_per_row; v += U * kWave) {
-      uint4 q[U];
+      u32x4 q[U];
 #pragma unroll
-      for (int u = 0; u < U; ++u) q[u] = src[v + u * kWave];
+      for (int u = 0; u < U; ++u) q[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + v + u * kWave));
 #pragma unroll
-      for (int u = 0; u < U; ++u) dst[v + u * kWave] = q[u];
+      for (int u = 0; u < U; ++u) __builtin_nontemporal_store(q[u], reinterpret_cast<u32x4*>(dst + v + u * kWave));
     }
     for (; v < vec_per_row; v += kWave) dst[v] = src[v];
   }

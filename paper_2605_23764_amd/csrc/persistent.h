@@ -268,7 +268,7 @@ __device__ __forceinline__ void run_tile_task(const SchedParams<BF16>& sp, const
   if (type == kTaskPermute) {
     const int row0 = sp.route.tiles.row0[m], rows = sp.route.tiles.rows[m];
     const int r0 = row0 + idx * kPermRows;
-    permute_rows<4>(sp.perm, r0, min(r0 + kPermRows, row0 + rows), wave, blockDim.x / kWave);
+    permute_rows<14>(sp.perm, r0, min(r0 + kPermRows, row0 + rows), wave, blockDim.x / kWave);
     sched_trigger(sp, kEvPerTile + m, wave, kScopeXcd);
   } else if (type == kTaskGemm1) {
     if constexpr (BF16) gemm_map_tile_bf16<kLayNN, kEpiSwiglu>(sp.g1, m, idx, __builtin_amdgcn_readfirstlane(sp.route.tiles.rows[m]) > kBM, smem);
