@@ -193,6 +193,22 @@ int moe_grouped_gemm(const MoeShape* shape, const void* d_w_down, const MoeSaved
 int moe_combine(const MoeShape* shape, const MoeSaved* saved, void* d_out,
                 void* d_workspace, size_t workspace_bytes, void* stream);
 
+/* ---- SwiGLU + Add microbenchmark (paper Section 6: tile interleaving and L2 reuse, Section 6.1;
+ *      static against dynamic scheduling, Section 6.2) ----
+ *   S[m,j]   = silu(X[m,j]) * X[m,N+j]      X [M,2N] bf16, S [M,N] bf16 (intermediate, written)
+ *   Out[m,j] = S[m,j] + Y[m,j]              Y, Out [M,N] bf16
+ * mode 0: two launches, one per operator; mode 1: one launch, row tiles in a static order with the Add
+ * tile close behind its SwiGLU tile, event counters; mode 2: one launch, the same tiles pulled from a
+ * shared ready queue that finished SwiGLU tiles feed; mode 3: as mode 2 with one ready queue per XCD (a
+ * tile's two tasks stay on the XCD that owns the tile).  Results are bit-identical in all modes.
+ * N must be a multiple of 8, all pointers device and 16-byte aligned; d_workspace >=
+ * moe_microbench_workspace_bytes(M).  A bounded wait that expires is reported by the status word:
+ * moe_microbench_last_status() (host-blocking 4-byte copy) returns MOE_OK or MOE_ERR_SCHED_TIMEOUT. */
+size_t moe_microbench_workspace_bytes(int M);
+int moe_microbench_swiglu_add(int M, int N, const void* d_x, const void* d_y, void* d_s, void* d_out, int mode,
+                              void* d_workspace, size_t workspace_bytes, void* stream);
+int moe_microbench_last_status(int M, const void* d_workspace);
+
 #ifdef __cplusplus
 }
 #endif

@@ -10,4 +10,5 @@ from .moe_ffn_oracle import (  # noqa: F401
     local_permutation,
     route,
     swiglu,
+    swiglu_add,
 )

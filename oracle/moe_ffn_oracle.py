@@ -97,6 +97,18 @@ def swiglu(h1, I):
     return g * sigmoid(g) * u
 
 
+def swiglu_add(x, y):
+    """The operator pair of the paper's Section 6 microbenchmarks: SwiGLU over an
+    [M, 2N] input (gate = first N columns), then an elementwise Add with y [M, N].
+    The intermediate is kept in fp64 (the definition has no rounding in between)."""
+    x = np.asarray(x, dtype=np.float64)
+    y = np.asarray(y, dtype=np.float64)
+    N = y.shape[1]
+    assert x.shape == (y.shape[0], 2 * N)
+    s = x[:, :N] * (1.0 / (1.0 + np.exp(-x[:, :N]))) * x[:, N:]
+    return dict(S=s, out=s + y)
+
+
 def forward(x, logits, w_gate_up, w_down, k, expert_base=0, E_local=None):
     """Forward MoE-FFN of one device's experts (paper Section 2.2, Figure 2a).
 

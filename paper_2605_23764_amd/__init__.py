@@ -4,6 +4,10 @@ only; every step of the layer runs in the HIP library.  Importing the package
 does not load the library; the first call does, and fails loudly if it is
 missing (there is no CPU fallback)."""
 from .binding import (  # noqa: F401
+    MB_DYNAMIC,
+    MB_DYNAMIC_XCD,
+    MB_SERIAL,
+    MB_STATIC,
     MOE_BF16,
     MOE_F32,
     MODE_PERSISTENT,
@@ -22,6 +26,9 @@ from .binding import (  # noqa: F401
     moe_ffn_last_status,
     moe_ffn_workspace_bytes,
     moe_grouped_gemm,
+    moe_microbench_last_status,
+    moe_microbench_swiglu_add,
+    moe_microbench_workspace_bytes,
     moe_grouped_gemm_swiglu,
     moe_permute,
     moe_route,

@@ -37,7 +37,7 @@ class _MoeSaved(ctypes.Structure):
 EXPORTS = (
     "moe_status_string", "moe_ffn_workspace_bytes", "moe_ffn_forward", "moe_ffn_backward",
     "moe_ffn_last_status", "moe_ffn_debug_set_spin_limit", "moe_route", "moe_permute", "moe_grouped_gemm_swiglu", "moe_grouped_gemm",
-    "moe_combine",
+    "moe_combine", "moe_microbench_workspace_bytes", "moe_microbench_swiglu_add", "moe_microbench_last_status",
 )
 
 
@@ -59,6 +59,8 @@ def load_library() -> ctypes.CDLL:
         lib.moe_status_string.argtypes = [ctypes.c_int]
         for name in EXPORTS[1:]:
             getattr(lib, name).restype = ctypes.c_int
+        lib.moe_microbench_workspace_bytes.restype = ctypes.c_size_t
+        lib.moe_microbench_workspace_bytes.argtypes = [ctypes.c_int]
         _LIB = lib
     return _LIB
 
@@ -214,3 +216,21 @@ def moe_combine(shape, saved: Saved, out, workspace, stream=None) -> None:
     wp, wb = _ws(workspace)
     _check(load_library().moe_combine(ctypes.byref(shape), ctypes.byref(sv), _ptr(out), wp, wb, _stream(stream)),
            "moe_combine")
+
+
+MB_SERIAL, MB_STATIC, MB_DYNAMIC, MB_DYNAMIC_XCD = 0, 1, 2, 3
+
+
+def moe_microbench_workspace_bytes(M: int) -> int:
+    return int(load_library().moe_microbench_workspace_bytes(int(M)))
+
+
+def moe_microbench_swiglu_add(M, N, x, y, s, out, mode, workspace, stream=None) -> None:
+    wp, wb = _ws(workspace)
+    _check(load_library().moe_microbench_swiglu_add(ctypes.c_int(M), ctypes.c_int(N), _ptr(x), _ptr(y), _ptr(s),
+                                                    _ptr(out), ctypes.c_int(mode), wp, wb, _stream(stream)),
+           "moe_microbench_swiglu_add")
+
+
+def moe_microbench_last_status(M, workspace) -> int:
+    return load_library().moe_microbench_last_status(ctypes.c_int(M), _ptr(workspace))

@@ -9,6 +9,7 @@
 #include "common.h"
 #include "gemm_bf16.h"
 #include "gemm_f32.h"
+#include "microbench.h"
 #include "permute_combine.h"
 #include "persistent.h"
 #include "route.h"
@@ -542,6 +543,52 @@ int moe_ffn_backward(const MoeShape* shape, const void* d_dy, const void* d_x, c
   return c.s.dtype == MOE_BF16
              ? run_backward<__bf16>(c, d_dy, d_w_gate_up, d_w_down, d_dx, d_dw_gate_up, d_dw_down, d_dtopk_w)
              : run_backward<float>(c, d_dy, d_w_gate_up, d_w_down, d_dx, d_dw_gate_up, d_dw_down, d_dtopk_w);
+}
+
+size_t moe_microbench_workspace_bytes(int M) {
+  const size_t n_tiles = M > 0 ? (size_t)(M + kMbTileRows - 1) / kMbTileRows : 0;
+  return align_up(n_tiles * 4) + align_up((kMbRingBase + 2 * n_tiles + 2 * kNumXcd) * 4);
+}
+
+int moe_microbench_swiglu_add(int M, int N, const void* d_x, const void* d_y, void* d_s, void* d_out, int mode,
+                              void* d_workspace, size_t workspace_bytes, void* stream) {
+  if (M < 0 || N <= 0 || N % 8 || mode < 0 || mode > 3) return MOE_ERR_INVALID_ARG;
+  if (M == 0) return MOE_OK;
+  const void* ptrs[] = {d_x, d_y, d_s, d_out, d_workspace};
+  for (const void* q : ptrs)
+    if (!q || !aligned16(q)) return MOE_ERR_INVALID_ARG;
+  if (workspace_bytes < moe_microbench_workspace_bytes(M)) return MOE_ERR_WORKSPACE_TOO_SMALL;
+  MicrobenchParams p;
+  p.X = static_cast<const __bf16*>(d_x); p.Y = static_cast<const __bf16*>(d_y);
+  p.S = static_cast<__bf16*>(d_s); p.Out = static_cast<__bf16*>(d_out);
+  p.M = M; p.N = N;
+  p.n_tiles = (M + kMbTileRows - 1) / kMbTileRows;
+  p.events = static_cast<uint32_t*>(d_workspace);
+  p.queue = reinterpret_cast<uint32_t*>(static_cast<char*>(d_workspace) + align_up((size_t)p.n_tiles * 4));
+  p.spin_limit = g_spin_limit;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int workers = device_cus() * 4;   // four 256-thread workgroups per CU; a multiple of 8
+  const int grid = p.n_tiles < workers ? (p.n_tiles + 7) / 8 * 8 : workers;
+  if (mode == 0) {
+    hipLaunchKernelGGL(mb_swiglu_kernel, dim3(grid), dim3(256), 0, st, p);
+    hipLaunchKernelGGL(mb_add_kernel, dim3(grid), dim3(256), 0, st, p);
+  } else {
+    hipLaunchKernelGGL(mb_clear_kernel, dim3((p.n_tiles + 255) / 256), dim3(256), 0, st, p, mode == 3 ? kNumXcd : 1);
+    if (mode == 1) hipLaunchKernelGGL(mb_static_kernel, dim3(grid), dim3(256), 0, st, p);
+    else if (mode == 2) hipLaunchKernelGGL(mb_dynamic_kernel<false>, dim3(grid), dim3(256), 0, st, p);
+    else hipLaunchKernelGGL(mb_dynamic_kernel<true>, dim3(grid), dim3(256), 0, st, p);
+  }
+  return launch_status();
+}
+
+int moe_microbench_last_status(int M, const void* d_workspace) {
+  if (M <= 0 || !d_workspace) return MOE_ERR_INVALID_ARG;
+  const size_t n_tiles = (size_t)(M + kMbTileRows - 1) / kMbTileRows;
+  uint32_t word = 0;
+  if (hipMemcpy(&word, static_cast<const char*>(d_workspace) + align_up(n_tiles * 4) + 8, 4, hipMemcpyDeviceToHost) !=
+      hipSuccess)
+    return MOE_ERR_LAUNCH;
+  return word ? MOE_ERR_SCHED_TIMEOUT : MOE_OK;
 }
 
 int moe_ffn_debug_set_spin_limit(uint32_t polls) {

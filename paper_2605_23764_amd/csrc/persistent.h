@@ -43,10 +43,10 @@
 #include "gemm_f32.h"
 #include "permute_combine.h"
 #include "route.h"
+#include "wave_sync.h"
 
 namespace moe {
 
-constexpr int kNumXcd = 8;
 constexpr int kPermRows = 32;            // rows per PERMUTE task
 constexpr int kCombineTokens = 32;       // tokens per COMBINE task
 constexpr int kRankChunksPerTask = 4;    // one chunk per wave
@@ -108,34 +108,6 @@ struct TraceRec { int32_t wg, kind, a, b; long long t_fetch, t_start, t_end; };
 #define MOE_TRACE_START
 #define MOE_TRACE_END(sp_)
 #endif
-
-// The scheduler's control flow is kept wave-uniform on purpose.  A lane-divergent
-// `if (threadIdx.x == 0) { atomic }` at the head of a loop that also contains
-// barriers was restructured by the compiler into nested loops in which lanes 1..63
-// never left the inner (barrier + ticket read) loop, so no new ticket was ever drawn
-// and the kernel spun forever.  Here wave 0 acts as a whole: single-lane atomics are
-// issued with the execution mask narrowed inside one assembly statement, polls are
-// uniform loads, and every branch below is scalar.
-
-// One atomic add of `inc` at p, issued by lane 0 only; returns the old value to all lanes.
-__device__ __forceinline__ uint32_t wave_atomic_add(uint32_t* p, uint32_t inc) {
-  uint32_t old;
-  uint64_t saved_exec;
-  asm volatile(
-      "s_mov_b64 %1, exec\n\t"
-      "s_mov_b64 exec, 1\n\t"
-      "global_atomic_add %0, %2, %3, %4 sc0\n\t"
-      "s_waitcnt vmcnt(0)\n\t"
-      "s_mov_b64 exec, %1"
-      : "=&v"(old), "=&s"(saved_exec)
-      : "v"(0u), "v"(inc), "s"(p)
-      : "memory");
-  return (uint32_t)__builtin_amdgcn_readfirstlane((int)old);
-}
-
-__device__ __forceinline__ uint32_t ev_load(const uint32_t* p) {
-  return (uint32_t)__builtin_amdgcn_readfirstlane((int)__hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-}
 
 // One ticket of queue `q` for the whole workgroup (wave 0 draws, LDS broadcasts).
 __device__ __forceinline__ int sched_fetch(uint32_t* qhead, int q, volatile int* s_box, int wave) {

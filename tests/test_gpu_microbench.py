@@ -1,0 +1,69 @@
+"""GPU parity of the SwiGLU + Add microbenchmark (paper Section 6) in its four launch
+modes, through the C ABI: each against the oracle, and the modes against each other bit
+for bit (they share the per-tile arithmetic)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2605_23764_amd as moe
+from oracle import swiglu_add
+from workloads import make_microbench_inputs
+from gpu_common import rel_err, to_f64
+
+pytestmark = pytest.mark.gpu
+MODES = (moe.MB_SERIAL, moe.MB_STATIC, moe.MB_DYNAMIC, moe.MB_DYNAMIC_XCD)
+
+
+def run(M, N, inp, mode, ws=None):
+    x = torch.from_numpy(inp["x"]).cuda().to(torch.bfloat16)
+    y = torch.from_numpy(inp["y"]).cuda().to(torch.bfloat16)
+    s = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    out = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    if ws is None:
+        ws = torch.empty(moe.moe_microbench_workspace_bytes(M), dtype=torch.uint8, device="cuda")
+    moe.moe_microbench_swiglu_add(M, N, x, y, s, out, mode, ws)
+    torch.cuda.synchronize()
+    assert moe.moe_microbench_last_status(M, ws) == 0 or mode == moe.MB_SERIAL
+    return s, out
+
+
+# one tile, a ragged last tile, fewer tiles than workers, several rounds per worker with a ragged tail
+@pytest.mark.parametrize("M,N", [(1, 8), (8, 64), (13, 2048), (1000, 2048), (8192 + 5, 2048), (20000 + 3, 512)])
+def test_modes_match_oracle_and_each_other(M, N):
+    inp = make_microbench_inputs(M, N, seed=M + N)
+    ref = swiglu_add(inp["x"], inp["y"])
+    got = {}
+    for mode in MODES:
+        print(f"microbench M={M} N={N} mode={mode}", flush=True)
+        s, out = run(M, N, inp, mode)
+        assert rel_err(to_f64(s), ref["S"]) <= 1e-2
+        assert rel_err(to_f64(out), ref["out"]) <= 1e-2
+        got[mode] = (s, out)
+    for mode in MODES[1:]:
+        assert torch.equal(got[mode][0], got[0][0]) and torch.equal(got[mode][1], got[0][1])
+
+
+def test_full_size_sampled_rows():
+    """M = 32K at the paper's widths: sampled rows against the oracle, all modes bit-identical."""
+    M, N = 32768, 2048
+    inp = make_microbench_inputs(M, N)
+    rows = np.random.default_rng(0).choice(M, 512, replace=False)
+    ref = swiglu_add(inp["x"][rows], inp["y"][rows])
+    outs = []
+    ws = torch.empty(moe.moe_microbench_workspace_bytes(M), dtype=torch.uint8, device="cuda")
+    for mode in MODES:
+        print(f"microbench full size mode={mode}", flush=True)
+        s, out = run(M, N, inp, mode, ws)     # the workspace is reused: each call clears what it needs
+        assert rel_err(to_f64(out[torch.from_numpy(rows).cuda()]), ref["out"]) <= 1e-2
+        outs.append(out)
+    assert all(torch.equal(o, outs[0]) for o in outs[1:])
+
+
+def test_argument_errors_and_empty():
+    ws = torch.empty(moe.moe_microbench_workspace_bytes(64), dtype=torch.uint8, device="cuda")
+    t = torch.zeros(64, 128, dtype=torch.bfloat16, device="cuda")
+    moe.moe_microbench_swiglu_add(0, 64, t, t, t, t, moe.MB_STATIC, ws)          # M = 0: nothing to do
+    for M, N, mode, w, status in ((64, 60, 0, ws, -1), (64, 64, 4, ws, -1), (64, 64, 1, ws[:16], -3)):
+        with pytest.raises(moe.MoeError) as ei:
+            moe.moe_microbench_swiglu_add(M, N, t, t, t, t, mode, w)
+        assert ei.value.status == status

@@ -16,5 +16,6 @@ from .configs import (  # noqa: F401
     bf16_round,
     expert_bias,
     make_inputs,
+    make_microbench_inputs,
     realised_local_counts,
 )

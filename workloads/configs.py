@@ -61,7 +61,7 @@ def bf16_round(a: np.ndarray) -> np.ndarray:
     return r.view(np.float32)
 
 
-_TENSOR_IDS = {"x": 0, "logits": 1, "w_gate_up": 2, "w_down": 3, "dy": 4, "ranks": 5}
+_TENSOR_IDS = {"x": 0, "logits": 1, "w_gate_up": 2, "w_down": 3, "dy": 4, "ranks": 5, "mb_x": 6, "mb_y": 7}
 
 
 def _normal(seed: int, tensor: str, shape, scale: float, bf16: bool) -> np.ndarray:
@@ -145,3 +145,9 @@ def realised_local_counts(cfg: MoeConfig, logits: np.ndarray) -> np.ndarray:
     top = np.argpartition(-logits, cfg.k - 1, axis=1)[:, : cfg.k]
     cnt = np.bincount(top.reshape(-1), minlength=cfg.E)
     return cnt[cfg.expert_base : cfg.expert_base + cfg.E_local]
+
+
+def make_microbench_inputs(M: int, N: int = 2048, seed: int = 2006) -> dict:
+    """Inputs of the SwiGLU + Add operator pair (the paper's Section 6): X [M, 2N] and
+    Y [M, N], standard normal, stored as bf16-representable fp32."""
+    return dict(x=_normal(seed, "mb_x", (M, 2 * N), 1.0, True), y=_normal(seed, "mb_y", (M, N), 1.0, True))
