@@ -201,13 +201,14 @@ int moe_combine(const MoeShape* shape, const MoeSaved* saved, void* d_out,
  * tile close behind its SwiGLU tile, event counters; mode 2: one launch, the same tiles pulled from a
  * shared ready queue that finished SwiGLU tiles feed; mode 3: as mode 2 with one ready queue per XCD (a
  * tile's two tasks stay on the XCD that owns the tile).  Results are bit-identical in all modes.
+ * tile_rows (1..64) is the number of rows of one tile task (modes 1-3; mode 0 uses it as its loop granule).
  * N must be a multiple of 8, all pointers device and 16-byte aligned; d_workspace >=
  * moe_microbench_workspace_bytes(M).  A bounded wait that expires is reported by the status word:
  * moe_microbench_last_status() (host-blocking 4-byte copy) returns MOE_OK or MOE_ERR_SCHED_TIMEOUT. */
 size_t moe_microbench_workspace_bytes(int M);
 int moe_microbench_swiglu_add(int M, int N, const void* d_x, const void* d_y, void* d_s, void* d_out, int mode,
-                              void* d_workspace, size_t workspace_bytes, void* stream);
-int moe_microbench_last_status(int M, const void* d_workspace);
+                              int tile_rows, void* d_workspace, size_t workspace_bytes, void* stream);
+int moe_microbench_last_status(const void* d_workspace);
 
 #ifdef __cplusplus
 }

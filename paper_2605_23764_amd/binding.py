@@ -225,12 +225,13 @@ def moe_microbench_workspace_bytes(M: int) -> int:
     return int(load_library().moe_microbench_workspace_bytes(int(M)))
 
 
-def moe_microbench_swiglu_add(M, N, x, y, s, out, mode, workspace, stream=None) -> None:
+def moe_microbench_swiglu_add(M, N, x, y, s, out, mode, tile_rows, workspace, stream=None) -> None:
     wp, wb = _ws(workspace)
     _check(load_library().moe_microbench_swiglu_add(ctypes.c_int(M), ctypes.c_int(N), _ptr(x), _ptr(y), _ptr(s),
-                                                    _ptr(out), ctypes.c_int(mode), wp, wb, _stream(stream)),
+                                                    _ptr(out), ctypes.c_int(mode), ctypes.c_int(tile_rows), wp, wb,
+                                                    _stream(stream)),
            "moe_microbench_swiglu_add")
 
 
-def moe_microbench_last_status(M, workspace) -> int:
-    return load_library().moe_microbench_last_status(ctypes.c_int(M), _ptr(workspace))
+def moe_microbench_last_status(workspace) -> int:
+    return load_library().moe_microbench_last_status(_ptr(workspace))

@@ -20,15 +20,15 @@
 
 namespace moe {
 
-constexpr int kMbTileRows = 8;     // rows per tile task
+constexpr int kMbMaxTileRows = 64;  // rows per tile task: 1 .. 64, chosen per call
 constexpr int kMbRingBase = 16 * kNumXcd;
 
 // Queue x of n_q (1: one device queue; 8: one per XCD, tile t belongs to queue t % 8).
 struct MbQueue { int n_local, ring; };   // tiles owned, first ring word
-__device__ __forceinline__ MbQueue mb_queue(int n_tiles, int n_q, int x) {
+__device__ __forceinline__ MbQueue mb_queue(int ring_base, int n_tiles, int n_q, int x) {
   MbQueue q;
   q.n_local = n_tiles > x ? (n_tiles - x + n_q - 1) / n_q : 0;
-  q.ring = kMbRingBase + x * 2 * ((n_tiles + n_q - 1) / n_q);
+  q.ring = ring_base + x * 2 * ((n_tiles + n_q - 1) / n_q);
   return q;
 }
 
@@ -39,9 +39,10 @@ struct MicrobenchParams {
   __bf16* Out;         // [M, N]
   int M, N;            // N multiple of 8
   uint32_t* events;    // [n_tiles] static mode: SwiGLU tile done
-  uint32_t* queue;     // [16x] head and [16x + 1] tail of queue x (8 headers), [2] status, rings from word kMbRingBase:
+  uint32_t* queue;     // [16x] head and [16x + 1] tail of queue x (8 headers), [2] status; rings from word ring_base:
                        // entries are local task id + 1, 0 = not yet published
-  int n_tiles;
+  int n_tiles, tile_rows;
+  int ring_base;       // first ring word, relative to queue
   uint32_t spin_limit;
 };
 
@@ -80,25 +81,25 @@ __device__ __forceinline__ void mb_add_rows(const MicrobenchParams& p, int r0, i
 
 __global__ __launch_bounds__(256) void mb_swiglu_kernel(MicrobenchParams p) {
   for (int t = blockIdx.x; t < p.n_tiles; t += gridDim.x)
-    mb_swiglu_rows(p, t * kMbTileRows, min(p.M, (t + 1) * kMbTileRows));
+    mb_swiglu_rows(p, t * p.tile_rows, min(p.M, (t + 1) * p.tile_rows));
 }
 __global__ __launch_bounds__(256) void mb_add_kernel(MicrobenchParams p) {
   for (int t = blockIdx.x; t < p.n_tiles; t += gridDim.x)
-    mb_add_rows(p, t * kMbTileRows, min(p.M, (t + 1) * kMbTileRows));
+    mb_add_rows(p, t * p.tile_rows, min(p.M, (t + 1) * p.tile_rows));
 }
 
 __global__ void mb_clear_kernel(MicrobenchParams p, int n_q) {
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < p.n_tiles; i += gridDim.x * blockDim.x) {
     p.events[i] = 0;
     const int x = i % n_q, j = i / n_q;
-    const MbQueue q = mb_queue(p.n_tiles, n_q, x);
+    const MbQueue q = mb_queue(p.ring_base, p.n_tiles, n_q, x);
     p.queue[q.ring + j] = (uint32_t)j + 1;          // every SwiGLU task is ready from the start
     p.queue[q.ring + q.n_local + j] = 0;            // Add tasks arrive later
   }
   if (blockIdx.x == 0 && threadIdx.x < kNumXcd) {
     const int x = threadIdx.x;
     p.queue[16 * x] = 0;
-    p.queue[16 * x + 1] = x < n_q ? (uint32_t)mb_queue(p.n_tiles, n_q, x).n_local : 0u;
+    p.queue[16 * x + 1] = x < n_q ? (uint32_t)mb_queue(p.ring_base, p.n_tiles, n_q, x).n_local : 0u;
     if (x == 0) p.queue[2] = 0;
   }
 }
@@ -122,7 +123,7 @@ __global__ __launch_bounds__(256) void mb_static_kernel(MicrobenchParams p) {
   for (int base = 0; base < p.n_tiles; base += W) {
     const int ts = base + w;
     if (ts < p.n_tiles) {
-      mb_swiglu_rows(p, ts * kMbTileRows, min(p.M, (ts + 1) * kMbTileRows));
+      mb_swiglu_rows(p, ts * p.tile_rows, min(p.M, (ts + 1) * p.tile_rows));
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
       __syncthreads();
       if (wave == 0) wave_atomic_add(&p.events[ts], 1u);
@@ -144,7 +145,7 @@ __global__ __launch_bounds__(256) void mb_static_kernel(MicrobenchParams p) {
       const int ok = __builtin_amdgcn_readfirstlane(s_box[0]);
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
       __syncthreads();
-      if (ok) mb_add_rows(p, ta * kMbTileRows, min(p.M, (ta + 1) * kMbTileRows));
+      if (ok) mb_add_rows(p, ta * p.tile_rows, min(p.M, (ta + 1) * p.tile_rows));
     }
   }
 }
@@ -159,7 +160,7 @@ __global__ __launch_bounds__(256) void mb_dynamic_kernel(MicrobenchParams p) {
   __shared__ int s_box[2];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int n_q = PER_XCD ? kNumXcd : 1, x = PER_XCD ? (int)(blockIdx.x % kNumXcd) : 0;
-  const MbQueue q = mb_queue(p.n_tiles, n_q, x);
+  const MbQueue q = mb_queue(p.ring_base, p.n_tiles, n_q, x);
   const uint32_t total = 2u * (uint32_t)q.n_local;
   uint32_t* head = &p.queue[16 * x];
   for (;;) {
@@ -186,7 +187,7 @@ __global__ __launch_bounds__(256) void mb_dynamic_kernel(MicrobenchParams p) {
       else __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
       if (task < q.n_local) {
         const int t = task * n_q + x;
-        mb_swiglu_rows(p, t * kMbTileRows, min(p.M, (t + 1) * kMbTileRows));
+        mb_swiglu_rows(p, t * p.tile_rows, min(p.M, (t + 1) * p.tile_rows));
         if (PER_XCD) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         else __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
         __syncthreads();
@@ -198,7 +199,7 @@ __global__ __launch_bounds__(256) void mb_dynamic_kernel(MicrobenchParams p) {
         }
       } else {
         const int t = (task - q.n_local) * n_q + x;
-        mb_add_rows(p, t * kMbTileRows, min(p.M, (t + 1) * kMbTileRows));
+        mb_add_rows(p, t * p.tile_rows, min(p.M, (t + 1) * p.tile_rows));
       }
     }
   }

@@ -545,14 +545,16 @@ int moe_ffn_backward(const MoeShape* shape, const void* d_dy, const void* d_x, c
              : run_backward<float>(c, d_dy, d_w_gate_up, d_w_down, d_dx, d_dw_gate_up, d_dw_down, d_dtopk_w);
 }
 
+// workspace: queue headers and status word | event counters [n_tiles] | rings; sized for one-row tiles
 size_t moe_microbench_workspace_bytes(int M) {
-  const size_t n_tiles = M > 0 ? (size_t)(M + kMbTileRows - 1) / kMbTileRows : 0;
-  return align_up(n_tiles * 4) + align_up((kMbRingBase + 2 * n_tiles + 2 * kNumXcd) * 4);
+  const size_t n = M > 0 ? (size_t)M : 0;
+  return align_up(kMbRingBase * 4) + align_up(n * 4) + align_up((2 * n + 2 * kNumXcd) * 4);
 }
 
 int moe_microbench_swiglu_add(int M, int N, const void* d_x, const void* d_y, void* d_s, void* d_out, int mode,
-                              void* d_workspace, size_t workspace_bytes, void* stream) {
-  if (M < 0 || N <= 0 || N % 8 || mode < 0 || mode > 3) return MOE_ERR_INVALID_ARG;
+                              int tile_rows, void* d_workspace, size_t workspace_bytes, void* stream) {
+  if (M < 0 || N <= 0 || N % 8 || mode < 0 || mode > 3 || tile_rows < 1 || tile_rows > kMbMaxTileRows)
+    return MOE_ERR_INVALID_ARG;
   if (M == 0) return MOE_OK;
   const void* ptrs[] = {d_x, d_y, d_s, d_out, d_workspace};
   for (const void* q : ptrs)
@@ -562,9 +564,12 @@ int moe_microbench_swiglu_add(int M, int N, const void* d_x, const void* d_y, vo
   p.X = static_cast<const __bf16*>(d_x); p.Y = static_cast<const __bf16*>(d_y);
   p.S = static_cast<__bf16*>(d_s); p.Out = static_cast<__bf16*>(d_out);
   p.M = M; p.N = N;
-  p.n_tiles = (M + kMbTileRows - 1) / kMbTileRows;
-  p.events = static_cast<uint32_t*>(d_workspace);
-  p.queue = reinterpret_cast<uint32_t*>(static_cast<char*>(d_workspace) + align_up((size_t)p.n_tiles * 4));
+  p.tile_rows = tile_rows;
+  p.n_tiles = (M + tile_rows - 1) / tile_rows;
+  // rings are addressed relative to the header block, so they start behind the event counters
+  p.queue = static_cast<uint32_t*>(d_workspace);
+  p.events = reinterpret_cast<uint32_t*>(static_cast<char*>(d_workspace) + align_up(kMbRingBase * 4));
+  p.ring_base = (int)((align_up(kMbRingBase * 4) + align_up((size_t)M * 4)) / 4);
   p.spin_limit = g_spin_limit;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int workers = device_cus() * 4;   // four 256-thread workgroups per CU; a multiple of 8
@@ -573,7 +578,8 @@ int moe_microbench_swiglu_add(int M, int N, const void* d_x, const void* d_y, vo
     hipLaunchKernelGGL(mb_swiglu_kernel, dim3(grid), dim3(256), 0, st, p);
     hipLaunchKernelGGL(mb_add_kernel, dim3(grid), dim3(256), 0, st, p);
   } else {
-    hipLaunchKernelGGL(mb_clear_kernel, dim3((p.n_tiles + 255) / 256), dim3(256), 0, st, p, mode == 3 ? kNumXcd : 1);
+    hipLaunchKernelGGL(mb_clear_kernel, dim3(std::min((p.n_tiles + 255) / 256, 1024)), dim3(256), 0, st, p,
+                       mode == 3 ? kNumXcd : 1);
     if (mode == 1) hipLaunchKernelGGL(mb_static_kernel, dim3(grid), dim3(256), 0, st, p);
     else if (mode == 2) hipLaunchKernelGGL(mb_dynamic_kernel<false>, dim3(grid), dim3(256), 0, st, p);
     else hipLaunchKernelGGL(mb_dynamic_kernel<true>, dim3(grid), dim3(256), 0, st, p);
@@ -581,12 +587,10 @@ int moe_microbench_swiglu_add(int M, int N, const void* d_x, const void* d_y, vo
   return launch_status();
 }
 
-int moe_microbench_last_status(int M, const void* d_workspace) {
-  if (M <= 0 || !d_workspace) return MOE_ERR_INVALID_ARG;
-  const size_t n_tiles = (size_t)(M + kMbTileRows - 1) / kMbTileRows;
+int moe_microbench_last_status(const void* d_workspace) {
+  if (!d_workspace) return MOE_ERR_INVALID_ARG;
   uint32_t word = 0;
-  if (hipMemcpy(&word, static_cast<const char*>(d_workspace) + align_up(n_tiles * 4) + 8, 4, hipMemcpyDeviceToHost) !=
-      hipSuccess)
+  if (hipMemcpy(&word, static_cast<const char*>(d_workspace) + 8, 4, hipMemcpyDeviceToHost) != hipSuccess)
     return MOE_ERR_LAUNCH;
   return word ? MOE_ERR_SCHED_TIMEOUT : MOE_OK;
 }

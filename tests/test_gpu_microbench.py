@@ -14,28 +14,29 @@ pytestmark = pytest.mark.gpu
 MODES = (moe.MB_SERIAL, moe.MB_STATIC, moe.MB_DYNAMIC, moe.MB_DYNAMIC_XCD)
 
 
-def run(M, N, inp, mode, ws=None):
+def run(M, N, inp, mode, tile_rows=8, ws=None):
     x = torch.from_numpy(inp["x"]).cuda().to(torch.bfloat16)
     y = torch.from_numpy(inp["y"]).cuda().to(torch.bfloat16)
     s = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
     out = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
     if ws is None:
         ws = torch.empty(moe.moe_microbench_workspace_bytes(M), dtype=torch.uint8, device="cuda")
-    moe.moe_microbench_swiglu_add(M, N, x, y, s, out, mode, ws)
+    moe.moe_microbench_swiglu_add(M, N, x, y, s, out, mode, tile_rows, ws)
     torch.cuda.synchronize()
-    assert moe.moe_microbench_last_status(M, ws) == 0 or mode == moe.MB_SERIAL
+    assert mode == moe.MB_SERIAL or moe.moe_microbench_last_status(ws) == 0
     return s, out
 
 
 # one tile, a ragged last tile, fewer tiles than workers, several rounds per worker with a ragged tail
-@pytest.mark.parametrize("M,N", [(1, 8), (8, 64), (13, 2048), (1000, 2048), (8192 + 5, 2048), (20000 + 3, 512)])
-def test_modes_match_oracle_and_each_other(M, N):
+@pytest.mark.parametrize("M,N,tile_rows", [(1, 8, 8), (8, 64, 1), (13, 2048, 8), (1000, 2048, 3), (8192 + 5, 2048, 8),
+                                           (20000 + 3, 512, 2), (5000, 1024, 64)])
+def test_modes_match_oracle_and_each_other(M, N, tile_rows):
     inp = make_microbench_inputs(M, N, seed=M + N)
     ref = swiglu_add(inp["x"], inp["y"])
     got = {}
     for mode in MODES:
-        print(f"microbench M={M} N={N} mode={mode}", flush=True)
-        s, out = run(M, N, inp, mode)
+        print(f"microbench M={M} N={N} tile_rows={tile_rows} mode={mode}", flush=True)
+        s, out = run(M, N, inp, mode, tile_rows)
         assert rel_err(to_f64(s), ref["S"]) <= 1e-2
         assert rel_err(to_f64(out), ref["out"]) <= 1e-2
         got[mode] = (s, out)
@@ -51,9 +52,9 @@ def test_full_size_sampled_rows():
     ref = swiglu_add(inp["x"][rows], inp["y"][rows])
     outs = []
     ws = torch.empty(moe.moe_microbench_workspace_bytes(M), dtype=torch.uint8, device="cuda")
-    for mode in MODES:
-        print(f"microbench full size mode={mode}", flush=True)
-        s, out = run(M, N, inp, mode, ws)     # the workspace is reused: each call clears what it needs
+    for mode, tile_rows in zip(MODES, (8, 2, 8, 1)):
+        print(f"microbench full size mode={mode} tile_rows={tile_rows}", flush=True)
+        s, out = run(M, N, inp, mode, tile_rows, ws)     # the workspace is reused: each call clears what it needs
         assert rel_err(to_f64(out[torch.from_numpy(rows).cuda()]), ref["out"]) <= 1e-2
         outs.append(out)
     assert all(torch.equal(o, outs[0]) for o in outs[1:])
@@ -62,8 +63,9 @@ def test_full_size_sampled_rows():
 def test_argument_errors_and_empty():
     ws = torch.empty(moe.moe_microbench_workspace_bytes(64), dtype=torch.uint8, device="cuda")
     t = torch.zeros(64, 128, dtype=torch.bfloat16, device="cuda")
-    moe.moe_microbench_swiglu_add(0, 64, t, t, t, t, moe.MB_STATIC, ws)          # M = 0: nothing to do
-    for M, N, mode, w, status in ((64, 60, 0, ws, -1), (64, 64, 4, ws, -1), (64, 64, 1, ws[:16], -3)):
+    moe.moe_microbench_swiglu_add(0, 64, t, t, t, t, moe.MB_STATIC, 8, ws)          # M = 0: nothing to do
+    for M, N, mode, rows, w, status in ((64, 60, 0, 8, ws, -1), (64, 64, 4, 8, ws, -1), (64, 64, 1, 0, ws, -1),
+                                        (64, 64, 1, 65, ws, -1), (64, 64, 1, 8, ws[:16], -3)):
         with pytest.raises(moe.MoeError) as ei:
-            moe.moe_microbench_swiglu_add(M, N, t, t, t, t, mode, w)
+            moe.moe_microbench_swiglu_add(M, N, t, t, t, t, mode, rows, w)
         assert ei.value.status == status
