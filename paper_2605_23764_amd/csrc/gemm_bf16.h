@@ -40,13 +40,10 @@ namespace moe {
 // weights [K, N] n-contiguous.  The backward graph (Section 2.2, Figure 2b) adds
 //   NT  act_grad / gate_grad: C[rows, N] = A[rows, K] * W_e[N, K]^T -- both operands
 //       k-contiguous, so the weight tile is staged like an activation tile (8 rows x
-//       64 k per line, XOR swizzle, plain 16-byte operand reads);
-//   TN  w2_grad / w1_grad: C_e[M, N] = A_e[rows_e, M]^T * B_e[rows_e, N] -- the
-//       reduction runs over the expert's rows, both operands are k-rows of
-//       contiguous m / n, so both are staged like a weight tile and fetched with
-//       transpose reads.  rows_e is ragged: k-rows past the segment are clamped at
-//       load time and zeroed in LDS before the last K step.
-enum GemmLayout { kLayNN = 0, kLayNT = 1, kLayTN = 2 };
+//       64 k per line, XOR swizzle, plain 16-byte operand reads).
+// The weight gradients (reduction over the expert's rows) have kernels of their own
+// (wgrad_panel.h, wgrad_bf16.h); they share GemmParams and the epilogue staging.
+enum GemmLayout { kLayNN = 0, kLayNT = 1 };
 enum GemmEpilogue { kEpiStore = 0, kEpiSwiglu = 1, kEpiSwigluGrad = 2 };
 
 constexpr int kBM = 256;            // tile row capacity (one M tile of the tile map)
@@ -73,14 +70,14 @@ struct GemmParams {
   __bf16* C2;         // SwiGLU only: optional pre-activation [rows, 2N] (gate|up), else null
   const __bf16* G;    // SwiGLU-grad only: pre-activations saved by the forward [rows, 2N]
   long strideB;       // elements between consecutive experts' weights (NN, NT)
-  long strideC;       // TN: elements between consecutive experts' outputs
-  int K, N;           // N = output columns (SwiGLU: I, weights have 2N columns); TN: K unused (rows of the expert)
-  int M;              // TN: output rows
+  long strideC;       // weight gradients: elements between consecutive experts' outputs
+  int K, N;           // N = output columns (SwiGLU: I, weights have 2N columns); weight gradients: K unused (rows of the expert)
+  int M;              // weight gradients: output rows
   int lda, ldb, ldc;
   int n_ntiles;       // ceil(N / 256) (SwiGLU: ceil(N / 128))
-  int n_mtiles;       // TN: ceil(M / 256)
-  int E_local;        // TN
-  const int32_t* offsets;   // TN: [E_local + 1] segment boundaries
+  int E_local;        // weight gradients
+  int k_lo;           // weight gradients, general kernel: experts with fewer rows are left to the register-stationary kernel
+  const int32_t* offsets;   // weight gradients: [E_local + 1] segment boundaries
   TileMap tiles;      // NN, NT
 };
 
@@ -149,30 +146,26 @@ constexpr int kTallRows = TileShape<true>::kRows;
 
 // Per-tile addressing state shared by the load and compute phases.
 struct GemmTileCtx {
-  const char* a_base;          // uniform: first row of the tile (TN: of the expert's segment), byte address
-  const char* b_base;          // uniform: expert's weights (TN: first row of the segment), byte address
-  uint32_t a_off[12];          // NN/NT: per lane byte offset of the chunk fetched for the i-th A line; TN: [0..1] column halves
-  uint32_t b_off[8];           // NN/TN: per lane byte offset inside a 4-row line per column half; NT: like a_off
-  uint32_t a_rd[4];            // operand read offset inside an A stage (NN/NT: per k slice; TN: per 32-row block)
-  uint32_t b_rd[4];            // operand read offset inside a B stage (NN/TN: per 32-column block; NT: per k slice)
+  const char* a_base;          // uniform: first row of the tile, byte address
+  const char* b_base;          // uniform: expert's weights, byte address
+  uint32_t a_off[12];          // per lane byte offset of the chunk fetched for the i-th A line
+  uint32_t b_off[8];           // NN: per lane byte offset inside a 4-row line per column half; NT: like a_off
+  uint32_t a_rd[4];            // operand read offset inside an A stage, per k slice
+  uint32_t b_rd[4];            // operand read offset inside a B stage (NN: per 32-column block; NT: per k slice)
   uint32_t lds0;               // LDS byte address of the staging area
   int nA;                      // A lines per wave per step
   int lda_bytes, ldb_bytes;
   int wave;
-  int kk;                      // TN: k-row of this lane inside a 4-row line (lane / 16)
-  int k_rows;                  // TN: rows of the expert's segment (the reduction length)
 };
 
 // The 16 wave-wide loads issued between two barriers: the A lines of one K step
-// (indices 0..kALoads-1, NN/NT: only nA of them real) followed by the B lines of a
+// (indices 0..kALoads-1, only nA of them real) followed by the B lines of a
 // later K step.  A loads always precede B loads, which the vmcnt waits rely on.
 struct GemmLoadGroup {
   const char* a_k;   // uniform source of the A lines, nullptr = none
   const char* b_k;   // uniform source of the B lines, nullptr = none
   uint32_t a_st;     // uniform LDS address of this wave's first A line
   uint32_t b_st;     // uniform LDS address of this wave's first B line
-  int a_row0;        // TN: first k-row this wave loads for A / B
-  int b_row0;
 };
 
 template <int LAY, bool TALL>
@@ -180,19 +173,10 @@ __device__ __forceinline__ GemmLoadGroup gemm_load_group(const GemmTileCtx& t, i
                                                          int b_stage) {
   typedef TileShape<TALL> S;
   GemmLoadGroup g;
-  g.a_row0 = 0; g.b_row0 = 0;
-  if (LAY == kLayTN) {
-    g.a_k = a_step >= 0 ? t.a_base : nullptr;
-    g.b_k = b_step >= 0 ? t.b_base : nullptr;
-    g.a_row0 = __builtin_amdgcn_readfirstlane(a_step * kBK + t.wave * 16);
-    g.b_row0 = __builtin_amdgcn_readfirstlane(b_step * kBK + t.wave * 16);
-    g.a_st = uniform_u32(t.lds0 + a_stage * S::kAStage + t.wave * 8 * kLine);
-  } else {
-    g.a_k = a_step >= 0 ? uniform_ptr(t.a_base + (size_t)a_step * (kBK * 2)) : nullptr;
-    g.a_st = uniform_u32(t.lds0 + a_stage * S::kAStage + t.wave * kLine);
-    if (LAY == kLayNT) g.b_k = b_step >= 0 ? uniform_ptr(t.b_base + (size_t)b_step * (kBK * 2)) : nullptr;
-    else g.b_k = b_step >= 0 ? uniform_ptr(t.b_base + (size_t)(b_step * kBK + t.wave * 16) * t.ldb_bytes) : nullptr;
-  }
+  g.a_k = a_step >= 0 ? uniform_ptr(t.a_base + (size_t)a_step * (kBK * 2)) : nullptr;
+  g.a_st = uniform_u32(t.lds0 + a_stage * S::kAStage + t.wave * kLine);
+  if (LAY == kLayNT) g.b_k = b_step >= 0 ? uniform_ptr(t.b_base + (size_t)b_step * (kBK * 2)) : nullptr;
+  else g.b_k = b_step >= 0 ? uniform_ptr(t.b_base + (size_t)(b_step * kBK + t.wave * 16) * t.ldb_bytes) : nullptr;
   if (LAY == kLayNT) g.b_st = uniform_u32(t.lds0 + S::kBReg + b_stage * S::kBStage + t.wave * kLine);
   else g.b_st = uniform_u32(t.lds0 + S::kBReg + b_stage * S::kBStage + t.wave * S::kBLoads * kLine);
   return g;
@@ -202,25 +186,15 @@ template <int LAY, bool TALL>
 __device__ __forceinline__ void gemm_issue_one(const GemmTileCtx& t, const GemmLoadGroup& g, int idx) {
   typedef TileShape<TALL> S;
   if (idx < S::kALoads) {
-    if (LAY == kLayTN) {
-      if (g.a_k != nullptr) {
-        const int krow = min(g.a_row0 + (idx >> 1) * 4 + t.kk, t.k_rows - 1);   // rows past the segment: re-read, zeroed later
-        lds_dma16(g.a_k, (uint32_t)(krow * t.lda_bytes) + t.a_off[idx & 1], g.a_st + idx * kLine);
-      }
-    } else {
-      if (g.a_k != nullptr && idx < t.nA) lds_dma16(g.a_k, t.a_off[idx], g.a_st + 4 * idx * kLine);
-    }
+    if (g.a_k != nullptr && idx < t.nA) lds_dma16(g.a_k, t.a_off[idx], g.a_st + 4 * idx * kLine);
   } else {
     const int i = idx - S::kALoads;
     if (g.b_k == nullptr) return;
     if (LAY == kLayNN) {
       // line i of this wave: k-row group i / halves, column half i % halves
       lds_dma16(g.b_k + (size_t)((i / S::kHalves) * 4) * t.ldb_bytes, t.b_off[i % S::kHalves], g.b_st + i * kLine);
-    } else if (LAY == kLayNT) {
-      lds_dma16(g.b_k, t.b_off[i], g.b_st + 4 * i * kLine);
     } else {
-      const int krow = min(g.b_row0 + (i >> 1) * 4 + t.kk, t.k_rows - 1);
-      lds_dma16(g.b_k, (uint32_t)(krow * t.ldb_bytes) + t.b_off[i & 1], g.b_st + i * kLine);
+      lds_dma16(g.b_k, t.b_off[i], g.b_st + 4 * i * kLine);
     }
   }
 }
@@ -230,16 +204,15 @@ __device__ __forceinline__ void gemm_issue_one(const GemmTileCtx& t, const GemmL
 // transpose reads per fragment, a k-contiguous one a single 16-byte read.
 template <int LAY, int NMT>
 struct GemmFrags {
-  s16x4 w[4][2];                       // NN, TN
+  s16x4 w[4][2];                       // NN
   bf16x8 wk[4];                        // NT
-  bf16x8 xf[NMT > 0 ? NMT : 1];        // NN, NT
-  s16x4 xt[NMT > 0 ? NMT : 1][2];      // TN
+  bf16x8 xf[NMT > 0 ? NMT : 1];
 };
 
 template <int LAY, int NMT>
 struct GemmSliceShape {
   static constexpr int n_wreads = LAY == kLayNT ? 4 : 8;
-  static constexpr int n_xreads = LAY == kLayTN ? 2 * NMT : NMT;
+  static constexpr int n_xreads = NMT;
   static constexpr int n_reads = n_wreads + n_xreads;
 };
 
@@ -256,10 +229,7 @@ __device__ __forceinline__ void gemm_read_one(GemmFrags<LAY, NMT>& f, int a, lds
           (lds_s16x4_ptr)(bs + t.b_rd[a >> 1] + ks * 4 * H * kLine + (a & 1) * H * kLine));
   } else {
     const int i = a - S::n_wreads;
-    if (LAY == kLayTN)
-      f.xt[i >> 1][i & 1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-          (lds_s16x4_ptr)(as + t.a_rd[i >> 1] + ks * 8 * kLine + (i & 1) * 2 * kLine));
-    else f.xf[i] = *(lds_bf16x8_cptr)(as + t.a_rd[ks] + i * 4 * kLine);
+    f.xf[i] = *(lds_bf16x8_cptr)(as + t.a_rd[ks] + i * 4 * kLine);
   }
 }
 
@@ -282,7 +252,7 @@ __device__ __forceinline__ void gemm_slice(f32x16 (&acc)[kMaxMT][4], const GemmF
 #pragma unroll
   for (int nt = 0; nt < 4; ++nt) wf[nt] = LAY == kLayNT ? cur.wk[nt] : join_tr(cur.w[nt][0], cur.w[nt][1]);
 #pragma unroll
-  for (int mt = 0; mt < NMT; ++mt) xf[mt] = LAY == kLayTN ? join_tr(cur.xt[mt][0], cur.xt[mt][1]) : cur.xf[mt];
+  for (int mt = 0; mt < NMT; ++mt) xf[mt] = cur.xf[mt];
 #pragma unroll
   for (int j = 0; j < n_mfma; ++j) {
     acc[j >> 2][j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j & 3], xf[j >> 2], acc[j >> 2][j & 3], 0, 0, 0);
@@ -306,24 +276,6 @@ __device__ __forceinline__ void gemm_read_frags(GemmFrags<LAY, NMT>& f, lds_cptr
   for (int a = 0; a < GemmSliceShape<LAY, NMT>::n_reads; ++a) gemm_read_one<LAY, NMT, TALL>(f, a, as, bs, ks, t);
 }
 
-// TN only: zero the k-rows >= k_valid of one A stage and one B stage (both hold
-// 64 k-rows x 256 contiguous elements as lines of 4 k-rows x 128), so that rows
-// past the expert's segment contribute nothing.  Whole workgroup; the caller
-// brackets it with barriers.
-__device__ __forceinline__ void gemm_zero_k_tail(char* smem, int a_stage, int b_stage, int k_valid) {
-  typedef __attribute__((address_space(3))) u32x4* lds_u32x4_ptr;
-  const lds_cptr lds = (lds_cptr)smem;
-  const u32x4 z = {0u, 0u, 0u, 0u};
-  for (int idx = threadIdx.x; idx < (kBK - k_valid) * 32; idx += kGemmThreads) {
-    const int kr = k_valid + (idx >> 5), c = idx & 31;
-    const int off = ((kr >> 4) * 8 + ((kr & 15) >> 2) * 2 + (c >> 4)) * kLine + (kr & 3) * 256 + (c & 15) * 16;
-    *(lds_u32x4_ptr)(lds + a_stage * kAStageBytes + off) = z;
-    *(lds_u32x4_ptr)(lds + kBRegion + b_stage * kBStageBytes + off) = z;
-  }
-  wait_lgkmcnt0();
-  __builtin_amdgcn_s_barrier();
-}
-
 // K loop of one tile for a wave with NMT active row sub-tiles.
 //
 // Step s computes from A stage s%2 and B stage s%3.  Its barrier sits in front of
@@ -334,10 +286,8 @@ __device__ __forceinline__ void gemm_zero_k_tail(char* smem, int a_stage, int b_
 // then B(s+3), issued four at a time behind the MFMAs of the following four
 // slices, while the first operands of step s+1 are already being read under the
 // last slice of step s.
-// k_tail (TN): valid k-rows of the last step if it is partial, else 0.
 template <int LAY, int NMT, bool TALL>
-__device__ __forceinline__ void gemm_k_loop(f32x16 (&acc)[kMaxMT][4], const GemmTileCtx& t, char* smem, int n_steps,
-                                            int k_tail) {
+__device__ __forceinline__ void gemm_k_loop(f32x16 (&acc)[kMaxMT][4], const GemmTileCtx& t, char* smem, int n_steps) {
   typedef TileShape<TALL> S;
   const lds_cptr lds = (lds_cptr)smem;
   if (n_steps <= 0) return;
@@ -354,7 +304,6 @@ __device__ __forceinline__ void gemm_k_loop(f32x16 (&acc)[kMaxMT][4], const Gemm
       wait_vmcnt<0>();
     }
     __builtin_amdgcn_s_barrier();
-    if (LAY == kLayTN && n_steps == 1 && k_tail) gemm_zero_k_tail(smem, 0, 0, k_tail);
   }
   GemmLoadGroup g = gemm_load_group<LAY, TALL>(t, n_steps > 1 ? 1 : -1, 1, n_steps > 2 ? 2 : -1, 2);   // A(1), B(2)
 #pragma unroll
@@ -382,8 +331,6 @@ __device__ __forceinline__ void gemm_k_loop(f32x16 (&acc)[kMaxMT][4], const Gemm
       wait_lgkmcnt0();
       if (s + 2 < n_steps) wait_vmcnt<S::kBLoads>(); else wait_vmcnt<0>();
       __builtin_amdgcn_s_barrier();
-      // the last step's operands have landed (nothing is in flight any more): blank its k-rows past the segment
-      if (LAY == kLayTN && s + 2 == n_steps && k_tail) gemm_zero_k_tail(smem, (s + 1) & 1, bs_next, k_tail);
       g = gemm_load_group<LAY, TALL>(t, s + 2 < n_steps ? s + 2 : -1, s & 1, s + 3 < n_steps ? s + 3 : -1, bs_i);
     }
     if (NMT > 0) {
@@ -420,7 +367,7 @@ __device__ __forceinline__ char* epilogue_region(char* smem, int wave) {
 
 // pk[nt][q]: this lane's 4 packed columns nt*32 + q*8 + (lane/32)*4 .. +3 of row lane%32.
 // Writes rows [0, rows_valid) x columns [0, cols_valid) of the block to gdst (row stride ld elements).
-template <int NB>
+template <int NB, bool NT = false>
 __device__ __forceinline__ void store_block_via_lds(char* region, const u32x2 (&pk)[NB][4], __bf16* gdst, long ld,
                                                     int rows_valid, int cols_valid) {
   typedef __attribute__((address_space(3))) char* lds_ptr;
@@ -449,19 +396,21 @@ __device__ __forceinline__ void store_block_via_lds(char* region, const u32x2 (&
   for (int it = 0; it < 32 * LPR / kWave; ++it) {
     const int row = it * (kWave / LPR) + row_l;
     const u32x4 v = *(lds_u32x4_cptr)(lp + it * (kWave / LPR) * kEpiRowBytes);
-    if (row < rows_valid && col_ok) *reinterpret_cast<u32x4*>(gp + (size_t)(it * (kWave / LPR)) * ld) = v;
+    if (row < rows_valid && col_ok) {
+      u32x4* dst = reinterpret_cast<u32x4*>(gp + (size_t)(it * (kWave / LPR)) * ld);
+      if (NT) __builtin_nontemporal_store(v, dst);
+      else *dst = v;
+    }
   }
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
 }
 
-// One output tile.  NN / NT: (t0, t1) = (M tile of the tile map, N tile of TileShape<TALL>::kCols
-// columns; SwiGLU: half as many output columns).  TN: (t0, t1, t2) = (expert, M tile, N tile) of that
-// expert's [M, N] gradient (wide shape only).
+// One output tile: (t0, t1) = (M tile of the tile map, N tile of TileShape<TALL>::kCols
+// columns; SwiGLU: half as many output columns).
 template <int LAY, int EPI, bool TALL>
-__device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int t1, int t2, char* smem) {
+__device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int t1, char* smem) {
   typedef TileShape<TALL> S;
-  static_assert(!(TALL && LAY == kLayTN), "weight gradients use the wide shape");
   const int tid = threadIdx.x;
   // opaque to the optimiser: per-lane setup is recomputed per tile instead of being hoisted out of
   // the tile loop and held (or spilled) across every K loop
@@ -472,53 +421,26 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
   const int l32 = lane & 31, lh = lane >> 5;
 
   // row_base: first tile row of this wave; n_mt: its 32-row blocks
-  int e, row0, rows, ntile, row_base, n_mt, n_steps, k_tail = 0;
-  if (LAY == kLayTN) {
-    e = t0;
-    ntile = t2;
-    row0 = t1 * kBM;                                          // first output row (of M)
-    rows = min(kBM, p.M - row0);
-    row_base = wm * 128;                                      // wave rows split the staged 256 columns of A^T
-    n_mt = min(kMaxMT, max(0, (rows - row_base + 31) >> 5));
-    const int seg0 = p.offsets[e], cnt = p.offsets[e + 1] - seg0;
-    n_steps = (cnt + kBK - 1) / kBK;
-    k_tail = cnt % kBK;
-  } else {
-    e = p.tiles.expert[t0];
-    row0 = p.tiles.row0[t0];
-    rows = p.tiles.rows[t0];
-    ntile = t1;
-    // rows per wave (row), a multiple of 32: tall = four wave rows, wide = two
-    const int per = TALL ? ((((rows + 31) >> 5) + 3) >> 2) << 5 : ((rows + 63) >> 6) << 5;
-    row_base = (TALL ? wave : wm) * per;
-    n_mt = (max(0, min(per, rows - row_base)) + 31) >> 5;
-    n_steps = p.K / kBK;
-  }
+  const int e = p.tiles.expert[t0], row0 = p.tiles.row0[t0], rows = p.tiles.rows[t0], ntile = t1;
+  // rows per wave (row), a multiple of 32: tall = four wave rows, wide = two
+  const int per = TALL ? ((((rows + 31) >> 5) + 3) >> 2) << 5 : ((rows + 63) >> 6) << 5;
+  const int row_base = (TALL ? wave : wm) * per;
+  const int n_mt = (max(0, min(per, rows - row_base)) + 31) >> 5;
+  const int n_steps = p.K / kBK;
 
   GemmTileCtx t;
   t.wave = wave;
-  t.kk = lane >> 4;
+  const int kk4 = lane >> 4;          // k-row of this lane inside a 4-k-row line
   t.nA = (rows + 31) >> 5;            // (8-row lines any operand read touches = 4*ceil(rows/32)) / 4 waves
   t.lda_bytes = p.lda * 2;
   t.ldb_bytes = p.ldb * 2;
-  t.k_rows = 0;
   // chunk position -> k chunk of an 8-row x 64-k line: lane -> (row r = lane/8, position pos = lane%8) holds
   // k chunk pos ^ ((row/2)%8); line L = wave + 4*i, so (row/2)%8 = 4*(wave&1) + r/2
   const int kc_r = lane >> 3;
   const int kc_c = (lane & 7) ^ ((4 * (wave & 1) + (kc_r >> 1)) & 7);
   // 4-k-row x 128-column line: lane -> (k-row kk = lane/16, position pos = lane%16) holds column chunk pos - 4*kk
-  const int tr_nl = (((lane & 15) - 4 * t.kk) & 15) * 8;
-  if (LAY == kLayTN) {
-    const int seg0 = p.offsets[e];
-    t.k_rows = p.offsets[e + 1] - seg0;
-    t.a_base = uniform_ptr(reinterpret_cast<const char*>(p.A + (size_t)seg0 * p.lda));
-    t.b_base = uniform_ptr(reinterpret_cast<const char*>(p.B + (size_t)seg0 * p.ldb));
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      t.a_off[h] = (uint32_t)(min(row0 + h * 128 + tr_nl, p.M - 8) * 2);
-      t.b_off[h] = (uint32_t)(min(ntile * kBN + h * 128 + tr_nl, p.N - 8) * 2);
-    }
-  } else {
+  const int tr_nl = (((lane & 15) - 4 * kk4) & 15) * 8;
+  {
     t.a_base = uniform_ptr(reinterpret_cast<const char*>(p.A + (size_t)row0 * p.lda));
     t.b_base = uniform_ptr(reinterpret_cast<const char*>(p.B + (size_t)e * p.strideB));
 #pragma unroll
@@ -537,14 +459,14 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
       int gcol;
       if (EPI == kEpiSwiglu) gcol = (tr_nl >> 6) * p.N + min(ntile * 64 + (tr_nl & 63), p.N - 8);
       else gcol = min(ntile * 128 + tr_nl, p.N - 8);
-      t.b_off[0] = (uint32_t)((t.kk * p.ldb + gcol) * 2);
+      t.b_off[0] = (uint32_t)((kk4 * p.ldb + gcol) * 2);
     } else {
 #pragma unroll
       for (int nh = 0; nh < 2; ++nh) {
         int gcol;
         if (EPI == kEpiSwiglu) gcol = nh * p.N + min(ntile * (kBN / 2) + tr_nl, p.N - 8);   // half 0 = gate, 1 = up
         else gcol = min(ntile * kBN + nh * 128 + tr_nl, p.N - 8);
-        t.b_off[nh] = (uint32_t)((t.kk * p.ldb + gcol) * 2);
+        t.b_off[nh] = (uint32_t)((kk4 * p.ldb + gcol) * 2);
       }
     }
   }
@@ -565,8 +487,7 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
     };
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      if (LAY == kLayTN) t.a_rd[q] = tr_off(wm * 128 + q * 32, 2);
-      else t.a_rd[q] = a0 + (uint32_t)((((q * 2 + lh) ^ f) & 7) << 4);
+      t.a_rd[q] = a0 + (uint32_t)((((q * 2 + lh) ^ f) & 7) << 4);
       if (LAY == kLayNT) t.b_rd[q] = w0 + (uint32_t)((((q * 2 + lh) ^ f) & 7) << 4);
       else if (TALL) t.b_rd[q] = tr_off(q * 32, 1);
       else t.b_rd[q] = tr_off((EPI == kEpiSwiglu) ? (q >> 1) * 128 + wn * 64 + (q & 1) * 32 : wn * 128 + q * 32, 2);
@@ -582,18 +503,17 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   switch (n_mt) {
-    case 0: gemm_k_loop<LAY, 0, TALL>(acc, t, smem, n_steps, k_tail); break;
-    case 1: gemm_k_loop<LAY, 1, TALL>(acc, t, smem, n_steps, k_tail); break;
-    case 2: gemm_k_loop<LAY, 2, TALL>(acc, t, smem, n_steps, k_tail); break;
-    case 3: gemm_k_loop<LAY, 3, TALL>(acc, t, smem, n_steps, k_tail); break;
+    case 0: gemm_k_loop<LAY, 0, TALL>(acc, t, smem, n_steps); break;
+    case 1: gemm_k_loop<LAY, 1, TALL>(acc, t, smem, n_steps); break;
+    case 2: gemm_k_loop<LAY, 2, TALL>(acc, t, smem, n_steps); break;
+    case 3: gemm_k_loop<LAY, 3, TALL>(acc, t, smem, n_steps); break;
     default:
-      if constexpr (!TALL) gemm_k_loop<LAY, 4, TALL>(acc, t, smem, n_steps, k_tail);   // a tall wave row has at most 96 rows
+      if constexpr (!TALL) gemm_k_loop<LAY, 4, TALL>(acc, t, smem, n_steps);   // a tall wave row has at most 96 rows
       break;
   }
 
   // ---- epilogue: lane holds row l32 of each 32 x 32 block and, per register group q,
   // the 4 consecutive columns q*8 + lh*4 .. +3; blocks leave through the wave's LDS region ----
-  __bf16* c_base = LAY == kLayTN ? p.C + (size_t)e * p.strideC : p.C;
   char* region = epilogue_region(smem, wave);
 #pragma unroll
   for (int mt = 0; mt < kMaxMT; ++mt) {
@@ -668,7 +588,7 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
         for (int q = 0; q < 4; ++q)
           pk[nt][q] = u32x2{pack_bf16(acc[mt][nt][q * 4 + 0], acc[mt][nt][q * 4 + 1]),
                             pack_bf16(acc[mt][nt][q * 4 + 2], acc[mt][nt][q * 4 + 3])};
-      store_block_via_lds<4>(region, pk, c_base + grow0 * p.ldc + c0, p.ldc, rows_valid, p.N - c0);
+      store_block_via_lds<4>(region, pk, p.C + grow0 * p.ldc + c0, p.ldc, rows_valid, p.N - c0);
     }
   }
 }
@@ -677,8 +597,8 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
 // map builder makes such tiles only with <= 384 rows and gives each a pair slot of its own).
 template <int LAY, int EPI>
 __device__ __forceinline__ void gemm_map_tile_bf16(const GemmParams& p, int mtile, int ntile, bool tall, char* smem) {
-  if (tall) gemm_tile_bf16<LAY, EPI, true>(p, mtile, ntile, 0, smem);
-  else gemm_tile_bf16<LAY, EPI, false>(p, mtile, ntile, 0, smem);
+  if (tall) gemm_tile_bf16<LAY, EPI, true>(p, mtile, ntile, smem);
+  else gemm_tile_bf16<LAY, EPI, false>(p, mtile, ntile, smem);
 }
 
 // Work item `rem` (0 .. 2*n_ntiles-1) of tile pair (m0, m0+1): a tall tile owns the whole slot as
@@ -727,24 +647,6 @@ void grouped_gemm_bf16_kernel(GemmParams p) {
     bool tall;
     if (!pair_work_item(p, 2 * (pl * 8 + xcd), rem, n_m, EPI == kEpiSwiglu ? kBN / 2 : kBN, mtile, ntile, tall)) continue;
     gemm_map_tile_bf16<LAY, EPI>(p, mtile, ntile, tall, smem);
-  }
-}
-
-// Weight gradients: one [M, N] output per expert, reduction over the expert's rows
-// (w2_grad, w1_grad of Section 2.2).  Experts without rows get zeros.
-__global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
-void grouped_wgrad_bf16_kernel(GemmParams p) {
-  __shared__ __attribute__((aligned(1024))) char smem[kGemmLdsBytes];
-  const int per_e = p.n_mtiles * p.n_ntiles;
-  const int total = p.E_local * per_e;
-  const int G = gridDim.x;
-  for (int it = 0; it * G < total; ++it) {
-    const int tile = xcd_tile_id(it, blockIdx.x, G);
-    if (tile >= total) continue;
-    const int e = __builtin_amdgcn_readfirstlane(tile / per_e);
-    const int rem = tile - e * per_e;
-    const int mt = __builtin_amdgcn_readfirstlane(rem / p.n_ntiles);
-    gemm_tile_bf16<kLayTN, kEpiStore, false>(p, e, mt, rem - mt * p.n_ntiles, smem);
   }
 }
 

@@ -13,6 +13,8 @@
 #include "permute_combine.h"
 #include "persistent.h"
 #include "route.h"
+#include "wgrad_bf16.h"
+#include "wgrad_panel.h"
 
 using namespace moe;
 
@@ -331,6 +333,21 @@ struct BwdCtx {
   TileMap tiles;
 };
 
+// Weight gradient of one GEMM: experts with up to 384 rows go to the register-stationary kernel when
+// the output splits into full 256 x 128 tiles, everything else to the general kernel.
+void launch_wgrad_bf16(GemmParams p, int grid, int n_cu, hipStream_t stream) {
+  p.k_lo = 0;
+  if (p.M % kWpM == 0 && p.N % kWpN == 0) {
+    const int n_nt = p.N / kWpN, panels = p.E_local * (p.M / kWpM);
+    int n_split = 1;   // smallest divisor of the tile count that gives every CU about four items
+    for (int d = 1; d <= n_nt; ++d)
+      if (n_nt % d == 0) { n_split = d; if ((long)panels * d >= 4L * n_cu) break; }
+    hipLaunchKernelGGL(grouped_wgrad_panel_bf16_kernel, dim3(grid), dim3(kWpThreads), 0, stream, p, n_split);
+    p.k_lo = kWpMaxRows + 1;
+  }
+  hipLaunchKernelGGL(grouped_wgrad2_bf16_kernel, dim3(2 * grid), dim3(kGemmThreads), 0, stream, p);
+}
+
 template <typename T>
 int run_backward(const BwdCtx& c, const void* dy, const void* w_gate_up, const void* w_down, void* dx,
                  void* dw_gate_up, void* dw_down, float* d_topk_w) {
@@ -378,9 +395,10 @@ int run_backward(const BwdCtx& c, const void* dy, const void* w_gate_up, const v
     p.A = static_cast<const T*>(c.sv.A); p.B = dYp; p.C = static_cast<T*>(dw_down);
     p.strideC = (long)s.I * s.H; p.M = s.I; p.N = s.H;
     p.lda = s.I; p.ldb = s.H; p.ldc = s.H;
-    p.n_mtiles = ceil_div(s.I, bm); p.n_ntiles = ceil_div(s.H, tn);
+    p.n_ntiles = ceil_div(s.H, tn);
+    if constexpr (!BF16) p.n_mtiles = ceil_div(s.I, bm);
     p.E_local = s.E_local; p.offsets = c.sv.offsets;
-    if constexpr (BF16) hipLaunchKernelGGL(grouped_wgrad_bf16_kernel, dim3(grid), dim3(kGemmThreads), 0, c.stream, p);
+    if constexpr (BF16) launch_wgrad_bf16(p, grid, c.n_cu, c.stream);
     else hipLaunchKernelGGL(grouped_wgrad_f32_kernel, dim3(grid), dim3(256), 0, c.stream, p);
   }
   // gate_grad: dXp = dH1 W_gate_up^T
@@ -402,9 +420,10 @@ int run_backward(const BwdCtx& c, const void* dy, const void* w_gate_up, const v
     p.A = static_cast<const T*>(c.sv.Xp); p.B = dH1; p.C = static_cast<T*>(dw_gate_up);
     p.strideC = (long)s.H * 2 * s.I; p.M = s.H; p.N = 2 * s.I;
     p.lda = s.H; p.ldb = 2 * s.I; p.ldc = 2 * s.I;
-    p.n_mtiles = ceil_div(s.H, bm); p.n_ntiles = ceil_div(2 * s.I, tn);
+    p.n_ntiles = ceil_div(2 * s.I, tn);
+    if constexpr (!BF16) p.n_mtiles = ceil_div(s.H, bm);
     p.E_local = s.E_local; p.offsets = c.sv.offsets;
-    if constexpr (BF16) hipLaunchKernelGGL(grouped_wgrad_bf16_kernel, dim3(grid), dim3(kGemmThreads), 0, c.stream, p);
+    if constexpr (BF16) launch_wgrad_bf16(p, grid, c.n_cu, c.stream);
     else hipLaunchKernelGGL(grouped_wgrad_f32_kernel, dim3(grid), dim3(256), 0, c.stream, p);
   }
   // backward Combine: dX[t] = sum over local slots of dXp[row_of[t,j]]

@@ -25,6 +25,11 @@ SMALL = [
     ("b_bf16_exact64", 64, 576, 320, 2, 2, 0, 2, "bf16", 39),     # 64 rows per expert: no reduction tail
     ("b_bf16_limits", 97, 128, 64, 256, 256, 0, 16, "bf16", 43),   # maximum k, E and E_local; most experts 0..10 rows
     ("b_bf16_tall", 1200, 192, 128, 4, 4, 0, 1, "bf16", 44),       # ~300 rows/expert: tall tiles in act_grad / gate_grad
+    # H, I multiples of 256: the weight gradients take the register-stationary kernel for experts of <= 384 rows
+    ("b_bf16_panel", 1000, 256, 256, 8, 8, 0, 2, "bf16", 45),       # ~250 rows/expert: 4 chunks, ragged last chunk
+    ("b_bf16_panel_k6", 1400, 512, 256, 8, 8, 0, 2, "bf16", 46),    # ~350 rows/expert: 6 chunks, two panels
+    ("b_bf16_panel_mix", 1150, 256, 512, 6, 6, 0, 2, "bf16", 47),   # ~383 rows/expert: some above 384 (general kernel)
+    ("b_bf16_panel_small", 300, 256, 256, 32, 10, 3, 4, "bf16", 48),  # ~37 rows/expert: one chunk
 ]
 
 
@@ -72,6 +77,15 @@ def test_mid_configs(name):
 def test_config_c5_full():
     """The full-size training configuration, compared element by element."""
     _run_case(CONFIGS["c5"])
+
+
+def test_panel_kernel_with_empty_experts():
+    """Register-stationary weight-gradient kernel: experts without rows must still get zeros."""
+    from gpu_common import small_config
+    cfg = small_config("b_panel_empty", 600, 256, 256, 8, 8, 0, 2, "bf16", 49)
+    run, bwd, ref, ref_b = _run_case(cfg, never_selected=(2, 5))
+    assert ref["counts"][2] == 0 and ref["counts"][5] == 0
+    assert torch.all(bwd.dw_gate_up[2] == 0) and torch.all(bwd.dw_down[5] == 0)
 
 
 def test_backward_argument_errors():
