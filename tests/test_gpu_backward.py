@@ -79,6 +79,14 @@ def test_config_c5_full():
     _run_case(CONFIGS["c5"])
 
 
+def test_config_c4_skewed_full():
+    """Skewed routing at full size: experts from a few rows to thousands, so both weight-gradient
+    kernels (register-stationary up to 384 rows, general above) work on the same launch."""
+    import dataclasses
+    run, bwd, ref, ref_b = _run_case(dataclasses.replace(CONFIGS["c4"], name="c4_bwd"))
+    assert ref["counts"].max() > 384 and ref["counts"].min() <= 384
+
+
 def test_panel_kernel_with_empty_experts():
     """Register-stationary weight-gradient kernel: experts without rows must still get zeros."""
     from gpu_common import small_config
