@@ -173,6 +173,7 @@ __global__ __launch_bounds__(256) void grouped_dgrad_f32_kernel(GemmBwdParamsF32
   for (int tile = blockIdx.x; tile < total; tile += gridDim.x) {
     const int mtile = tile / p.n_ntiles, n0 = (tile % p.n_ntiles) * kFBN;
     const int e = p.tiles.expert[mtile], row0 = p.tiles.row0[mtile], rows = p.tiles.rows[mtile];
+    if (rows <= 0) continue;   // the empty half of a pair slot (block-uniform)
     float acc[4][4] = {};
     gemm_tile_f32_strided(p.A + (size_t)row0 * p.lda, p.lda, 1, p.B + (size_t)e * p.strideB + (size_t)n0 * p.ldb, 1,
                           p.ldb, rows, p.N - n0, p.K, smem, acc);

@@ -32,6 +32,7 @@ __device__ __forceinline__ void gemm_tile_f32(const GemmParamsF32& p, int mtile,
   const int e = p.tiles.expert[mtile];
   const int row0 = p.tiles.row0[mtile];
   const int rows = p.tiles.rows[mtile];
+  if (rows <= 0) return;   // the empty half of a pair slot (block-uniform)
   const int n0 = ntile * kFBN;
 
   const int a_r = tid >> 2, a_k = (tid & 3) * 4;
