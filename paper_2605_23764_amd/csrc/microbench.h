@@ -113,9 +113,9 @@ __global__ void mb_clear_kernel(MicrobenchParams p, int n_q) {
 // round), which it waits for through that tile's event counter.  The order is a pure function of
 // (w, r): nothing is decided, fetched or updated at run time except the counters.
 // Because producer and consumer are known to share an XCD, the hand-off needs no device-wide
-// release (which writes back that XCD's whole L2): the producer waits until its stores have
-// reached the L2, the consumer reads rows it has never touched in this launch through that
-// same L2.  Workgroup w runs on XCD w % 8 (round-robin dispatch, as everywhere in this library).
+// release (which writes back that XCD's whole L2): every producing wave waits until its stores have
+// reached the L2 (wait_own_stores), the consumer reads rows it has never touched in this launch
+// through that same L2.  Workgroup w runs on XCD w % 8 (round-robin dispatch, as everywhere in this library).
 __global__ __launch_bounds__(256) void mb_static_kernel(MicrobenchParams p) {
   __shared__ int s_box[2];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -125,6 +125,7 @@ __global__ __launch_bounds__(256) void mb_static_kernel(MicrobenchParams p) {
     if (ts < p.n_tiles) {
       mb_swiglu_rows(p, ts * p.tile_rows, min(p.M, (ts + 1) * p.tile_rows));
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      wait_own_stores();
       __syncthreads();
       if (wave == 0) wave_atomic_add(&p.events[ts], 1u);
     }
@@ -188,8 +189,12 @@ __global__ __launch_bounds__(256) void mb_dynamic_kernel(MicrobenchParams p) {
       if (task < q.n_local) {
         const int t = task * n_q + x;
         mb_swiglu_rows(p, t * p.tile_rows, min(p.M, (t + 1) * p.tile_rows));
-        if (PER_XCD) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        else __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        if (PER_XCD) {
+          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+          wait_own_stores();
+        } else {
+          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        }
         __syncthreads();
         if (wave == 0) {
           const uint32_t slot = wave_atomic_add(head + 1, 1u);

@@ -148,8 +148,12 @@ __device__ __forceinline__ bool sched_wait(const SchedParams<BF16>& sp, int ev, 
 template <bool BF16>
 __device__ __forceinline__ void sched_trigger(const SchedParams<BF16>& sp, int ev, int wave, int scope = kScopeDevice,
                                               uint32_t inc = 1u) {
-  if (scope == kScopeDevice) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-  else __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // stores acknowledged by the XCD's L2
+  if (scope == kScopeDevice) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+  } else {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    wait_own_stores();                                          // ... acknowledged by the XCD's L2
+  }
   __syncthreads();
   if (wave == 0) wave_atomic_add(&sp.events[ev], inc);
 }

@@ -14,6 +14,13 @@ constexpr int kNumXcd = 8;   // accelerator dies; workgroup b of a launch runs o
 // issued with the execution mask narrowed inside one assembly statement, polls are
 // uniform loads, and every branch below is scalar.
 
+// This wave's earlier global stores have been acknowledged by the L2 (s_waitcnt vmcnt(0); stores are
+// write-through in the L1).  A release between workgroups behind the SAME L2 needs exactly this on
+// every storing wave, followed by a workgroup barrier, before the counter moves: a workgroup-scope
+// fence alone emits no such wait (a workgroup shares its L1), and the counter's atomic, issued by one
+// wave, could then reach the L2 ahead of another wave's data.
+__device__ __forceinline__ void wait_own_stores() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 // One atomic add of `inc` at p, issued by lane 0 only; returns the old value to all lanes.
 __device__ __forceinline__ uint32_t wave_atomic_add(uint32_t* p, uint32_t inc) {
   uint32_t old;

@@ -44,6 +44,20 @@ def test_modes_match_oracle_and_each_other(M, N, tile_rows):
         assert torch.equal(got[mode][0], got[0][0]) and torch.equal(got[mode][1], got[0][1])
 
 
+def test_xcd_local_handoff_repeats():
+    """The XCD-local hand-off (modes 1 and 3) signals a tile only after every storing wave's data has
+    reached the shared L2.  Small tiles make the consumer read within a microsecond of the signal; the
+    intermediate starts as NaN each time, so a consumer that ran ahead of the data would show it."""
+    M, N, rows = 20003, 512, 2
+    inp = make_microbench_inputs(M, N, seed=7)
+    want_s, want_out = run(M, N, inp, moe.MB_SERIAL, rows)
+    ws = torch.empty(moe.moe_microbench_workspace_bytes(M), dtype=torch.uint8, device="cuda")
+    for rep in range(12):
+        for mode in (moe.MB_STATIC, moe.MB_DYNAMIC_XCD):
+            s, out = run(M, N, inp, mode, rows, ws)
+            assert torch.equal(out, want_out) and torch.equal(s, want_s), (rep, mode)
+
+
 def test_full_size_sampled_rows():
     """M = 32K at the paper's widths: sampled rows against the oracle, all modes bit-identical."""
     M, N = 32768, 2048
