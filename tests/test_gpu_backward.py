@@ -56,6 +56,29 @@ def test_small_shapes(case):
     _run_case(small_config(*case))
 
 
+def _random_cases(n, seed):
+    """Seeded random small problems: H, I multiples of 64 up to 512 (so some hit the register-stationary
+    weight-gradient kernel, some the general one, some both), any E_local / base / k the limits allow."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        H = int(rng.choice([64, 128, 192, 256, 320, 512]))
+        I = int(rng.choice([64, 128, 256, 384]))
+        E = int(rng.choice([2, 4, 8, 16, 32]))
+        E_local = int(rng.integers(1, E + 1))
+        base = int(rng.integers(0, E - E_local + 1))
+        k = int(rng.integers(1, min(E, 8) + 1))
+        T = int(rng.integers(1, 2500))
+        cases.append((f"rnd{i}_T{T}_H{H}_I{I}_E{E}_{E_local}_{base}_k{k}", T, H, I, E, E_local, base, k, "bf16", 500 + i))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_cases(14, 2024), ids=lambda c: c[0])
+def test_random_small_shapes(case):
+    from gpu_common import small_config
+    _run_case(small_config(*case))
+
+
 def test_experts_without_rows_get_zero_gradients():
     from gpu_common import small_config
     cfg = small_config("b_empty", 200, 64, 64, 32, 6, 20, 2, "bf16", 41)
