@@ -282,7 +282,10 @@ int run_persistent(const Ctx& c, const void* x, const float* logits, const void*
   sp.max_mtiles = (int)max_mtiles(c.s);
   sp.max_tasks_per_q = (int)max_tasks_per_queue(c.s);
   sp.n_rank_tasks = (sp.route.n_groups + kRankChunksPerTask - 1) / kRankChunksPerTask;
-  sp.n_comb_tasks = (c.s.T + kCombineTokens - 1) / kCombineTokens;
+  // COMBINE tasks of 32 tokens, halved (down to 4, one per wave) while there are fewer tasks than CUs
+  sp.comb_tokens = kCombineTokens;
+  while (sp.comb_tokens > 4 && (c.s.T + sp.comb_tokens - 1) / sp.comb_tokens < c.n_cu) sp.comb_tokens >>= 1;
+  sp.n_comb_tasks = (c.s.T + sp.comb_tokens - 1) / sp.comb_tokens;
   sp.spin_limit = g_spin_limit;
   sp.timeout_status = MOE_ERR_SCHED_TIMEOUT;
   hipLaunchKernelGGL(sched_clear_kernel, dim3(1), dim3(256), 0, c.stream, sp.events, (int)n_events(c.s), sp.qhead,

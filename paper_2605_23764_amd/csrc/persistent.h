@@ -48,7 +48,7 @@
 namespace moe {
 
 constexpr int kPermRows = 32;            // rows per PERMUTE task
-constexpr int kCombineTokens = 32;       // tokens per COMBINE task
+constexpr int kCombineTokens = 32;       // tokens per COMBINE task (fewer when that would leave CUs without one)
 constexpr int kRankChunksPerTask = 4;    // one chunk per wave
 constexpr int kGemm2Lag = 1;             // GEMM-2 of tile pair j is queued behind GEMM-1 of pair j + lag
 
@@ -82,6 +82,7 @@ struct SchedParams {
   int32_t* meta;
   int max_mtiles, max_tasks_per_q;
   int n_rank_tasks, n_comb_tasks;
+  int comb_tokens;         // tokens per COMBINE task
   uint32_t spin_limit;     // polls before a wait gives up (MOE_ERR_SCHED_TIMEOUT)
   int32_t timeout_status;
 };
@@ -331,8 +332,8 @@ void persistent_forward_kernel(SchedParams<BF16> sp) {
       MOE_TRACE_FETCH(3, t, 0)
       if (!sched_wait(sp, kEvGemm2, g2_total, s_box, wave)) continue;
       MOE_TRACE_START
-      const int t0 = t * kCombineTokens;
-      for (int i = wave; i < kCombineTokens; i += blockDim.x / kWave)
+      const int t0 = t * sp.comb_tokens;
+      for (int i = wave; i < sp.comb_tokens; i += blockDim.x / kWave)
         if (t0 + i < sp.comb.T) combine_token<BF16>(sp.comb, t0 + i);
       MOE_TRACE_END(sp)
     }
