@@ -101,6 +101,14 @@ def main():
         except moe.MoeError as e:
             print(f"bench.py: mode {name} unavailable: {e}", file=sys.stderr)
     best = min(ms, key=ms.get)
+    # inference (no saved tensors): GEMM-1 gathers the token rows itself, the permuted copy is not made;
+    # reported beside the headline, which keeps the saved tensors a training step needs
+    infer_ms = {}
+    for name, mode in modes.items():
+        if name in ms:
+            infer_ms[name] = timed(lambda: moe.moe_ffn_forward(shape, dev["x"], dev["logits"], dev["w_gate_up"],
+                                                               dev["w_down"], out, None, ws, mode),
+                                   args.steps, args.warmup)
     R = int(saved.offsets.cpu()[-1])
     bwd_ms = None
     if with_bwd:
@@ -172,6 +180,7 @@ def main():
         "roofline": roof,
         "detail": {
             "us_per_layer": {k: v * 1e3 for k, v in ms.items()},
+            "us_per_layer_inference": {k: v * 1e3 for k, v in infer_ms.items()},
             "stage_us": stage_us,
             "dispatch_to_combine_us_serialized": sum(v for k, v in stage_us.items() if k != "route"),
             "grouped_gemm_tflops": gemm_tflops,

@@ -69,6 +69,8 @@ struct GemmParams {
   __bf16* C;          // [rows, ldc]
   __bf16* C2;         // SwiGLU only: optional pre-activation [rows, 2N] (gate|up), else null
   const __bf16* G;    // SwiGLU-grad only: pre-activations saved by the forward [rows, 2N]
+  const int32_t* gather;   // NN, optional: row r of the tile map is row gather[r] of A (A = the unpermuted tokens:
+                           // the Dispatch permutation applied while loading, no permuted copy needed)
   long strideB;       // elements between consecutive experts' weights (NN, NT)
   long strideC;       // weight gradients: elements between consecutive experts' outputs
   int K, N;           // N = output columns (SwiGLU: I, weights have 2N columns); weight gradients: K unused (rows of the expert)
@@ -441,12 +443,15 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
   // 4-k-row x 128-column line: lane -> (k-row kk = lane/16, position pos = lane%16) holds column chunk pos - 4*kk
   const int tr_nl = (((lane & 15) - 4 * kk4) & 15) * 8;
   {
-    t.a_base = uniform_ptr(reinterpret_cast<const char*>(p.A + (size_t)row0 * p.lda));
+    const bool gathered = LAY == kLayNN && p.gather != nullptr;   // uniform
+    t.a_base = uniform_ptr(reinterpret_cast<const char*>(gathered ? p.A : p.A + (size_t)row0 * p.lda));
     t.b_base = uniform_ptr(reinterpret_cast<const char*>(p.B + (size_t)e * p.strideB));
 #pragma unroll
     for (int i = 0; i < S::kALoads; ++i) {
       const int row = min((wave + 4 * i) * 8 + kc_r, rows - 1);      // rows past the end re-read the last row; never stored
-      t.a_off[i] = (uint32_t)((row * p.lda + kc_c * 8) * 2);
+      // gathered: offsets are relative to the first token (the caller guarantees that A spans < 4 GB)
+      const long arow = gathered ? (long)p.gather[row0 + row] : (long)row;
+      t.a_off[i] = (uint32_t)((arow * p.lda + kc_c * 8) * 2);
     }
     if (LAY == kLayNT) {
 #pragma unroll

@@ -100,7 +100,14 @@ struct Ctx {
   MoeSaved sv;      // resolved buffers (caller's or workspace fallback)
   hipStream_t stream;
   int n_cu;
+  bool keep_xp;     // the caller passed MoeSaved: the permuted copy of x is an output
 };
+
+// Inference (no MoeSaved): nobody reads the permuted copy of x, so bf16 GEMM-1 applies the permutation
+// while loading (32-bit offsets: x must span < 4 GB) and the PERMUTE step is dropped.
+bool gathers_x(const Ctx& c) {
+  return !c.keep_xp && c.s.dtype == MOE_BF16 && (size_t)c.s.T * c.s.H * 2 < ((size_t)1 << 32);
+}
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -126,6 +133,7 @@ int make_ctx(Ctx& c, const MoeShape* shape, const MoeSaved* saved, void* ws, siz
   if (ws_bytes < c.L.fwd_total) return MOE_ERR_WORKSPACE_TOO_SMALL;
   c.ws = static_cast<char*>(ws);
   c.stream = static_cast<hipStream_t>(stream);
+  c.keep_xp = saved != nullptr;
   if (saved) {
     c.sv = *saved;
     const void* must[] = {saved->topk_idx, saved->topk_w, saved->counts, saved->offsets, saved->row_of,
@@ -225,11 +233,16 @@ P gemm2_params(const Ctx& c, const void* w_down) {
   return p;
 }
 
-int run_gemm1(const Ctx& c, const void* w_gate_up) {
-  if (c.s.dtype == MOE_BF16)
-    hipLaunchKernelGGL((grouped_gemm_bf16_kernel<kLayNN, kEpiSwiglu>), dim3(gemm_grid(c)), dim3(kGemmThreads), 0, c.stream,
-                       gemm1_params<GemmParams, __bf16>(c, w_gate_up));
-  else
+// x_gather: non-null = read the token rows of x through token_of instead of the permuted copy (bf16 only)
+int run_gemm1(const Ctx& c, const void* w_gate_up, const void* x_gather = nullptr) {
+  if (c.s.dtype == MOE_BF16) {
+    GemmParams p = gemm1_params<GemmParams, __bf16>(c, w_gate_up);
+    if (x_gather) {
+      p.A = static_cast<const __bf16*>(x_gather);
+      p.gather = c.sv.token_of;
+    }
+    hipLaunchKernelGGL((grouped_gemm_bf16_kernel<kLayNN, kEpiSwiglu>), dim3(gemm_grid(c)), dim3(kGemmThreads), 0, c.stream, p);
+  } else
     hipLaunchKernelGGL(grouped_gemm_f32_kernel<kEpiSwiglu>, dim3(gemm_grid(c) * 4), dim3(256), 0, c.stream,
                        gemm1_params<GemmParamsF32, float>(c, w_gate_up));
   return launch_status();
@@ -275,6 +288,14 @@ int run_persistent(const Ctx& c, const void* x, const float* logits, const void*
   sp.g1 = gemm1_params<P, T>(c, w_gate_up);
   sp.g2 = gemm2_params<P, T>(c, w_down);
   sp.comb = combine_params(c, out);
+  sp.no_permute = 0;
+  if constexpr (BF16) {
+    if (gathers_x(c)) {
+      sp.g1.A = static_cast<const T*>(x);
+      sp.g1.gather = c.sv.token_of;
+      sp.no_permute = 1;
+    }
+  }
   sp.events = reinterpret_cast<uint32_t*>(c.ws + c.L.events);
   sp.qhead = reinterpret_cast<uint32_t*>(c.ws + c.L.qhead);
   sp.tasks = reinterpret_cast<TaskDesc*>(c.ws + c.L.tasks);
@@ -526,8 +547,8 @@ int moe_ffn_forward(const MoeShape* shape, const void* d_x, const float* d_logit
     return c.s.dtype == MOE_BF16 ? run_persistent<true>(c, d_x, d_logits, d_w_gate_up, d_w_down, d_out)
                                  : run_persistent<false>(c, d_x, d_logits, d_w_gate_up, d_w_down, d_out);
   if ((st = run_route(c, d_logits)) != MOE_OK) return st;
-  if ((st = run_permute(c, d_x)) != MOE_OK) return st;
-  if ((st = run_gemm1(c, d_w_gate_up)) != MOE_OK) return st;
+  if (!gathers_x(c) && (st = run_permute(c, d_x)) != MOE_OK) return st;
+  if ((st = run_gemm1(c, d_w_gate_up, gathers_x(c) ? d_x : nullptr)) != MOE_OK) return st;
   if ((st = run_gemm2(c, d_w_down)) != MOE_OK) return st;
   return run_combine(c, d_out);
 }

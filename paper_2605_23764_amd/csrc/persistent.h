@@ -83,6 +83,7 @@ struct SchedParams {
   int max_mtiles, max_tasks_per_q;
   int n_rank_tasks, n_comb_tasks;
   int comb_tokens;         // tokens per COMBINE task
+  int no_permute;          // inference: nobody needs Xp, GEMM-1 gathers its rows from x through token_of
   uint32_t spin_limit;     // polls before a wait gives up (MOE_ERR_SCHED_TIMEOUT)
   int32_t timeout_status;
 };
@@ -176,7 +177,7 @@ __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
     const int Pq = n_pairs > q ? (n_pairs - q + kNumXcd - 1) / kNumXcd : 0;
     TaskDesc* tq = sp.tasks + (size_t)q * sp.max_tasks_per_q;
     int n = 0;
-    for (int j = 0; j < Pq; ++j)
+    for (int j = 0; j < (sp.no_permute ? 0 : Pq); ++j)
       for (int s = 0; s < 2; ++s) {
         const int m = 2 * (q + kNumXcd * j) + s;
         if (m >= n_mtiles) continue;
@@ -197,7 +198,8 @@ __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
         const int parts0 = parts_of(m0), parts1 = n_sib > 1 ? parts_of(m0 + 1) : 0;
         for (int i = lane; i < n_nt * n_sib; i += kWave) {
           const int nt = i / n_sib, sib = i - nt * n_sib;
-          tq[n + i] = TaskDesc{kTaskGemm1 | (nt << 8), m0 + sib, kEvPerTile + m0 + sib, sib ? parts1 : parts0};
+          tq[n + i] = sp.no_permute ? TaskDesc{kTaskGemm1 | (nt << 8), m0 + sib, kEvRank, sp.n_rank_tasks}
+                                    : TaskDesc{kTaskGemm1 | (nt << 8), m0 + sib, kEvPerTile + m0 + sib, sib ? parts1 : parts0};
         }
         n += n_nt * n_sib;
       }
@@ -230,13 +232,19 @@ __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
 
 template <bool BF16>
 __device__ __forceinline__ void run_tile_task(const SchedParams<BF16>& sp, const TaskDesc& td, char* smem, volatile int* s_box,
-                                              int wave, long long& t_start, uint32_t& gemm2_done) {
+                                              int wave, long long& t_start, uint32_t& gemm2_done, bool& rank_seen) {
   const int type_n = __builtin_amdgcn_readfirstlane(td.type_n);
   const int type = type_n & 0xFF, idx = type_n >> 8, m = __builtin_amdgcn_readfirstlane(td.m);
-  // PERMUTE waits on the routing tasks of every XCD; the GEMM tiles wait on tasks of their own XCD queue
-  if (!sched_wait(sp, __builtin_amdgcn_readfirstlane(td.dep_event), (uint32_t)__builtin_amdgcn_readfirstlane(td.threshold), s_box, wave,
-                  type == kTaskPermute ? kScopeDevice : kScopeXcd))
+  const int dep = __builtin_amdgcn_readfirstlane(td.dep_event);
+  // A task that needs the routing results (PERMUTE; GEMM-1 when it gathers) waits for the RANK tasks of
+  // every XCD, device scope; the permutation never changes afterwards, so a worker does that once.
+  // The rest of the chain waits on tasks of its own XCD queue.
+  if (dep == kEvRank) {
+    if (!rank_seen && !sched_wait(sp, dep, (uint32_t)__builtin_amdgcn_readfirstlane(td.threshold), s_box, wave, kScopeDevice)) return;
+    rank_seen = true;
+  } else if (!sched_wait(sp, dep, (uint32_t)__builtin_amdgcn_readfirstlane(td.threshold), s_box, wave, kScopeXcd)) {
     return;
+  }
 #if defined(MOE_SCHED_TRACE)
   t_start = wall_clock64();
 #else
@@ -309,13 +317,14 @@ void persistent_forward_kernel(SchedParams<BF16> sp) {
       const int q = blockIdx.x % kNumXcd;   // workgroups are dealt to XCDs round-robin by id
       const int count = __builtin_amdgcn_readfirstlane(sp.meta[kMetaQueueCount0 + q]);
       uint32_t gemm2_done = 0;
+      bool rank_seen = false;
       for (;;) {
         const int t = sched_fetch(sp.qhead, kQXcd0 + q, s_box, wave);
         if (t >= count) break;
         const TaskDesc td = sp.tasks[(size_t)q * sp.max_tasks_per_q + t];
         MOE_TRACE_FETCH(td.type_n & 0xFF, td.m, td.type_n >> 8)
         long long t_start = 0;
-        run_tile_task(sp, td, smem, s_box, wave, t_start, gemm2_done);
+        run_tile_task(sp, td, smem, s_box, wave, t_start, gemm2_done, rank_seen);
 #if defined(MOE_SCHED_TRACE)
         tr_.t_start = t_start;
 #endif

@@ -110,6 +110,43 @@ def test_saved_null_uses_workspace():
     assert torch.equal(out2, run.out)
 
 
+@pytest.mark.parametrize("mode", [0, 1], ids=["serialized", "persistent"])
+@pytest.mark.parametrize("case", [
+    ("i_small", 300, 128, 64, 8, 8, 0, 2, "bf16", 61), ("i_tall", 1200, 192, 128, 4, 4, 0, 1, "bf16", 62),
+    ("i_shard", 513, 320, 64, 64, 7, 50, 8, "bf16", 63), ("i_multi", 3000, 128, 128, 4, 4, 0, 2, "bf16", 64),
+    ("i_f32", 300, 128, 64, 8, 8, 0, 2, "f32", 65)], ids=lambda c: c[0])
+def test_inference_mode_skips_the_permuted_copy(case, mode):
+    """saved == NULL (inference): bf16 GEMM-1 reads the token rows through the permutation and the PERMUTE
+    step is dropped; the output must equal the training-mode output bit for bit, in both launch modes."""
+    import paper_2605_23764_amd as moe
+    from gpu_common import run_forward, small_config
+    cfg = small_config(*case)
+    inp = make_inputs(cfg)
+    run = run_forward(cfg, inp, mode=mode)
+    out2 = torch.full_like(run.out, float("nan"))
+    ws2 = torch.empty_like(run.workspace)
+    moe.moe_ffn_forward(run.shape, run.dev["x"], run.dev["logits"], run.dev["w_gate_up"], run.dev["w_down"],
+                        out2, None, ws2, mode)
+    torch.cuda.synchronize()
+    if mode == 1:
+        assert moe.moe_ffn_last_status(run.shape, ws2) == 0
+    assert torch.equal(out2, run.out)
+
+
+def test_inference_mode_full_size():
+    import paper_2605_23764_amd as moe
+    from gpu_common import run_forward
+    cfg = CONFIGS["c3"]
+    inp = make_inputs(cfg)
+    run = run_forward(cfg, inp)
+    for mode in (0, 1):
+        out2 = torch.full_like(run.out, float("nan"))
+        moe.moe_ffn_forward(run.shape, run.dev["x"], run.dev["logits"], run.dev["w_gate_up"], run.dev["w_down"],
+                            out2, None, run.workspace, mode)
+        torch.cuda.synchronize()
+        assert torch.equal(out2, run.out), mode
+
+
 def test_argument_errors_are_reported_on_the_host():
     import paper_2605_23764_amd as moe
     shape = moe.make_shape(64, 64, 64, 4, 4, 0, 2, torch.float32)
