@@ -122,7 +122,10 @@ int moe_ffn_workspace_bytes(const MoeShape* shape, size_t* fwd_bytes, size_t* bw
  *   d_w_gate_up[E_local,H,2I]   dtype, gate = columns 0..I-1, up = I..2I-1
  *   d_w_down   [E_local,I,H]    dtype
  *   d_out      [T,H]            dtype (overwritten)
- *   saved      nullable; if non-NULL every member except H1 must be non-NULL
+ *   saved      nullable; if non-NULL every member except H1 must be non-NULL.
+ *              NULL (inference): only `out` is produced; with bf16 the first grouped
+ *              GEMM then reads the token rows of x through the permutation and the
+ *              permuted copy is not made at all
  *   d_workspace, workspace_bytes  >= moe_ffn_workspace_bytes(...).fwd_bytes
  *   mode       MoeMode
  * Returns after enqueueing.  A scheduler timeout (MOE_MODE_PERSISTENT only) is
