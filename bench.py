@@ -7,7 +7,8 @@ A step is one pass of the whole forward hot path (routing, dispatch permute,
 grouped GEMM-1 + SwiGLU, grouped GEMM-2, weighted combine) over one batch of
 seeded synthetic input already resident in HBM; `value` is its duration.  With
 --workload c5 a step is forward + backward.  For the other bf16 workloads the
-backward graph is timed as well and reported under "detail".  Prints ONE JSON line.
+backward graph is timed as well and reported under "detail", beside per-iteration
+median / minimum times and a cold-cache variant of the forward.  Prints ONE JSON line.
 """
 import argparse
 import json
@@ -88,6 +89,18 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps * 1e3   # ms per step
 
+    def timed_each(fn, steps, before=None):
+        """Per-iteration durations (ms) from HIP events on the launch stream; `before` runs untimed ahead of each."""
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        for i, (e0, e1) in enumerate(evs):
+            if before is not None:
+                before(i)
+            e0.record(stream)
+            fn(i)
+            e1.record(stream)
+        torch.cuda.synchronize()
+        return [e0.elapsed_time(e1) for e0, e1 in evs]
+
     modes = {"serialized": moe.MODE_SERIALIZED}
     if os.environ.get("MOE_BENCH_PERSISTENT", "1") == "1":
         modes["persistent"] = moe.MODE_PERSISTENT
@@ -109,6 +122,30 @@ def main():
             infer_ms[name] = timed(lambda: moe.moe_ffn_forward(shape, dev["x"], dev["logits"], dev["w_gate_up"],
                                                                dev["w_down"], out, None, ws, mode),
                                    args.steps, args.warmup)
+    # per-iteration spread of the same step (events), and a cold variant: three sets of inputs, saved tensors,
+    # workspace and output used in rotation, with a 1 GiB fill (4x the 256 MB Infinity Cache) ahead of each timed
+    # iteration, so that neither the 4 MB L2s nor the Infinity Cache hold anything of the step from before
+    spread, cold = {}, {}
+    n_sets = 3
+    sets = [(dev, saved, ws, out)]
+    for _ in range(n_sets - 1):
+        sets.append(({n: t.clone() for n, t in dev.items()}, moe.alloc_saved(shape, store_h1=with_bwd),
+                     moe.alloc_workspace(shape), torch.empty_like(out)))
+    flush = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+
+    def step_set(mode, i):
+        d, sv, w, o = sets[i % n_sets]
+        moe.moe_ffn_forward(shape, d["x"], d["logits"], d["w_gate_up"], d["w_down"], o, sv, w, mode)
+
+    for name, mode in modes.items():
+        if name in ms:
+            warm = sorted(timed_each(lambda i: step(mode), args.steps))
+            spread[name] = {"median": warm[len(warm) // 2] * 1e3, "min": warm[0] * 1e3}
+            for i in range(n_sets):
+                step_set(mode, i)
+            c = sorted(timed_each(lambda i: step_set(mode, i), args.steps, before=lambda i: flush.fill_(float(i))))
+            cold[name] = {"median": c[len(c) // 2] * 1e3, "min": c[0] * 1e3}
+    del flush, sets
     R = int(saved.offsets.cpu()[-1])
     bwd_ms = None
     if with_bwd:
@@ -181,6 +218,8 @@ def main():
         "detail": {
             "us_per_layer": {k: v * 1e3 for k, v in ms.items()},
             "us_per_layer_inference": {k: v * 1e3 for k, v in infer_ms.items()},
+            "us_per_layer_events": spread,
+            "us_per_layer_cold": cold,
             "stage_us": stage_us,
             "dispatch_to_combine_us_serialized": sum(v for k, v in stage_us.items() if k != "route"),
             "grouped_gemm_tflops": gemm_tflops,
