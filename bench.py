@@ -29,6 +29,22 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 # timed run, so the figure of the last profiled build is carried here.
 MEASURED_TRAFFIC_BYTES = {"c3": (975434.6 * 2.024 + 98108.0) * 1024}
 
+# Power bound.  The SMI sensors, polled from outside while `--hold` keeps one kernel running, show the GEMMs, the
+# whole forward and the whole backward at the 1400 W board limit with the clock pulled down to 1.97-2.17 GHz,
+# and the copy-like kernels at 880-960 W and 2.4 GHz.  Energy per unit of work from the probes at full rate
+# (register-only MFMAs on random data: 2.10 PFLOP/s at 1334 W; read-only, write-only and copy streams of random
+# data: 3.95 / 6.9 / 4.85 TB/s at 873 / 994 / 945 W; idle 292 W), carried here because a timed run cannot poll them.
+# A kernel cannot finish sooner than its MFMA + HBM energy divided by (cap - idle), whatever it overlaps.
+POWER_CAP_W, POWER_IDLE_W = 1400.0, 292.0
+PJ_PER_FLOP_MFMA_BF16 = (1334.0 - 292.0) / 2.10e15 * 1e12
+PJ_PER_BYTE_READ = (873.0 - 292.0) / 3.95e12 * 1e12
+PJ_PER_BYTE_WRITE = 2 * (945.0 - 292.0) / 4.85e12 * 1e12 - PJ_PER_BYTE_READ
+
+
+def power_floor_us(flops, bytes_read, bytes_written):
+    joule = (flops * PJ_PER_FLOP_MFMA_BF16 + bytes_read * PJ_PER_BYTE_READ + bytes_written * PJ_PER_BYTE_WRITE) * 1e-12
+    return joule / (POWER_CAP_W - POWER_IDLE_W) * 1e6
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -38,6 +54,11 @@ def main():
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-backward", action="store_true")
+    ap.add_argument("--hold", default=None, metavar="STAGE:SECONDS[,STAGE:SECONDS...]",
+                    help="instead of the benchmark, run each named stage (idle, route, permute, gemm1_swiglu, gemm2, "
+                         "combine, forward, backward, probe_mfma_random, probe_mfma_ones, probe_copy, torch_read_sum, "
+                         "torch_fill) back to back for SECONDS and print wall-clock marks, so that "
+                         "an outside poll of the SMI power / clock sensors can be matched to it")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs one GPU's expert-parallel share on ONE GPU; "
@@ -78,6 +99,41 @@ def main():
 
     def step_bwd():
         moe.moe_ffn_backward(shape, dy, dev["x"], dev["w_gate_up"], dev["w_down"], saved, dx, dw1, dw2, dtw, ws_b)
+
+    if args.hold:
+        step(moe.MODE_SERIALIZED)
+        torch.cuda.synchronize()
+        held = {"idle": None, "forward": lambda: step(moe.MODE_SERIALIZED),
+                "route": lambda: moe.moe_route(shape, dev["logits"], saved, ws),
+                "permute": lambda: moe.moe_permute(shape, dev["x"], saved, ws),
+                "gemm1_swiglu": lambda: moe.moe_grouped_gemm_swiglu(shape, dev["w_gate_up"], saved, ws),
+                "gemm2": lambda: moe.moe_grouped_gemm(shape, dev["w_down"], saved, ws),
+                "combine": lambda: moe.moe_combine(shape, saved, out, ws)}
+        if with_bwd:
+            held["backward"] = step_bwd
+        p_sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+        p_src = torch.empty(1 << 29, dtype=torch.float32, device="cuda").normal_().view(torch.uint8)   # power depends on the data
+        p_dst = torch.empty_like(p_src)
+        held["probe_mfma_random"] = lambda: moe.moe_probe_mfma_bf16(256, 1 << 16, 1, p_sink)
+        held["probe_mfma_ones"] = lambda: moe.moe_probe_mfma_bf16(256, 1 << 16, 0, p_sink)
+        held["probe_copy"] = lambda: moe.moe_probe_copy(p_src, p_dst, p_src.numel())
+        held["torch_read_sum"] = lambda: p_src.view(torch.float32).sum()     # read-only stream of 2 GiB
+        held["torch_fill"] = lambda: p_dst.fill_(1)                          # write-only stream of 2 GiB
+        for item in args.hold.split(","):
+            name, secs = item.split(":")
+            fn, n, t0 = held[name], 0, time.time()
+            while time.time() - t0 < float(secs):
+                if fn is None:
+                    time.sleep(0.05)
+                else:
+                    for _ in range(10):
+                        fn()
+                    torch.cuda.synchronize()
+                    n += 10
+            t1 = time.time()
+            print(json.dumps({"hold": name, "t_start": round(t0, 2), "t_end": round(t1, 2), "calls": n,
+                              "us_per_call": (t1 - t0) / n * 1e6 if n else None}), flush=True)
+        return
 
     def timed(fn, steps, warmup):
         for _ in range(warmup):
@@ -146,6 +202,22 @@ def main():
             c = sorted(timed_each(lambda i: step_set(mode, i), args.steps, before=lambda i: flush.fill_(float(i))))
             cold[name] = {"median": c[len(c) // 2] * 1e3, "min": c[0] * 1e3}
     del flush, sets
+    # ceilings measured on this GPU with nothing else in the way (register-only MFMA loop with random / constant
+    # operands: 256 workgroups x 4 waves x 65536 MFMAs of 32768 flop; 2 GiB streaming copy)
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    cp_src = torch.empty(1 << 29, dtype=torch.float32, device="cuda").normal_().view(torch.uint8)
+    cp_dst = torch.empty_like(cp_src)
+    n_wg, n_mfma = 256, 1 << 16
+    probe_ms = {
+        "mfma_random": timed(lambda: moe.moe_probe_mfma_bf16(n_wg, n_mfma, 1, sink), 5, 2),
+        "mfma_ones": timed(lambda: moe.moe_probe_mfma_bf16(n_wg, n_mfma, 0, sink), 5, 2),
+        "copy": timed(lambda: moe.moe_probe_copy(cp_src, cp_dst, cp_src.numel()), 10, 3),
+    }
+    probe_flop = n_wg * 4 * n_mfma * 32768.0
+    ceilings = {"mfma_bf16_random_operands_tflops": probe_flop / (probe_ms["mfma_random"] * 1e-3) / 1e12,
+                "mfma_bf16_constant_operands_tflops": probe_flop / (probe_ms["mfma_ones"] * 1e-3) / 1e12,
+                "copy_GBs_read_plus_write": 2.0 * cp_src.numel() / (probe_ms["copy"] * 1e-3) / 1e9}
+    del cp_src, cp_dst
     R = int(saved.offsets.cpu()[-1])
     bwd_ms = None
     if with_bwd:
@@ -229,8 +301,23 @@ def main():
             "permute_GBs": bytes_perm / (stage_us["permute"] * 1e-6) / 1e9,
             "combine_GBs": bytes_comb / (stage_us["combine"] * 1e-6) / 1e9,
             "hbm_peak_GBs": HBM_PEAK_GBS, "mfma_bf16_peak_tflops": MFMA_BF16_PEAK_TFLOPS,
+            "measured_ceilings": ceilings,
         },
     }
+
+    if cfg.dtype == "bf16":
+        rd1, wr1 = (active * H * 2 * I + R * H) * eb, R * I * eb * (3 if with_bwd else 1)   # H1 stored for the backward
+        rd2, wr2 = (active * I * H + R * I) * eb, R * H * eb
+        f1 = power_floor_us(flops1, rd1, wr1)
+        f2 = power_floor_us(flops2, rd2, wr2)
+        f_all = f1 + f2 + power_floor_us(0, bytes_perm / 2 + R * H * eb + 4.0 * T * cfg.E, bytes_perm / 2 + T * H * eb)
+        res["detail"]["power_bound"] = {
+            "board_cap_W": POWER_CAP_W, "idle_W": POWER_IDLE_W, "pJ_per_flop_mfma_bf16": PJ_PER_FLOP_MFMA_BF16,
+            "pJ_per_byte_hbm_read": PJ_PER_BYTE_READ, "pJ_per_byte_hbm_write": PJ_PER_BYTE_WRITE,
+            "gemm1_floor_us": f1, "gemm1_frac": f1 / stage_us["gemm1_swiglu"],
+            "gemm2_floor_us": f2, "gemm2_frac": f2 / stage_us["gemm2"],
+            "forward_floor_us": f_all, "forward_frac": f_all / (ms["serialized"] * 1e3),
+        }
 
     if bwd_ms is not None:
         # backward: 2x the forward GEMM work (act_grad, gate_grad, w2_grad, w1_grad); bytes: weights read once,

@@ -213,6 +213,20 @@ int moe_microbench_swiglu_add(int M, int N, const void* d_x, const void* d_y, vo
                               int tile_rows, void* d_workspace, size_t workspace_bytes, void* stream);
 int moe_microbench_last_status(const void* d_workspace);
 
+/* ---- Ceiling probes (measurement aids for the benchmark; no step of the layer) ----
+ * What this GPU sustains on the two resources the grouped GEMMs and the permute / combine steps are
+ * priced against (Section 5.1 evaluates the operators against hardware utilisation), with nothing
+ * else in the way; both only enqueue one kernel on `stream`.
+ * moe_probe_mfma_bf16: n_workgroups x 4 waves, each issuing mfma_per_wave (a multiple of 8)
+ *   32x32x16 bf16 MFMAs on registers only = n_workgroups * 4 * mfma_per_wave * 32768 flop;
+ *   random_operands != 0 uses pseudo-random values in [1, 2) instead of all ones (the sustained rate
+ *   depends on the data).  d_sink: 4 bytes of device memory, 4-byte aligned, never written.
+ * moe_probe_copy: streaming copy of `bytes` (a multiple of 16; pointers device, 16-byte aligned,
+ *   not overlapping).
+ * Both return MOE_OK, MOE_ERR_INVALID_ARG or MOE_ERR_LAUNCH. */
+int moe_probe_mfma_bf16(int n_workgroups, int mfma_per_wave, int random_operands, void* d_sink, void* stream);
+int moe_probe_copy(const void* d_src, void* d_dst, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

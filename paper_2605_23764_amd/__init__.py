@@ -31,6 +31,8 @@ from .binding import (  # noqa: F401
     moe_microbench_workspace_bytes,
     moe_grouped_gemm_swiglu,
     moe_permute,
+    moe_probe_copy,
+    moe_probe_mfma_bf16,
     moe_route,
     moe_status_string,
 )

@@ -38,6 +38,7 @@ EXPORTS = (
     "moe_status_string", "moe_ffn_workspace_bytes", "moe_ffn_forward", "moe_ffn_backward",
     "moe_ffn_last_status", "moe_ffn_debug_set_spin_limit", "moe_route", "moe_permute", "moe_grouped_gemm_swiglu", "moe_grouped_gemm",
     "moe_combine", "moe_microbench_workspace_bytes", "moe_microbench_swiglu_add", "moe_microbench_last_status",
+    "moe_probe_mfma_bf16", "moe_probe_copy",
 )
 
 
@@ -235,3 +236,14 @@ def moe_microbench_swiglu_add(M, N, x, y, s, out, mode, tile_rows, workspace, st
 
 def moe_microbench_last_status(workspace) -> int:
     return load_library().moe_microbench_last_status(_ptr(workspace))
+
+
+def moe_probe_mfma_bf16(n_workgroups, mfma_per_wave, random_operands, sink, stream=None) -> None:
+    _check(load_library().moe_probe_mfma_bf16(ctypes.c_int(n_workgroups), ctypes.c_int(mfma_per_wave),
+                                              ctypes.c_int(1 if random_operands else 0), _ptr(sink), _stream(stream)),
+           "moe_probe_mfma_bf16")
+
+
+def moe_probe_copy(src, dst, nbytes, stream=None) -> None:
+    _check(load_library().moe_probe_copy(_ptr(src), _ptr(dst), ctypes.c_size_t(nbytes), _stream(stream)),
+           "moe_probe_copy")

@@ -12,6 +12,7 @@
 #include "microbench.h"
 #include "permute_combine.h"
 #include "persistent.h"
+#include "probe.h"
 #include "route.h"
 #include "wgrad_bf16.h"
 #include "wgrad_panel.h"
@@ -627,6 +628,27 @@ int moe_microbench_swiglu_add(int M, int N, const void* d_x, const void* d_y, vo
     else if (mode == 2) hipLaunchKernelGGL(mb_dynamic_kernel<false>, dim3(grid), dim3(256), 0, st, p);
     else hipLaunchKernelGGL(mb_dynamic_kernel<true>, dim3(grid), dim3(256), 0, st, p);
   }
+  return launch_status();
+}
+
+int moe_probe_mfma_bf16(int n_workgroups, int mfma_per_wave, int random_operands, void* d_sink, void* stream) {
+  if (n_workgroups < 1 || n_workgroups > (1 << 20) || mfma_per_wave < 8 || mfma_per_wave % 8 || mfma_per_wave > (1 << 24) ||
+      !d_sink || (reinterpret_cast<uintptr_t>(d_sink) & 3))
+    return MOE_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(probe_mfma_bf16_kernel, dim3(n_workgroups), dim3(kProbeThreads), 0, static_cast<hipStream_t>(stream),
+                     mfma_per_wave, random_operands ? 1 : 0, static_cast<float*>(d_sink));
+  return launch_status();
+}
+
+int moe_probe_copy(const void* d_src, void* d_dst, size_t bytes, void* stream) {
+  if (!d_src || !d_dst || bytes % 16 || ((reinterpret_cast<uintptr_t>(d_src) | reinterpret_cast<uintptr_t>(d_dst)) & 15))
+    return MOE_ERR_INVALID_ARG;
+  if (bytes == 0) return MOE_OK;
+  const size_t n16 = bytes / 16;
+  const size_t want = (n16 + kProbeThreads - 1) / kProbeThreads;
+  const int grid = (int)(want < (size_t)(device_cus() * 8) ? want : (size_t)(device_cus() * 8));
+  hipLaunchKernelGGL(probe_copy_kernel, dim3(grid), dim3(kProbeThreads), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const u32x4*>(d_src), static_cast<u32x4*>(d_dst), n16);
   return launch_status();
 }
 

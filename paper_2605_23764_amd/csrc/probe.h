@@ -1,0 +1,56 @@
+// Ceiling probes: what this GPU sustains on the two resources the kernels of the
+// layer are priced against, measured with nothing else in the way.  They are
+// measurement aids for the benchmark (the roofline figures are quoted against the
+// datasheet peaks AND against these), not steps of the layer.
+//   mfma   register-only loop of v_mfma_f32_32x32x16_bf16, 4 waves per workgroup
+//          (one per SIMD), 8 independent accumulator blocks per wave so that the
+//          pipe never waits for a result; operands either all 1.0 or pseudo-random
+//          values in [1, 2): the rate depends on the data (power management).
+//   copy   grid-stride streaming copy, 16 bytes per lane, non-temporal both ways.
+#pragma once
+#include "common.h"
+
+namespace moe {
+
+constexpr int kProbeThreads = 256;
+
+__global__ __launch_bounds__(kProbeThreads) void probe_mfma_bf16_kernel(int n_mfma, int random_operands, float* sink) {
+  const int lane = threadIdx.x & 63;
+  uint32_t s = (blockIdx.x * kProbeThreads + threadIdx.x) * 2654435761u + 12345u;
+  bf16x8 a[4], b[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    uint32_t w[4], v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      // two bf16 per word: exponent of 1.0, 7 random mantissa bits each (or none)
+      s = s * 1664525u + 1013904223u;
+      w[j] = 0x3f803f80u | (random_operands ? ((s >> 9) & 0x007f007fu) : 0u);
+      s = s * 1664525u + 1013904223u;
+      v[j] = 0x3f803f80u | (random_operands ? ((s >> 9) & 0x007f007fu) : 0u);
+    }
+    a[i] = __builtin_bit_cast(bf16x8, u32x4{w[0], w[1], w[2], w[3]});
+    b[i] = __builtin_bit_cast(bf16x8, u32x4{v[0], v[1], v[2], v[3]});
+  }
+  f32x16 acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+  for (int m = 0; m < n_mfma; m += 8) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j & 3], b[(j >> 1) & 3], acc[j], 0, 0, 0);
+  }
+  float t = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) t += acc[i][lane & 15];
+  if (t == -1.f) sink[0] = t;   // never true (the sums are positive): keeps the loop alive
+}
+
+__global__ __launch_bounds__(kProbeThreads) void probe_copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * kProbeThreads;
+  for (size_t i = (size_t)blockIdx.x * kProbeThreads + threadIdx.x; i < n16; i += stride)
+    __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
+}  // namespace moe

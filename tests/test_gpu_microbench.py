@@ -83,3 +83,23 @@ def test_argument_errors_and_empty():
         with pytest.raises(moe.MoeError) as ei:
             moe.moe_microbench_swiglu_add(M, N, t, t, t, t, mode, rows, w)
         assert ei.value.status == status
+
+
+def test_ceiling_probes():
+    """The copy probe is a byte-exact copy (ragged size, several grid strides); the MFMA probe runs, leaves
+    its sink untouched and rejects bad arguments."""
+    for nbytes in (0, 16, 16 * 1000 + 16, 64 * 1024 * 1024 + 48):
+        src = torch.randint(0, 255, (nbytes + 16,), dtype=torch.uint8, device="cuda")
+        dst = torch.zeros_like(src)
+        moe.moe_probe_copy(src, dst, nbytes)
+        torch.cuda.synchronize()
+        assert torch.equal(dst[:nbytes], src[:nbytes]) and int(dst[nbytes:].sum()) == 0
+    sink = torch.full((1,), 3.0, dtype=torch.float32, device="cuda")
+    for rnd in (0, 1):
+        moe.moe_probe_mfma_bf16(64, 64, rnd, sink)
+    torch.cuda.synchronize()
+    assert float(sink[0]) == 3.0
+    with pytest.raises(moe.MoeError):
+        moe.moe_probe_mfma_bf16(64, 12, 1, sink)     # not a multiple of 8
+    with pytest.raises(moe.MoeError):
+        moe.moe_probe_copy(sink, sink, 8)            # not a multiple of 16
