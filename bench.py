@@ -30,15 +30,15 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 MEASURED_TRAFFIC_BYTES = {"c3": (975434.6 * 2.024 + 98108.0) * 1024}
 
 # Power bound.  The SMI sensors, polled from outside while `--hold` keeps one kernel running, show the GEMMs, the
-# whole forward and the whole backward at the 1400 W board limit with the clock pulled down to 1.97-2.17 GHz,
-# and the copy-like kernels at 880-960 W and 2.4 GHz.  Energy per unit of work from the probes at full rate
-# (register-only MFMAs on random data: 2.10 PFLOP/s at 1334 W; read-only, write-only and copy streams of random
-# data: 3.95 / 6.9 / 4.85 TB/s at 873 / 994 / 945 W; idle 292 W), carried here because a timed run cannot poll them.
+# whole forward and the whole backward at the 1400 W board limit with the clock pulled down to 1.9-2.2 GHz,
+# and the copy-like kernels at 890-990 W and 2.4 GHz.  Energy per unit of work from the probes at full rate
+# (register-only MFMAs on random data: 2.12 PFLOP/s at 1331 W; read-only, write-only and copy streams of random
+# data: 3.95 / 6.9 / 5.24 TB/s at 866 / 989 / 986 W; idle 294 W), carried here because a timed run cannot poll them.
 # A kernel cannot finish sooner than its MFMA + HBM energy divided by (cap - idle), whatever it overlaps.
-POWER_CAP_W, POWER_IDLE_W = 1400.0, 292.0
-PJ_PER_FLOP_MFMA_BF16 = (1334.0 - 292.0) / 2.10e15 * 1e12
-PJ_PER_BYTE_READ = (873.0 - 292.0) / 3.95e12 * 1e12
-PJ_PER_BYTE_WRITE = 2 * (945.0 - 292.0) / 4.85e12 * 1e12 - PJ_PER_BYTE_READ
+POWER_CAP_W, POWER_IDLE_W = 1400.0, 294.0
+PJ_PER_FLOP_MFMA_BF16 = (1331.0 - POWER_IDLE_W) / 2.12e15 * 1e12
+PJ_PER_BYTE_READ = (866.0 - POWER_IDLE_W) / 3.95e12 * 1e12
+PJ_PER_BYTE_WRITE = 2 * (986.0 - POWER_IDLE_W) / 5.24e12 * 1e12 - PJ_PER_BYTE_READ
 
 
 def power_floor_us(flops, bytes_read, bytes_written):
@@ -330,6 +330,9 @@ def main():
             "algorithmic_GBs": bytes_b / (bwd_ms * 1e-3) / 1e9, "algorithmic_bytes": bytes_b,
             "frac_of_hbm_peak": bytes_b / (bwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         }
+        if cfg.dtype == "bf16":   # about half of the backward's bytes are reads, half writes
+            fb = power_floor_us(flops_b, bytes_b / 2, bytes_b / 2)
+            res["detail"]["backward"].update({"power_floor_us": fb, "power_frac": fb / (bwd_ms * 1e3)})
 
     if not args.no_cpu_baseline:
         import oracle

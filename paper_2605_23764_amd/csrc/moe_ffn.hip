@@ -645,7 +645,7 @@ int moe_probe_copy(const void* d_src, void* d_dst, size_t bytes, void* stream) {
     return MOE_ERR_INVALID_ARG;
   if (bytes == 0) return MOE_OK;
   const size_t n16 = bytes / 16;
-  const size_t want = (n16 + kProbeThreads - 1) / kProbeThreads;
+  const size_t want = (n16 + (size_t)kProbeThreads * kProbeCopyUnroll - 1) / ((size_t)kProbeThreads * kProbeCopyUnroll);
   const int grid = (int)(want < (size_t)(device_cus() * 8) ? want : (size_t)(device_cus() * 8));
   hipLaunchKernelGGL(probe_copy_kernel, dim3(grid), dim3(kProbeThreads), 0, static_cast<hipStream_t>(stream),
                      static_cast<const u32x4*>(d_src), static_cast<u32x4*>(d_dst), n16);

@@ -6,7 +6,8 @@
 //          (one per SIMD), 8 independent accumulator blocks per wave so that the
 //          pipe never waits for a result; operands either all 1.0 or pseudo-random
 //          values in [1, 2): the rate depends on the data (power management).
-//   copy   grid-stride streaming copy, 16 bytes per lane, non-temporal both ways.
+//   copy   streaming copy in contiguous 32 KB blocks per workgroup, 16 bytes per lane and
+//          access, 8 loads in flight per lane, non-temporal both ways.
 #pragma once
 #include "common.h"
 
@@ -47,10 +48,25 @@ __global__ __launch_bounds__(kProbeThreads) void probe_mfma_bf16_kernel(int n_mf
   if (t == -1.f) sink[0] = t;   // never true (the sums are positive): keeps the loop alive
 }
 
+// A workgroup moves contiguous 32 KB blocks: 8 rounds of 4 KB, all 8 loads of a lane in flight before its stores.
+constexpr int kProbeCopyUnroll = 8;
 __global__ __launch_bounds__(kProbeThreads) void probe_copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t n16) {
-  const size_t stride = (size_t)gridDim.x * kProbeThreads;
-  for (size_t i = (size_t)blockIdx.x * kProbeThreads + threadIdx.x; i < n16; i += stride)
-    __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+  constexpr size_t kBlock = (size_t)kProbeThreads * kProbeCopyUnroll;   // 16-byte units per block
+  const size_t n_blocks = (n16 + kBlock - 1) / kBlock;
+  for (size_t b = blockIdx.x; b < n_blocks; b += gridDim.x) {
+    const size_t i0 = b * kBlock + threadIdx.x;
+    u32x4 v[kProbeCopyUnroll];
+#pragma unroll
+    for (int j = 0; j < kProbeCopyUnroll; ++j) {
+      const size_t i = i0 + (size_t)j * kProbeThreads;
+      if (i < n16) v[j] = __builtin_nontemporal_load(src + i);
+    }
+#pragma unroll
+    for (int j = 0; j < kProbeCopyUnroll; ++j) {
+      const size_t i = i0 + (size_t)j * kProbeThreads;
+      if (i < n16) __builtin_nontemporal_store(v[j], dst + i);
+    }
+  }
 }
 
 }  // namespace moe
