@@ -223,6 +223,22 @@ def main():
     if with_bwd:
         step(moe.MODE_SERIALIZED)          # saved activations the backward reads
         bwd_ms = timed(step_bwd, args.steps, args.warmup)
+    # training step that keeps no permuted copy of x (MoeSaved.Xp = NULL): GEMM-1 and w1_grad read x through the
+    # permutation; reported beside the headline, which runs the explicit Dispatch permute
+    noxp_ms, noxp_bwd_ms = {}, None
+    if cfg.dtype == "bf16":
+        saved_nx = moe.alloc_saved(shape, store_h1=with_bwd, keep_xp=False)
+        for name, mode in modes.items():
+            if name in ms:
+                noxp_ms[name] = timed(lambda: moe.moe_ffn_forward(shape, dev["x"], dev["logits"], dev["w_gate_up"],
+                                                                  dev["w_down"], out, saved_nx, ws, mode),
+                                      args.steps, args.warmup)
+        if with_bwd:
+            moe.moe_ffn_forward(shape, dev["x"], dev["logits"], dev["w_gate_up"], dev["w_down"], out, saved_nx, ws,
+                                moe.MODE_SERIALIZED)
+            noxp_bwd_ms = timed(lambda: moe.moe_ffn_backward(shape, dy, dev["x"], dev["w_gate_up"], dev["w_down"], saved_nx,
+                                                             dx, dw1, dw2, dtw, ws_b), args.steps, args.warmup)
+        del saved_nx
 
     # ---- per-operator durations: the serialized sequence with HIP events between launches
     stages = [
@@ -290,6 +306,8 @@ def main():
         "detail": {
             "us_per_layer": {k: v * 1e3 for k, v in ms.items()},
             "us_per_layer_inference": {k: v * 1e3 for k, v in infer_ms.items()},
+            "us_per_layer_no_permuted_copy": {k: v * 1e3 for k, v in noxp_ms.items()},
+            "backward_us_no_permuted_copy": noxp_bwd_ms * 1e3 if noxp_bwd_ms is not None else None,
             "us_per_layer_events": spread,
             "us_per_layer_cold": cold,
             "stage_us": stage_us,

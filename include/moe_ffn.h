@@ -78,7 +78,10 @@ typedef struct MoeShape {
  *   row_of   [T,k]  i32  row of slot (t,j) in expert-contiguous order, -1 if
  *                        the slot's expert is not local
  *   token_of [R_max] i32, slot_of [R_max] i32  inverse maps (first R entries)
- *   Xp [R_max,H]  dispatched tokens          (dtype)
+ *   Xp [R_max,H]  dispatched tokens          (dtype)  may be NULL: no permuted copy is
+ *                        kept; bf16 GEMM-1 and the backward's w1_grad then read x through
+ *                        token_of (Section 4.2: no extra trip through HBM), other cases
+ *                        make the copy in workspace memory
  *   H1 [R_max,2I] GEMM-1 output, gate|up     (dtype)  may be NULL: not stored
  *   A  [R_max,I]  SwiGLU output              (dtype)
  *   Yp [R_max,H]  GEMM-2 output              (dtype)
@@ -122,10 +125,10 @@ int moe_ffn_workspace_bytes(const MoeShape* shape, size_t* fwd_bytes, size_t* bw
  *   d_w_gate_up[E_local,H,2I]   dtype, gate = columns 0..I-1, up = I..2I-1
  *   d_w_down   [E_local,I,H]    dtype
  *   d_out      [T,H]            dtype (overwritten)
- *   saved      nullable; if non-NULL every member except H1 must be non-NULL.
- *              NULL (inference): only `out` is produced; with bf16 the first grouped
- *              GEMM then reads the token rows of x through the permutation and the
- *              permuted copy is not made at all
+ *   saved      nullable; if non-NULL every member except H1 and Xp must be non-NULL.
+ *              NULL (inference): only `out` is produced.  Without a caller's Xp (saved
+ *              NULL or saved->Xp NULL) the first grouped bf16 GEMM reads the token rows
+ *              of x through the permutation and the permuted copy is not made at all
  *   d_workspace, workspace_bytes  >= moe_ffn_workspace_bytes(...).fwd_bytes
  *   mode       MoeMode
  * Returns after enqueueing.  A scheduler timeout (MOE_MODE_PERSISTENT only) is
@@ -141,6 +144,8 @@ int moe_ffn_forward(const MoeShape* shape, const void* d_x, const float* d_logit
  * w2_grad, SwiGLU_grad, gate_grad, w1_grad, backward Combine) plus the
  * gradient of the routing weights.  `saved` must come from a forward call with
  * H1 stored, on the same inputs.
+ *   d_x           [T,H]  dtype   the forward's input; read only if saved->Xp is NULL
+ *                                (then required, as is saved->token_of)
  *   d_dy          [T,H]  dtype   upstream gradient
  *   d_dx          [T,H]  dtype   overwritten; zero rows for tokens with no local slot
  *   d_dw_gate_up  [E_local,H,2I] dtype, overwritten (zeros for experts with no rows)

@@ -103,7 +103,7 @@ class Saved:
     row_of: torch.Tensor
     token_of: torch.Tensor
     slot_of: torch.Tensor
-    Xp: torch.Tensor
+    Xp: Optional[torch.Tensor]
     H1: Optional[torch.Tensor]
     A: torch.Tensor
     Yp: torch.Tensor
@@ -113,7 +113,9 @@ class Saved:
         return _MoeSaved(*(f(getattr(self, n)) for n, _ in _MoeSaved._fields_))
 
 
-def alloc_saved(shape: _MoeShape, device="cuda", store_h1: bool = False) -> Saved:
+def alloc_saved(shape: _MoeShape, device="cuda", store_h1: bool = False, keep_xp: bool = True) -> Saved:
+    """keep_xp=False: no permuted copy of x is kept (MoeSaved.Xp = NULL); forward and backward then read x through
+    the permutation."""
     T, H, I, k, El = shape.T, shape.H, shape.I, shape.k, shape.E_local
     Rm = T * min(k, El)
     dt = _torch_dtype(shape)
@@ -127,7 +129,7 @@ def alloc_saved(shape: _MoeShape, device="cuda", store_h1: bool = False) -> Save
         row_of=torch.empty(T * k + 4, **i32)[: T * k].view(T, k),
         token_of=torch.empty(Rm + 4, **i32)[:Rm],
         slot_of=torch.empty(Rm + 4, **i32)[:Rm],
-        Xp=torch.empty(Rm * H + 8, dtype=dt, device=device)[: Rm * H].view(Rm, H),
+        Xp=torch.empty(Rm * H + 8, dtype=dt, device=device)[: Rm * H].view(Rm, H) if keep_xp else None,
         H1=torch.empty(Rm * 2 * I + 8, dtype=dt, device=device)[: Rm * 2 * I].view(Rm, 2 * I) if store_h1 else None,
         A=torch.empty(Rm * I + 8, dtype=dt, device=device)[: Rm * I].view(Rm, I),
         Yp=torch.empty(Rm * H + 8, dtype=dt, device=device)[: Rm * H].view(Rm, H),

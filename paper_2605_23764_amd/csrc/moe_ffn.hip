@@ -101,11 +101,12 @@ struct Ctx {
   MoeSaved sv;      // resolved buffers (caller's or workspace fallback)
   hipStream_t stream;
   int n_cu;
-  bool keep_xp;     // the caller passed MoeSaved: the permuted copy of x is an output
+  bool keep_xp;     // the caller passed MoeSaved with Xp: the permuted copy of x is an output
 };
 
-// Inference (no MoeSaved): nobody reads the permuted copy of x, so bf16 GEMM-1 applies the permutation
-// while loading (32-bit offsets: x must span < 4 GB) and the PERMUTE step is dropped.
+// No MoeSaved (inference) or MoeSaved without Xp (the backward then reads x through the permutation as
+// well): nobody reads a permuted copy of x, so bf16 GEMM-1 applies the permutation while loading (32-bit
+// offsets: x must span < 4 GB) and the PERMUTE step is dropped.
 bool gathers_x(const Ctx& c) {
   return !c.keep_xp && c.s.dtype == MOE_BF16 && (size_t)c.s.T * c.s.H * 2 < ((size_t)1 << 32);
 }
@@ -134,14 +135,15 @@ int make_ctx(Ctx& c, const MoeShape* shape, const MoeSaved* saved, void* ws, siz
   if (ws_bytes < c.L.fwd_total) return MOE_ERR_WORKSPACE_TOO_SMALL;
   c.ws = static_cast<char*>(ws);
   c.stream = static_cast<hipStream_t>(stream);
-  c.keep_xp = saved != nullptr;
+  c.keep_xp = saved != nullptr && saved->Xp != nullptr;
   if (saved) {
     c.sv = *saved;
     const void* must[] = {saved->topk_idx, saved->topk_w, saved->counts, saved->offsets, saved->row_of,
-                          saved->token_of, saved->slot_of, saved->Xp, saved->A, saved->Yp};
+                          saved->token_of, saved->slot_of, saved->A, saved->Yp};
     for (const void* q : must)
       if (!q || !aligned16(q)) return MOE_ERR_INVALID_ARG;
-    if (saved->H1 && !aligned16(saved->H1)) return MOE_ERR_INVALID_ARG;
+    if ((saved->H1 && !aligned16(saved->H1)) || (saved->Xp && !aligned16(saved->Xp))) return MOE_ERR_INVALID_ARG;
+    if (!saved->Xp) c.sv.Xp = c.ws + c.L.Xp;   // scratch for the paths that cannot gather (fp32, x of 4 GB or more)
   } else {
     const Layout& L = c.L;
     c.sv.topk_idx = reinterpret_cast<int32_t*>(c.ws + L.topk_idx);
@@ -360,9 +362,13 @@ struct BwdCtx {
 
 // Weight gradient of one GEMM: experts with up to 384 rows go to the register-stationary kernel when
 // the output splits into full 256 x 128 tiles, everything else to the general kernel.
-void launch_wgrad_bf16(GemmParams p, int grid, int n_cu, hipStream_t stream) {
+bool wgrad_panel_fits(int M, int N) { return M % kWpM == 0 && N % kWpN == 0; }
+
+// p.gather != nullptr: the register-stationary kernel reads the rows of p.A through it; the general kernel
+// reads `a_general`, in which the caller has placed the rows of the experts that kernel takes.
+void launch_wgrad_bf16(GemmParams p, int grid, int n_cu, hipStream_t stream, const __bf16* a_general = nullptr) {
   p.k_lo = 0;
-  if (p.M % kWpM == 0 && p.N % kWpN == 0) {
+  if (wgrad_panel_fits(p.M, p.N)) {
     const int n_nt = p.N / kWpN, panels = p.E_local * (p.M / kWpM);
     int n_split = 1;   // smallest divisor of the tile count that gives every CU about four items
     for (int d = 1; d <= n_nt; ++d)
@@ -370,11 +376,12 @@ void launch_wgrad_bf16(GemmParams p, int grid, int n_cu, hipStream_t stream) {
     hipLaunchKernelGGL(grouped_wgrad_panel_bf16_kernel, dim3(grid), dim3(kWpThreads), 0, stream, p, n_split);
     p.k_lo = kWpMaxRows + 1;
   }
+  if (p.gather) { p.A = a_general; p.gather = nullptr; }
   hipLaunchKernelGGL(grouped_wgrad2_bf16_kernel, dim3(2 * grid), dim3(kGemmThreads), 0, stream, p);
 }
 
 template <typename T>
-int run_backward(const BwdCtx& c, const void* dy, const void* w_gate_up, const void* w_down, void* dx,
+int run_backward(const BwdCtx& c, const void* dy, const void* x, const void* w_gate_up, const void* w_down, void* dx,
                  void* dw_gate_up, void* dw_down, float* d_topk_w) {
   constexpr bool BF16 = std::is_same<T, __bf16>::value;
   const MoeShape& s = c.s;
@@ -426,6 +433,37 @@ int run_backward(const BwdCtx& c, const void* dy, const void* w_gate_up, const v
     if constexpr (BF16) launch_wgrad_bf16(p, grid, c.n_cu, c.stream);
     else hipLaunchKernelGGL(grouped_wgrad_f32_kernel, dim3(grid), dim3(256), 0, c.stream, p);
   }
+  // w1_grad: dW_gate_up[e] = Xp_e^T dH1_e.  Runs ahead of gate_grad so that, when the forward kept no
+  // permuted copy (saved->Xp == NULL), the dXp buffer can first hold the rows of Xp that are needed here.
+  {
+    P p{};
+    p.A = static_cast<const T*>(c.sv.Xp); p.B = dH1; p.C = static_cast<T*>(dw_gate_up);
+    p.strideC = (long)s.H * 2 * s.I; p.M = s.H; p.N = 2 * s.I;
+    p.lda = s.H; p.ldb = 2 * s.I; p.ldc = 2 * s.I;
+    p.n_ntiles = ceil_div(2 * s.I, tn);
+    if constexpr (!BF16) p.n_mtiles = ceil_div(s.H, bm);
+    p.E_local = s.E_local; p.offsets = c.sv.offsets;
+    if (!c.sv.Xp) {
+      PermuteParams pp;
+      pp.x = x; pp.Xp = dXp; pp.token_of = c.sv.token_of; pp.meta = c.tiles.meta;
+      pp.H = s.H; pp.elem_bytes = elem_bytes(s);
+      const long want = ((long)r_max(s) + 3) / 4;
+      const int g = (int)(want < (long)c.n_cu * 8 ? (want > 0 ? want : 1) : (long)c.n_cu * 8);
+      bool gather = false;
+      if constexpr (BF16) gather = (size_t)s.T * s.H * 2 < ((size_t)1 << 32);   // 32-bit row offsets
+      if (gather) {
+        // only the rows the general kernel will read: experts above the other kernel's limit, or all of them
+        const int k_lo = wgrad_panel_fits(p.M, p.N) ? kWpMaxRows + 1 : 0;
+        hipLaunchKernelGGL(permute_large_experts_kernel, dim3(g), dim3(256), 0, c.stream, pp, c.sv.offsets, s.E_local, k_lo);
+        if constexpr (BF16) { p.A = static_cast<const T*>(x); p.gather = c.sv.token_of; }
+      } else {
+        hipLaunchKernelGGL(permute_kernel, dim3(g), dim3(256), 0, c.stream, pp);
+        p.A = dXp;
+      }
+    }
+    if constexpr (BF16) launch_wgrad_bf16(p, grid, c.n_cu, c.stream, dXp);
+    else hipLaunchKernelGGL(grouped_wgrad_f32_kernel, dim3(grid), dim3(256), 0, c.stream, p);
+  }
   // gate_grad: dXp = dH1 W_gate_up^T
   {
     P p{};
@@ -438,18 +476,6 @@ int run_backward(const BwdCtx& c, const void* dy, const void* w_gate_up, const v
       hipLaunchKernelGGL((grouped_gemm_bf16_kernel<kLayNT, kEpiStore>), dim3(grid), dim3(kGemmThreads), 0, c.stream, p);
     else
       hipLaunchKernelGGL(grouped_dgrad_f32_kernel<kEpiStore>, dim3(grid), dim3(256), 0, c.stream, p);
-  }
-  // w1_grad: dW_gate_up[e] = Xp_e^T dH1_e
-  {
-    P p{};
-    p.A = static_cast<const T*>(c.sv.Xp); p.B = dH1; p.C = static_cast<T*>(dw_gate_up);
-    p.strideC = (long)s.H * 2 * s.I; p.M = s.H; p.N = 2 * s.I;
-    p.lda = s.H; p.ldb = 2 * s.I; p.ldc = 2 * s.I;
-    p.n_ntiles = ceil_div(2 * s.I, tn);
-    if constexpr (!BF16) p.n_mtiles = ceil_div(s.H, bm);
-    p.E_local = s.E_local; p.offsets = c.sv.offsets;
-    if constexpr (BF16) launch_wgrad_bf16(p, grid, c.n_cu, c.stream);
-    else hipLaunchKernelGGL(grouped_wgrad_f32_kernel, dim3(grid), dim3(256), 0, c.stream, p);
   }
   // backward Combine: dX[t] = sum over local slots of dXp[row_of[t,j]]
   {
@@ -572,10 +598,12 @@ int moe_ffn_backward(const MoeShape* shape, const void* d_dy, const void* d_x, c
   if (workspace_bytes < c.L.total) return MOE_ERR_WORKSPACE_TOO_SMALL;
   const void* must[] = {d_dy, d_w_gate_up, d_w_down, d_dx, d_dw_gate_up, d_dw_down, d_dtopk_w,
                         saved->topk_w, saved->counts, saved->offsets, saved->row_of,
-                        saved->Xp, saved->H1, saved->A, saved->Yp};
+                        saved->H1, saved->A, saved->Yp};
   for (const void* q : must)
     if (!q || !aligned16(q)) return MOE_ERR_INVALID_ARG;
-  (void)d_x;   // the dispatched copy saved->Xp is used instead
+  // the dispatched copy saved->Xp is used if the forward kept one; otherwise x is read through the permutation
+  if (saved->Xp ? !aligned16(saved->Xp) : (!d_x || !aligned16(d_x) || !saved->token_of || !aligned16(saved->token_of)))
+    return MOE_ERR_INVALID_ARG;
   c.ws = static_cast<char*>(d_workspace);
   c.sv = *saved;
   c.stream = static_cast<hipStream_t>(stream);
@@ -585,8 +613,8 @@ int moe_ffn_backward(const MoeShape* shape, const void* d_dy, const void* d_x, c
   c.tiles.rows = reinterpret_cast<int32_t*>(c.ws + c.L.tile_rows);
   c.tiles.meta = reinterpret_cast<int32_t*>(c.ws + c.L.meta);
   return c.s.dtype == MOE_BF16
-             ? run_backward<__bf16>(c, d_dy, d_w_gate_up, d_w_down, d_dx, d_dw_gate_up, d_dw_down, d_dtopk_w)
-             : run_backward<float>(c, d_dy, d_w_gate_up, d_w_down, d_dx, d_dw_gate_up, d_dw_down, d_dtopk_w);
+             ? run_backward<__bf16>(c, d_dy, d_x, d_w_gate_up, d_w_down, d_dx, d_dw_gate_up, d_dw_down, d_dtopk_w)
+             : run_backward<float>(c, d_dy, d_x, d_w_gate_up, d_w_down, d_dx, d_dw_gate_up, d_dw_down, d_dtopk_w);
 }
 
 // workspace: queue headers and status word | event counters [n_tiles] | rings; sized for one-row tiles

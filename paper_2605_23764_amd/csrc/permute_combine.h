@@ -53,6 +53,22 @@ __global__ __launch_bounds__(256) void permute_kernel(PermuteParams p) {
     permute_rows<4>(p, r0, min(R, r0 + n_waves), wave, n_waves);
 }
 
+// The same copy for the rows of experts with at least k_lo rows only (offsets: E_local + 1 prefix sums of
+// the rows per expert).  Used by the backward when the forward kept no permuted copy: the register-
+// stationary weight-gradient kernel reads x through the permutation itself, the general kernel (experts
+// above its row limit) reads this partial copy.
+__global__ __launch_bounds__(256) void permute_large_experts_kernel(PermuteParams p, const int32_t* offsets, int E_local,
+                                                                    int k_lo) {
+  const int n_waves = blockDim.x / kWave;
+  const int wave = threadIdx.x / kWave;
+  for (int e = 0; e < E_local; ++e) {
+    const int seg0 = offsets[e], seg1 = offsets[e + 1];
+    if (seg1 - seg0 < k_lo) continue;
+    for (int r0 = seg0 + blockIdx.x * n_waves; r0 < seg1; r0 += gridDim.x * n_waves)
+      permute_rows<4>(p, r0, min(seg1, r0 + n_waves), wave, n_waves);
+  }
+}
+
 struct CombineParams {
   const void* Yp;          // [R_max,H]
   void* out;               // [T,H]

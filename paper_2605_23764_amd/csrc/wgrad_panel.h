@@ -37,12 +37,17 @@ constexpr int kWpMaxKC = 6;                        // 64-row chunks: rows_e <= 3
 constexpr int kWpMaxRows = kWpMaxKC * kWpBK;
 constexpr int kWpLoads = 16 / kWpWaves;            // wave-wide loads per wave per entry (2)
 constexpr int kWpEpiStores = 8;                    // store instructions per wave per epilogue
-constexpr int kWpLdsBytes = kWpDepth * kWpSlot + kWpWaves * kEpiWaveBytes;   // 148 KB
+constexpr int kWpTokBytes = 2048;                  // gathered A: byte offset of every row of the expert's segment (<= 384 x 4 B)
+constexpr int kWpTokOff = kWpDepth * kWpSlot + kWpWaves * kEpiWaveBytes;
+constexpr int kWpLdsBytes = kWpTokOff + kWpTokBytes;                          // 150 KB
+static_assert(kWpMaxRows * 4 <= kWpTokBytes, "row-offset table");
 static_assert(kWpLdsBytes <= kGemmLdsBytes, "LDS budget");
 
 struct WpCtx {
   const char* a_base;      // uniform: first row of the expert's segment in A / B, byte addresses
-  const char* b_base;
+  const char* b_base;      //          (gathered A: row 0 of the whole matrix, rows found through a_rows)
+  const __attribute__((address_space(3))) uint32_t* a_rows;   // gathered A: byte offset of segment row k, else unused
+  int gathered;
   uint32_t lane_col;       // per lane: byte offset of the column chunk it fetches inside a 128-column line
   uint32_t a_rd;           // transpose-read offset of this wave's 32-row block inside a panel entry
   uint32_t b_rd[4];        // ... of the four 32-column blocks inside a B entry
@@ -72,6 +77,7 @@ __device__ __forceinline__ void wp_issue_entry(const WpCtx& t, int g) {
   const uint32_t slot = uniform_u32(t.lds0 + (uint32_t)(g % kWpDepth) * kWpSlot);
   const char* base;
   int kc, col, ld_bytes;
+  const bool a_rows = g < 2 * KC && t.gathered;   // uniform
   if (g < 2 * KC) {
     kc = g >> 1;
     col = t.a_col0 + (g & 1) * 128;
@@ -90,7 +96,8 @@ __device__ __forceinline__ void wp_issue_entry(const WpCtx& t, int g) {
   for (int i = 0; i < kWpLoads; ++i) {
     const int L = t.wave * kWpLoads + i;                                   // line = group of 4 k-rows
     const int krow = min(kc * kWpBK + L * 4 + t.kk, t.k_rows - 1);         // rows past the segment: re-read; masked in the panel
-    lds_dma16(base, (uint32_t)(krow * ld_bytes) + col_bytes, slot + L * kLine);
+    const uint32_t row_bytes = a_rows ? t.a_rows[krow] : (uint32_t)(krow * ld_bytes);
+    lds_dma16(base, row_bytes + col_bytes, slot + L * kLine);
   }
 }
 
@@ -267,6 +274,8 @@ __device__ __forceinline__ void wp_item(const WpCtx& t, int row0, char* smem) {
 
 // Launch condition: p.M % 256 == 0, p.N % 128 == 0, (p.N / 128) % n_split == 0.  Experts with more than
 // 384 rows are left alone (the general kernel takes them); experts without rows get zeros.
+// p.gather != nullptr: row k of expert e's segment of A is row p.gather[offsets[e] + k] of p.A (the
+// dispatch permutation applied while loading; the caller guarantees that p.A spans < 4 GB).
 __global__ __launch_bounds__(kWpThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void grouped_wgrad_panel_bf16_kernel(GemmParams p, int n_split) {
   __shared__ __attribute__((aligned(1024))) char smem[kWpLdsBytes];
@@ -296,8 +305,17 @@ void grouped_wgrad_panel_bf16_kernel(GemmParams p, int n_split) {
     t.NT = NT;
     t.lda_bytes = p.lda * 2;
     t.ldb_bytes = p.ldb * 2;
-    t.a_base = uniform_ptr(reinterpret_cast<const char*>(p.A + (size_t)seg0 * p.lda));
+    t.gathered = p.gather != nullptr;
+    t.a_base = uniform_ptr(reinterpret_cast<const char*>(t.gathered ? p.A : p.A + (size_t)seg0 * p.lda));
     t.b_base = uniform_ptr(reinterpret_cast<const char*>(p.B + (size_t)seg0 * p.ldb));
+    t.a_rows = (const __attribute__((address_space(3))) uint32_t*)(smem + kWpTokOff);
+    if (t.gathered) {
+      // every item closes with a barrier, so nobody still reads the previous item's table
+      if ((int)threadIdx.x < cnt)
+        ((__attribute__((address_space(3))) uint32_t*)(smem + kWpTokOff))[threadIdx.x] =
+            (uint32_t)p.gather[seg0 + threadIdx.x] * (uint32_t)(p.lda * 2);
+      __syncthreads();
+    }
     t.a_col0 = mp * kWpM;
     t.b_col0 = sp * NT * kWpN;
     // lane -> (k-row kk of the line, position lane % 16) holds column chunk (position - 4*kk) mod 16

@@ -119,6 +119,61 @@ def test_panel_kernel_with_empty_experts():
     assert torch.all(bwd.dw_gate_up[2] == 0) and torch.all(bwd.dw_down[5] == 0)
 
 
+# without a kept permuted copy (MoeSaved.Xp = NULL): GEMM-1 and w1_grad read x through the permutation.
+# Cases: register-stationary kernel only; both weight-gradient kernels (experts above 384 rows take the
+# partial copy); shapes the register-stationary kernel cannot take (everything through the copy); tiny
+# experts and experts without rows; fp32 (full copy in workspace memory).
+NO_XP = [SMALL[i] for i in (0, 3, 4, 9, 11, 12, 13, 14)] + [
+    ("b_bf16_noxp_big", 2600, 256, 256, 4, 4, 0, 2, "bf16", 61),     # ~1300 rows/expert: general kernel only
+    ("b_bf16_noxp_mix", 1900, 512, 256, 16, 9, 2, 3, "bf16", 62),    # a mix around the 384-row limit
+]
+
+
+@pytest.mark.parametrize("mode", ["serialized", "persistent"])
+@pytest.mark.parametrize("case", NO_XP, ids=[c[0] for c in NO_XP])
+def test_without_permuted_copy(case, mode):
+    """Same values through the same kernels, so every gradient is bit-identical to the run that keeps Xp; the
+    forward's outputs likewise; and both satisfy the oracle."""
+    import paper_2605_23764_amd as moe
+    from gpu_common import check_backward, check_forward, check_routing, run_backward, run_forward, small_config
+    cfg = small_config(*case)
+    inp = make_inputs(cfg, with_dy=True)
+    if case[0] == "b_bf16_noxp_mix":
+        inp["logits"][:, 4] = -50.0                      # an expert without rows among them
+    m = moe.MODE_PERSISTENT if mode == "persistent" else moe.MODE_SERIALIZED
+    ref = oracle.forward(inp["x"], inp["logits"], inp["w_gate_up"], inp["w_down"], cfg.k, cfg.expert_base, cfg.E_local)
+    ref_b = oracle.backward(inp["dy"], ref, inp["w_gate_up"], inp["w_down"])
+    kept = run_forward(cfg, inp, mode=m, store_h1=True)
+    print(cfg.name, mode, "counts", ref["counts"][:10].tolist(), flush=True)
+    run = run_forward(cfg, inp, mode=m, store_h1=True, keep_xp=False)
+    assert run.saved.Xp is None
+    check_routing(run, ref)
+    check_forward(run, ref, cfg.dtype, store_h1=True)
+    R = int(ref["offsets"][-1])
+    assert torch.equal(run.out, kept.out)
+    for name in ("A", "H1", "Yp"):
+        assert torch.equal(getattr(run.saved, name)[:R], getattr(kept.saved, name)[:R]), name
+    bwd_kept = run_backward(cfg, inp, kept)
+    bwd = run_backward(cfg, inp, run)
+    check_backward(bwd, ref_b, ref["counts"], cfg.dtype)
+    assert torch.equal(bwd.dw_gate_up, bwd_kept.dw_gate_up) and torch.equal(bwd.dw_down, bwd_kept.dw_down)
+    assert torch.equal(bwd.dx, bwd_kept.dx) and torch.equal(bwd.dtopk_w, bwd_kept.dtopk_w)
+
+
+def test_without_permuted_copy_c5_full():
+    import paper_2605_23764_amd as moe
+    from gpu_common import check_backward, check_forward, run_backward, run_forward
+    cfg = CONFIGS["c5"]
+    inp = make_inputs(cfg, with_dy=True)
+    ref = oracle.forward(inp["x"], inp["logits"], inp["w_gate_up"], inp["w_down"], cfg.k, cfg.expert_base, cfg.E_local)
+    ref_b = oracle.backward(inp["dy"], ref, inp["w_gate_up"], inp["w_down"])
+    run = run_forward(cfg, inp, store_h1=True, keep_xp=False)
+    check_forward(run, ref, cfg.dtype, store_h1=True)
+    bwd = run_backward(cfg, inp, run)
+    errs = check_backward(bwd, ref_b, ref["counts"], cfg.dtype)
+    print("c5 without Xp", {k: "%.2e" % v for k, v in errs.items()}, flush=True)
+
+
 def test_backward_argument_errors():
     import paper_2605_23764_amd as moe
     from gpu_common import run_forward, small_config
@@ -138,6 +193,10 @@ def test_backward_argument_errors():
     with pytest.raises(moe.MoeError) as ei:
         moe.moe_ffn_backward(*args, ws[:1024])
     assert ei.value.status == -3
+    no_xp = run_forward(cfg, inp, store_h1=True, keep_xp=False)
+    with pytest.raises(moe.MoeError) as ei:      # without a kept permuted copy the backward needs x
+        moe.moe_ffn_backward(run.shape, dy, None, run.dev["w_gate_up"], run.dev["w_down"], no_xp.saved, dx, dw1, dw2, dtw, ws)
+    assert ei.value.status == -1
     no_h1 = moe.alloc_saved(run.shape, store_h1=False)
     with pytest.raises(moe.MoeError) as ei:      # saved without the GEMM-1 pre-activations
         moe.moe_ffn_backward(run.shape, dy, run.dev["x"], run.dev["w_gate_up"], run.dev["w_down"], no_h1,
