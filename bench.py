@@ -23,11 +23,11 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 
 # HBM bytes per launch of the dominant kernel (grouped GEMM-1 + SwiGLU), from separate
-# `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` runs of this command: counter KiB per
-# dispatch, FETCH_SIZE scaled by 2.024 and WRITE_SIZE by 1.000 (what the same counters read
-# for the permute kernel, a plain copy of known size).  Counters cannot be read inside a
+# `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` runs of `bench.py --headline-only`: counter KiB per
+# dispatch, FETCH_SIZE scaled by 2.0000 and WRITE_SIZE by 0.9999 (2 097 152 KiB divided by what the same
+# counters read for the 2 GiB copy of `moe_probe_copy` in the same run).  Counters cannot be read inside a
 # timed run, so the figure of the last profiled build is carried here.
-MEASURED_TRAFFIC_BYTES = {"c3": (975434.6 * 2.024 + 98108.0) * 1024}
+MEASURED_TRAFFIC_BYTES = {"c3": (976169.3 * 2.0000 + 98876.0 * 0.9999) * 1024}
 
 # Power bound.  The SMI sensors, polled from outside while `--hold` keeps one kernel running, show the GEMMs, the
 # whole forward and the whole backward at the 1400 W board limit with the clock pulled down to 1.9-2.2 GHz,
@@ -54,6 +54,9 @@ def main():
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-backward", action="store_true")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="time only the ceiling probes, the headline step, the backward and the stages (no inference / "
+                         "cold / no-copy variants): the form the rocprofv3 summaries are taken from")
     ap.add_argument("--hold", default=None, metavar="STAGE:SECONDS[,STAGE:SECONDS...]",
                     help="instead of the benchmark, run each named stage (idle, route, permute, gemm1_swiglu, gemm2, "
                          "combine, forward, backward, probe_mfma_random, probe_mfma_ones, probe_copy, torch_read_sum, "
@@ -174,7 +177,7 @@ def main():
     # reported beside the headline, which keeps the saved tensors a training step needs
     infer_ms = {}
     for name, mode in modes.items():
-        if name in ms:
+        if name in ms and not args.headline_only:
             infer_ms[name] = timed(lambda: moe.moe_ffn_forward(shape, dev["x"], dev["logits"], dev["w_gate_up"],
                                                                dev["w_down"], out, None, ws, mode),
                                    args.steps, args.warmup)
@@ -184,17 +187,17 @@ def main():
     spread, cold = {}, {}
     n_sets = 3
     sets = [(dev, saved, ws, out)]
-    for _ in range(n_sets - 1):
+    for _ in range(0 if args.headline_only else n_sets - 1):
         sets.append(({n: t.clone() for n, t in dev.items()}, moe.alloc_saved(shape, store_h1=with_bwd),
                      moe.alloc_workspace(shape), torch.empty_like(out)))
-    flush = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+    flush = torch.empty(1 if args.headline_only else 1 << 28, dtype=torch.float32, device="cuda")
 
     def step_set(mode, i):
         d, sv, w, o = sets[i % n_sets]
         moe.moe_ffn_forward(shape, d["x"], d["logits"], d["w_gate_up"], d["w_down"], o, sv, w, mode)
 
     for name, mode in modes.items():
-        if name in ms:
+        if name in ms and not args.headline_only:
             warm = sorted(timed_each(lambda i: step(mode), args.steps))
             spread[name] = {"median": warm[len(warm) // 2] * 1e3, "min": warm[0] * 1e3}
             for i in range(n_sets):
@@ -204,20 +207,22 @@ def main():
     del flush, sets
     # ceilings measured on this GPU with nothing else in the way (register-only MFMA loop with random / constant
     # operands: 256 workgroups x 4 waves x 65536 MFMAs of 32768 flop; 2 GiB streaming copy)
-    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
-    cp_src = torch.empty(1 << 29, dtype=torch.float32, device="cuda").normal_().view(torch.uint8)
-    cp_dst = torch.empty_like(cp_src)
-    n_wg, n_mfma = 256, 1 << 16
-    probe_ms = {
-        "mfma_random": timed(lambda: moe.moe_probe_mfma_bf16(n_wg, n_mfma, 1, sink), 5, 2),
-        "mfma_ones": timed(lambda: moe.moe_probe_mfma_bf16(n_wg, n_mfma, 0, sink), 5, 2),
-        "copy": timed(lambda: moe.moe_probe_copy(cp_src, cp_dst, cp_src.numel()), 10, 3),
-    }
-    probe_flop = n_wg * 4 * n_mfma * 32768.0
-    ceilings = {"mfma_bf16_random_operands_tflops": probe_flop / (probe_ms["mfma_random"] * 1e-3) / 1e12,
-                "mfma_bf16_constant_operands_tflops": probe_flop / (probe_ms["mfma_ones"] * 1e-3) / 1e12,
-                "copy_GBs_read_plus_write": 2.0 * cp_src.numel() / (probe_ms["copy"] * 1e-3) / 1e9}
-    del cp_src, cp_dst
+    ceilings = None
+    if True:   # also under --headline-only: the copy probe is the known-size kernel that calibrates the HBM counters
+        sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+        cp_src = torch.empty(1 << 29, dtype=torch.float32, device="cuda").normal_().view(torch.uint8)
+        cp_dst = torch.empty_like(cp_src)
+        n_wg, n_mfma = 256, 1 << 16
+        probe_ms = {
+            "mfma_random": timed(lambda: moe.moe_probe_mfma_bf16(n_wg, n_mfma, 1, sink), 5, 2),
+            "mfma_ones": timed(lambda: moe.moe_probe_mfma_bf16(n_wg, n_mfma, 0, sink), 5, 2),
+            "copy": timed(lambda: moe.moe_probe_copy(cp_src, cp_dst, cp_src.numel()), 10, 3),
+        }
+        probe_flop = n_wg * 4 * n_mfma * 32768.0
+        ceilings = {"mfma_bf16_random_operands_tflops": probe_flop / (probe_ms["mfma_random"] * 1e-3) / 1e12,
+                    "mfma_bf16_constant_operands_tflops": probe_flop / (probe_ms["mfma_ones"] * 1e-3) / 1e12,
+                    "copy_GBs_read_plus_write": 2.0 * cp_src.numel() / (probe_ms["copy"] * 1e-3) / 1e9}
+        del cp_src, cp_dst
     R = int(saved.offsets.cpu()[-1])
     bwd_ms = None
     if with_bwd:
@@ -226,7 +231,7 @@ def main():
     # training step that keeps no permuted copy of x (MoeSaved.Xp = NULL): GEMM-1 and w1_grad read x through the
     # permutation; reported beside the headline, which runs the explicit Dispatch permute
     noxp_ms, noxp_bwd_ms = {}, None
-    if cfg.dtype == "bf16":
+    if cfg.dtype == "bf16" and not args.headline_only:
         saved_nx = moe.alloc_saved(shape, store_h1=with_bwd, keep_xp=False)
         for name, mode in modes.items():
             if name in ms:
