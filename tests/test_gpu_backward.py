@@ -160,6 +160,22 @@ def test_without_permuted_copy(case, mode):
     assert torch.equal(bwd.dx, bwd_kept.dx) and torch.equal(bwd.dtopk_w, bwd_kept.dtopk_w)
 
 
+@pytest.mark.parametrize("case", _random_cases(10, 77), ids=lambda c: c[0])
+def test_without_permuted_copy_random_shapes(case):
+    """Seeded random small problems through forward (single launch) and backward without a permuted copy."""
+    import paper_2605_23764_amd as moe
+    from gpu_common import check_backward, check_forward, check_routing, run_backward, run_forward, small_config
+    cfg = small_config(*case)
+    inp = make_inputs(cfg, with_dy=True)
+    ref = oracle.forward(inp["x"], inp["logits"], inp["w_gate_up"], inp["w_down"], cfg.k, cfg.expert_base, cfg.E_local)
+    ref_b = oracle.backward(inp["dy"], ref, inp["w_gate_up"], inp["w_down"])
+    print(cfg.name, "counts", ref["counts"][:10].tolist(), flush=True)
+    run = run_forward(cfg, inp, mode=moe.MODE_PERSISTENT, store_h1=True, keep_xp=False)
+    check_routing(run, ref)
+    check_forward(run, ref, cfg.dtype, store_h1=True)
+    check_backward(run_backward(cfg, inp, run), ref_b, ref["counts"], cfg.dtype)
+
+
 def test_without_permuted_copy_c5_full():
     import paper_2605_23764_amd as moe
     from gpu_common import check_backward, check_forward, run_backward, run_forward
