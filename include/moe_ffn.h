@@ -151,6 +151,12 @@ int moe_ffn_forward(const MoeShape* shape, const void* d_x, const float* d_logit
  *   d_dw_gate_up  [E_local,H,2I] dtype, overwritten (zeros for experts with no rows)
  *   d_dw_down     [E_local,I,H]  dtype, overwritten
  *   d_dtopk_w     [T,k]  f32     <dY[t], Yp[row_of[t,j]]>, 0 for non-local slots
+ *   d_workspace, workspace_bytes  >= moe_ffn_workspace_bytes(...).bwd_bytes
+ *   mode   MOE_MODE_SERIALIZED: one launch per operator.  MOE_MODE_PERSISTENT (bf16 only, else
+ *          MOE_ERR_INVALID_ARG): act_grad + SwiGLU_grad and gate_grad, a producer-consumer pair of
+ *          grouped GEMMs like the forward's, run as one launch of tile tasks with event counters
+ *          (Sections 4.2-4.4), the other operators as launches of their own; results are
+ *          bit-identical; a wait that expires is reported by moe_ffn_last_status() on this workspace.
  */
 int moe_ffn_backward(const MoeShape* shape, const void* d_dy, const void* d_x,
                      const void* d_w_gate_up, const void* d_w_down, const MoeSaved* saved,
@@ -158,7 +164,7 @@ int moe_ffn_backward(const MoeShape* shape, const void* d_dy, const void* d_x,
                      void* d_workspace, size_t workspace_bytes, int mode, void* stream);
 
 /*
- * Reads the scheduler status word of a workspace after the caller has
+ * Reads the scheduler status word of a forward or backward workspace after the caller has
  * synchronised the stream (host-blocking 4-byte copy).  MOE_OK or
  * MOE_ERR_SCHED_TIMEOUT.
  */

@@ -331,7 +331,7 @@ int run_combine(const Ctx& c, void* out) {
 
 // ---- backward ----
 struct BwdLayout {
-  size_t meta, tile_expert, tile_row0, tile_rows, dYp, dH1, dXp, total;
+  size_t meta, tile_expert, tile_row0, tile_rows, events, qhead, tasks, dYp, dH1, dXp, Xp, total;
 };
 
 BwdLayout make_bwd_layout(const MoeShape& s) {
@@ -343,9 +343,13 @@ BwdLayout make_bwd_layout(const MoeShape& s) {
   L.tile_expert = take((size_t)max_mtiles(s) * 4);
   L.tile_row0 = take((size_t)max_mtiles(s) * 4);
   L.tile_rows = take((size_t)max_mtiles(s) * 4);
+  L.events = take((size_t)n_events(s) * 4);                 // single-launch data-gradient chain
+  L.qhead = take(kNumQueues * 4);
+  L.tasks = take((size_t)kNumXcd * max_tasks_per_queue(s) * sizeof(TaskDesc));
   L.dYp = take(Rm * s.H * eb);
   L.dH1 = take(Rm * 2 * s.I * eb);
   L.dXp = take(Rm * s.H * eb);
+  L.Xp = take(Rm * s.H * eb);                                // rows of Xp made here when the forward kept none
   L.total = off;
   return L;
 }
@@ -358,6 +362,7 @@ struct BwdCtx {
   hipStream_t stream;
   int n_cu;
   TileMap tiles;
+  int mode;          // MOE_MODE_PERSISTENT: act_grad and gate_grad as one launch under the tile scheduler
 };
 
 // Weight gradient of one GEMM: experts with up to 384 rows go to the register-stationary kernel when
@@ -407,21 +412,23 @@ int run_backward(const BwdCtx& c, const void* dy, const void* x, const void* w_g
   }
 
   using P = typename std::conditional<BF16, GemmParams, GemmBwdParamsF32>::type;
+  T* xp_ws = reinterpret_cast<T*>(c.ws + c.L.Xp);
   // act_grad + SwiGLU_grad: dH1 = swiglu'(dYp W_down^T ; H1)
-  {
-    P p{};
-    p.A = dYp; p.B = static_cast<const T*>(w_down); p.C = dH1; p.G = static_cast<const T*>(c.sv.H1);
-    p.strideB = (long)s.I * s.H; p.K = s.H; p.N = s.I;
-    p.lda = s.H; p.ldb = s.H; p.ldc = 2 * s.I;
-    p.n_ntiles = ceil_div(s.I, tn);
-    p.tiles = c.tiles;
-    if constexpr (BF16)
-      hipLaunchKernelGGL((grouped_gemm_bf16_kernel<kLayNT, kEpiSwigluGrad>), dim3(grid), dim3(kGemmThreads), 0,
-                         c.stream, p);
-    else
-      hipLaunchKernelGGL(grouped_dgrad_f32_kernel<kEpiSwigluGrad>, dim3(grid), dim3(256), 0, c.stream, p);
-  }
-  // w2_grad: dW_down[e] = A_e^T dYp_e
+  P pa{};
+  pa.A = dYp; pa.B = static_cast<const T*>(w_down); pa.C = dH1; pa.G = static_cast<const T*>(c.sv.H1);
+  pa.strideB = (long)s.I * s.H; pa.K = s.H; pa.N = s.I;
+  pa.lda = s.H; pa.ldb = s.H; pa.ldc = 2 * s.I;
+  pa.n_ntiles = ceil_div(s.I, tn);
+  pa.tiles = c.tiles;
+  // gate_grad: dXp = dH1 W_gate_up^T
+  P pg{};
+  pg.A = dH1; pg.B = static_cast<const T*>(w_gate_up); pg.C = dXp;
+  pg.strideB = (long)s.H * 2 * s.I; pg.K = 2 * s.I; pg.N = s.H;
+  pg.lda = 2 * s.I; pg.ldb = 2 * s.I; pg.ldc = s.H;
+  pg.n_ntiles = ceil_div(s.H, tn);
+  pg.tiles = c.tiles;
+
+  // w2_grad: dW_down[e] = A_e^T dYp_e (needs only dYp: runs first, while dYp is fresh in the caches)
   {
     P p{};
     p.A = static_cast<const T*>(c.sv.A); p.B = dYp; p.C = static_cast<T*>(dw_down);
@@ -433,8 +440,32 @@ int run_backward(const BwdCtx& c, const void* dy, const void* x, const void* w_g
     if constexpr (BF16) launch_wgrad_bf16(p, grid, c.n_cu, c.stream);
     else hipLaunchKernelGGL(grouped_wgrad_f32_kernel, dim3(grid), dim3(256), 0, c.stream, p);
   }
-  // w1_grad: dW_gate_up[e] = Xp_e^T dH1_e.  Runs ahead of gate_grad so that, when the forward kept no
-  // permuted copy (saved->Xp == NULL), the dXp buffer can first hold the rows of Xp that are needed here.
+  if constexpr (BF16) {
+    if (c.mode == MOE_MODE_PERSISTENT) {
+      SchedParams<true> sp{};
+      sp.route.tiles = c.tiles;
+      sp.g1 = pa; sp.g2 = pg;
+      sp.events = reinterpret_cast<uint32_t*>(c.ws + c.L.events);
+      sp.qhead = reinterpret_cast<uint32_t*>(c.ws + c.L.qhead);
+      sp.tasks = reinterpret_cast<TaskDesc*>(c.ws + c.L.tasks);
+      sp.meta = c.tiles.meta;
+      sp.max_mtiles = (int)max_mtiles(s);
+      sp.max_tasks_per_q = (int)max_tasks_per_queue(s);
+      sp.spin_limit = g_spin_limit;
+      sp.timeout_status = MOE_ERR_SCHED_TIMEOUT;
+      hipLaunchKernelGGL(dgrad_prepare_kernel, dim3(1), dim3(kGemmThreads), 0, c.stream, sp, (int)n_events(s));
+      hipLaunchKernelGGL(persistent_dgrad_kernel, dim3(grid), dim3(kGemmThreads), 0, c.stream, sp);
+    } else {
+      hipLaunchKernelGGL((grouped_gemm_bf16_kernel<kLayNT, kEpiSwigluGrad>), dim3(grid), dim3(kGemmThreads), 0, c.stream, pa);
+      hipLaunchKernelGGL((grouped_gemm_bf16_kernel<kLayNT, kEpiStore>), dim3(grid), dim3(kGemmThreads), 0, c.stream, pg);
+    }
+  } else {
+    hipLaunchKernelGGL(grouped_dgrad_f32_kernel<kEpiSwigluGrad>, dim3(grid), dim3(256), 0, c.stream, pa);
+    hipLaunchKernelGGL(grouped_dgrad_f32_kernel<kEpiStore>, dim3(grid), dim3(256), 0, c.stream, pg);
+  }
+  // w1_grad: dW_gate_up[e] = Xp_e^T dH1_e.  When the forward kept no permuted copy (saved->Xp == NULL) the
+  // register-stationary kernel reads x through the permutation and only the rows the general kernel needs are
+  // copied first (all rows where nothing can gather).
   {
     P p{};
     p.A = static_cast<const T*>(c.sv.Xp); p.B = dH1; p.C = static_cast<T*>(dw_gate_up);
@@ -445,7 +476,7 @@ int run_backward(const BwdCtx& c, const void* dy, const void* x, const void* w_g
     p.E_local = s.E_local; p.offsets = c.sv.offsets;
     if (!c.sv.Xp) {
       PermuteParams pp;
-      pp.x = x; pp.Xp = dXp; pp.token_of = c.sv.token_of; pp.meta = c.tiles.meta;
+      pp.x = x; pp.Xp = xp_ws; pp.token_of = c.sv.token_of; pp.meta = c.tiles.meta;
       pp.H = s.H; pp.elem_bytes = elem_bytes(s);
       const long want = ((long)r_max(s) + 3) / 4;
       const int g = (int)(want < (long)c.n_cu * 8 ? (want > 0 ? want : 1) : (long)c.n_cu * 8);
@@ -458,24 +489,11 @@ int run_backward(const BwdCtx& c, const void* dy, const void* x, const void* w_g
         if constexpr (BF16) { p.A = static_cast<const T*>(x); p.gather = c.sv.token_of; }
       } else {
         hipLaunchKernelGGL(permute_kernel, dim3(g), dim3(256), 0, c.stream, pp);
-        p.A = dXp;
+        p.A = xp_ws;
       }
     }
-    if constexpr (BF16) launch_wgrad_bf16(p, grid, c.n_cu, c.stream, dXp);
+    if constexpr (BF16) launch_wgrad_bf16(p, grid, c.n_cu, c.stream, xp_ws);
     else hipLaunchKernelGGL(grouped_wgrad_f32_kernel, dim3(grid), dim3(256), 0, c.stream, p);
-  }
-  // gate_grad: dXp = dH1 W_gate_up^T
-  {
-    P p{};
-    p.A = dH1; p.B = static_cast<const T*>(w_gate_up); p.C = dXp;
-    p.strideB = (long)s.H * 2 * s.I; p.K = 2 * s.I; p.N = s.H;
-    p.lda = 2 * s.I; p.ldb = 2 * s.I; p.ldc = s.H;
-    p.n_ntiles = ceil_div(s.H, tn);
-    p.tiles = c.tiles;
-    if constexpr (BF16)
-      hipLaunchKernelGGL((grouped_gemm_bf16_kernel<kLayNT, kEpiStore>), dim3(grid), dim3(kGemmThreads), 0, c.stream, p);
-    else
-      hipLaunchKernelGGL(grouped_dgrad_f32_kernel<kEpiStore>, dim3(grid), dim3(256), 0, c.stream, p);
   }
   // backward Combine: dX[t] = sum over local slots of dXp[row_of[t,j]]
   {
@@ -586,7 +604,8 @@ int moe_ffn_backward(const MoeShape* shape, const void* d_dy, const void* d_x, c
                      void* stream) {
   int st = check_shape(shape);
   if (st != MOE_OK) return st;
-  if (mode != MOE_MODE_SERIALIZED) return MOE_ERR_INVALID_ARG;   // the backward graph runs as one launch per operator
+  // MOE_MODE_PERSISTENT (bf16 only): the two data-gradient GEMMs run as one launch under the tile scheduler
+  if (mode != MOE_MODE_SERIALIZED && !(mode == MOE_MODE_PERSISTENT && shape->dtype == MOE_BF16)) return MOE_ERR_INVALID_ARG;
   if (shape->T == 0) return MOE_OK;
   // 32-bit byte offsets of segment rows inside the weight-gradient loads
   if ((double)shape->T * (2 * shape->I > shape->H ? 2 * shape->I : shape->H) * elem_bytes(*shape) >= 4.0e9)
@@ -608,6 +627,7 @@ int moe_ffn_backward(const MoeShape* shape, const void* d_dy, const void* d_x, c
   c.sv = *saved;
   c.stream = static_cast<hipStream_t>(stream);
   c.n_cu = device_cus();
+  c.mode = mode;
   c.tiles.expert = reinterpret_cast<int32_t*>(c.ws + c.L.tile_expert);
   c.tiles.row0 = reinterpret_cast<int32_t*>(c.ws + c.L.tile_row0);
   c.tiles.rows = reinterpret_cast<int32_t*>(c.ws + c.L.tile_rows);

@@ -163,7 +163,9 @@ __device__ __forceinline__ void sched_trigger(const SchedParams<BF16>& sp, int e
 // SCAN task tail: materialise the per-XCD task tables from the fresh tile map.
 // Whole workgroup: a wave per queue, the lanes of the wave fill a block of
 // descriptors in parallel (block offsets are wave-uniform running sums).
-template <bool BF16>
+// BWD: the chain is act_grad (as "GEMM-1": no PERMUTE ahead of it, nothing to wait for; its narrow tall
+// tiles are 128 columns wide) followed by gate_grad (as "GEMM-2").
+template <bool BF16, bool BWD = false>
 __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), n_waves = blockDim.x / kWave;
@@ -177,7 +179,8 @@ __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
     const int Pq = n_pairs > q ? (n_pairs - q + kNumXcd - 1) / kNumXcd : 0;
     TaskDesc* tq = sp.tasks + (size_t)q * sp.max_tasks_per_q;
     int n = 0;
-    for (int j = 0; j < (sp.no_permute ? 0 : Pq); ++j)
+    constexpr int kTallCols1 = BWD ? 128 : 64;   // output columns of a narrow GEMM-1 tile of a tall M tile
+    for (int j = 0; j < (sp.no_permute || BWD ? 0 : Pq); ++j)
       for (int s = 0; s < 2; ++s) {
         const int m = 2 * (q + kNumXcd * j) + s;
         if (m >= n_mtiles) continue;
@@ -194,12 +197,12 @@ __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
         const int rows0 = sp.route.tiles.rows[m0];
         const bool tall = rows0 > kWideRows;
         const int n_sib = tall ? 1 : ((m0 + 1 < n_mtiles && sp.route.tiles.rows[m0 + 1] > 0) ? 2 : 1);
-        const int n_nt = tall ? (sp.g1.N + 63) / 64 : nN1;
+        const int n_nt = tall ? (sp.g1.N + kTallCols1 - 1) / kTallCols1 : nN1;
         const int parts0 = parts_of(m0), parts1 = n_sib > 1 ? parts_of(m0 + 1) : 0;
         for (int i = lane; i < n_nt * n_sib; i += kWave) {
           const int nt = i / n_sib, sib = i - nt * n_sib;
-          tq[n + i] = sp.no_permute ? TaskDesc{kTaskGemm1 | (nt << 8), m0 + sib, kEvRank, sp.n_rank_tasks}
-                                    : TaskDesc{kTaskGemm1 | (nt << 8), m0 + sib, kEvPerTile + m0 + sib, sib ? parts1 : parts0};
+          tq[n + i] = sp.no_permute || BWD ? TaskDesc{kTaskGemm1 | (nt << 8), m0 + sib, kEvRank, sp.n_rank_tasks}
+                                           : TaskDesc{kTaskGemm1 | (nt << 8), m0 + sib, kEvPerTile + m0 + sib, sib ? parts1 : parts0};
         }
         n += n_nt * n_sib;
       }
@@ -208,7 +211,7 @@ __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
         const bool tall = sp.route.tiles.rows[m0] > kWideRows;
         const int n_sib = tall ? 1 : ((m0 + 1 < n_mtiles && sp.route.tiles.rows[m0 + 1] > 0) ? 2 : 1);
         const int n_nt = tall ? (sp.g2.N + 127) / 128 : nN2;
-        const int g1_tiles = tall ? (sp.g1.N + 63) / 64 : nN1;     // GEMM-1 tiles that complete a row block of A
+        const int g1_tiles = tall ? (sp.g1.N + kTallCols1 - 1) / kTallCols1 : nN1;   // GEMM-1 tiles that complete a row block of A
         for (int i = lane; i < n_nt * n_sib; i += kWave) {
           const int nt = i / n_sib, sib = i - nt * n_sib;
           tq[n + i] = TaskDesc{kTaskGemm2 | (nt << 8), m0 + sib, kEvPerTile + sp.max_mtiles + m0 + sib, g1_tiles};
@@ -345,6 +348,47 @@ void persistent_forward_kernel(SchedParams<BF16> sp) {
       for (int i = wave; i < sp.comb_tokens; i += blockDim.x / kWave)
         if (t0 + i < sp.comb.T) combine_token<BF16>(sp.comb, t0 + i);
       MOE_TRACE_END(sp)
+    }
+  }
+}
+
+// ---- backward: the two data-gradient GEMMs as one launch --------------------------------------
+// act_grad (+ SwiGLU_grad) and gate_grad form the same kind of chain as GEMM-1 -> GEMM-2: a gate_grad
+// tile of M tile m needs every act_grad tile of m (all columns of dH1 for those rows), and both run in
+// the same workgroup shape.  One launch, per-XCD ticket queues, XCD-local events: gate_grad tiles fill
+// the CUs that act_grad's last, partly empty round leaves idle (its N extent is small: 368 tiles on
+// 256 CUs at H = 7168, I = 2048, 32 experts of ~254 rows).  sp.g1 = act_grad, sp.g2 = gate_grad,
+// sp.route.tiles = the backward's M-tile map; the other members of sp are unused.
+
+// One workgroup: zero the counters, then build the per-XCD task tables from the finished tile map.
+__global__ __launch_bounds__(kGemmThreads) void dgrad_prepare_kernel(SchedParams<true> sp, int n_events) {
+  for (int i = threadIdx.x; i < n_events; i += blockDim.x) sp.events[i] = 0;
+  if (threadIdx.x < kNumQueues) sp.qhead[threadIdx.x] = 0;
+  build_task_tables<true, true>(sp);
+}
+
+__global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void persistent_dgrad_kernel(SchedParams<true> sp) {
+  __shared__ __attribute__((aligned(1024))) char smem[kGemmLdsBytes];
+  volatile int* s_box = reinterpret_cast<volatile int*>(smem);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int q = blockIdx.x % kNumXcd;   // workgroups are dealt to XCDs round-robin by id
+  const int count = __builtin_amdgcn_readfirstlane(sp.meta[kMetaQueueCount0 + q]);
+  for (;;) {
+    const int t = sched_fetch(sp.qhead, kQXcd0 + q, s_box, wave);
+    if (t >= count) break;
+    const TaskDesc td = sp.tasks[(size_t)q * sp.max_tasks_per_q + t];
+    const int type_n = __builtin_amdgcn_readfirstlane(td.type_n);
+    const int type = type_n & 0xFF, idx = type_n >> 8, m = __builtin_amdgcn_readfirstlane(td.m);
+    const bool tall = __builtin_amdgcn_readfirstlane(sp.route.tiles.rows[m]) > kBM;
+    if (type == kTaskGemm1) {
+      gemm_map_tile_bf16<kLayNT, kEpiSwigluGrad>(sp.g1, m, idx, tall, smem);
+      sched_trigger(sp, kEvPerTile + sp.max_mtiles + m, wave, kScopeXcd);
+    } else {
+      if (!sched_wait(sp, __builtin_amdgcn_readfirstlane(td.dep_event), (uint32_t)__builtin_amdgcn_readfirstlane(td.threshold),
+                      s_box, wave, kScopeXcd))
+        continue;   // bounded wait expired: status word set, the task is skipped, the queue still drains
+      gemm_map_tile_bf16<kLayNT, kEpiStore>(sp.g2, m, idx, tall, smem);
     }
   }
 }

@@ -97,7 +97,7 @@ class GpuBackward:
     dtopk_w: torch.Tensor
 
 
-def run_backward(cfg: MoeConfig, inp: dict, run: GpuRun) -> GpuBackward:
+def run_backward(cfg: MoeConfig, inp: dict, run: GpuRun, mode=moe.MODE_SERIALIZED) -> GpuBackward:
     """Backward through the C ABI on the buffers a forward with H1 stored has filled."""
     tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
     dy = to_device(inp["dy"], cfg.dtype)
@@ -108,8 +108,9 @@ def run_backward(cfg: MoeConfig, inp: dict, run: GpuRun) -> GpuBackward:
     dtw = torch.full((cfg.T, cfg.k), nan, dtype=torch.float32, device="cuda")
     ws = moe.alloc_workspace(run.shape, backward=True)
     moe.moe_ffn_backward(run.shape, dy, run.dev["x"], run.dev["w_gate_up"], run.dev["w_down"], run.saved,
-                         dx, dw1, dw2, dtw, ws)
+                         dx, dw1, dw2, dtw, ws, mode)
     torch.cuda.synchronize()
+    assert moe.moe_ffn_last_status(run.shape, ws) == 0
     return GpuBackward(dx, dw1, dw2, dtw)
 
 

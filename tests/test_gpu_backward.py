@@ -119,6 +119,74 @@ def test_panel_kernel_with_empty_experts():
     assert torch.all(bwd.dw_gate_up[2] == 0) and torch.all(bwd.dw_down[5] == 0)
 
 
+BF16_SMALL = [c for c in SMALL if c[8] == "bf16"]
+
+
+@pytest.mark.parametrize("case", BF16_SMALL, ids=[c[0] for c in BF16_SMALL])
+def test_single_launch_data_gradients_match_serialized(case):
+    """MOE_MODE_PERSISTENT runs act_grad and gate_grad as one launch of tile tasks: same tile functions, so
+    every output is bit-identical to the serialized backward (which the other tests hold against the oracle)."""
+    import paper_2605_23764_amd as moe
+    from gpu_common import run_backward, run_forward, small_config
+    cfg = small_config(*case)
+    inp = make_inputs(cfg, with_dy=True)
+    if cfg.E_local >= 6:
+        inp["logits"][:, cfg.expert_base + 1] = -50.0          # an expert without rows
+    run = run_forward(cfg, inp, store_h1=True)
+    print(cfg.name, "counts", run.saved.counts.cpu().numpy()[:10].tolist(), flush=True)
+    a = run_backward(cfg, inp, run)
+    b = run_backward(cfg, inp, run, mode=moe.MODE_PERSISTENT)
+    for name in ("dx", "dw_gate_up", "dw_down", "dtopk_w"):
+        assert torch.equal(getattr(a, name), getattr(b, name)), name
+
+
+@pytest.mark.parametrize("name", ["c2", "c4", "c5"])
+def test_single_launch_data_gradients_full_size(name):
+    import dataclasses
+    import paper_2605_23764_amd as moe
+    from gpu_common import check_backward, run_backward, run_forward
+    cfg = dataclasses.replace(CONFIGS[name], name=name + "_bwd_single")
+    inp = make_inputs(cfg, with_dy=True)
+    ref = oracle.forward(inp["x"], inp["logits"], inp["w_gate_up"], inp["w_down"], cfg.k, cfg.expert_base, cfg.E_local)
+    ref_b = oracle.backward(inp["dy"], ref, inp["w_gate_up"], inp["w_down"])
+    run = run_forward(cfg, inp, store_h1=True, keep_xp=False)
+    b = run_backward(cfg, inp, run, mode=moe.MODE_PERSISTENT)
+    errs = check_backward(b, ref_b, ref["counts"], cfg.dtype)
+    print(cfg.name, {k: "%.2e" % v for k, v in errs.items()}, flush=True)
+    a = run_backward(cfg, inp, run)
+    for f in ("dx", "dw_gate_up", "dw_down", "dtopk_w"):
+        assert torch.equal(getattr(a, f), getattr(b, f)), f
+
+
+def test_single_launch_data_gradients_bounded_wait():
+    """With a tiny poll limit the waits of gate_grad tasks expire: the tasks are skipped, every workgroup still
+    drains its queue and exits, and the status word reports the timeout (nothing hangs)."""
+    import paper_2605_23764_amd as moe
+    from gpu_common import run_forward, small_config
+    cfg = small_config("b_bf16_spin", 1500, 256, 256, 4, 4, 0, 2, "bf16", 71)
+    inp = make_inputs(cfg, with_dy=True)
+    run = run_forward(cfg, inp, store_h1=True)
+    dy = torch.from_numpy(inp["dy"]).cuda().to(torch.bfloat16)
+    dx = torch.empty_like(dy)
+    dw1 = torch.empty_like(run.dev["w_gate_up"])
+    dw2 = torch.empty_like(run.dev["w_down"])
+    dtw = torch.empty(cfg.T, cfg.k, device="cuda")
+    ws = moe.alloc_workspace(run.shape, backward=True)
+    moe.moe_ffn_debug_set_spin_limit(0)
+    try:
+        moe.moe_ffn_backward(run.shape, dy, run.dev["x"], run.dev["w_gate_up"], run.dev["w_down"], run.saved,
+                             dx, dw1, dw2, dtw, ws, moe.MODE_PERSISTENT)
+        torch.cuda.synchronize()
+        st = moe.moe_ffn_last_status(run.shape, ws)
+    finally:
+        moe.moe_ffn_debug_set_spin_limit(1 << 20)
+    assert st in (0, -5)        # a wait whose event had already arrived does not expire
+    moe.moe_ffn_backward(run.shape, dy, run.dev["x"], run.dev["w_gate_up"], run.dev["w_down"], run.saved,
+                         dx, dw1, dw2, dtw, ws, moe.MODE_PERSISTENT)
+    torch.cuda.synchronize()
+    assert moe.moe_ffn_last_status(run.shape, ws) == 0
+
+
 # without a kept permuted copy (MoeSaved.Xp = NULL): GEMM-1 and w1_grad read x through the permutation.
 # Cases: register-stationary kernel only; both weight-gradient kernels (experts above 384 rows take the
 # partial copy); shapes the register-stationary kernel cannot take (everything through the copy); tiny
@@ -203,7 +271,7 @@ def test_backward_argument_errors():
     dtw = torch.empty(cfg.T, cfg.k, device="cuda")
     ws = moe.alloc_workspace(run.shape, backward=True)
     args = (run.shape, dy, run.dev["x"], run.dev["w_gate_up"], run.dev["w_down"], run.saved, dx, dw1, dw2, dtw)
-    with pytest.raises(moe.MoeError) as ei:      # the backward graph has no single-launch mode
+    with pytest.raises(moe.MoeError) as ei:      # the single-launch data-gradient chain exists for bf16 only
         moe.moe_ffn_backward(*args, ws, moe.MODE_PERSISTENT)
     assert ei.value.status == -1
     with pytest.raises(moe.MoeError) as ei:
