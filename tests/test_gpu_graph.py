@@ -1,4 +1,4 @@
-"""HIP graph capture of the layer: the forward (both launch modes) and the backward consist of
+"""HIP graph capture of the layer: the forward and the backward (both launch modes each) consist of
 kernel launches only (counters are cleared by a fill kernel, not a memset), so a caller can
 capture them once and replay.  Every replay, with fresh inputs and eager work in between, must
 reproduce the eager result bit for bit."""
@@ -38,7 +38,7 @@ def test_forward_and_backward_replay_from_a_graph(mode):
 
     def layer():
         moe.moe_ffn_forward(shape, x, logits, w1, w2, out, saved, ws_f, mode)
-        moe.moe_ffn_backward(shape, dy, x, w1, w2, saved, dx, dw1, dw2, dtw, ws_b)
+        moe.moe_ffn_backward(shape, dy, x, w1, w2, saved, dx, dw1, dw2, dtw, ws_b, mode)   # same mode: see moe_ffn.h
 
     def snapshot():
         torch.cuda.synchronize()
@@ -65,7 +65,7 @@ def test_forward_and_backward_replay_from_a_graph(mode):
         graph.replay()
         got = snapshot()
         if mode == moe.MODE_PERSISTENT:
-            assert moe.moe_ffn_last_status(shape, ws_f) == 0
+            assert moe.moe_ffn_last_status(shape, ws_f) == 0 and moe.moe_ffn_last_status(shape, ws_b) == 0
         for t in (out, dx, dw1, dw2, dtw):
             t.fill_(float("nan"))
         layer()
