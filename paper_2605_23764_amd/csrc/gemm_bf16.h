@@ -80,6 +80,8 @@ struct GemmParams {
   int E_local;        // weight gradients
   int k_lo;           // weight gradients, general kernel: experts with fewer rows are left to the register-stationary kernel
   const int32_t* offsets;   // weight gradients: [E_local + 1] segment boundaries
+  uint32_t* tickets;        // weight gradients, register-stationary kernel: 8 zeroed counters (one per XCD) from which
+                            // the workgroups draw their items; nullptr = fixed round-robin assignment
   TileMap tiles;      // NN, NT
 };
 

@@ -331,7 +331,7 @@ int run_combine(const Ctx& c, void* out) {
 
 // ---- backward ----
 struct BwdLayout {
-  size_t meta, tile_expert, tile_row0, tile_rows, events, qhead, tasks, dYp, dH1, dXp, Xp, total;
+  size_t meta, tile_expert, tile_row0, tile_rows, events, qhead, tasks, tickets, dYp, dH1, dXp, Xp, total;
 };
 
 BwdLayout make_bwd_layout(const MoeShape& s) {
@@ -346,6 +346,7 @@ BwdLayout make_bwd_layout(const MoeShape& s) {
   L.events = take((size_t)n_events(s) * 4);                 // single-launch data-gradient chain
   L.qhead = take(kNumQueues * 4);
   L.tasks = take((size_t)kNumXcd * max_tasks_per_queue(s) * sizeof(TaskDesc));
+  L.tickets = take(2 * kNumXcd * 4);                         // item counters of the two weight-gradient launches
   L.dYp = take(Rm * s.H * eb);
   L.dH1 = take(Rm * 2 * s.I * eb);
   L.dXp = take(Rm * s.H * eb);
@@ -398,8 +399,9 @@ int run_backward(const BwdCtx& c, const void* dy, const void* x, const void* w_g
   auto ceil_div = [](int a, int b) { return (a + b - 1) / b; };
   const int grid = BF16 ? (c.n_cu + 7) / 8 * 8 : c.n_cu * 4;
 
+  uint32_t* tickets = reinterpret_cast<uint32_t*>(c.ws + c.L.tickets);   // [0, 8): w2_grad, [8, 16): w1_grad
   hipLaunchKernelGGL(tile_map_kernel, dim3(1), dim3(kWave), 0, c.stream, c.sv.counts, s.E_local, bm,
-                     BF16 ? kRowGranule : kFBM, tile_tall(s), c.tiles);
+                     BF16 ? kRowGranule : kFBM, tile_tall(s), c.tiles, tickets, 2 * kNumXcd);
 
   // backward Dispatch
   BwdDispatchParams bd;
@@ -437,7 +439,7 @@ int run_backward(const BwdCtx& c, const void* dy, const void* x, const void* w_g
     p.n_ntiles = ceil_div(s.H, tn);
     if constexpr (!BF16) p.n_mtiles = ceil_div(s.I, bm);
     p.E_local = s.E_local; p.offsets = c.sv.offsets;
-    if constexpr (BF16) launch_wgrad_bf16(p, grid, c.n_cu, c.stream);
+    if constexpr (BF16) { p.tickets = tickets; launch_wgrad_bf16(p, grid, c.n_cu, c.stream); }
     else hipLaunchKernelGGL(grouped_wgrad_f32_kernel, dim3(grid), dim3(256), 0, c.stream, p);
   }
   if constexpr (BF16) {
@@ -492,7 +494,7 @@ int run_backward(const BwdCtx& c, const void* dy, const void* x, const void* w_g
         p.A = xp_ws;
       }
     }
-    if constexpr (BF16) launch_wgrad_bf16(p, grid, c.n_cu, c.stream, xp_ws);
+    if constexpr (BF16) { p.tickets = tickets + kNumXcd; launch_wgrad_bf16(p, grid, c.n_cu, c.stream, xp_ws); }
     else hipLaunchKernelGGL(grouped_wgrad_f32_kernel, dim3(grid), dim3(256), 0, c.stream, p);
   }
   // backward Combine: dX[t] = sum over local slots of dXp[row_of[t,j]]

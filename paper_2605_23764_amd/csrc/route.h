@@ -413,8 +413,10 @@ __global__ __launch_bounds__(256) void rank_kernel(RouteParams p) {
 
 // M-tile map from the rows per expert alone (the backward rebuilds it from the
 // saved counts instead of keeping the forward's workspace alive).
+// Also zeroes `n_zero` words at `zero` (counters the kernels that follow draw tickets from).
 __global__ __launch_bounds__(kWave) void tile_map_kernel(const int32_t* counts, int E_local, int BM, int granule,
-                                                         int tall, TileMap tiles) {
+                                                         int tall, TileMap tiles, uint32_t* zero, int n_zero) {
+  for (int i = threadIdx.x; i < n_zero; i += kWave) zero[i] = 0;
   build_tile_map(E_local, counts, BM, granule, tall, nullptr, nullptr, tiles);
 }
 

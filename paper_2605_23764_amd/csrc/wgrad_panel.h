@@ -22,6 +22,7 @@
 // here (M % 256 == 0, N % 128 == 0 is a launch condition), so those counts are exact.
 #pragma once
 #include "gemm_bf16.h"
+#include "wave_sync.h"
 
 namespace moe {
 
@@ -286,14 +287,38 @@ void grouped_wgrad_panel_bf16_kernel(GemmParams p, int n_split) {
   int lane = lane_id();
   asm volatile("" : "+v"(lane));
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  for (int it = 0; it * G < total; ++it) {
-    const int id = xcd_tile_id(it, blockIdx.x, G);
-    if (id >= total) continue;
-    // items of one expert and column range are neighbours: they share the B chunks through the L2
-    const int e = __builtin_amdgcn_readfirstlane(id / per_e);
-    const int r = id - e * per_e;
-    const int sp = __builtin_amdgcn_readfirstlane(r / n_mp);
-    const int mp = r - sp * n_mp;
+  // The n_mp row panels of one (expert, column range) read the same B chunks: a "group".  With p.tickets,
+  // group g belongs to XCD g % 8, so that B is fetched into one L2 only, and the workgroups of an XCD draw
+  // its items from a shared counter (wave 0 draws, LDS broadcasts; the staging area is quiet between
+  // items): items cost 4 to 6 chunks of work depending on the expert's rows, and a fixed assignment leaves
+  // some workgroups 5-8 % more than the mean.  Without tickets: fixed round-robin assignment.
+  const int xcd = blockIdx.x & 7;
+  const int n_groups = p.E_local * n_split;
+  const int groups_x = n_groups > xcd ? (n_groups - xcd + 7) >> 3 : 0;
+  volatile int* s_box = reinterpret_cast<volatile int*>(smem);
+  for (int it = 0;; ++it) {
+    int e, sp, mp;
+    if (p.tickets) {
+      if (wave == 0) s_box[0] = (int)wave_atomic_add(&p.tickets[xcd], 1u);
+      __syncthreads();
+      const int ticket = __builtin_amdgcn_readfirstlane(s_box[0]);
+      __syncthreads();
+      const int k = ticket / n_mp;
+      if (k >= groups_x) break;
+      const int g = xcd + 8 * k;
+      e = __builtin_amdgcn_readfirstlane(g / n_split);
+      sp = g - e * n_split;
+      mp = ticket - k * n_mp;
+    } else {
+      if (it * G >= total) break;
+      const int id = xcd_tile_id(it, blockIdx.x, G);
+      if (id >= total) continue;
+      // items of one expert and column range are neighbours: they share the B chunks through the L2
+      e = __builtin_amdgcn_readfirstlane(id / per_e);
+      const int r = id - e * per_e;
+      sp = __builtin_amdgcn_readfirstlane(r / n_mp);
+      mp = r - sp * n_mp;
+    }
     const int seg0 = __builtin_amdgcn_readfirstlane(p.offsets[e]);
     const int cnt = __builtin_amdgcn_readfirstlane(p.offsets[e + 1]) - seg0;
     if (cnt > kWpMaxRows) continue;
