@@ -24,6 +24,7 @@ enum MetaWord {
   kMetaMTiles = 0,   // number of M tiles in the tile map
   kMetaRows = 1,     // R: rows in expert-contiguous order
   kMetaStatus = 2,   // scheduler status (0 ok, MOE_ERR_SCHED_TIMEOUT)
+  kMetaMaxRows = 3,  // rows of the largest expert
   kMetaWords = 16
 };
 

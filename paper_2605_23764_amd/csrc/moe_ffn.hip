@@ -439,7 +439,7 @@ int run_backward(const BwdCtx& c, const void* dy, const void* x, const void* w_g
     p.n_ntiles = ceil_div(s.H, tn);
     if constexpr (!BF16) p.n_mtiles = ceil_div(s.I, bm);
     p.E_local = s.E_local; p.offsets = c.sv.offsets;
-    if constexpr (BF16) { p.tickets = tickets; launch_wgrad_bf16(p, grid, c.n_cu, c.stream); }
+    if constexpr (BF16) { p.tickets = tickets; p.tiles = c.tiles; launch_wgrad_bf16(p, grid, c.n_cu, c.stream); }
     else hipLaunchKernelGGL(grouped_wgrad_f32_kernel, dim3(grid), dim3(256), 0, c.stream, p);
   }
   if constexpr (BF16) {
@@ -494,7 +494,7 @@ int run_backward(const BwdCtx& c, const void* dy, const void* x, const void* w_g
         p.A = xp_ws;
       }
     }
-    if constexpr (BF16) { p.tickets = tickets + kNumXcd; launch_wgrad_bf16(p, grid, c.n_cu, c.stream, xp_ws); }
+    if constexpr (BF16) { p.tickets = tickets + kNumXcd; p.tiles = c.tiles; launch_wgrad_bf16(p, grid, c.n_cu, c.stream, xp_ws); }
     else hipLaunchKernelGGL(grouped_wgrad_f32_kernel, dim3(grid), dim3(256), 0, c.stream, p);
   }
   // backward Combine: dX[t] = sum over local slots of dXp[row_of[t,j]]

@@ -240,10 +240,11 @@ __device__ __forceinline__ void build_tile_map(int E_local, const int32_t* cnt, 
     const int incl = wave_incl_scan(t.is_tall ? t.n : (t.n >> 1), lane);
     total_slots += __shfl(incl, kWave - 1, kWave);
   }
-  int row_run = 0, slot_run = 0, single_run = 0;
+  int row_run = 0, slot_run = 0, single_run = 0, max_rows = 0;
   for (int e0 = 0; e0 < E_local; e0 += kWave) {
     const int e = e0 + lane;
     const int c = e < E_local ? cnt[e] : 0;
+    max_rows = max(max_rows, c);
     const ExpertTiling t = expert_tiling(c, BM, granule, tall);
     const int ns = t.is_tall ? t.n : (t.n >> 1);          // slots
     const int n1 = t.is_tall ? 0 : (t.n & 1);             // left-over single
@@ -273,8 +274,11 @@ __device__ __forceinline__ void build_tile_map(int E_local, const int32_t* cnt, 
     slot_run += __shfl(slot_incl, kWave - 1, kWave);
     single_run += __shfl(single_incl, kWave - 1, kWave);
   }
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) max_rows = max(max_rows, __shfl_xor(max_rows, off, kWave));
   if (lane == 0) {
     if (offsets) offsets[E_local] = row_run;
+    tiles.meta[kMetaMaxRows] = max_rows;
     tiles.meta[kMetaMTiles] = 2 * total_slots + single_run;
     tiles.meta[kMetaRows] = row_run;
     tiles.meta[kMetaStatus] = 0;

@@ -217,6 +217,8 @@ void grouped_wgrad2_bf16_kernel(GemmParams p) {
   const int per_e = n_mt * n_nt;
   const int total = p.E_local * per_e;
   const int G = gridDim.x;
+  // nothing to do when the other kernel takes every expert (p.tiles.meta: the M-tile map's header, or nullptr)
+  if (p.k_lo > 0 && p.tiles.meta && __builtin_amdgcn_readfirstlane(p.tiles.meta[kMetaMaxRows]) < p.k_lo) return;
   for (int it = 0; it * G < total; ++it) {
     const int tile = xcd_tile_id(it, blockIdx.x, G);
     if (tile >= total) continue;
