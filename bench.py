@@ -207,22 +207,21 @@ def main():
     del flush, sets
     # ceilings measured on this GPU with nothing else in the way (register-only MFMA loop with random / constant
     # operands: 256 workgroups x 4 waves x 65536 MFMAs of 32768 flop; 2 GiB streaming copy)
-    ceilings = None
-    if True:   # also under --headline-only: the copy probe is the known-size kernel that calibrates the HBM counters
-        sink = torch.zeros(1, dtype=torch.float32, device="cuda")
-        cp_src = torch.empty(1 << 29, dtype=torch.float32, device="cuda").normal_().view(torch.uint8)
-        cp_dst = torch.empty_like(cp_src)
-        n_wg, n_mfma = 256, 1 << 16
-        probe_ms = {
-            "mfma_random": timed(lambda: moe.moe_probe_mfma_bf16(n_wg, n_mfma, 1, sink), 5, 2),
-            "mfma_ones": timed(lambda: moe.moe_probe_mfma_bf16(n_wg, n_mfma, 0, sink), 5, 2),
-            "copy": timed(lambda: moe.moe_probe_copy(cp_src, cp_dst, cp_src.numel()), 10, 3),
-        }
-        probe_flop = n_wg * 4 * n_mfma * 32768.0
-        ceilings = {"mfma_bf16_random_operands_tflops": probe_flop / (probe_ms["mfma_random"] * 1e-3) / 1e12,
-                    "mfma_bf16_constant_operands_tflops": probe_flop / (probe_ms["mfma_ones"] * 1e-3) / 1e12,
-                    "copy_GBs_read_plus_write": 2.0 * cp_src.numel() / (probe_ms["copy"] * 1e-3) / 1e9}
-        del cp_src, cp_dst
+    # (also under --headline-only: the copy probe is the known-size kernel that calibrates the HBM counters)
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    cp_src = torch.empty(1 << 29, dtype=torch.float32, device="cuda").normal_().view(torch.uint8)
+    cp_dst = torch.empty_like(cp_src)
+    n_wg, n_mfma = 256, 1 << 16
+    probe_ms = {
+        "mfma_random": timed(lambda: moe.moe_probe_mfma_bf16(n_wg, n_mfma, 1, sink), 5, 2),
+        "mfma_ones": timed(lambda: moe.moe_probe_mfma_bf16(n_wg, n_mfma, 0, sink), 5, 2),
+        "copy": timed(lambda: moe.moe_probe_copy(cp_src, cp_dst, cp_src.numel()), 10, 3),
+    }
+    probe_flop = n_wg * 4 * n_mfma * 32768.0
+    ceilings = {"mfma_bf16_random_operands_tflops": probe_flop / (probe_ms["mfma_random"] * 1e-3) / 1e12,
+                "mfma_bf16_constant_operands_tflops": probe_flop / (probe_ms["mfma_ones"] * 1e-3) / 1e12,
+                "copy_GBs_read_plus_write": 2.0 * cp_src.numel() / (probe_ms["copy"] * 1e-3) / 1e9}
+    del cp_src, cp_dst
     R = int(saved.offsets.cpu()[-1])
     bwd_ms = None
     if with_bwd:
@@ -248,8 +247,9 @@ def main():
         if with_bwd:
             moe.moe_ffn_forward(shape, dev["x"], dev["logits"], dev["w_gate_up"], dev["w_down"], out, saved_nx, ws,
                                 moe.MODE_SERIALIZED)
+            bmode = moe.MODE_SERIALIZED if bwd_best == "serialized" else moe.MODE_PERSISTENT   # the faster one above
             noxp_bwd_ms = timed(lambda: moe.moe_ffn_backward(shape, dy, dev["x"], dev["w_gate_up"], dev["w_down"], saved_nx,
-                                                             dx, dw1, dw2, dtw, ws_b), args.steps, args.warmup)
+                                                             dx, dw1, dw2, dtw, ws_b, bmode), args.steps, args.warmup)
         del saved_nx
 
     # ---- per-operator durations: the serialized sequence with HIP events between launches
@@ -349,6 +349,8 @@ def main():
             "forward_floor_us": f_all, "forward_frac": f_all / (ms["serialized"] * 1e3),
         }
 
+    if fwd_bwd:
+        res["config"]["backward_mode"] = bwd_best
     if bwd_ms is not None:
         # backward: 2x the forward GEMM work (act_grad, gate_grad, w2_grad, w1_grad); bytes: weights read once,
         # weight gradients written once, activations and activation gradients read / written once per use
