@@ -341,12 +341,17 @@ __device__ __forceinline__ void rank_chunk(const RouteParams& p, int group, int3
   unsigned long long* s_mask = reinterpret_cast<unsigned long long*>(s_lds);   // [E_local]
   int32_t* s_base = s_lds + 2 * kMaxE;                                           // [2][E_local] first row per half
   const int sub0 = group * (kChunk / kSub);
-  int run = 0;   // rows of the experts before this block of 64
-  for (int e0 = 0; e0 < p.E_local; e0 += kWave) {
-    const int e = e0 + lane;
+  // The table walk is a chain of round trips to the L2, so it is spread over all 64 lanes: with fewer than 64
+  // local experts, `parts` lanes share an expert and take every parts-th batch of rows (E_local = 32: 8 round
+  // trips instead of 16 at T = 8192); their partial sums are added with a butterfly.
+  const int ew = p.E_local >= kWave ? kWave : (p.E_local <= 1 ? 1 : 1 << (32 - __builtin_clz(p.E_local - 1)));
+  const int parts = kWave / ew, part = lane >> __builtin_ctz(ew), el = lane & (ew - 1);
+  int run = 0;   // rows of the experts before this block of ew
+  for (int e0 = 0; e0 < p.E_local; e0 += ew) {
+    const int e = e0 + el;
     int total = 0, before = 0, own0 = 0;
     if (e < p.E_local) {
-      for (int c0 = 0; c0 < p.n_sub; c0 += kHistBatch) {
+      for (int c0 = part * kHistBatch; c0 < p.n_sub; c0 += kHistBatch * parts) {
         int v[kHistBatch];
 #pragma unroll
         for (int u = 0; u < kHistBatch; ++u) v[u] = c0 + u < p.n_sub ? p.chunk_cnt[(size_t)(c0 + u) * p.E_local + e] : 0;
@@ -358,8 +363,13 @@ __device__ __forceinline__ void rank_chunk(const RouteParams& p, int group, int3
         }
       }
     }
-    const int incl = wave_incl_scan(total, lane);
-    if (e < p.E_local) {
+    for (int off = ew; off < kWave; off <<= 1) {   // own0 is non-zero in one part only
+      total += __shfl_xor(total, off, kWave);
+      before += __shfl_xor(before, off, kWave);
+      own0 += __shfl_xor(own0, off, kWave);
+    }
+    const int incl = wave_incl_scan(part == 0 ? total : 0, lane);   // lanes 0..ew-1: running sum over the experts
+    if (part == 0 && e < p.E_local) {
       const int first = run + incl - total + before;
       s_mask[e] = 0ull;
       s_base[e] = first;
