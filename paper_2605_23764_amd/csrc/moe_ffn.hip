@@ -193,8 +193,8 @@ int launch_status() { return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_
 int run_route(const Ctx& c, const float* logits) {
   RouteParams p = route_params(c, logits);
   hipLaunchKernelGGL(route_kernel, dim3(p.n_sub), dim3(512), 0, c.stream, p);
-  hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, c.stream, p);
-  hipLaunchKernelGGL(rank_kernel, dim3((p.n_groups + 3) / 4), dim3(256), 0, c.stream, p);
+  hipLaunchKernelGGL(scan_rank_kernel, dim3(1 + (p.n_groups + kScanRankWaves - 1) / kScanRankWaves), dim3(kScanRankWaves * kWave), 0,
+                     c.stream, p);
   return launch_status();
 }
 

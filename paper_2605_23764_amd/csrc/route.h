@@ -413,16 +413,20 @@ __global__ __launch_bounds__(512) void route_kernel(RouteParams p) {
   route_chunk(p, blockIdx.x, s_idx, s_val);
 }
 
-__global__ __launch_bounds__(1024) void scan_kernel(RouteParams p) {
-  __shared__ int32_t s_cnt[kMaxE + 2];
-  __shared__ int32_t s_part[16 * kMaxE];
-  scan_all(p, s_cnt, s_part);
-}
-
-__global__ __launch_bounds__(256) void rank_kernel(RouteParams p) {
-  __shared__ int32_t s_lds[4 * kRankLdsWords];
-  int group = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
-  if (group < p.n_groups) rank_chunk(p, group, s_lds + (threadIdx.x / kWave) * kRankLdsWords);
+// The two steps that need nothing but the finished histogram table, side by side in one launch:
+// workgroup 0 sums the table into counts, offsets and the M-tile map; every other workgroup ranks 4
+// groups of 64 tokens, one per wave.  Grid: 1 + ceil(n_groups / 4) workgroups of 256 threads.
+constexpr int kScanRankWaves = 4;
+__global__ __launch_bounds__(kScanRankWaves * kWave) void scan_rank_kernel(RouteParams p) {
+  __shared__ int32_t s_lds[kScanRankWaves * kRankLdsWords];   // rank: 4 * kMaxE words per wave; scan: (5 * kMaxE + 66) words
+  static_assert(kScanRankWaves * kRankLdsWords >= (kScanRankWaves + 1) * kMaxE + 2 + 64, "LDS of the scan step");
+  if (blockIdx.x == 0) {
+    scan_all(p, s_lds, s_lds + kMaxE + 64);
+    return;
+  }
+  const int wave = threadIdx.x / kWave;
+  const int group = (blockIdx.x - 1) * kScanRankWaves + wave;
+  if (group < p.n_groups) rank_chunk(p, group, s_lds + wave * kRankLdsWords);
 }
 
 // M-tile map from the rows per expert alone (the backward rebuilds it from the
