@@ -341,6 +341,9 @@ def main():
         f1 = power_floor_us(flops1, rd1, wr1)
         f2 = power_floor_us(flops2, rd2, wr2)
         f_all = f1 + f2 + power_floor_us(0, bytes_perm / 2 + R * H * eb + 4.0 * T * cfg.E, bytes_perm / 2 + T * H * eb)
+        # the same kernel against the third bound: at the board's power limit its MFMA + HBM energy needs f1 microseconds
+        res["roofline"]["power_bound"] = {"min_us_at_board_power_limit": f1, "measured_us": stage_us["gemm1_swiglu"],
+                                          "frac": f1 / stage_us["gemm1_swiglu"]}
         res["detail"]["power_bound"] = {
             "board_cap_W": POWER_CAP_W, "idle_W": POWER_IDLE_W, "pJ_per_flop_mfma_bf16": PJ_PER_FLOP_MFMA_BF16,
             "pJ_per_byte_hbm_read": PJ_PER_BYTE_READ, "pJ_per_byte_hbm_write": PJ_PER_BYTE_WRITE,
