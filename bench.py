@@ -24,33 +24,25 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 
 # HBM bytes per launch of the dominant kernel (grouped GEMM-1 + SwiGLU), from separate
 # `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` runs of `bench.py --headline-only`: counter KiB per
-# dispatch, FETCH_SIZE scaled by 2.0000 and WRITE_SIZE by 0.9999 (2 097 152 KiB divided by what the same
-# counters read for the 2 GiB copy of `moe_probe_copy` in the same run).  Counters cannot be read inside a
-# timed run, so the figure of the last profiled build is carried here.
-MEASURED_TRAFFIC_BYTES = {"c3": (976169.3 * 2.0000 + 98876.0 * 0.9999) * 1024}
-
-# Power bound.  The SMI sensors, polled from outside while `--hold` keeps one kernel running, show the GEMMs, the
-# whole forward and the whole backward at the 1400 W board limit with the clock pulled down to 1.9-2.2 GHz,
-# and the copy-like kernels at 890-990 W and 2.4 GHz.  Energy per unit of work from the probes at full rate
-# (register-only MFMAs on random data: 2.12 PFLOP/s at 1331 W; read-only, write-only and copy streams of random
-# data: 3.95 / 6.9 / 5.24 TB/s at 866 / 989 / 986 W; idle 294 W), carried here because a timed run cannot poll them.
-# A kernel cannot finish sooner than its MFMA + HBM energy divided by (cap - idle), whatever it overlaps.
-POWER_CAP_W, POWER_IDLE_W = 1400.0, 294.0
-PJ_PER_FLOP_MFMA_BF16 = (1331.0 - POWER_IDLE_W) / 2.12e15 * 1e12
-PJ_PER_BYTE_READ = (866.0 - POWER_IDLE_W) / 3.95e12 * 1e12
-PJ_PER_BYTE_WRITE = 2 * (986.0 - POWER_IDLE_W) / 5.24e12 * 1e12 - PJ_PER_BYTE_READ
+# dispatch, each scaled by what the same counter reads for the 2 GiB copy of `moe_probe_copy` in the same run
+# (FETCH_SIZE x 2.0000, WRITE_SIZE x 0.9999).  Counters cannot be read inside a timed run, so the figure of the
+# last profiled build is carried here, tagged with the hash of the kernel source it was measured on; when the
+# source has changed since, `traffic` is reported as null rather than a stale number.
+MEASURED_TRAFFIC = {"c3": {"bytes": (976169.3 * 2.0000 + 98876.0 * 0.9999) * 1024,
+                           "gemm_bf16_h_sha256_16": "unprofiled"}}
 
 
-def power_floor_us(flops, bytes_read, bytes_written):
-    joule = (flops * PJ_PER_FLOP_MFMA_BF16 + bytes_read * PJ_PER_BYTE_READ + bytes_written * PJ_PER_BYTE_WRITE) * 1e-12
-    return joule / (POWER_CAP_W - POWER_IDLE_W) * 1e6
+def gemm_source_tag():
+    import hashlib
+    with open(os.path.join(ROOT, "paper_2605_23764_amd", "csrc", "gemm_bf16.h"), "rb") as f:
+        return hashlib.sha256(f.read()).hexdigest()[:16]
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-backward", action="store_true")
@@ -59,7 +51,7 @@ def main():
                          "cold / no-copy variants): the form the rocprofv3 summaries are taken from")
     ap.add_argument("--hold", default=None, metavar="STAGE:SECONDS[,STAGE:SECONDS...]",
                     help="instead of the benchmark, run each named stage (idle, route, permute, gemm1_swiglu, gemm2, "
-                         "combine, forward, backward, probe_mfma_random, probe_mfma_ones, probe_copy, torch_read_sum, "
+                         "combine, forward, backward, probe_mfma_random, probe_mfma_ones, probe_copy, probe_read, "
                          "torch_fill) back to back for SECONDS and print wall-clock marks, so that "
                          "an outside poll of the SMI power / clock sensors can be matched to it")
     args = ap.parse_args()
@@ -120,7 +112,7 @@ def main():
         held["probe_mfma_random"] = lambda: moe.moe_probe_mfma_bf16(256, 1 << 16, 1, p_sink)
         held["probe_mfma_ones"] = lambda: moe.moe_probe_mfma_bf16(256, 1 << 16, 0, p_sink)
         held["probe_copy"] = lambda: moe.moe_probe_copy(p_src, p_dst, p_src.numel())
-        held["torch_read_sum"] = lambda: p_src.view(torch.float32).sum()     # read-only stream of 2 GiB
+        held["probe_read"] = lambda: moe.moe_probe_read(p_src, p_src.numel(), p_sink)   # read-only stream of 2 GiB
         held["torch_fill"] = lambda: p_dst.fill_(1)                          # write-only stream of 2 GiB
         for item in args.hold.split(","):
             name, secs = item.split(":")
@@ -216,11 +208,13 @@ def main():
         "mfma_random": timed(lambda: moe.moe_probe_mfma_bf16(n_wg, n_mfma, 1, sink), 5, 2),
         "mfma_ones": timed(lambda: moe.moe_probe_mfma_bf16(n_wg, n_mfma, 0, sink), 5, 2),
         "copy": timed(lambda: moe.moe_probe_copy(cp_src, cp_dst, cp_src.numel()), 10, 3),
+        "read": timed(lambda: moe.moe_probe_read(cp_src, cp_src.numel(), sink), 10, 3),
     }
     probe_flop = n_wg * 4 * n_mfma * 32768.0
     ceilings = {"mfma_bf16_random_operands_tflops": probe_flop / (probe_ms["mfma_random"] * 1e-3) / 1e12,
                 "mfma_bf16_constant_operands_tflops": probe_flop / (probe_ms["mfma_ones"] * 1e-3) / 1e12,
-                "copy_GBs_read_plus_write": 2.0 * cp_src.numel() / (probe_ms["copy"] * 1e-3) / 1e9}
+                "copy_GBs_read_plus_write": 2.0 * cp_src.numel() / (probe_ms["copy"] * 1e-3) / 1e9,
+                "read_only_GBs": cp_src.numel() / (probe_ms["read"] * 1e-3) / 1e9}
     del cp_src, cp_dst
     R = int(saved.offsets.cpu()[-1])
     bwd_ms = None
@@ -275,6 +269,24 @@ def main():
     for i, (name, _) in enumerate(stages):
         stage_us[name] = float(np.mean([ev[it][i].elapsed_time(ev[it][i + 1]) for it in range(args.steps)]) * 1e3)
 
+    # ---- the paper's interval, Dispatch to Combine (Section 5.2), in both launch modes: routing once, then HIP events
+    # around moe_dispatch_to_combine (serialized: four launches; persistent: exactly one)
+    d2c_us = {}
+    for name, mode in modes.items():
+        if name not in ms:
+            continue
+
+        def reroute(_i):   # untimed: the routing launches also reset the tile scheduler's counters and queues
+            moe.moe_route(shape, dev["logits"], saved, ws)
+
+        def d2c(_i, mode=mode):
+            moe.moe_dispatch_to_combine(shape, dev["x"], dev["w_gate_up"], dev["w_down"], out, saved, ws, mode)
+        for i in range(args.warmup):
+            reroute(i)
+            d2c(i)
+        t_ = sorted(timed_each(d2c, args.steps, before=reroute))
+        d2c_us[name] = {"mean": float(np.mean(t_)) * 1e3, "median": t_[len(t_) // 2] * 1e3, "min": t_[0] * 1e3}
+
     T, H, I, El = cfg.T, cfg.H, cfg.I, cfg.E_local
     active = int((saved.counts.cpu() > 0).sum())
     flops1, flops2 = 2.0 * R * H * 2 * I, 2.0 * R * I * H
@@ -288,15 +300,18 @@ def main():
     gemm_tflops = (flops1 + flops2) / (g1 + g2) / 1e12
     ridge = MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)
     hbm_bound = (flops1 / bytes1) < ridge
+    kname = "grouped_gemm_bf16_kernel<NN, swiglu>" if cfg.dtype == "bf16" else "grouped_gemm_f32_kernel<swiglu>"
     if hbm_bound:
-        roof = {"bound": "hbm", "kernel": "grouped_gemm_bf16_kernel<swiglu>", "achieved": bytes1 / g1 / 1e9,
+        roof = {"bound": "hbm", "kernel": kname, "achieved": bytes1 / g1 / 1e9,
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bytes1 / g1 / 1e9 / HBM_PEAK_GBS, "traffic": None}
     else:
-        roof = {"bound": "mfma", "kernel": "grouped_gemm_bf16_kernel<swiglu>", "achieved": flops1 / g1 / 1e12,
+        roof = {"bound": "mfma", "kernel": kname, "achieved": flops1 / g1 / 1e12,
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": flops1 / g1 / 1e12 / MFMA_BF16_PEAK_TFLOPS,
                 "traffic": None}
 
-    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(cfg.name) if with_bwd else None   # profiled with H1 stored
+    tr = MEASURED_TRAFFIC.get(cfg.name)
+    if tr is not None and with_bwd and tr["gemm_bf16_h_sha256_16"] == gemm_source_tag():   # profiled with H1 stored
+        roof["traffic"] = tr["bytes"]
     fwd_bwd = cfg.name == "c5"
     step_ms = ms[best] + (bwd_ms if fwd_bwd else 0.0)
     res = {
@@ -312,7 +327,8 @@ def main():
         "vs_baseline": None,
         "dtype": cfg.dtype,
         "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: T={T} H={H} I={I} E={cfg.E} E_local={El} k={cfg.k} R={R}",
+        "config": {"workload": f"{cfg.name}: T={T} H={H} I={I} E={cfg.E} E_local={El} k={cfg.k} R={R}"
+                               + (" (router bias -2.4*log10(Zipf rank), seeded rank permutation)" if cfg.name == "c4" else ""),
                    "mode": best, "active_experts": active},
         "roofline": roof,
         "detail": {
@@ -323,7 +339,14 @@ def main():
             "us_per_layer_events": spread,
             "us_per_layer_cold": cold,
             "stage_us": stage_us,
-            "dispatch_to_combine_us_serialized": sum(v for k, v in stage_us.items() if k != "route"),
+            "dispatch_to_combine_us": d2c_us,
+            "dispatch_to_combine_us_sum_of_stages": sum(v for k, v in stage_us.items() if k != "route"),
+            # every operand read once, every result written once (the figures the roofline fractions are quoted on)
+            "algorithmic": {"route": {"bytes": 4.0 * T * cfg.E + 12.0 * T * cfg.k},
+                            "permute": {"bytes": bytes_perm},
+                            "gemm1_swiglu": {"bytes": bytes1, "flops": flops1, "bytes_with_stored_H1": bytes1 + 2 * R * I * eb},
+                            "gemm2": {"bytes": bytes2, "flops": flops2},
+                            "combine": {"bytes": bytes_comb}},
             "grouped_gemm_tflops": gemm_tflops,
             "grouped_gemm_frac_of_bf16_mfma_peak": gemm_tflops / MFMA_BF16_PEAK_TFLOPS,
             "gemm1_tflops": flops1 / g1 / 1e12, "gemm2_tflops": flops2 / g2 / 1e12,
@@ -334,23 +357,6 @@ def main():
             "measured_ceilings": ceilings,
         },
     }
-
-    if cfg.dtype == "bf16":
-        rd1, wr1 = (active * H * 2 * I + R * H) * eb, R * I * eb * (3 if with_bwd else 1)   # H1 stored for the backward
-        rd2, wr2 = (active * I * H + R * I) * eb, R * H * eb
-        f1 = power_floor_us(flops1, rd1, wr1)
-        f2 = power_floor_us(flops2, rd2, wr2)
-        f_all = f1 + f2 + power_floor_us(0, bytes_perm / 2 + R * H * eb + 4.0 * T * cfg.E, bytes_perm / 2 + T * H * eb)
-        # the same kernel against the third bound: at the board's power limit its MFMA + HBM energy needs f1 microseconds
-        res["roofline"]["power_bound"] = {"min_us_at_board_power_limit": f1, "measured_us": stage_us["gemm1_swiglu"],
-                                          "frac": f1 / stage_us["gemm1_swiglu"]}
-        res["detail"]["power_bound"] = {
-            "board_cap_W": POWER_CAP_W, "idle_W": POWER_IDLE_W, "pJ_per_flop_mfma_bf16": PJ_PER_FLOP_MFMA_BF16,
-            "pJ_per_byte_hbm_read": PJ_PER_BYTE_READ, "pJ_per_byte_hbm_write": PJ_PER_BYTE_WRITE,
-            "gemm1_floor_us": f1, "gemm1_frac": f1 / stage_us["gemm1_swiglu"],
-            "gemm2_floor_us": f2, "gemm2_frac": f2 / stage_us["gemm2"],
-            "forward_floor_us": f_all, "forward_frac": f_all / (ms["serialized"] * 1e3),
-        }
 
     if fwd_bwd:
         res["config"]["backward_mode"] = bwd_best
@@ -365,9 +371,6 @@ def main():
             "algorithmic_GBs": bytes_b / (bwd_ms * 1e-3) / 1e9, "algorithmic_bytes": bytes_b,
             "frac_of_hbm_peak": bytes_b / (bwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         }
-        if cfg.dtype == "bf16":   # about half of the backward's bytes are reads, half writes
-            fb = power_floor_us(flops_b, bytes_b / 2, bytes_b / 2)
-            res["detail"]["backward"].update({"power_floor_us": fb, "power_frac": fb / (bwd_ms * 1e3)})
 
     if not args.no_cpu_baseline:
         import oracle

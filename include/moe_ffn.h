@@ -7,15 +7,20 @@
  * projections), SwiGLU, grouped GEMM-2 (down projection), Combine (accumulate
  * the top-k contributions weighted by the routing scores), and the seven-node
  * backward graph.  The layer can run as one kernel launch per operator
- * ("serialized", the paper's kernel-by-kernel baseline of Section 2.3) or as a
- * single persistent launch that executes a static tile task list with
- * event-counter dependencies (the paper's Sections 4.3-4.4).
+ * ("serialized", the paper's kernel-by-kernel baseline of Section 2.3) or with
+ * everything from Dispatch to Combine (the interval the paper times, Section 5.2)
+ * as a single persistent launch that executes a static tile task list with
+ * event-counter dependencies (the paper's Sections 4.3-4.4); routing runs ahead
+ * of that launch as two small kernels.
  *
  * Conventions
  *   - Every pointer named d_* or documented "device" is device (HBM) memory on
  *     the current HIP device; everything else is host memory.
  *   - All tensors are row-major and contiguous.  Device pointers must be
- *     16-byte aligned.
+ *     16-byte aligned.  MOE_MODE_PERSISTENT additionally requires 128-byte
+ *     alignment of the workspace and of MoeSaved.Xp and MoeSaved.A (tiles of
+ *     these buffers change hands between compute units inside the launch, and
+ *     no cache line may be shared by two tiles); MOE_ERR_INVALID_ARG otherwise.
  *   - The library never allocates or frees device memory, never synchronises
  *     the stream and never reads results back: all work is enqueued on
  *     `stream`.  The caller owns every buffer and the stream.
@@ -44,14 +49,15 @@ typedef enum MoeStatus {
   MOE_ERR_UNSUPPORTED_SHAPE = -2, /* shape outside the limits listed at MoeShape */
   MOE_ERR_WORKSPACE_TOO_SMALL = -3,
   MOE_ERR_LAUNCH = -4,            /* a HIP launch or API call failed */
-  MOE_ERR_SCHED_TIMEOUT = -5      /* persistent scheduler: a bounded wait expired */
+  MOE_ERR_SCHED_TIMEOUT = -5,     /* persistent scheduler: a bounded wait expired */
+  MOE_ERR_XCD_PLACEMENT = -6      /* microbenchmark modes 1 and 3: workgroups of one class (id % 8) span several XCDs */
 } MoeStatus;
 
 typedef enum MoeDtype { MOE_F32 = 0, MOE_BF16 = 1 } MoeDtype;
 
 typedef enum MoeMode {
   MOE_MODE_SERIALIZED = 0, /* one launch per operator, stream ordered */
-  MOE_MODE_PERSISTENT = 1  /* one launch, tile tasks + event counters  */
+  MOE_MODE_PERSISTENT = 1  /* Dispatch to Combine as one launch: tile tasks + event counters */
 } MoeMode;
 
 /*
@@ -80,7 +86,7 @@ typedef struct MoeShape {
  *   token_of [R_max] i32, slot_of [R_max] i32  inverse maps (first R entries)
  *   Xp [R_max,H]  dispatched tokens          (dtype)  may be NULL: no permuted copy is
  *                        kept; bf16 GEMM-1 and the backward's w1_grad then read x through
- *                        token_of (Section 4.2: no extra trip through HBM), other cases
+ *                        token_of (Section 4.4: no extra trip through HBM), other cases
  *                        make the copy in workspace memory
  *   H1 [R_max,2I] GEMM-1 output, gate|up     (dtype)  may be NULL: not stored
  *   A  [R_max,I]  SwiGLU output              (dtype)
@@ -130,7 +136,11 @@ int moe_ffn_workspace_bytes(const MoeShape* shape, size_t* fwd_bytes, size_t* bw
  *              NULL or saved->Xp NULL) the first grouped bf16 GEMM reads the token rows
  *              of x through the permutation and the permuted copy is not made at all
  *   d_workspace, workspace_bytes  >= moe_ffn_workspace_bytes(...).fwd_bytes
- *   mode       MoeMode
+ *   mode       MoeMode.  MOE_MODE_PERSISTENT: the router and the prefix-sum / rank step run as two
+ *              launches, then ONE launch runs every Dispatch, GEMM-1, GEMM-2 and Combine tile task.
+ *              Its workers hand tiles over through the L2 of the accelerator die (XCD) they share;
+ *              they verify at run time (hardware XCC id) that the workers of a queue all sit on one die
+ *              and use device-wide fences for that queue otherwise.
  * Returns after enqueueing.  A scheduler timeout (MOE_MODE_PERSISTENT only) is
  * reported by moe_ffn_last_status().
  */
@@ -180,12 +190,41 @@ int moe_ffn_last_status(const MoeShape* shape, const void* d_workspace);
  */
 int moe_ffn_debug_set_spin_limit(uint32_t polls);
 
+/*
+ * Test hook for the schedulers' fallback (paper Section 4.3: an event is triggered only once the task's
+ * outputs are readable by the consumer).  Nonzero makes the single-launch forward and backward behave as
+ * if every queue's workers had reported several XCDs: every tile hand-off uses device-wide release / acquire fences
+ * instead of the XCD-local ones.  Results are unchanged.  Host-only, process-wide.
+ */
+int moe_ffn_debug_force_device_scope(int on);
+
+/*
+ * Test hook for checking the device-built schedule itself (paper Section 4.3: thresholds equal producer
+ * counts, queue order is topological): byte offsets of the scheduler's tables inside the forward
+ * (backward = 0) or backward (backward != 0) workspace and the constants needed to decode them.
+ * out[0..6]  = offsets of: meta words, tile_expert, tile_row0, tile_rows (int32 per M tile), event counters
+ *              (uint32), queue heads, task descriptors ([8 queues][max_tasks_per_queue] x {type | index << 8,
+ *              M tile, dependent event (-1: none), threshold}, int32 each)
+ * out[7..9]  = max M tiles, max tasks per queue, number of event counters
+ * out[10,11] = first per-tile event (Xp rows of M tile m ready: +m; A rows ready: + max M tiles + m), the
+ *              event counting finished GEMM-2 tiles
+ * out[12..14] = meta word indices: number of M tiles, first of the 8 queue lengths, GEMM-2 tile total
+ * out[15..22] = queues, rows per PERMUTE task, GEMM-1 N tiles, GEMM-2 N tiles, wide tile rows, tall tile rows
+ *              (0: none), lag (in tile pairs) of GEMM-2 tasks behind GEMM-1 tasks, bytes per descriptor
+ * out[23]    = backward: N tiles of act_grad (the chain's first GEMM)
+ * out[24]    = meta word index: workers of the last single launch that fell back to device-wide fences
+ * n_out must be at least MOE_LAYOUT_WORDS.  Host-only.
+ */
+#define MOE_LAYOUT_WORDS 25
+int moe_ffn_debug_layout(const MoeShape* shape, int backward, int64_t* out, int n_out);
+
 /* ---- Stage entry points (the serialized path's operators, one launch each;
  *      used by the unit tests and the benchmark).  Same buffers as above. ---- */
 
 /* Routing + Dispatch bookkeeping (paper Section 2.2, routing; Section 5.1,
  * tile offsets derived from the routing result at run time): fills topk_idx, topk_w, counts, offsets, row_of,
- * token_of, slot_of of `saved` and the tile map in the workspace. */
+ * token_of, slot_of of `saved`, the tile map in the workspace and the tile scheduler's task tables (built for
+ * this `saved`: with or without Dispatch tasks, depending on saved->Xp). */
 int moe_route(const MoeShape* shape, const float* d_logits, const MoeSaved* saved,
               void* d_workspace, size_t workspace_bytes, void* stream);
 
@@ -207,6 +246,16 @@ int moe_grouped_gemm(const MoeShape* shape, const void* d_w_down, const MoeSaved
 int moe_combine(const MoeShape* shape, const MoeSaved* saved, void* d_out,
                 void* d_workspace, size_t workspace_bytes, void* stream);
 
+/* Dispatch to Combine, the interval the paper times (Section 5.2), on the routing results moe_route left in the
+ * SAME `saved` and workspace: Dispatch permute, GEMM-1 + SwiGLU, GEMM-2, Combine.  mode MOE_MODE_SERIALIZED: one
+ * launch per operator (Section 2.3's kernel-by-kernel execution); MOE_MODE_PERSISTENT: exactly one launch of
+ * tile tasks with event counters (Sections 4.3-4.4; alignment rule at the top of this file), which consumes
+ * the counters and queues moe_route prepared: one call per moe_route call (a second one finds every ticket
+ * taken and does nothing).  Results are bit-identical.  moe_ffn_forward(mode) = moe_route + this. */
+int moe_dispatch_to_combine(const MoeShape* shape, const void* d_x, const void* d_w_gate_up, const void* d_w_down,
+                            void* d_out, const MoeSaved* saved, void* d_workspace, size_t workspace_bytes, int mode,
+                            void* stream);
+
 /* ---- SwiGLU + Add microbenchmark (paper Section 6: tile interleaving and L2 reuse, Section 6.1;
  *      static against dynamic scheduling, Section 6.2) ----
  *   S[m,j]   = silu(X[m,j]) * X[m,N+j]      X [M,2N] bf16, S [M,N] bf16 (intermediate, written)
@@ -217,8 +266,12 @@ int moe_combine(const MoeShape* shape, const MoeSaved* saved, void* d_out,
  * tile's two tasks stay on the XCD that owns the tile).  Results are bit-identical in all modes.
  * tile_rows (1..64) is the number of rows of one tile task (modes 1-3; mode 0 uses it as its loop granule).
  * N must be a multiple of 8, all pointers device and 16-byte aligned; d_workspace >=
- * moe_microbench_workspace_bytes(M).  A bounded wait that expires is reported by the status word:
- * moe_microbench_last_status() (host-blocking 4-byte copy) returns MOE_OK or MOE_ERR_SCHED_TIMEOUT. */
+ * moe_microbench_workspace_bytes(M).  Modes 1 and 3 hand S tiles over between compute units behind one
+ * L2: they require d_s 128-byte aligned and tiles of whole 128-byte lines (tile_rows * N * 2 a multiple
+ * of 128), MOE_ERR_INVALID_ARG otherwise, and their workers check (hardware XCC id) that the workgroups of
+ * one class (id % 8), which hand tiles to each other, all run on one XCD.
+ * The status word reports what went wrong inside a launch: moe_microbench_last_status() (host-blocking
+ * 4-byte copy) returns MOE_OK, MOE_ERR_SCHED_TIMEOUT (a bounded wait expired) or MOE_ERR_XCD_PLACEMENT. */
 size_t moe_microbench_workspace_bytes(int M);
 int moe_microbench_swiglu_add(int M, int N, const void* d_x, const void* d_y, void* d_s, void* d_out, int mode,
                               int tile_rows, void* d_workspace, size_t workspace_bytes, void* stream);
@@ -226,17 +279,20 @@ int moe_microbench_last_status(const void* d_workspace);
 
 /* ---- Ceiling probes (measurement aids for the benchmark; no step of the layer) ----
  * What this GPU sustains on the two resources the grouped GEMMs and the permute / combine steps are
- * priced against (Section 5.1 evaluates the operators against hardware utilisation), with nothing
- * else in the way; both only enqueue one kernel on `stream`.
+ * priced against (Section 2.3 judges the operators by hardware utilisation), with nothing
+ * else in the way; each only enqueues one kernel on `stream`.
  * moe_probe_mfma_bf16: n_workgroups x 4 waves, each issuing mfma_per_wave (a multiple of 8)
  *   32x32x16 bf16 MFMAs on registers only = n_workgroups * 4 * mfma_per_wave * 32768 flop;
  *   random_operands != 0 uses pseudo-random values in [1, 2) instead of all ones (the sustained rate
  *   depends on the data).  d_sink: 4 bytes of device memory, 4-byte aligned, never written.
  * moe_probe_copy: streaming copy of `bytes` (a multiple of 16; pointers device, 16-byte aligned,
  *   not overlapping).
- * Both return MOE_OK, MOE_ERR_INVALID_ARG or MOE_ERR_LAUNCH. */
+ * moe_probe_read: the same stream without the stores (read-only); d_sink: 4 bytes of device memory,
+ *   4-byte aligned, left unchanged.
+ * All return MOE_OK, MOE_ERR_INVALID_ARG or MOE_ERR_LAUNCH. */
 int moe_probe_mfma_bf16(int n_workgroups, int mfma_per_wave, int random_operands, void* d_sink, void* stream);
 int moe_probe_copy(const void* d_src, void* d_dst, size_t bytes, void* stream);
+int moe_probe_read(const void* d_src, size_t bytes, void* d_sink, void* stream);
 
 #ifdef __cplusplus
 }

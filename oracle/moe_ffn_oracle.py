@@ -92,7 +92,7 @@ def sigmoid(z):
 
 def swiglu(h1, I):
     """SwiGLU between the two GMMs (paper Section 2.2; widths 2I -> I as in the
-    Section 5.4 microbenchmark): A = g*sigmoid(g)*u, g = h1[:, :I], u = h1[:, I:]."""
+    Section 6 microbenchmark): A = g*sigmoid(g)*u, g = h1[:, :I], u = h1[:, I:]."""
     g, u = h1[:, :I], h1[:, I:]
     return g * sigmoid(g) * u
 

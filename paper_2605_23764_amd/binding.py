@@ -38,8 +38,10 @@ EXPORTS = (
     "moe_status_string", "moe_ffn_workspace_bytes", "moe_ffn_forward", "moe_ffn_backward",
     "moe_ffn_last_status", "moe_ffn_debug_set_spin_limit", "moe_route", "moe_permute", "moe_grouped_gemm_swiglu", "moe_grouped_gemm",
     "moe_combine", "moe_microbench_workspace_bytes", "moe_microbench_swiglu_add", "moe_microbench_last_status",
-    "moe_probe_mfma_bf16", "moe_probe_copy",
+    "moe_probe_mfma_bf16", "moe_probe_copy", "moe_probe_read",
+    "moe_ffn_debug_force_device_scope", "moe_ffn_debug_layout", "moe_dispatch_to_combine",
 )
+LAYOUT_WORDS = 25   # MOE_LAYOUT_WORDS
 
 
 def library_path() -> str:
@@ -221,6 +223,15 @@ def moe_combine(shape, saved: Saved, out, workspace, stream=None) -> None:
            "moe_combine")
 
 
+def moe_dispatch_to_combine(shape, x, w_gate_up, w_down, out, saved: Saved, workspace, mode: int = MODE_SERIALIZED,
+                            stream=None) -> None:
+    sv = saved.c_struct()
+    wp, wb = _ws(workspace)
+    _check(load_library().moe_dispatch_to_combine(ctypes.byref(shape), _ptr(x), _ptr(w_gate_up), _ptr(w_down), _ptr(out),
+                                                  ctypes.byref(sv), wp, wb, ctypes.c_int(mode), _stream(stream)),
+           "moe_dispatch_to_combine")
+
+
 MB_SERIAL, MB_STATIC, MB_DYNAMIC, MB_DYNAMIC_XCD = 0, 1, 2, 3
 
 
@@ -244,6 +255,24 @@ def moe_probe_mfma_bf16(n_workgroups, mfma_per_wave, random_operands, sink, stre
     _check(load_library().moe_probe_mfma_bf16(ctypes.c_int(n_workgroups), ctypes.c_int(mfma_per_wave),
                                               ctypes.c_int(1 if random_operands else 0), _ptr(sink), _stream(stream)),
            "moe_probe_mfma_bf16")
+
+
+def moe_ffn_debug_force_device_scope(on: bool) -> None:
+    _check(load_library().moe_ffn_debug_force_device_scope(ctypes.c_int(1 if on else 0)),
+           "moe_ffn_debug_force_device_scope")
+
+
+def moe_ffn_debug_layout(shape, backward: bool = False):
+    """The LAYOUT_WORDS integers of moe_ffn_debug_layout (offsets of the scheduler's tables in the workspace)."""
+    out = (ctypes.c_int64 * LAYOUT_WORDS)()
+    _check(load_library().moe_ffn_debug_layout(ctypes.byref(shape), ctypes.c_int(1 if backward else 0), out,
+                                               ctypes.c_int(LAYOUT_WORDS)), "moe_ffn_debug_layout")
+    return list(out)
+
+
+def moe_probe_read(src, nbytes, sink, stream=None) -> None:
+    _check(load_library().moe_probe_read(_ptr(src), ctypes.c_size_t(nbytes), _ptr(sink), _stream(stream)),
+           "moe_probe_read")
 
 
 def moe_probe_copy(src, dst, nbytes, stream=None) -> None:

@@ -39,8 +39,10 @@ struct MicrobenchParams {
   __bf16* Out;         // [M, N]
   int M, N;            // N multiple of 8
   uint32_t* events;    // [n_tiles] static mode: SwiGLU tile done
-  uint32_t* queue;     // [16x] head and [16x + 1] tail of queue x (8 headers), [2] status; rings from word ring_base:
-                       // entries are local task id + 1, 0 = not yet published
+  uint32_t* queue;     // [16x] head and [16x + 1] tail of queue x (8 headers); [4..6] placement check (wave_sync.h);
+                       // rings from word ring_base: entries are local task id + 1, 0 = not yet published
+  uint32_t* status;    // one word, zeroed per call: bit 0 = a bounded wait expired, bit 1 = in a mode that relies on
+                       // XCD-local hand-offs the workgroups of one class (id % 8) do not all run on one XCD
   int n_tiles, tile_rows;
   int ring_base;       // first ring word, relative to queue
   uint32_t spin_limit;
@@ -100,8 +102,21 @@ __global__ void mb_clear_kernel(MicrobenchParams p, int n_q) {
     const int x = threadIdx.x;
     p.queue[16 * x] = 0;
     p.queue[16 * x + 1] = x < n_q ? (uint32_t)mb_queue(p.ring_base, p.n_tiles, n_q, x).n_local : 0u;
-    if (x == 0) p.queue[2] = 0;
+    if (x == 0) *p.status = 0;
+    if (x < 3) p.queue[4 + x] = 0;
   }
+}
+
+// Status bits (wave-uniform: called by the whole of wave 0).
+__device__ __forceinline__ void mb_flag(const MicrobenchParams& p, uint32_t bit) {
+  wave_atomic_or(p.status, bit);
+}
+// Modes 1 and 3 hand tiles over between the workgroups of one class (id % 8) through the L2 they are taken to
+// share.  Every worker reports the XCD it runs on; the one that reports last sees all reports and flags the launch
+// if some class is spread over several XCDs.  No worker waits for this.
+__device__ __forceinline__ void mb_check_placement(const MicrobenchParams& p, int wave) {
+  if (wave == 0 && placement_report(&p.queue[4], (int)(blockIdx.x % kNumXcd)) == gridDim.x - 1 && !placement_all_ok(&p.queue[4]))
+    mb_flag(p, 2u);
 }
 
 // Both single-launch kernels keep their control flow wave-uniform: wave 0 draws tickets, polls
@@ -114,12 +129,16 @@ __global__ void mb_clear_kernel(MicrobenchParams p, int n_q) {
 // (w, r): nothing is decided, fetched or updated at run time except the counters.
 // Because producer and consumer are known to share an XCD, the hand-off needs no device-wide
 // release (which writes back that XCD's whole L2): every producing wave waits until its stores have
-// reached the L2 (wait_own_stores), the consumer reads rows it has never touched in this launch
-// through that same L2.  Workgroup w runs on XCD w % 8 (round-robin dispatch, as everywhere in this library).
+// reached the L2 (wait_own_stores), the consumer reads lines its CU has never touched in this launch
+// through that same L2 (the host requires tiles of whole 128-byte lines in this mode, so no line of S is
+// shared by two tiles and no CU's vector L1 can hold a stale one).  Workers w and w + 8 share an XCD when
+// workgroups are dealt round-robin; every worker reports the XCD it really runs on and the status word
+// tells if a class (w % 8) was spread over several.
 __global__ __launch_bounds__(256) void mb_static_kernel(MicrobenchParams p) {
   __shared__ int s_box[2];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int W = gridDim.x, w = blockIdx.x;
+  mb_check_placement(p, wave);
   for (int base = 0; base < p.n_tiles; base += W) {
     const int ts = base + w;
     if (ts < p.n_tiles) {
@@ -139,7 +158,7 @@ __global__ __launch_bounds__(256) void mb_static_kernel(MicrobenchParams p) {
           if (++polls > p.spin_limit) { ok = 0; break; }
           __builtin_amdgcn_s_sleep(1);
         }
-        if (!ok) __hip_atomic_store(&p.queue[2], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (!ok) mb_flag(p, 1u);
         s_box[0] = ok;          // every lane stores the same value
       }
       __syncthreads();
@@ -164,6 +183,7 @@ __global__ __launch_bounds__(256) void mb_dynamic_kernel(MicrobenchParams p) {
   const MbQueue q = mb_queue(p.ring_base, p.n_tiles, n_q, x);
   const uint32_t total = 2u * (uint32_t)q.n_local;
   uint32_t* head = &p.queue[16 * x];
+  if (PER_XCD) mb_check_placement(p, wave);
   for (;;) {
     if (wave == 0) {
       int task = -1;                                     // no tickets left
@@ -175,7 +195,7 @@ __global__ __launch_bounds__(256) void mb_dynamic_kernel(MicrobenchParams p) {
           if (e != 0) { task = (int)e - 1; break; }
           __builtin_amdgcn_s_sleep(1);
         }
-        if (task == -2) __hip_atomic_store(&p.queue[2], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (task == -2) mb_flag(p, 1u);
       }
       s_box[0] = task;          // every lane stores the same value
     }

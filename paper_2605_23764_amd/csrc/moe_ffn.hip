@@ -5,6 +5,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "backward.h"
 #include "common.h"
 #include "gemm_bf16.h"
@@ -112,6 +114,10 @@ bool gathers_x(const Ctx& c) {
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+// Single-launch modes hand tiles over between CUs behind one L2 without invalidating the CUs' vector L1;
+// that is only sound if no 128-byte line is shared by two tasks' rows, i.e. if the buffers that are both
+// written and read inside the launch start on a line boundary (rows are multiples of 128 bytes).
+bool aligned128(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 127u) == 0; }
 
 int device_cus() {
   static int cached[64] = {0};
@@ -189,14 +195,6 @@ RouteParams route_params(const Ctx& c, const float* logits) {
 }
 
 int launch_status() { return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_LAUNCH; }
-
-int run_route(const Ctx& c, const float* logits) {
-  RouteParams p = route_params(c, logits);
-  hipLaunchKernelGGL(route_kernel, dim3(p.n_sub), dim3(512), 0, c.stream, p);
-  hipLaunchKernelGGL(scan_rank_kernel, dim3(1 + (p.n_groups + kScanRankWaves - 1) / kScanRankWaves), dim3(kScanRankWaves * kWave), 0,
-                     c.stream, p);
-  return launch_status();
-}
 
 PermuteParams permute_params(const Ctx& c, const void* x);
 
@@ -280,9 +278,15 @@ PermuteParams permute_params(const Ctx& c, const void* x) {
 // trip plus a short sleep: the default is several seconds).
 uint32_t g_spin_limit = 1u << 20;
 
+// Test hook: nonzero makes the single-launch schedulers behave as if every queue's workers had reported
+// several XCDs (device-scope fences on every chain event).
+int g_force_device_scope = 0;
+
+// Everything the scheduler's kernels need; pointers the caller does not have yet may be null (the routing
+// launches only read the shapes, the tile counts and the table addresses).
 template <bool BF16>
-int run_persistent(const Ctx& c, const void* x, const float* logits, const void* w_gate_up, const void* w_down,
-                   void* out) {
+SchedParams<BF16> sched_params(const Ctx& c, const void* x, const float* logits, const void* w_gate_up, const void* w_down,
+                               void* out) {
   using P = typename std::conditional<BF16, GemmParams, GemmParamsF32>::type;
   using T = typename std::conditional<BF16, __bf16, float>::type;
   SchedParams<BF16> sp;
@@ -305,15 +309,37 @@ int run_persistent(const Ctx& c, const void* x, const float* logits, const void*
   sp.meta = reinterpret_cast<int32_t*>(c.ws + c.L.meta);
   sp.max_mtiles = (int)max_mtiles(c.s);
   sp.max_tasks_per_q = (int)max_tasks_per_queue(c.s);
-  sp.n_rank_tasks = (sp.route.n_groups + kRankChunksPerTask - 1) / kRankChunksPerTask;
+  sp.n_events = (int)n_events(c.s);
   // COMBINE tasks of 32 tokens, halved (down to 4, one per wave) while there are fewer tasks than CUs
   sp.comb_tokens = kCombineTokens;
   while (sp.comb_tokens > 4 && (c.s.T + sp.comb_tokens - 1) / sp.comb_tokens < c.n_cu) sp.comb_tokens >>= 1;
   sp.n_comb_tasks = (c.s.T + sp.comb_tokens - 1) / sp.comb_tokens;
+  sp.force_device_scope = g_force_device_scope;
   sp.spin_limit = g_spin_limit;
   sp.timeout_status = MOE_ERR_SCHED_TIMEOUT;
-  hipLaunchKernelGGL(sched_clear_kernel, dim3(1), dim3(256), 0, c.stream, sp.events, (int)n_events(c.s), sp.qhead,
-                     sp.meta);
+  return sp;
+}
+
+// Routing, two launches: the router (top-k, softmax, per-chunk histograms), then prefix sums + M-tile map +
+// stable ranks.  The second launch also zeroes the tile scheduler's counters and writes its task tables (one
+// workgroup, beside the rank groups), so that either launch mode can follow.
+template <bool BF16>
+int run_route_t(const Ctx& c, const float* logits) {
+  const SchedParams<BF16> sp = sched_params<BF16>(c, nullptr, logits, nullptr, nullptr, nullptr);
+  const RouteParams& rp = sp.route;
+  hipLaunchKernelGGL(route_kernel, dim3(rp.n_sub), dim3(512), 0, c.stream, rp);
+  hipLaunchKernelGGL(sched_prepare_kernel<BF16>, dim3(1 + (rp.n_groups + kScanRankWaves - 1) / kScanRankWaves),
+                     dim3(kScanRankWaves * kWave), 0, c.stream, sp);
+  return launch_status();
+}
+int run_route(const Ctx& c, const float* logits) {
+  return c.s.dtype == MOE_BF16 ? run_route_t<true>(c, logits) : run_route_t<false>(c, logits);
+}
+
+// Dispatch to Combine as ONE launch of tile tasks (after run_route on the same MoeSaved).
+template <bool BF16>
+int run_persistent(const Ctx& c, const void* x, const void* w_gate_up, const void* w_down, void* out) {
+  const SchedParams<BF16> sp = sched_params<BF16>(c, x, nullptr, w_gate_up, w_down, out);
   hipLaunchKernelGGL(persistent_forward_kernel<BF16>, dim3(gemm_grid(c)), dim3(kGemmThreads), 0, c.stream, sp);
   return launch_status();
 }
@@ -453,9 +479,11 @@ int run_backward(const BwdCtx& c, const void* dy, const void* x, const void* w_g
       sp.meta = c.tiles.meta;
       sp.max_mtiles = (int)max_mtiles(s);
       sp.max_tasks_per_q = (int)max_tasks_per_queue(s);
+      sp.n_events = (int)n_events(s);
+      sp.force_device_scope = g_force_device_scope;
       sp.spin_limit = g_spin_limit;
       sp.timeout_status = MOE_ERR_SCHED_TIMEOUT;
-      hipLaunchKernelGGL(dgrad_prepare_kernel, dim3(1), dim3(kGemmThreads), 0, c.stream, sp, (int)n_events(s));
+      hipLaunchKernelGGL(dgrad_prepare_kernel, dim3(1), dim3(kGemmThreads), 0, c.stream, sp);
       hipLaunchKernelGGL(persistent_dgrad_kernel, dim3(grid), dim3(kGemmThreads), 0, c.stream, sp);
     } else {
       hipLaunchKernelGGL((grouped_gemm_bf16_kernel<kLayNT, kEpiSwigluGrad>), dim3(grid), dim3(kGemmThreads), 0, c.stream, pa);
@@ -509,6 +537,60 @@ int run_backward(const BwdCtx& c, const void* dy, const void* x, const void* w_g
   return launch_status();
 }
 
+
+// ---- SwiGLU + Add microbenchmark: host side shared by the two entry points ----
+size_t mb_workspace_bytes(int M) {
+  const size_t n = M > 0 ? (size_t)M : 0;
+  return align_up(kMbRingBase * 4) + align_up(n * 4) + align_up((2 * n + 2 * kNumXcd) * 4);
+}
+
+int mb_check_args(int M, int N, const void* x, const void* y, const void* s, const void* out, int mode, int tile_rows,
+                  const void* ws) {
+  if (M < 0 || N <= 0 || N % 8 || mode < 0 || mode > 3 || tile_rows < 1 || tile_rows > kMbMaxTileRows)
+    return MOE_ERR_INVALID_ARG;
+  if (M == 0) return MOE_OK;
+  const void* ptrs[] = {x, y, s, out, ws};
+  for (const void* q : ptrs)
+    if (!q || !aligned16(q)) return MOE_ERR_INVALID_ARG;
+  // modes 1 and 3 hand S tiles over between CUs behind one L2 without touching the CUs' vector L1: a tile must
+  // consist of whole 128-byte lines, or a CU could keep a line it read for one tile while its neighbour is written
+  if ((mode == 1 || mode == 3) && (!aligned128(s) || ((size_t)tile_rows * N * 2) % 128 != 0)) return MOE_ERR_INVALID_ARG;
+  return MOE_OK;
+}
+
+// `ws` holds mb_workspace_bytes(M) bytes; `status` = where the status word goes (nullptr: word 2 of ws).
+int mb_launch(int M, int N, const void* d_x, const void* d_y, void* d_s, void* d_out, int mode, int tile_rows, void* ws,
+              uint32_t* status, void* stream) {
+  const int chk = mb_check_args(M, N, d_x, d_y, d_s, d_out, mode, tile_rows, ws);
+  if (chk != MOE_OK || M == 0) return chk;
+  MicrobenchParams p;
+  p.X = static_cast<const __bf16*>(d_x); p.Y = static_cast<const __bf16*>(d_y);
+  p.S = static_cast<__bf16*>(d_s); p.Out = static_cast<__bf16*>(d_out);
+  p.M = M; p.N = N;
+  p.tile_rows = tile_rows;
+  p.n_tiles = (M + tile_rows - 1) / tile_rows;
+  // rings are addressed relative to the header block, so they start behind the event counters
+  p.queue = static_cast<uint32_t*>(ws);
+  p.status = status ? status : p.queue + 2;
+  p.events = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + align_up(kMbRingBase * 4));
+  p.ring_base = (int)((align_up(kMbRingBase * 4) + align_up((size_t)M * 4)) / 4);
+  p.spin_limit = g_spin_limit;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int workers = device_cus() * 4;   // four 256-thread workgroups per CU; a multiple of 8
+  const int grid = p.n_tiles < workers ? (p.n_tiles + 7) / 8 * 8 : workers;
+  if (mode == 0) {
+    hipLaunchKernelGGL(mb_swiglu_kernel, dim3(grid), dim3(256), 0, st, p);
+    hipLaunchKernelGGL(mb_add_kernel, dim3(grid), dim3(256), 0, st, p);
+  } else {
+    hipLaunchKernelGGL(mb_clear_kernel, dim3(std::min((p.n_tiles + 255) / 256, 1024)), dim3(256), 0, st, p,
+                       mode == 3 ? kNumXcd : 1);
+    if (mode == 1) hipLaunchKernelGGL(mb_static_kernel, dim3(grid), dim3(256), 0, st, p);
+    else if (mode == 2) hipLaunchKernelGGL(mb_dynamic_kernel<false>, dim3(grid), dim3(256), 0, st, p);
+    else hipLaunchKernelGGL(mb_dynamic_kernel<true>, dim3(grid), dim3(256), 0, st, p);
+  }
+  return launch_status();
+}
+
 }  // namespace
 
 extern "C" {
@@ -521,6 +603,7 @@ const char* moe_status_string(int status) {
     case MOE_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
     case MOE_ERR_LAUNCH: return "HIP launch failed";
     case MOE_ERR_SCHED_TIMEOUT: return "persistent scheduler wait timed out";
+    case MOE_ERR_XCD_PLACEMENT: return "workgroups of one class (id % 8) span several XCDs";
     default: return "unknown status";
   }
 }
@@ -579,6 +662,37 @@ int moe_combine(const MoeShape* shape, const MoeSaved* saved, void* d_out, void*
   return run_combine(c, d_out);
 }
 
+// Dispatch -> GEMM-1 + SwiGLU -> GEMM-2 -> Combine on routing results that are already in `saved` / the workspace.
+static int run_dispatch_to_combine(const Ctx& c, const void* d_x, const void* d_w_gate_up, const void* d_w_down,
+                                   void* d_out, int mode) {
+  if (mode != MOE_MODE_SERIALIZED && mode != MOE_MODE_PERSISTENT) return MOE_ERR_INVALID_ARG;
+  const void* ptrs[] = {d_x, d_w_gate_up, d_w_down, d_out};
+  for (const void* q : ptrs)
+    if (!q || !aligned16(q)) return MOE_ERR_INVALID_ARG;
+  if (mode == MOE_MODE_PERSISTENT) {
+    // Xp (PERMUTE -> GEMM-1) and A (GEMM-1 -> GEMM-2) change hands inside the launch; the workspace holds
+    // their fallback storage at 256-byte offsets
+    if (!aligned128(c.ws) || !aligned128(c.sv.Xp) || !aligned128(c.sv.A)) return MOE_ERR_INVALID_ARG;
+    return c.s.dtype == MOE_BF16 ? run_persistent<true>(c, d_x, d_w_gate_up, d_w_down, d_out)
+                                 : run_persistent<false>(c, d_x, d_w_gate_up, d_w_down, d_out);
+  }
+  int st;
+  if (!gathers_x(c) && (st = run_permute(c, d_x)) != MOE_OK) return st;
+  if ((st = run_gemm1(c, d_w_gate_up, gathers_x(c) ? d_x : nullptr)) != MOE_OK) return st;
+  if ((st = run_gemm2(c, d_w_down)) != MOE_OK) return st;
+  return run_combine(c, d_out);
+}
+
+int moe_dispatch_to_combine(const MoeShape* shape, const void* d_x, const void* d_w_gate_up, const void* d_w_down,
+                            void* d_out, const MoeSaved* saved, void* d_workspace, size_t workspace_bytes, int mode,
+                            void* stream) {
+  Ctx c;
+  int st = make_ctx(c, shape, saved, d_workspace, workspace_bytes, stream);
+  if (st != MOE_OK || c.s.T == 0) return st;
+  if (!saved) return MOE_ERR_INVALID_ARG;
+  return run_dispatch_to_combine(c, d_x, d_w_gate_up, d_w_down, d_out, mode);
+}
+
 int moe_ffn_forward(const MoeShape* shape, const void* d_x, const float* d_logits, const void* d_w_gate_up,
                     const void* d_w_down, void* d_out, const MoeSaved* saved, void* d_workspace,
                     size_t workspace_bytes, int mode, void* stream) {
@@ -590,14 +704,10 @@ int moe_ffn_forward(const MoeShape* shape, const void* d_x, const float* d_logit
   const void* ptrs[] = {d_x, d_logits, d_w_gate_up, d_w_down, d_out};
   for (const void* q : ptrs)
     if (!q || !aligned16(q)) return MOE_ERR_INVALID_ARG;
-  if (mode == MOE_MODE_PERSISTENT)
-    return c.s.dtype == MOE_BF16 ? run_persistent<true>(c, d_x, d_logits, d_w_gate_up, d_w_down, d_out)
-                                 : run_persistent<false>(c, d_x, d_logits, d_w_gate_up, d_w_down, d_out);
+  if (mode == MOE_MODE_PERSISTENT && (!aligned128(c.ws) || !aligned128(c.sv.Xp) || !aligned128(c.sv.A)))
+    return MOE_ERR_INVALID_ARG;   // before anything is enqueued
   if ((st = run_route(c, d_logits)) != MOE_OK) return st;
-  if (!gathers_x(c) && (st = run_permute(c, d_x)) != MOE_OK) return st;
-  if ((st = run_gemm1(c, d_w_gate_up, gathers_x(c) ? d_x : nullptr)) != MOE_OK) return st;
-  if ((st = run_gemm2(c, d_w_down)) != MOE_OK) return st;
-  return run_combine(c, d_out);
+  return run_dispatch_to_combine(c, d_x, d_w_gate_up, d_w_down, d_out, mode);
 }
 
 int moe_ffn_backward(const MoeShape* shape, const void* d_dy, const void* d_x, const void* d_w_gate_up,
@@ -616,6 +726,8 @@ int moe_ffn_backward(const MoeShape* shape, const void* d_dy, const void* d_x, c
   c.s = *shape;
   c.L = make_bwd_layout(c.s);
   if (!d_workspace || !aligned16(d_workspace) || !saved) return MOE_ERR_INVALID_ARG;
+  // dH1 (act_grad -> gate_grad inside the single launch) lives in the workspace at a 256-byte offset
+  if (mode == MOE_MODE_PERSISTENT && !aligned128(d_workspace)) return MOE_ERR_INVALID_ARG;
   if (workspace_bytes < c.L.total) return MOE_ERR_WORKSPACE_TOO_SMALL;
   const void* must[] = {d_dy, d_w_gate_up, d_w_down, d_dx, d_dw_gate_up, d_dw_down, d_dtopk_w,
                         saved->topk_w, saved->counts, saved->offsets, saved->row_of,
@@ -640,45 +752,16 @@ int moe_ffn_backward(const MoeShape* shape, const void* d_dy, const void* d_x, c
 }
 
 // workspace: queue headers and status word | event counters [n_tiles] | rings; sized for one-row tiles
-size_t moe_microbench_workspace_bytes(int M) {
-  const size_t n = M > 0 ? (size_t)M : 0;
-  return align_up(kMbRingBase * 4) + align_up(n * 4) + align_up((2 * n + 2 * kNumXcd) * 4);
-}
+size_t moe_microbench_workspace_bytes(int M) { return mb_workspace_bytes(M); }
 
 int moe_microbench_swiglu_add(int M, int N, const void* d_x, const void* d_y, void* d_s, void* d_out, int mode,
                               int tile_rows, void* d_workspace, size_t workspace_bytes, void* stream) {
-  if (M < 0 || N <= 0 || N % 8 || mode < 0 || mode > 3 || tile_rows < 1 || tile_rows > kMbMaxTileRows)
-    return MOE_ERR_INVALID_ARG;
-  if (M == 0) return MOE_OK;
-  const void* ptrs[] = {d_x, d_y, d_s, d_out, d_workspace};
-  for (const void* q : ptrs)
-    if (!q || !aligned16(q)) return MOE_ERR_INVALID_ARG;
-  if (workspace_bytes < moe_microbench_workspace_bytes(M)) return MOE_ERR_WORKSPACE_TOO_SMALL;
-  MicrobenchParams p;
-  p.X = static_cast<const __bf16*>(d_x); p.Y = static_cast<const __bf16*>(d_y);
-  p.S = static_cast<__bf16*>(d_s); p.Out = static_cast<__bf16*>(d_out);
-  p.M = M; p.N = N;
-  p.tile_rows = tile_rows;
-  p.n_tiles = (M + tile_rows - 1) / tile_rows;
-  // rings are addressed relative to the header block, so they start behind the event counters
-  p.queue = static_cast<uint32_t*>(d_workspace);
-  p.events = reinterpret_cast<uint32_t*>(static_cast<char*>(d_workspace) + align_up(kMbRingBase * 4));
-  p.ring_base = (int)((align_up(kMbRingBase * 4) + align_up((size_t)M * 4)) / 4);
-  p.spin_limit = g_spin_limit;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  const int workers = device_cus() * 4;   // four 256-thread workgroups per CU; a multiple of 8
-  const int grid = p.n_tiles < workers ? (p.n_tiles + 7) / 8 * 8 : workers;
-  if (mode == 0) {
-    hipLaunchKernelGGL(mb_swiglu_kernel, dim3(grid), dim3(256), 0, st, p);
-    hipLaunchKernelGGL(mb_add_kernel, dim3(grid), dim3(256), 0, st, p);
-  } else {
-    hipLaunchKernelGGL(mb_clear_kernel, dim3(std::min((p.n_tiles + 255) / 256, 1024)), dim3(256), 0, st, p,
-                       mode == 3 ? kNumXcd : 1);
-    if (mode == 1) hipLaunchKernelGGL(mb_static_kernel, dim3(grid), dim3(256), 0, st, p);
-    else if (mode == 2) hipLaunchKernelGGL(mb_dynamic_kernel<false>, dim3(grid), dim3(256), 0, st, p);
-    else hipLaunchKernelGGL(mb_dynamic_kernel<true>, dim3(grid), dim3(256), 0, st, p);
+  if (M > 0 && d_workspace && workspace_bytes < mb_workspace_bytes(M)) {
+    // argument errors take precedence over the size of the workspace
+    const int st = mb_check_args(M, N, d_x, d_y, d_s, d_out, mode, tile_rows, d_workspace);
+    return st != MOE_OK ? st : MOE_ERR_WORKSPACE_TOO_SMALL;
   }
-  return launch_status();
+  return mb_launch(M, N, d_x, d_y, d_s, d_out, mode, tile_rows, d_workspace, nullptr, stream);
 }
 
 int moe_probe_mfma_bf16(int n_workgroups, int mfma_per_wave, int random_operands, void* d_sink, void* stream) {
@@ -702,16 +785,57 @@ int moe_probe_copy(const void* d_src, void* d_dst, size_t bytes, void* stream) {
   return launch_status();
 }
 
+int moe_probe_read(const void* d_src, size_t bytes, void* d_sink, void* stream) {
+  if (!d_src || !d_sink || bytes % 16 || (reinterpret_cast<uintptr_t>(d_src) & 15) || (reinterpret_cast<uintptr_t>(d_sink) & 3))
+    return MOE_ERR_INVALID_ARG;
+  if (bytes == 0) return MOE_OK;
+  const size_t n16 = bytes / 16;
+  const size_t want = (n16 + (size_t)kProbeThreads * kProbeCopyUnroll - 1) / ((size_t)kProbeThreads * kProbeCopyUnroll);
+  const int grid = (int)(want < (size_t)(device_cus() * 8) ? want : (size_t)(device_cus() * 8));
+  hipLaunchKernelGGL(probe_read_kernel, dim3(grid), dim3(kProbeThreads), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const u32x4*>(d_src), n16, static_cast<uint32_t*>(d_sink));
+  return launch_status();
+}
+
 int moe_microbench_last_status(const void* d_workspace) {
   if (!d_workspace) return MOE_ERR_INVALID_ARG;
   uint32_t word = 0;
   if (hipMemcpy(&word, static_cast<const char*>(d_workspace) + 8, 4, hipMemcpyDeviceToHost) != hipSuccess)
     return MOE_ERR_LAUNCH;
-  return word ? MOE_ERR_SCHED_TIMEOUT : MOE_OK;
+  return (word & 2u) ? MOE_ERR_XCD_PLACEMENT : (word ? MOE_ERR_SCHED_TIMEOUT : MOE_OK);
 }
 
 int moe_ffn_debug_set_spin_limit(uint32_t polls) {
   g_spin_limit = polls;
+  return MOE_OK;
+}
+
+int moe_ffn_debug_force_device_scope(int on) {
+  g_force_device_scope = on ? 1 : 0;
+  return MOE_OK;
+}
+
+int moe_ffn_debug_layout(const MoeShape* shape, int backward, int64_t* out, int n_out) {
+  int st = check_shape(shape);
+  if (st != MOE_OK) return st;
+  if (!out || n_out < MOE_LAYOUT_WORDS) return MOE_ERR_INVALID_ARG;
+  int64_t v[MOE_LAYOUT_WORDS] = {0};
+  if (backward) {
+    const BwdLayout L = make_bwd_layout(*shape);
+    v[0] = (int64_t)L.meta; v[1] = (int64_t)L.tile_expert; v[2] = (int64_t)L.tile_row0; v[3] = (int64_t)L.tile_rows;
+    v[4] = (int64_t)L.events; v[5] = (int64_t)L.qhead; v[6] = (int64_t)L.tasks;
+  } else {
+    const Layout L = make_layout(*shape);
+    v[0] = (int64_t)L.meta; v[1] = (int64_t)L.tile_expert; v[2] = (int64_t)L.tile_row0; v[3] = (int64_t)L.tile_rows;
+    v[4] = (int64_t)L.events; v[5] = (int64_t)L.qhead; v[6] = (int64_t)L.tasks;
+  }
+  v[7] = max_mtiles(*shape); v[8] = max_tasks_per_queue(*shape); v[9] = n_events(*shape);
+  v[10] = kEvPerTile; v[11] = kEvGemm2; v[12] = kMetaMTiles; v[13] = kMetaQueueCount0; v[14] = kMetaGemm2Total;
+  v[15] = kNumXcd; v[16] = kPermRows; v[17] = gemm1_ntiles(*shape); v[18] = gemm2_ntiles(*shape);
+  v[19] = tile_bm(*shape); v[20] = tile_tall(*shape); v[21] = kGemm2Lag; v[22] = (int64_t)sizeof(TaskDesc);
+  v[23] = backward ? (shape->dtype == MOE_BF16 ? (shape->I + kBN - 1) / kBN : shape->I / kFBN) : 0;   // act_grad N tiles
+  v[24] = kMetaFallbackWorkers;
+  for (int i = 0; i < MOE_LAYOUT_WORDS; ++i) out[i] = v[i];
   return MOE_OK;
 }
 

@@ -12,14 +12,19 @@
 // (Section 4.3's progress argument).  Handlers are the same device functions the
 // serialized launches run, so results are bit-identical for any legal order.
 //
+// The single launch covers the paper's own interval, Dispatch to Combine (Section 5.2 starts the
+// clock at Dispatch).  Routing runs ahead of it as two small launches at full occupancy (the
+// router, then prefix sums + stable ranks): a worker here is a 4-wave workgroup that owns a whole
+// CU for the sake of the GEMM tiles, the wrong shape for the latency-bound routing steps.  The
+// second routing launch also zeroes the event counters and queue heads and materialises the task
+// descriptors, so nothing but the persistent kernel itself stands between Dispatch and Combine.
+//
 // Queues
-//   G  (global)   ROUTE x sub-chunks, SCAN, RANK x groups (SCAN and RANK both wait
-//                 only for the ROUTE tasks)                     - static, host-known
 //   X0..X7        one per XCD: PERMUTE parts, GEMM-1 tiles, GEMM-2 tiles of the M-tile
 //                 pairs dealt to that XCD (pair % 8), so tiles sharing an activation
 //                 or weight panel sit behind one L2.  These TDs depend on the routing result
 //                 (Section 5.1: tile offsets are only known once routing is) and are materialised on
-//                 the device by the SCAN task.  GEMM-2 tiles of pair j are queued
+//                 the device by the workgroup that finishes the prefix sums.  GEMM-2 tiles of pair j are queued
 //                 behind the GEMM-1 tiles of pair j+1: a consumer is issued about
 //                 one sweep after its producers, close enough for L2 reuse, far
 //                 enough not to stall the queue.
@@ -31,10 +36,17 @@
 // 30 us per task when all CUs do it) and a device-scope acquire (buffer_inv) drops
 // the L2 contents the sibling tiles are sharing.  Inside an XCD it is enough that the
 // producer's stores have been acknowledged by the L2 before the counter moves; every
-// address is written once before its first read within a launch, so there is no
-// stale line to invalidate on the consumer side.  Events that cross XCDs (routing,
-// and GEMM-2 -> COMBINE) keep the full device-scope fences; since COMBINE needs every
+// 128-byte line of Xp and A is written by one task, completely, before any task reads it
+// within a launch (rows are multiples of 128 bytes and the host requires 128-byte aligned
+// buffers in this mode), so no CU can hold a stale copy of a line in its vector L1 and
+// there is nothing to invalidate on the consumer side.  The event that crosses XCDs
+// (GEMM-2 -> COMBINE) keeps the full device-scope fences; since COMBINE needs every
 // GEMM-2 tile, a worker publishes its GEMM-2 completions once, after its queue has drained.
+//
+// Placement is checked, not assumed: every worker reads the id of the XCD it really runs on
+// (hardware register XCC_ID) and reports it when it starts; a queue whose workers do not all
+// sit on one XCD (another partition mode, a CU mask) uses device-scope fences for its chain
+// events instead.
 #pragma once
 #include <type_traits>
 
@@ -49,24 +61,27 @@ namespace moe {
 
 constexpr int kPermRows = 32;            // rows per PERMUTE task
 constexpr int kCombineTokens = 32;       // tokens per COMBINE task (fewer when that would leave CUs without one)
-constexpr int kRankChunksPerTask = 4;    // one chunk per wave
 constexpr int kGemm2Lag = 1;             // GEMM-2 of tile pair j is queued behind GEMM-1 of pair j + lag
 
 enum TaskType { kTaskPermute = 0, kTaskGemm1 = 1, kTaskGemm2 = 2 };
 
 // Event counters (uint32, zero at kernel start).
-enum EventId { kEvRoute = 0, kEvScan = 1, kEvRank = 2, kEvGemm2 = 3, kEvPerTile = 4 };
+enum EventId { kEvArrive = 0, kEvGemm2 = 3, kEvPerTile = 4 };
+//   kEvArrive .. +2              placement check: workers that have started, and per queue the XCDs its workers run on
+//   kEvGemm2                     finished GEMM-2 tiles, published device-wide
 //   kEvPerTile + m               rows of M tile m are in Xp      (PERMUTE parts of m)
 //   kEvPerTile + max_mtiles + m  A rows of M tile m are complete (GEMM-1 tiles of m)
+constexpr int kNoEvent = -1;             // dep_event of a task that waits for nothing
 
-enum QueueId { kQGlobal = 0, kQXcd0 = 1, kQCombine = 1 + kNumXcd, kNumQueues = 16 };
+enum QueueId { kQXcd0 = 0, kQCombine = kNumXcd, kNumQueues = 16 };
 
-enum SchedMetaWord { kMetaQueueCount0 = 4, kMetaGemm2Total = 12 };   // after MetaWord
+enum SchedMetaWord { kMetaQueueCount0 = 4, kMetaGemm2Total = 12, kMetaFallbackWorkers = 13 };   // after MetaWord
+//   kMetaFallbackWorkers         workers of the last single launch that used device-wide fences for their chain events
 
 struct TaskDesc {
   int32_t type_n;      // TaskType | (N tile or part index << 8)
   int32_t m;           // M tile
-  int32_t dep_event;   // counter that must reach `threshold` before the task may start
+  int32_t dep_event;   // counter that must reach `threshold` before the task may start (kNoEvent: none)
   int32_t threshold;
 };
 
@@ -81,9 +96,11 @@ struct SchedParams {
   TaskDesc* tasks;         // [kNumXcd][max_tasks_per_q]
   int32_t* meta;
   int max_mtiles, max_tasks_per_q;
-  int n_rank_tasks, n_comb_tasks;
+  int n_events;
+  int n_comb_tasks;
   int comb_tokens;         // tokens per COMBINE task
-  int no_permute;          // inference: nobody needs Xp, GEMM-1 gathers its rows from x through token_of
+  int no_permute;          // nobody needs Xp: GEMM-1 gathers its rows from x through token_of
+  int force_device_scope;  // test hook: behave as if a worker had reported a foreign XCD
   uint32_t spin_limit;     // polls before a wait gives up (MOE_ERR_SCHED_TIMEOUT)
   int32_t timeout_status;
 };
@@ -120,10 +137,41 @@ __device__ __forceinline__ int sched_fetch(uint32_t* qhead, int q, volatile int*
   return t;
 }
 
-// Wait until events[ev] >= threshold (bounded).  Returns false on timeout after
-// recording the status word; the caller then skips the task without triggering.
 enum EventScope { kScopeDevice = 0, kScopeXcd = 1 };
 
+// Start-up report of a worker that serves queue `q`: the XCD it really runs on (wave_sync.h, placement check).
+template <bool BF16>
+__device__ __forceinline__ void sched_arrive(const SchedParams<BF16>& sp, int q, int wave) {
+  if (wave == 0) placement_report(&sp.events[kEvArrive], q, sp.force_device_scope != 0);
+}
+
+// Scope of the chain events of this worker's queue: XCD-local if all workers of the queue have reported the same
+// XCD, device-wide otherwise (also when the bounded wait for the reports expires, which is recorded in the
+// status word).  Every worker of a queue reaches the same verdict, since it is taken after all have reported.
+// Called once per worker, ahead of its first wait or trigger.
+template <bool BF16>
+__device__ __forceinline__ int sched_chain_scope(const SchedParams<BF16>& sp, int q, volatile int* s_box, int wave) {
+  if (wave == 0) {
+    uint32_t polls = 0;
+    int scope = kScopeXcd;
+    for (;;) {
+      if (ev_load(&sp.events[kEvArrive]) >= gridDim.x) break;
+      if (++polls > sp.spin_limit) { scope = kScopeDevice; break; }
+      __builtin_amdgcn_s_sleep(1);
+    }
+    if (scope == kScopeDevice) __hip_atomic_store(&sp.meta[kMetaStatus], sp.timeout_status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else if (!placement_class_ok(&sp.events[kEvArrive], q)) scope = kScopeDevice;
+    if (scope == kScopeDevice) wave_atomic_add(reinterpret_cast<uint32_t*>(&sp.meta[kMetaFallbackWorkers]), 1u);
+    s_box[1] = scope;
+  }
+  __syncthreads();
+  const int scope = __builtin_amdgcn_readfirstlane(s_box[1]);
+  __syncthreads();
+  return scope;
+}
+
+// Wait until events[ev] >= threshold (bounded).  Returns false on timeout after
+// recording the status word; the caller then skips the task without triggering.
 template <bool BF16>
 __device__ __forceinline__ bool sched_wait(const SchedParams<BF16>& sp, int ev, uint32_t threshold, volatile int* s_box,
                                            int wave, int scope = kScopeDevice) {
@@ -146,7 +194,8 @@ __device__ __forceinline__ bool sched_wait(const SchedParams<BF16>& sp, int ev, 
   return ok != 0;
 }
 
-// Outputs of this workgroup become visible device-wide, then the counter moves.
+// Outputs of this workgroup become visible (device-wide, or to the workgroups behind the same L2), then
+// the counter moves.
 template <bool BF16>
 __device__ __forceinline__ void sched_trigger(const SchedParams<BF16>& sp, int ev, int wave, int scope = kScopeDevice,
                                               uint32_t inc = 1u) {
@@ -160,13 +209,16 @@ __device__ __forceinline__ void sched_trigger(const SchedParams<BF16>& sp, int e
   if (wave == 0) wave_atomic_add(&sp.events[ev], inc);
 }
 
-// SCAN task tail: materialise the per-XCD task tables from the fresh tile map.
-// Whole workgroup: a wave per queue, the lanes of the wave fill a block of
-// descriptors in parallel (block offsets are wave-uniform running sums).
+// Zero the counters and queue heads, then materialise the per-XCD task tables from the fresh tile map.
+// Whole workgroup, after the tile map is complete: a wave per queue, the lanes of the wave fill a block
+// of descriptors in parallel (block offsets are wave-uniform running sums).
 // BWD: the chain is act_grad (as "GEMM-1": no PERMUTE ahead of it, nothing to wait for; its narrow tall
 // tiles are 128 columns wide) followed by gate_grad (as "GEMM-2").
 template <bool BF16, bool BWD = false>
 __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
+  for (int i = threadIdx.x; i < sp.n_events; i += blockDim.x) sp.events[i] = 0;
+  if (threadIdx.x < kNumQueues) sp.qhead[threadIdx.x] = 0;
+  if (threadIdx.x == 0) sp.meta[kMetaFallbackWorkers] = 0;
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), n_waves = blockDim.x / kWave;
   const int n_mtiles = sp.meta[kMetaMTiles];
@@ -175,18 +227,19 @@ __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
   const int n_pairs = (n_mtiles + 1) >> 1;
   auto parts_of = [&](int m) { return (sp.route.tiles.rows[m] + kPermRows - 1) / kPermRows; };
   constexpr int kWideRows = BF16 ? kBM : (1 << 30);   // a bf16 tile with more rows runs in the tall shape
+  const bool permute = !(sp.no_permute || BWD);
   for (int q = wave; q < kNumXcd; q += n_waves) {
     const int Pq = n_pairs > q ? (n_pairs - q + kNumXcd - 1) / kNumXcd : 0;
     TaskDesc* tq = sp.tasks + (size_t)q * sp.max_tasks_per_q;
     int n = 0;
     constexpr int kTallCols1 = BWD ? 128 : 64;   // output columns of a narrow GEMM-1 tile of a tall M tile
-    for (int j = 0; j < (sp.no_permute || BWD ? 0 : Pq); ++j)
+    for (int j = 0; j < (permute ? Pq : 0); ++j)
       for (int s = 0; s < 2; ++s) {
         const int m = 2 * (q + kNumXcd * j) + s;
         if (m >= n_mtiles) continue;
         const int parts = parts_of(m);   // 0 for the unused half of a tall tile's slot
         for (int part = lane; part < parts; part += kWave)
-          tq[n + part] = TaskDesc{kTaskPermute | (part << 8), m, kEvRank, sp.n_rank_tasks};
+          tq[n + part] = TaskDesc{kTaskPermute | (part << 8), m, kNoEvent, 0};
         n += parts;
       }
     // GEMM tiles of a slot N-tile-major with the two siblings adjacent (they stream the same weight panel
@@ -201,8 +254,8 @@ __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
         const int parts0 = parts_of(m0), parts1 = n_sib > 1 ? parts_of(m0 + 1) : 0;
         for (int i = lane; i < n_nt * n_sib; i += kWave) {
           const int nt = i / n_sib, sib = i - nt * n_sib;
-          tq[n + i] = sp.no_permute || BWD ? TaskDesc{kTaskGemm1 | (nt << 8), m0 + sib, kEvRank, sp.n_rank_tasks}
-                                           : TaskDesc{kTaskGemm1 | (nt << 8), m0 + sib, kEvPerTile + m0 + sib, sib ? parts1 : parts0};
+          tq[n + i] = permute ? TaskDesc{kTaskGemm1 | (nt << 8), m0 + sib, kEvPerTile + m0 + sib, sib ? parts1 : parts0}
+                              : TaskDesc{kTaskGemm1 | (nt << 8), m0 + sib, kNoEvent, 0};
         }
         n += n_nt * n_sib;
       }
@@ -233,21 +286,32 @@ __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
   }
 }
 
+// Second routing launch (both launch modes): prefix sums and M-tile map by workgroup 0, stable ranks by the
+// others, plus, in workgroup 0, the tile scheduler's counters and task tables.
+template <bool BF16>
+__global__ __launch_bounds__(kScanRankWaves * kWave) void sched_prepare_kernel(SchedParams<BF16> sp) {
+  __shared__ int32_t s_lds[kScanRankWaves * kRankLdsWords];   // rank: 4 * kMaxE words per wave; scan: (5 * kMaxE + 66) words
+  if (blockIdx.x == 0) {
+    scan_all(sp.route, s_lds, s_lds + kMaxE + 64);
+    __threadfence_block();
+    __syncthreads();   // tile map (written by wave 0) complete before every wave reads it
+    build_task_tables<BF16>(sp);
+    return;
+  }
+  const int wave = threadIdx.x / kWave;
+  const int group = (blockIdx.x - 1) * kScanRankWaves + wave;
+  if (group < sp.route.n_groups) rank_chunk(sp.route, group, s_lds + wave * kRankLdsWords);
+}
+
 template <bool BF16>
 __device__ __forceinline__ void run_tile_task(const SchedParams<BF16>& sp, const TaskDesc& td, char* smem, volatile int* s_box,
-                                              int wave, long long& t_start, uint32_t& gemm2_done, bool& rank_seen) {
+                                              int wave, int q, long long& t_start, uint32_t& gemm2_done, int& scope) {
   const int type_n = __builtin_amdgcn_readfirstlane(td.type_n);
   const int type = type_n & 0xFF, idx = type_n >> 8, m = __builtin_amdgcn_readfirstlane(td.m);
   const int dep = __builtin_amdgcn_readfirstlane(td.dep_event);
-  // A task that needs the routing results (PERMUTE; GEMM-1 when it gathers) waits for the RANK tasks of
-  // every XCD, device scope; the permutation never changes afterwards, so a worker does that once.
-  // The rest of the chain waits on tasks of its own XCD queue.
-  if (dep == kEvRank) {
-    if (!rank_seen && !sched_wait(sp, dep, (uint32_t)__builtin_amdgcn_readfirstlane(td.threshold), s_box, wave, kScopeDevice)) return;
-    rank_seen = true;
-  } else if (!sched_wait(sp, dep, (uint32_t)__builtin_amdgcn_readfirstlane(td.threshold), s_box, wave, kScopeXcd)) {
-    return;
-  }
+  if (scope < 0) scope = sched_chain_scope(sp, q, s_box, wave);
+  // the chain waits on tasks of its own XCD queue
+  if (dep != kNoEvent && !sched_wait(sp, dep, (uint32_t)__builtin_amdgcn_readfirstlane(td.threshold), s_box, wave, scope)) return;
 #if defined(MOE_SCHED_TRACE)
   t_start = wall_clock64();
 #else
@@ -257,11 +321,11 @@ __device__ __forceinline__ void run_tile_task(const SchedParams<BF16>& sp, const
     const int row0 = sp.route.tiles.row0[m], rows = sp.route.tiles.rows[m];
     const int r0 = row0 + idx * kPermRows;
     permute_rows<14>(sp.perm, r0, min(r0 + kPermRows, row0 + rows), wave, blockDim.x / kWave);
-    sched_trigger(sp, kEvPerTile + m, wave, kScopeXcd);
+    sched_trigger(sp, kEvPerTile + m, wave, scope);
   } else if (type == kTaskGemm1) {
     if constexpr (BF16) gemm_map_tile_bf16<kLayNN, kEpiSwiglu>(sp.g1, m, idx, __builtin_amdgcn_readfirstlane(sp.route.tiles.rows[m]) > kBM, smem);
     else gemm_tile_f32<kEpiSwiglu>(sp.g1, m, idx, reinterpret_cast<float*>(smem));
-    sched_trigger(sp, kEvPerTile + sp.max_mtiles + m, wave, kScopeXcd);
+    sched_trigger(sp, kEvPerTile + sp.max_mtiles + m, wave, scope);
   } else {
     if constexpr (BF16) gemm_map_tile_bf16<kLayNN, kEpiStore>(sp.g2, m, idx, __builtin_amdgcn_readfirstlane(sp.route.tiles.rows[m]) > kBM, smem);
     else gemm_tile_f32<kEpiStore>(sp.g2, m, idx, reinterpret_cast<float*>(smem));
@@ -278,77 +342,43 @@ void persistent_forward_kernel(SchedParams<BF16> sp) {
   __shared__ __attribute__((aligned(1024))) char smem[kGemmLdsBytes];
   // between tasks the staging area is idle: its first words carry the ticket and the wait result
   volatile int* s_box = reinterpret_cast<volatile int*>(smem);
-  int32_t* s_scratch = reinterpret_cast<int32_t*>(smem + 64);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   MOE_TRACE_DECL
 
-  // ---- queue G: routing.  SCAN (tile map, task tables) and the RANK tasks both need only the
-  // finished histogram table, so they run side by side ----
-  const int n_sub = sp.route.n_sub;
-  const int n_g = n_sub + 1 + sp.n_rank_tasks;
-  for (;;) {
-    const int t = sched_fetch(sp.qhead, kQGlobal, s_box, wave);
-    if (t >= n_g) break;
-    if (t < n_sub) {
-      MOE_TRACE_FETCH(10, t, 0) MOE_TRACE_START
-      route_chunk(sp.route, t, s_scratch, reinterpret_cast<float*>(s_scratch + kSub * kMaxK));
-      sched_trigger(sp, kEvRoute, wave);
-      MOE_TRACE_END(sp)
-    } else if (t == n_sub) {
-      MOE_TRACE_FETCH(11, t, 0)
-      if (!sched_wait(sp, kEvRoute, (uint32_t)n_sub, s_box, wave)) continue;
-      MOE_TRACE_START
-      scan_all(sp.route, s_scratch, s_scratch + kMaxE + 64);
-      __syncthreads();   // tile map (written by wave 0) complete before every wave reads it
-      build_task_tables(sp);
-      sched_trigger(sp, kEvScan, wave);
-      MOE_TRACE_END(sp)
-    } else {
-      MOE_TRACE_FETCH(12, t, 0)
-      if (!sched_wait(sp, kEvRoute, (uint32_t)n_sub, s_box, wave)) continue;
-      MOE_TRACE_START
-      const int group = (t - n_sub - 1) * kRankChunksPerTask + wave;
-      if (wave < kRankChunksPerTask && group < sp.route.n_groups) rank_chunk(sp.route, group, s_scratch + wave * kRankLdsWords);
-      sched_trigger(sp, kEvRank, wave);
+  // ---- queue X of this workgroup's XCD: dispatch + grouped GEMMs ----
+  const int q = blockIdx.x % kNumXcd;   // workgroups are dealt to XCDs round-robin: one XCD per class (checked: sched_arrive)
+  sched_arrive(sp, q, wave);
+  {
+    const int count = __builtin_amdgcn_readfirstlane(sp.meta[kMetaQueueCount0 + q]);
+    uint32_t gemm2_done = 0;
+    int scope = -1;
+    for (;;) {
+      const int t = sched_fetch(sp.qhead, kQXcd0 + q, s_box, wave);
+      if (t >= count) break;
+      const TaskDesc td = sp.tasks[(size_t)q * sp.max_tasks_per_q + t];
+      MOE_TRACE_FETCH(td.type_n & 0xFF, td.m, td.type_n >> 8)
+      long long t_start = 0;
+      run_tile_task(sp, td, smem, s_box, wave, q, t_start, gemm2_done, scope);
+#if defined(MOE_SCHED_TRACE)
+      tr_.t_start = t_start;
+#endif
       MOE_TRACE_END(sp)
     }
+    if (gemm2_done) sched_trigger(sp, kEvGemm2, wave, kScopeDevice, gemm2_done);
   }
 
-  // ---- queue X of this workgroup's XCD: dispatch + grouped GEMMs ----
-  if (sched_wait(sp, kEvScan, 1u, s_box, wave)) {
-    {
-      const int q = blockIdx.x % kNumXcd;   // workgroups are dealt to XCDs round-robin by id
-      const int count = __builtin_amdgcn_readfirstlane(sp.meta[kMetaQueueCount0 + q]);
-      uint32_t gemm2_done = 0;
-      bool rank_seen = false;
-      for (;;) {
-        const int t = sched_fetch(sp.qhead, kQXcd0 + q, s_box, wave);
-        if (t >= count) break;
-        const TaskDesc td = sp.tasks[(size_t)q * sp.max_tasks_per_q + t];
-        MOE_TRACE_FETCH(td.type_n & 0xFF, td.m, td.type_n >> 8)
-        long long t_start = 0;
-        run_tile_task(sp, td, smem, s_box, wave, t_start, gemm2_done, rank_seen);
-#if defined(MOE_SCHED_TRACE)
-        tr_.t_start = t_start;
-#endif
-        MOE_TRACE_END(sp)
-      }
-      if (gemm2_done) sched_trigger(sp, kEvGemm2, wave, kScopeDevice, gemm2_done);
-    }
-
-    // ---- queue C: combine ----
-    const uint32_t g2_total = (uint32_t)__builtin_amdgcn_readfirstlane(sp.meta[kMetaGemm2Total]);
-    for (;;) {
-      const int t = sched_fetch(sp.qhead, kQCombine, s_box, wave);
-      if (t >= sp.n_comb_tasks) break;
-      MOE_TRACE_FETCH(3, t, 0)
-      if (!sched_wait(sp, kEvGemm2, g2_total, s_box, wave)) continue;
-      MOE_TRACE_START
-      const int t0 = t * sp.comb_tokens;
-      for (int i = wave; i < sp.comb_tokens; i += blockDim.x / kWave)
-        if (t0 + i < sp.comb.T) combine_token<BF16>(sp.comb, t0 + i);
-      MOE_TRACE_END(sp)
-    }
+  // ---- queue C: combine ----
+  const uint32_t g2_total = (uint32_t)__builtin_amdgcn_readfirstlane(sp.meta[kMetaGemm2Total]);
+  for (;;) {
+    const int t = sched_fetch(sp.qhead, kQCombine, s_box, wave);
+    if (t >= sp.n_comb_tasks) break;
+    MOE_TRACE_FETCH(3, t, 0)
+    if (!sched_wait(sp, kEvGemm2, g2_total, s_box, wave)) continue;
+    MOE_TRACE_START
+    const int t0 = t * sp.comb_tokens;
+    for (int i = wave; i < sp.comb_tokens; i += blockDim.x / kWave)
+      if (t0 + i < sp.comb.T) combine_token<BF16>(sp.comb, t0 + i);
+    MOE_TRACE_END(sp)
   }
 }
 
@@ -361,9 +391,7 @@ void persistent_forward_kernel(SchedParams<BF16> sp) {
 // sp.route.tiles = the backward's M-tile map; the other members of sp are unused.
 
 // One workgroup: zero the counters, then build the per-XCD task tables from the finished tile map.
-__global__ __launch_bounds__(kGemmThreads) void dgrad_prepare_kernel(SchedParams<true> sp, int n_events) {
-  for (int i = threadIdx.x; i < n_events; i += blockDim.x) sp.events[i] = 0;
-  if (threadIdx.x < kNumQueues) sp.qhead[threadIdx.x] = 0;
+__global__ __launch_bounds__(kGemmThreads) void dgrad_prepare_kernel(SchedParams<true> sp) {
   build_task_tables<true, true>(sp);
 }
 
@@ -372,8 +400,10 @@ void persistent_dgrad_kernel(SchedParams<true> sp) {
   __shared__ __attribute__((aligned(1024))) char smem[kGemmLdsBytes];
   volatile int* s_box = reinterpret_cast<volatile int*>(smem);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-  const int q = blockIdx.x % kNumXcd;   // workgroups are dealt to XCDs round-robin by id
+  const int q = blockIdx.x % kNumXcd;   // workgroups are dealt to XCDs round-robin by id (checked: sched_arrive)
+  sched_arrive(sp, q, wave);
   const int count = __builtin_amdgcn_readfirstlane(sp.meta[kMetaQueueCount0 + q]);
+  int scope = -1;
   for (;;) {
     const int t = sched_fetch(sp.qhead, kQXcd0 + q, s_box, wave);
     if (t >= count) break;
@@ -383,23 +413,16 @@ void persistent_dgrad_kernel(SchedParams<true> sp) {
     const bool tall = __builtin_amdgcn_readfirstlane(sp.route.tiles.rows[m]) > kBM;
     if (type == kTaskGemm1) {
       gemm_map_tile_bf16<kLayNT, kEpiSwigluGrad>(sp.g1, m, idx, tall, smem);
-      sched_trigger(sp, kEvPerTile + sp.max_mtiles + m, wave, kScopeXcd);
+      if (scope < 0) scope = sched_chain_scope(sp, q, s_box, wave);
+      sched_trigger(sp, kEvPerTile + sp.max_mtiles + m, wave, scope);
     } else {
+      if (scope < 0) scope = sched_chain_scope(sp, q, s_box, wave);
       if (!sched_wait(sp, __builtin_amdgcn_readfirstlane(td.dep_event), (uint32_t)__builtin_amdgcn_readfirstlane(td.threshold),
-                      s_box, wave, kScopeXcd))
+                      s_box, wave, scope))
         continue;   // bounded wait expired: status word set, the task is skipped, the queue still drains
       gemm_map_tile_bf16<kLayNT, kEpiStore>(sp.g2, m, idx, tall, smem);
     }
   }
-}
-
-// Zeroes the scheduler's counters, queue heads and status word (one small launch
-// ahead of the persistent kernel; a fill kernel rather than a memset node so the
-// pair can be captured in a graph).
-__global__ void sched_clear_kernel(uint32_t* events, int n_events, uint32_t* qhead, int32_t* meta) {
-  for (int i = threadIdx.x; i < n_events; i += blockDim.x) events[i] = 0;
-  if (threadIdx.x < kNumQueues) qhead[threadIdx.x] = 0;
-  if (threadIdx.x == 0) meta[kMetaStatus] = 0;
 }
 
 }  // namespace moe

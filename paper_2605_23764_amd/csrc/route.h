@@ -1,8 +1,7 @@
 // Routing and Dispatch bookkeeping kernels (paper Section 2.2: routing and
 // Dispatch; Section 5.1: tile offsets derived from the routing result at run time).
 //
-// Three steps, each a device function so that the serialized launches and the
-// persistent scheduler run the same code:
+// Three steps, each a device function:
 //   route_chunk  top-k + softmax for the 64 tokens of a chunk, per-chunk expert histogram
 //   scan_all     prefix sums over chunks and experts, counts/offsets, M-tile map
 //   rank_chunk   stable row of every local slot, inverse maps
@@ -413,21 +412,11 @@ __global__ __launch_bounds__(512) void route_kernel(RouteParams p) {
   route_chunk(p, blockIdx.x, s_idx, s_val);
 }
 
-// The two steps that need nothing but the finished histogram table, side by side in one launch:
-// workgroup 0 sums the table into counts, offsets and the M-tile map; every other workgroup ranks 4
-// groups of 64 tokens, one per wave.  Grid: 1 + ceil(n_groups / 4) workgroups of 256 threads.
+// The two steps that need nothing but the finished histogram table run side by side in one launch
+// (sched_prepare_kernel): workgroup 0 sums the table into counts, offsets and the M-tile map; every other
+// workgroup ranks 4 groups of 64 tokens, one per wave.  Grid: 1 + ceil(n_groups / 4) workgroups of 256 threads.
 constexpr int kScanRankWaves = 4;
-__global__ __launch_bounds__(kScanRankWaves * kWave) void scan_rank_kernel(RouteParams p) {
-  __shared__ int32_t s_lds[kScanRankWaves * kRankLdsWords];   // rank: 4 * kMaxE words per wave; scan: (5 * kMaxE + 66) words
-  static_assert(kScanRankWaves * kRankLdsWords >= (kScanRankWaves + 1) * kMaxE + 2 + 64, "LDS of the scan step");
-  if (blockIdx.x == 0) {
-    scan_all(p, s_lds, s_lds + kMaxE + 64);
-    return;
-  }
-  const int wave = threadIdx.x / kWave;
-  const int group = (blockIdx.x - 1) * kScanRankWaves + wave;
-  if (group < p.n_groups) rank_chunk(p, group, s_lds + wave * kRankLdsWords);
-}
+static_assert(kScanRankWaves * kRankLdsWords >= (kScanRankWaves + 1) * kMaxE + 2 + 64, "LDS of the scan step");
 
 // M-tile map from the rows per expert alone (the backward rebuilds it from the
 // saved counts instead of keeping the forward's workspace alive).

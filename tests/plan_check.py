@@ -1,0 +1,111 @@
+"""Host-side checks of the schedule the single-launch kernels build on the device (paper Section 4.3: a task
+waits for one event counter to reach a static threshold; thresholds equal producer counts; queue order is a
+topological order of the DAG, consumed in order, hence no deadlock).  Pure Python on a copy of the workspace:
+decode the task tables, check coverage / thresholds / order, and interpret the queues with counters."""
+import dataclasses
+
+import numpy as np
+
+PERMUTE, GEMM1, GEMM2 = 0, 1, 2
+
+
+@dataclasses.dataclass
+class Plan:
+    n_mtiles: int
+    rows: np.ndarray            # rows per M tile
+    queues: list                # per queue: list of (type, index, m, dep_event, threshold)
+    gemm2_total: int
+    ev_per_tile: int
+    max_mtiles: int
+
+
+def decode_plan(ws: np.ndarray, lay) -> Plan:
+    """ws: the workspace as uint8; lay: the integers of moe_ffn_debug_layout."""
+    i32 = lambda off, n: ws[off: off + 4 * n].view(np.int32)
+    meta = i32(lay[0], 16)
+    max_m, max_q, n_q = lay[7], lay[8], lay[15]
+    n_m = int(meta[lay[12]])
+    rows = i32(lay[3], max_m)[:n_m].copy()
+    queues = []
+    for q in range(n_q):
+        n = int(meta[lay[13] + q])
+        assert 0 <= n <= max_q, (q, n)
+        td = i32(lay[6] + q * max_q * lay[22], 4 * n).reshape(n, 4)
+        queues.append([(int(t & 0xFF), int(t >> 8), int(m), int(d), int(th)) for t, m, d, th in td])
+    return Plan(n_m, rows, queues, int(meta[lay[14]]), lay[10], max_m)
+
+
+def expected_tiles(plan: Plan, n1_wide, n1_tall, n2_wide, n2_tall, wide_rows, perm_rows, permute):
+    """Per M tile with rows: (PERMUTE parts, GEMM-1 N tiles, GEMM-2 N tiles)."""
+    exp = {}
+    for m in range(plan.n_mtiles):
+        r = int(plan.rows[m])
+        if r <= 0:
+            continue
+        tall = r > wide_rows
+        exp[m] = ((r + perm_rows - 1) // perm_rows if permute else 0, n1_tall if tall else n1_wide,
+                  n2_tall if tall else n2_wide)
+    return exp
+
+
+def check_plan(plan: Plan, exp: dict, n_queues=8):
+    """Raises AssertionError naming the first violated property."""
+    seen = {}
+    for q, tasks in enumerate(plan.queues):
+        for pos, (ty, idx, m, dep, thr) in enumerate(tasks):
+            assert m in exp, f"queue {q} pos {pos}: task on M tile {m} that has no rows"
+            assert (m // 2) % n_queues == q, f"M tile {m} in queue {q}: its pair belongs to queue {(m // 2) % n_queues}"
+            key = (ty, m, idx)
+            assert key not in seen, f"task {key} appears twice"
+            seen[key] = (q, pos, dep, thr)
+    n_g2 = 0
+    for m, (parts, n1, n2) in exp.items():
+        for ty, n in ((PERMUTE, parts), (GEMM1, n1), (GEMM2, n2)):
+            for idx in range(n):
+                assert (ty, m, idx) in seen, f"task {(ty, m, idx)} is missing"
+        n_g2 += n2
+    assert len(seen) == sum(sum(v) for v in exp.values()), "tasks beyond the expected index ranges"
+    # thresholds = producer counts, dependent events = the producers' trigger events, producers precede consumers
+    for (ty, m, idx), (q, pos, dep, thr) in seen.items():
+        parts, n1, n2 = exp[m]
+        if ty == PERMUTE or (ty == GEMM1 and parts == 0):
+            assert dep == -1, f"{(ty, m, idx)} must not wait"
+            continue
+        want_dep, want_thr, prod = ((plan.ev_per_tile + m, parts, PERMUTE) if ty == GEMM1
+                                    else (plan.ev_per_tile + plan.max_mtiles + m, n1, GEMM1))
+        assert dep == want_dep, f"{(ty, m, idx)} waits on event {dep}, producers trigger {want_dep}"
+        assert thr == want_thr, f"{(ty, m, idx)} threshold {thr} != {want_thr} producer tasks"
+        for pi in range(want_thr):
+            pq, ppos, _, _ = seen[(prod, m, pi)]
+            assert pq == q and ppos < pos, f"producer {(prod, m, pi)} does not precede {(ty, m, idx)} in queue {q}"
+    assert plan.gemm2_total == n_g2, f"GEMM-2 total {plan.gemm2_total} != {n_g2} GEMM-2 tasks"
+
+
+def simulate(plan: Plan, workers_per_queue=1):
+    """In-order interpretation of the queues with event counters: every worker takes the next ticket of its
+    queue and may only run the task once its event has reached the threshold; a finished task bumps its
+    trigger event.  Returns the number of steps; raises AssertionError on deadlock."""
+    events = {}
+    heads = [0] * len(plan.queues)
+    running = [[] for _ in plan.queues]     # tasks held by workers (waiting or runnable)
+    done, total, steps = 0, sum(len(t) for t in plan.queues), 0
+    while done < total:
+        progressed = False
+        for q, tasks in enumerate(plan.queues):
+            while len(running[q]) < workers_per_queue and heads[q] < len(tasks):
+                running[q].append(tasks[heads[q]])
+                heads[q] += 1
+            still = []
+            for (ty, idx, m, dep, thr) in running[q]:
+                if dep == -1 or events.get(dep, 0) >= thr:
+                    trig = {PERMUTE: plan.ev_per_tile + m, GEMM1: plan.ev_per_tile + plan.max_mtiles + m, GEMM2: "g2"}[ty]
+                    events[trig] = events.get(trig, 0) + 1
+                    done += 1
+                    progressed = True
+                else:
+                    still.append((ty, idx, m, dep, thr))
+            running[q] = still
+        steps += 1
+        assert progressed, f"deadlock after {done} of {total} tasks: waiting {[r[:1] for r in running if r]}"
+    assert events.get("g2", 0) == plan.gemm2_total, "COMBINE would wait for a GEMM-2 total that is never reached"
+    return steps

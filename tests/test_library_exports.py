@@ -47,6 +47,43 @@ def test_status_strings_and_workspace_query(lib):
     assert lib.moe_ffn_workspace_bytes(None, None, None) == -1
 
 
+def test_single_launch_alignment_is_checked_on_the_host(lib):
+    """The single-launch modes need 128-byte aligned hand-over buffers; the check happens on the host before
+    anything is enqueued, so made-up addresses are enough to see it (no launch happens on this path)."""
+    import ctypes
+    from paper_2605_23764_amd.binding import _MoeSaved
+    s = moe.make_shape(64, 64, 64, 4, 4, 0, 1, moe.MOE_BF16)
+    fwd, bwd = moe.moe_ffn_workspace_bytes(s)
+    P = ctypes.c_void_p
+    base = 0x7f0000000000
+
+    def saved(a_off=0, xp_off=0):
+        addr = {n: base + (i + 1) * 0x1000000 for i, (n, _) in enumerate(_MoeSaved._fields_)}
+        addr["A"] += a_off
+        addr["Xp"] += xp_off
+        return _MoeSaved(*(P(addr[n]) for n, _ in _MoeSaved._fields_))
+
+    def forward(sv, ws):
+        return lib.moe_ffn_forward(ctypes.byref(s), P(base + 0x100), P(base + 0x200), P(base + 0x300), P(base + 0x400),
+                                   P(base + 0x500), ctypes.byref(sv), P(ws), ctypes.c_size_t(fwd), 1, None)
+    assert forward(saved(a_off=16), base) == -1
+    assert forward(saved(xp_off=64), base) == -1
+    assert forward(saved(), base + 16) == -1
+    sv = saved()
+    assert lib.moe_ffn_backward(ctypes.byref(s), P(base + 0x100), P(base + 0x200), P(base + 0x300), P(base + 0x400),
+                                ctypes.byref(sv), P(base + 0x500), P(base + 0x600), P(base + 0x700), P(base + 0x800),
+                                P(base + 0x900 + 16), ctypes.c_size_t(bwd), 1, None) == -1
+    # microbenchmark modes 1 and 3: tiles of whole 128-byte lines on a 128-byte aligned intermediate
+    lib.moe_microbench_swiglu_add.argtypes = None
+    for mode in (1, 3):
+        assert lib.moe_microbench_swiglu_add(4096, 8, P(base), P(base + 0x100000), P(base + 0x200000), P(base + 0x300000),
+                                             mode, 1, P(base + 0x400000), ctypes.c_size_t(1 << 20), None) == -1
+        assert lib.moe_microbench_swiglu_add(4096, 8, P(base), P(base + 0x100000), P(base + 0x200000 + 16),
+                                             P(base + 0x300000), mode, 8, P(base + 0x400000), ctypes.c_size_t(1 << 20),
+                                             None) == -1
+    assert "XCD" in moe.moe_status_string(-6)
+
+
 def test_bench_refuses_more_than_one_gpu():
     """One GPU's share is all this build runs: bench.py --gpus 2 must exit with a message."""
     import os

@@ -1,0 +1,64 @@
+"""CPU tests of the schedule checker itself (tests/plan_check.py) on a hand-made plan: it accepts a legal
+schedule and names each planted mistake (paper Section 4.3: thresholds, topological queue order, progress)."""
+import copy
+
+import numpy as np
+import pytest
+
+from plan_check import GEMM1, GEMM2, PERMUTE, Plan, check_plan, expected_tiles, simulate
+
+EV, MAXM = 2, 6
+
+
+def hand_plan():
+    # M tiles 0, 1 (pair 0 -> queue 0): 40 and 20 rows; M tile 2 (pair 1 -> queue 1): 300 rows (tall); tile 3 unused
+    rows = np.array([40, 20, 300, 0], dtype=np.int32)
+    q0 = [(PERMUTE, 0, 0, -1, 0), (PERMUTE, 1, 0, -1, 0), (PERMUTE, 0, 1, -1, 0),
+          (GEMM1, 0, 0, EV + 0, 2), (GEMM1, 0, 1, EV + 1, 1), (GEMM1, 1, 0, EV + 0, 2), (GEMM1, 1, 1, EV + 1, 1),
+          (GEMM2, 0, 0, EV + MAXM + 0, 2), (GEMM2, 0, 1, EV + MAXM + 1, 2)]
+    q1 = [(PERMUTE, i, 2, -1, 0) for i in range(10)]
+    q1 += [(GEMM1, i, 2, EV + 2, 10) for i in range(3)]
+    q1 += [(GEMM2, i, 2, EV + MAXM + 2, 3) for i in range(2)]
+    return Plan(4, rows, [q0, q1] + [[] for _ in range(6)], 4, EV, MAXM)
+
+
+def exp_of(plan):
+    return expected_tiles(plan, n1_wide=2, n1_tall=3, n2_wide=1, n2_tall=2, wide_rows=256, perm_rows=32, permute=True)
+
+
+def test_legal_plan_passes_and_runs_to_completion():
+    plan = hand_plan()
+    check_plan(plan, exp_of(plan))
+    assert simulate(plan, 1) > 0 and simulate(plan, 4) > 0
+
+
+def _mutations():
+    def thr_up(p): p.queues[0][3] = (GEMM1, 0, 0, EV + 0, 3)
+    def thr_down(p): p.queues[1][10] = (GEMM1, 0, 2, EV + 2, 9)
+    def wrong_event(p): p.queues[0][7] = (GEMM2, 0, 0, EV + MAXM + 1, 2)
+    def consumer_first(p): p.queues[0].insert(2, p.queues[0].pop(7))           # GEMM-2 ahead of its GEMM-1 tiles
+    def dropped(p): p.queues[1].pop(4)
+    def doubled(p): p.queues[0].append(p.queues[0][4])
+    def wrong_queue(p): p.queues[2].append(p.queues[1].pop())
+    def total_off(p): p.gemm2_total += 1
+    def phantom(p): p.queues[3].append((GEMM1, 0, 3, -1, 0))                   # task on a tile without rows
+    return [thr_up, thr_down, wrong_event, consumer_first, dropped, doubled, wrong_queue, total_off, phantom]
+
+
+@pytest.mark.parametrize("mutate", _mutations(), ids=lambda f: f.__name__)
+def test_planted_mistake_is_named(mutate):
+    plan = copy.deepcopy(hand_plan())
+    mutate(plan)
+    with pytest.raises(AssertionError):
+        check_plan(plan, exp_of(hand_plan()))
+
+
+def test_interpreter_reports_deadlock():
+    plan = copy.deepcopy(hand_plan())
+    plan.queues[0][3] = (GEMM1, 0, 0, EV + 0, 3)       # waits for a third PERMUTE part that does not exist
+    with pytest.raises(AssertionError, match="deadlock"):
+        simulate(plan, 1)
+    plan = copy.deepcopy(hand_plan())
+    plan.queues[0].insert(0, plan.queues[0].pop(7))    # a consumer at the head of an in-order queue with one worker
+    with pytest.raises(AssertionError, match="deadlock"):
+        simulate(plan, 1)
