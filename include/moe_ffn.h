@@ -277,6 +277,21 @@ int moe_microbench_swiglu_add(int M, int N, const void* d_x, const void* d_y, vo
                               int tile_rows, void* d_workspace, size_t workspace_bytes, void* stream);
 int moe_microbench_last_status(const void* d_workspace);
 
+/*
+ * moe_microbench_swiglu_add for callers that cannot allocate device memory or pass a workspace (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the event counters and ready
+ * rings live in a device array inside the library (394 KB per GPU, held until the process ends) instead
+ * of a caller's workspace.  Same arguments, checks, kernels and results as moe_microbench_swiglu_add.
+ *   M         at most 32768 (MOE_ERR_UNSUPPORTED_SHAPE beyond)
+ *   d_status  nullable device word, 4-byte aligned, caller-owned: receives the launch's status word
+ *             (0 ok, bit 0 a bounded wait expired, bit 1 wrong XCD placement); it is zeroed by the call
+ * Calls no hipMalloc / hipFree or any allocating routine; only enqueues kernels on `stream`.  The first call
+ * on a device looks up the array's address (make it outside graph capture).  All calls on one GPU share the
+ * array: each call clears what it needs, and calls that overlap in time on one GPU (two streams) race.
+ */
+int moe_microbench_swiglu_add_static_scratch(int M, int N, const void* d_x, const void* d_y, void* d_s, void* d_out,
+                                             int mode, int tile_rows, uint32_t* d_status, void* stream);
+
 /* ---- Ceiling probes (measurement aids for the benchmark; no step of the layer) ----
  * What this GPU sustains on the two resources the grouped GEMMs and the permute / combine steps are
  * priced against (Section 2.3 judges the operators by hardware utilisation), with nothing

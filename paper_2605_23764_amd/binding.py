@@ -38,7 +38,7 @@ EXPORTS = (
     "moe_status_string", "moe_ffn_workspace_bytes", "moe_ffn_forward", "moe_ffn_backward",
     "moe_ffn_last_status", "moe_ffn_debug_set_spin_limit", "moe_route", "moe_permute", "moe_grouped_gemm_swiglu", "moe_grouped_gemm",
     "moe_combine", "moe_microbench_workspace_bytes", "moe_microbench_swiglu_add", "moe_microbench_last_status",
-    "moe_probe_mfma_bf16", "moe_probe_copy", "moe_probe_read",
+    "moe_probe_mfma_bf16", "moe_probe_copy", "moe_probe_read", "moe_microbench_swiglu_add_static_scratch",
     "moe_ffn_debug_force_device_scope", "moe_ffn_debug_layout", "moe_dispatch_to_combine",
 )
 LAYOUT_WORDS = 25   # MOE_LAYOUT_WORDS
@@ -255,6 +255,12 @@ def moe_probe_mfma_bf16(n_workgroups, mfma_per_wave, random_operands, sink, stre
     _check(load_library().moe_probe_mfma_bf16(ctypes.c_int(n_workgroups), ctypes.c_int(mfma_per_wave),
                                               ctypes.c_int(1 if random_operands else 0), _ptr(sink), _stream(stream)),
            "moe_probe_mfma_bf16")
+
+
+def moe_microbench_swiglu_add_static_scratch(M, N, x, y, s, out, mode, tile_rows, status=None, stream=None) -> None:
+    _check(load_library().moe_microbench_swiglu_add_static_scratch(
+        ctypes.c_int(M), ctypes.c_int(N), _ptr(x), _ptr(y), _ptr(s), _ptr(out), ctypes.c_int(mode),
+        ctypes.c_int(tile_rows), _ptr(status), _stream(stream)), "moe_microbench_swiglu_add_static_scratch")
 
 
 def moe_ffn_debug_force_device_scope(on: bool) -> None:

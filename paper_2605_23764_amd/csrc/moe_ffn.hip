@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <mutex>
 
 #include "backward.h"
 #include "common.h"
@@ -591,6 +592,29 @@ int mb_launch(int M, int N, const void* d_x, const void* d_y, void* d_s, void* d
   return launch_status();
 }
 
+// Scratch of the entry point that allocates nothing: the microbenchmark's workspace for up to kMbScratchMaxM
+// rows as a file-scope device array (each GPU the library runs on holds its own copy until the process ends).
+// In host code the array's name is only a handle for hipGetSymbolAddress; the device address is looked up once
+// per device, with that device current, and kept.
+constexpr int kMbScratchMaxM = 32768;
+constexpr size_t kMbScratchBytes = 512 + (size_t)kMbScratchMaxM * 4 + ((2 * (size_t)kMbScratchMaxM + 2 * kNumXcd) * 4 + 255) / 256 * 256;
+static __device__ __align__(256) __attribute__((used)) unsigned char g_mb_scratch[kMbScratchBytes];
+
+int mb_scratch_ptr(void** out) {
+  static std::mutex mu;
+  static void* ptr[64] = {nullptr};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MOE_ERR_LAUNCH;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    void* q = nullptr;
+    if (hipGetSymbolAddress(&q, HIP_SYMBOL(g_mb_scratch)) != hipSuccess || !q) return MOE_ERR_LAUNCH;
+    ptr[dev] = q;
+  }
+  *out = ptr[dev];
+  return MOE_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -762,6 +786,16 @@ int moe_microbench_swiglu_add(int M, int N, const void* d_x, const void* d_y, vo
     return st != MOE_OK ? st : MOE_ERR_WORKSPACE_TOO_SMALL;
   }
   return mb_launch(M, N, d_x, d_y, d_s, d_out, mode, tile_rows, d_workspace, nullptr, stream);
+}
+
+int moe_microbench_swiglu_add_static_scratch(int M, int N, const void* d_x, const void* d_y, void* d_s, void* d_out,
+                                             int mode, int tile_rows, uint32_t* d_status, void* stream) {
+  if (M > kMbScratchMaxM) return MOE_ERR_UNSUPPORTED_SHAPE;
+  if (d_status && (reinterpret_cast<uintptr_t>(d_status) & 3)) return MOE_ERR_INVALID_ARG;
+  void* scratch = nullptr;
+  const int st = mb_scratch_ptr(&scratch);
+  if (st != MOE_OK) return st;
+  return mb_launch(M, N, d_x, d_y, d_s, d_out, mode, tile_rows, scratch, d_status, stream);
 }
 
 int moe_probe_mfma_bf16(int n_workgroups, int mfma_per_wave, int random_operands, void* d_sink, void* stream) {

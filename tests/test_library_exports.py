@@ -81,6 +81,7 @@ def test_single_launch_alignment_is_checked_on_the_host(lib):
         assert lib.moe_microbench_swiglu_add(4096, 8, P(base), P(base + 0x100000), P(base + 0x200000 + 16),
                                              P(base + 0x300000), mode, 8, P(base + 0x400000), ctypes.c_size_t(1 << 20),
                                              None) == -1
+    assert lib.moe_microbench_swiglu_add_static_scratch(32769, 64, P(base), P(base), P(base), P(base), 1, 8, None, None) == -2
     assert "XCD" in moe.moe_status_string(-6)
 
 
