@@ -49,7 +49,7 @@ enum GemmEpilogue { kEpiStore = 0, kEpiSwiglu = 1, kEpiSwigluGrad = 2 };
 constexpr int kBM = 256;            // tile row capacity (one M tile of the tile map)
 constexpr int kBN = 256;            // weight columns staged per tile
 constexpr int kBK = 64;             // K step
-constexpr int kRowGranule = 32;     // M tiles of one expert are equal multiples of this
+constexpr int kRowGranule = 64;     // an expert's rows are dealt to its M tiles in units of this (two wave rows x 32)
 constexpr int kAStages = 2;
 constexpr int kBStages = 3;
 constexpr int kGemmThreads = 256;
@@ -61,6 +61,11 @@ constexpr int kBStageBytes = kBLines * kLine;        // 32 KB
 constexpr int kBRegion = kAStages * kAStageBytes;    // weights stages start here
 constexpr int kGemmLdsBytes = kBRegion + kBStages * kBStageBytes;   // 160 KB
 constexpr int kMaxMT = kBM / 64;                     // 32-row MFMA sub-tiles per wave row (4)
+// Rows a wide tile can take: 256 staged through LDS plus, per wave row, one more 32-row block whose operand
+// fragments the waves fetch straight from global memory into registers (see gemm_k_loop, NX).  An expert with
+// 257..320 rows is then ONE wide tile: its weights stream once, its staged activation bytes per K step stay
+// those of a 256-row tile, and the MFMA work grows by the real rows only.
+constexpr int kWideRows = kBM + 64;
 constexpr int kBLinesPerWave = kBLines / 4;          // 8
 
 struct GemmParams {
@@ -113,6 +118,20 @@ __device__ __forceinline__ void lds_dma16(const char* sbase, uint32_t voff, uint
                : "memory", "m0");
 }
 
+// One slice of the register-fed row block: lane (row l32, half lh) fetches the 16 bytes that are its MFMA operand
+// for k slice KS of a K step (k = 16*KS + 8*lh .. +7).  Plain global load in assembly, so that the hand-kept
+// vmcnt accounting of the pipeline covers it; the value is valid once a later wait has retired it.
+template <int KS>
+__device__ __forceinline__ void load_xblock(bf16x8& dst, const char* sbase, uint32_t voff) {
+  asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3" : "=v"(dst) : "v"(voff), "s"(sbase), "n"(KS * 32) : "memory");
+}
+// Retires the four fragments of a K step, behind which at most N memory operations have been issued (see
+// gemm_k_loop); names the registers so that no use can be scheduled ahead of the wait.
+template <int N>
+__device__ __forceinline__ void wait_xblock(bf16x8 (&f)[4]) {
+  asm volatile("s_waitcnt vmcnt(%4)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]) : "n"(N) : "memory");
+}
+
 // Pin a wave-uniform value into scalar registers (readfirstlane returns a signed
 // int: widen through uint32_t, or the low half sign-extends into the high half).
 __device__ __forceinline__ uint32_t uniform_u32(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
@@ -156,6 +175,7 @@ struct GemmTileCtx {
   uint32_t b_off[8];           // NN: per lane byte offset inside a 4-row line per column half; NT: like a_off
   uint32_t a_rd[4];            // operand read offset inside an A stage, per k slice
   uint32_t b_rd[4];            // operand read offset inside a B stage (NN: per 32-column block; NT: per k slice)
+  uint32_t x_off;              // register-fed row block: per lane byte offset of (row, k half) inside the K step
   uint32_t lds0;               // LDS byte address of the staging area
   int nA;                      // A lines per wave per step
   int lda_bytes, ldb_bytes;
@@ -242,16 +262,24 @@ __device__ __forceinline__ bf16x8 join_tr(s16x4 lo, s16x4 hi) {
   return __builtin_bit_cast(bf16x8, (s16x8){lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w});
 }
 
-// One 16-wide k slice for a wave: NMT x 4 MFMAs on `cur`.  Behind the MFMAs, one
-// per slot, go the operand reads that fill `nxt` (slice ks_n of the stages
-// as_n / bs_n) and four of the load group's global -> LDS copies, so LDS latency
+// One 16-wide k slice for a wave: (NMT + NX) x 4 MFMAs on `cur` (NX = 1: the last row block's activation
+// fragment is `xblk`, held in registers).  Behind the MFMAs, one per slot, go the operand reads that fill `nxt`
+// (slice ks_n of the stages as_n / bs_n) and four of the load group's global -> LDS copies, so LDS latency
 // and load issue hide under MFMA time.  sched_barrier pins that order.
-template <int LAY, int NMT, bool TALL>
+// The accumulators of the register-fed block live in architectural VGPRs (the 256 accumulation registers hold the
+// four staged blocks), which only an assembly statement with register-class constraints can pin: left to
+// the register allocator the fifth block's accumulators wander between the two files, 64 moves per slice.
+__device__ __forceinline__ void mfma_vgpr_acc(f32x16& acc, const bf16x8& a, const bf16x8& b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+
+template <int LAY, int NMT, bool TALL, int NX = 0>
 __device__ __forceinline__ void gemm_slice(f32x16 (&acc)[kMaxMT][4], const GemmFrags<LAY, NMT>& cur,
                                            GemmFrags<LAY, NMT>& nxt, bool read_next, lds_cptr as_n, lds_cptr bs_n,
-                                           int ks_n, const GemmTileCtx& t, const GemmLoadGroup& g, int load0) {
+                                           int ks_n, const GemmTileCtx& t, const GemmLoadGroup& g, int load0,
+                                           f32x16 (&accx)[4], const bf16x8& xblk) {
   typedef GemmSliceShape<LAY, NMT> S;
-  constexpr int n_mfma = NMT * 4, n_act = S::n_reads + 4;
+  constexpr int n_mfma = (NMT + NX) * 4, n_act = S::n_reads + 4;
   bf16x8 wf[4], xf[NMT > 0 ? NMT : 1];
 #pragma unroll
   for (int nt = 0; nt < 4; ++nt) wf[nt] = LAY == kLayNT ? cur.wk[nt] : join_tr(cur.w[nt][0], cur.w[nt][1]);
@@ -259,7 +287,8 @@ __device__ __forceinline__ void gemm_slice(f32x16 (&acc)[kMaxMT][4], const GemmF
   for (int mt = 0; mt < NMT; ++mt) xf[mt] = cur.xf[mt];
 #pragma unroll
   for (int j = 0; j < n_mfma; ++j) {
-    acc[j >> 2][j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j & 3], xf[j >> 2], acc[j >> 2][j & 3], 0, 0, 0);
+    if (j < NMT * 4) acc[j >> 2][j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j & 3], xf[j >> 2], acc[j >> 2][j & 3], 0, 0, 0);
+    else mfma_vgpr_acc(accx[j & 3], wf[j & 3], xblk);
 #pragma unroll
     for (int a = 0; a < n_act; ++a) {
       if ((a * n_mfma) / n_act != j) continue;
@@ -290,11 +319,31 @@ __device__ __forceinline__ void gemm_read_frags(GemmFrags<LAY, NMT>& f, lds_cptr
 // then B(s+3), issued four at a time behind the MFMAs of the following four
 // slices, while the first operands of step s+1 are already being read under the
 // last slice of step s.
-template <int LAY, int NMT, bool TALL>
-__device__ __forceinline__ void gemm_k_loop(f32x16 (&acc)[kMaxMT][4], const GemmTileCtx& t, char* smem, int n_steps) {
+//
+// NX = 1 (wide tiles of 257..320 rows, NMT = 4): this wave also owns a fifth 32-row block whose
+// activation fragments bypass LDS: four 16-byte loads per lane and K step, straight into the MFMA operand
+// layout.  The fragments of step s + 1 are requested at the top of step s, ahead of that step's copies in the
+// wave's in-order stream of memory operations, so the barrier's wait of step s (which retires everything
+// older than the last 8 copies) has retired them too: three slices of load-to-use distance and no change to
+// the pipeline's wait counts.  The loads are assembly with register outputs, i.e. the registers are written
+// behind the compiler's back until a wait has retired them; the window from request to retirement therefore
+// lies inside ONE loop trip (a value carried around the loop may be copied by the compiler at the back
+// edge, which must only happen to retired values) and ends, right behind the barrier's wait, in a statement
+// that names the registers, so that the compiler can neither use nor copy them earlier.
+template <int LAY, int NMT, bool TALL, int NX = 0>
+__device__ __forceinline__ void gemm_k_loop(f32x16 (&acc)[kMaxMT][4], f32x16 (&accx)[4], const GemmTileCtx& t, char* smem,
+                                            int n_steps) {
   typedef TileShape<TALL> S;
+  static_assert(NX == 0 || (NMT == kMaxMT && !TALL), "the register-fed block extends a full wide tile");
   const lds_cptr lds = (lds_cptr)smem;
   if (n_steps <= 0) return;
+  bf16x8 xb[4], xn[4];                           // register-fed block: one fragment per k slice; this step's, next step's
+  auto load_x = [&](bf16x8 (&f)[4], int step) __attribute__((always_inline)) {
+    const char* base = uniform_ptr(t.a_base + (size_t)step * (kBK * 2));
+    load_xblock<0>(f[0], base, t.x_off); load_xblock<1>(f[1], base, t.x_off);
+    load_xblock<2>(f[2], base, t.x_off); load_xblock<3>(f[3], base, t.x_off);
+  };
+  if (NX) load_x(xb, 0);
   {
     const GemmLoadGroup g0 = gemm_load_group<LAY, TALL>(t, 0, 0, 0, 0);                       // A(0), B(0)
 #pragma unroll
@@ -308,6 +357,7 @@ __device__ __forceinline__ void gemm_k_loop(f32x16 (&acc)[kMaxMT][4], const Gemm
       wait_vmcnt<0>();
     }
     __builtin_amdgcn_s_barrier();
+    if (NX) wait_xblock<S::kBLoads>(xb);   // already retired by the wait above: this one names the registers
   }
   GemmLoadGroup g = gemm_load_group<LAY, TALL>(t, n_steps > 1 ? 1 : -1, 1, n_steps > 2 ? 2 : -1, 2);   // A(1), B(2)
 #pragma unroll
@@ -320,34 +370,43 @@ __device__ __forceinline__ void gemm_k_loop(f32x16 (&acc)[kMaxMT][4], const Gemm
     const lds_cptr as = lds + (s & 1) * S::kAStage;
     const lds_cptr bs = lds + S::kBReg + bs_i * S::kBStage;
     const int bs_next = bs_i == kBStages - 1 ? 0 : bs_i + 1;
+    const bool more = s + 1 < n_steps;
+    if (NX && more) load_x(xn, s + 1);
 #pragma unroll
     for (int ks = 0; ks < 3; ++ks) {
       if (NMT > 0) {
-        gemm_slice<LAY, NMT, TALL>(acc, cur, nxt, true, as, bs, ks + 1, t, g, 4 + 4 * ks);
+        gemm_slice<LAY, NMT, TALL, NX>(acc, cur, nxt, true, as, bs, ks + 1, t, g, 4 + 4 * ks, accx, xb[ks]);
         cur = nxt;
       } else {
 #pragma unroll
         for (int i = 0; i < 4; ++i) gemm_issue_one<LAY, TALL>(t, g, 4 + 4 * ks + i);
       }
     }
-    const bool more = s + 1 < n_steps;
     if (more) {
       wait_lgkmcnt0();
       if (s + 2 < n_steps) wait_vmcnt<S::kBLoads>(); else wait_vmcnt<0>();
       __builtin_amdgcn_s_barrier();
+      // the next step's fragments are older than the copies the wait above lets pass: retired; from this
+      // statement on (it names the registers) they are ordinary values
+      if (NX) wait_xblock<S::kBLoads>(xn);
       g = gemm_load_group<LAY, TALL>(t, s + 2 < n_steps ? s + 2 : -1, s & 1, s + 3 < n_steps ? s + 3 : -1, bs_i);
     }
     if (NMT > 0) {
       // `more` false: no loads left (both sources null) and nothing further to read
-      gemm_slice<LAY, NMT, TALL>(acc, cur, nxt, more, lds + ((s + 1) & 1) * S::kAStage,
-                                 lds + S::kBReg + bs_next * S::kBStage, 0, t, g, 0);
+      gemm_slice<LAY, NMT, TALL, NX>(acc, cur, nxt, more, lds + ((s + 1) & 1) * S::kAStage,
+                                     lds + S::kBReg + bs_next * S::kBStage, 0, t, g, 0, accx, xb[3]);
       if (more) cur = nxt;
     } else if (more) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) gemm_issue_one<LAY, TALL>(t, g, i);
     }
+    if (NX && more) {
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) xb[ks] = xn[ks];
+    }
     bs_i = bs_next;
   }
+  if (NX) asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");   // the last assembly MFMA's result before any read of it
   __builtin_amdgcn_s_barrier();   // all stages free before the next tile's first loads
 }
 
@@ -411,10 +470,12 @@ __device__ __forceinline__ void store_block_via_lds(char* region, const u32x2 (&
 }
 
 // One output tile: (t0, t1) = (M tile of the tile map, N tile of TileShape<TALL>::kCols
-// columns; SwiGLU: half as many output columns).
-template <int LAY, int EPI, bool TALL>
+// columns; SwiGLU: half as many output columns).  X5: a wide tile of 257..320 rows (rows past 256 go
+// through the register-fed block of each wave row).
+template <int LAY, int EPI, bool TALL, int X5 = 0>
 __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int t1, char* smem) {
   typedef TileShape<TALL> S;
+  static_assert(!(TALL && X5), "one shape at a time");
   const int tid = threadIdx.x;
   // opaque to the optimiser: per-lane setup is recomputed per tile instead of being hoisted out of
   // the tile loop and held (or spilled) across every K loop
@@ -427,15 +488,18 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
   // row_base: first tile row of this wave; n_mt: its 32-row blocks
   const int e = p.tiles.expert[t0], row0 = p.tiles.row0[t0], rows = p.tiles.rows[t0], ntile = t1;
   // rows per wave (row), a multiple of 32: tall = four wave rows, wide = two
-  const int per = TALL ? ((((rows + 31) >> 5) + 3) >> 2) << 5 : ((rows + 63) >> 6) << 5;
+  const int rows_lds = X5 ? kBM : rows;               // rows staged through LDS
+  const int per = TALL ? ((((rows + 31) >> 5) + 3) >> 2) << 5 : ((rows_lds + 63) >> 6) << 5;
   const int row_base = (TALL ? wave : wm) * per;
-  const int n_mt = (max(0, min(per, rows - row_base)) + 31) >> 5;
+  const int n_mt = (max(0, min(per, rows_lds - row_base)) + 31) >> 5;
   const int n_steps = p.K / kBK;
+  const int x_row0 = kBM + wm * 32;                   // X5: first row of this wave row's register-fed block
+  const bool has_x = X5 && rows > x_row0;             // wave-uniform
 
   GemmTileCtx t;
   t.wave = wave;
   const int kk4 = lane >> 4;          // k-row of this lane inside a 4-k-row line
-  t.nA = (rows + 31) >> 5;            // (8-row lines any operand read touches = 4*ceil(rows/32)) / 4 waves
+  t.nA = (rows_lds + 31) >> 5;        // (8-row lines any operand read touches = 4*ceil(rows/32)) / 4 waves
   t.lda_bytes = p.lda * 2;
   t.ldb_bytes = p.ldb * 2;
   // chunk position -> k chunk of an 8-row x 64-k line: lane -> (row r = lane/8, position pos = lane%8) holds
@@ -454,6 +518,11 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
       // gathered: offsets are relative to the first token (the caller guarantees that A spans < 4 GB)
       const long arow = gathered ? (long)p.gather[row0 + row] : (long)row;
       t.a_off[i] = (uint32_t)((arow * p.lda + kc_c * 8) * 2);
+    }
+    if (X5) {
+      const int row = min(x_row0 + l32, rows - 1);
+      const long arow = gathered ? (long)p.gather[row0 + row] : (long)row;
+      t.x_off = (uint32_t)((arow * p.lda + lh * 8) * 2);
     }
     if (LAY == kLayNT) {
 #pragma unroll
@@ -501,7 +570,8 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
     }
   }
 
-  f32x16 acc[kMaxMT][4];
+  constexpr int kAccMT = kMaxMT + X5;
+  f32x16 acc[kMaxMT][4], accx[4];   // accx: the register-fed fifth block (X5 only)
 #pragma unroll
   for (int i = 0; i < kMaxMT; ++i)
 #pragma unroll
@@ -509,24 +579,38 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  switch (n_mt) {
-    case 0: gemm_k_loop<LAY, 0, TALL>(acc, t, smem, n_steps); break;
-    case 1: gemm_k_loop<LAY, 1, TALL>(acc, t, smem, n_steps); break;
-    case 2: gemm_k_loop<LAY, 2, TALL>(acc, t, smem, n_steps); break;
-    case 3: gemm_k_loop<LAY, 3, TALL>(acc, t, smem, n_steps); break;
-    default:
-      if constexpr (!TALL) gemm_k_loop<LAY, 4, TALL>(acc, t, smem, n_steps);   // a tall wave row has at most 96 rows
-      break;
+  if constexpr (X5) {
+    // 256 staged rows: every wave row is full; the fifth block exists for wave row 0, and for wave row 1 above 288 rows
+    if (has_x) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) accx[j][r] = 0.f;
+      gemm_k_loop<LAY, kMaxMT, false, 1>(acc, accx, t, smem, n_steps);
+    } else {
+      gemm_k_loop<LAY, kMaxMT, false, 0>(acc, accx, t, smem, n_steps);
+    }
+  } else {
+    switch (n_mt) {
+      case 0: gemm_k_loop<LAY, 0, TALL>(acc, accx, t, smem, n_steps); break;
+      case 1: gemm_k_loop<LAY, 1, TALL>(acc, accx, t, smem, n_steps); break;
+      case 2: gemm_k_loop<LAY, 2, TALL>(acc, accx, t, smem, n_steps); break;
+      case 3: gemm_k_loop<LAY, 3, TALL>(acc, accx, t, smem, n_steps); break;
+      default:
+        if constexpr (!TALL) gemm_k_loop<LAY, 4, TALL>(acc, accx, t, smem, n_steps);   // a tall wave row has at most 96 rows
+        break;
+    }
   }
 
   // ---- epilogue: lane holds row l32 of each 32 x 32 block and, per register group q,
   // the 4 consecutive columns q*8 + lh*4 .. +3; blocks leave through the wave's LDS region ----
   char* region = epilogue_region(smem, wave);
 #pragma unroll
-  for (int mt = 0; mt < kMaxMT; ++mt) {
-    const int m0 = row_base + mt * 32;                // first row of the block inside the tile
+  for (int mt = 0; mt < kAccMT; ++mt) {
+    const int m0 = mt < kMaxMT ? row_base + mt * 32 : x_row0;   // first row of the block inside the tile
     const int rows_valid = min(32, rows - m0);
-    if (mt >= n_mt || rows_valid <= 0) continue;      // wave-uniform
+    if ((mt < kMaxMT ? mt >= n_mt : !has_x) || rows_valid <= 0) continue;      // wave-uniform
+    const f32x16* am = mt < kMaxMT ? acc[mt < kMaxMT ? mt : 0] : accx;         // resolved at compile time (unrolled)
     const size_t grow0 = (size_t)(row0 + m0);
     const size_t grow = grow0 + l32;                  // this lane's row (may be past the end: never stored)
     if (EPI == kEpiSwiglu) {
@@ -539,8 +623,8 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
           float g[4], u[4], a[4];
 #pragma unroll
           for (int x = 0; x < 4; ++x) {
-            g[x] = acc[mt][ng][q * 4 + x];
-            u[x] = acc[mt][ng + 2][q * 4 + x];
+            g[x] = am[ng][q * 4 + x];
+            u[x] = am[ng + 2][q * 4 + x];
             a[x] = g[x] * sigmoidf_(g[x]) * u[x];
           }
           pa[ng][q] = u32x2{pack_bf16(a[0], a[1]), pack_bf16(a[2], a[3])};
@@ -575,7 +659,7 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
           float dg[4], du[4];
 #pragma unroll
           for (int x = 0; x < 4; ++x) {
-            const float da = acc[mt][nt][q * 4 + x];
+            const float da = am[nt][q * 4 + x];
             const float sg = sigmoidf_(g[x]);
             dg[x] = da * u[x] * sg * (1.f + g[x] * (1.f - sg));
             du[x] = da * g[x] * sg;
@@ -593,18 +677,21 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
       for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
         for (int q = 0; q < 4; ++q)
-          pk[nt][q] = u32x2{pack_bf16(acc[mt][nt][q * 4 + 0], acc[mt][nt][q * 4 + 1]),
-                            pack_bf16(acc[mt][nt][q * 4 + 2], acc[mt][nt][q * 4 + 3])};
+          pk[nt][q] = u32x2{pack_bf16(am[nt][q * 4 + 0], am[nt][q * 4 + 1]),
+                            pack_bf16(am[nt][q * 4 + 2], am[nt][q * 4 + 3])};
       store_block_via_lds<4>(region, pk, p.C + grow0 * p.ldc + c0, p.ldc, rows_valid, p.N - c0);
     }
   }
 }
 
-// A tile of the M-tile map runs in the tall shape iff it has more than 256 rows (the
-// map builder makes such tiles only with <= 384 rows and gives each a pair slot of its own).
+// Shape of a tile of the M-tile map by its rows: wide up to 256, wide with the register-fed block up to 320,
+// tall above (the map builder makes such tiles only with <= 384 rows and gives each a pair slot of its own).
+__device__ __forceinline__ bool tile_is_tall(int rows) { return rows > kWideRows; }
+
 template <int LAY, int EPI>
 __device__ __forceinline__ void gemm_map_tile_bf16(const GemmParams& p, int mtile, int ntile, bool tall, char* smem) {
   if (tall) gemm_tile_bf16<LAY, EPI, true>(p, mtile, ntile, smem);
+  else if (__builtin_amdgcn_readfirstlane(p.tiles.rows[mtile]) > kBM) gemm_tile_bf16<LAY, EPI, false, 1>(p, mtile, ntile, smem);
   else gemm_tile_bf16<LAY, EPI, false>(p, mtile, ntile, smem);
 }
 
@@ -613,7 +700,7 @@ __device__ __forceinline__ void gemm_map_tile_bf16(const GemmParams& p, int mtil
 // Returns false for an item that does not exist.
 __device__ __forceinline__ bool pair_work_item(const GemmParams& p, int m0, int rem, int n_m, int out_cols_per_ntile,
                                                int& mtile, int& ntile, bool& tall) {
-  tall = __builtin_amdgcn_readfirstlane(p.tiles.rows[m0]) > kBM;   // scalar: the branch below contains barriers
+  tall = tile_is_tall(__builtin_amdgcn_readfirstlane(p.tiles.rows[m0]));   // scalar: the branch below contains barriers
   if (tall) {
     mtile = m0;
     ntile = rem;

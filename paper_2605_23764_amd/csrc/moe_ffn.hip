@@ -40,6 +40,7 @@ inline int n_groups(const MoeShape& s) { return (s.T + kChunk - 1) / kChunk; }
 // pair slots of the tile map: a tall tile (> BM rows) takes two entries, a wide tile of a split expert has > BM/2 rows
 inline long max_mtiles(const MoeShape& s) { return 2 * (r_max(s) / tile_bm(s)) + 2 * s.E_local + 2; }
 inline int tile_tall(const MoeShape& s) { return s.dtype == MOE_BF16 ? kTallRows : 0; }
+inline int tile_wide_max(const MoeShape& s) { return s.dtype == MOE_BF16 ? kWideRows : kFBM; }
 inline int gemm1_ntiles(const MoeShape& s) { return s.dtype == MOE_BF16 ? (s.I + kBN / 2 - 1) / (kBN / 2) : s.I / kFBN; }
 inline int gemm2_ntiles(const MoeShape& s) { return s.dtype == MOE_BF16 ? (s.H + kBN - 1) / kBN : s.H / kFBN; }
 inline long n_events(const MoeShape& s) { return kEvPerTile + 2 * max_mtiles(s); }
@@ -192,6 +193,7 @@ RouteParams route_params(const Ctx& c, const float* logits) {
   p.BM = tile_bm(c.s);
   p.granule = c.s.dtype == MOE_BF16 ? kRowGranule : kFBM;
   p.tall = tile_tall(c.s);
+  p.wide_max = tile_wide_max(c.s);
   return p;
 }
 
@@ -427,7 +429,7 @@ int run_backward(const BwdCtx& c, const void* dy, const void* x, const void* w_g
   const int grid = BF16 ? (c.n_cu + 7) / 8 * 8 : c.n_cu * 4;
 
   uint32_t* tickets = reinterpret_cast<uint32_t*>(c.ws + c.L.tickets);   // [0, 8): w2_grad, [8, 16): w1_grad
-  hipLaunchKernelGGL(tile_map_kernel, dim3(1), dim3(kWave), 0, c.stream, c.sv.counts, s.E_local, bm,
+  hipLaunchKernelGGL(tile_map_kernel, dim3(1), dim3(kWave), 0, c.stream, c.sv.counts, s.E_local, tile_wide_max(s),
                      BF16 ? kRowGranule : kFBM, tile_tall(s), c.tiles, tickets, 2 * kNumXcd);
 
   // backward Dispatch
@@ -866,7 +868,7 @@ int moe_ffn_debug_layout(const MoeShape* shape, int backward, int64_t* out, int 
   v[7] = max_mtiles(*shape); v[8] = max_tasks_per_queue(*shape); v[9] = n_events(*shape);
   v[10] = kEvPerTile; v[11] = kEvGemm2; v[12] = kMetaMTiles; v[13] = kMetaQueueCount0; v[14] = kMetaGemm2Total;
   v[15] = kNumXcd; v[16] = kPermRows; v[17] = gemm1_ntiles(*shape); v[18] = gemm2_ntiles(*shape);
-  v[19] = tile_bm(*shape); v[20] = tile_tall(*shape); v[21] = kGemm2Lag; v[22] = (int64_t)sizeof(TaskDesc);
+  v[19] = tile_wide_max(*shape); v[20] = tile_tall(*shape); v[21] = kGemm2Lag; v[22] = (int64_t)sizeof(TaskDesc);
   v[23] = backward ? (shape->dtype == MOE_BF16 ? (shape->I + kBN - 1) / kBN : shape->I / kFBN) : 0;   // act_grad N tiles
   v[24] = kMetaFallbackWorkers;
   for (int i = 0; i < MOE_LAYOUT_WORDS; ++i) out[i] = v[i];

@@ -226,7 +226,7 @@ __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
   // the tile map lists M tiles in pairs (siblings of one expert where possible); queue q owns pairs q, q+8, ...
   const int n_pairs = (n_mtiles + 1) >> 1;
   auto parts_of = [&](int m) { return (sp.route.tiles.rows[m] + kPermRows - 1) / kPermRows; };
-  constexpr int kWideRows = BF16 ? kBM : (1 << 30);   // a bf16 tile with more rows runs in the tall shape
+  constexpr int kTallAbove = BF16 ? kWideRows : (1 << 30);   // a bf16 tile with more rows runs in the tall shape
   const bool permute = !(sp.no_permute || BWD);
   for (int q = wave; q < kNumXcd; q += n_waves) {
     const int Pq = n_pairs > q ? (n_pairs - q + kNumXcd - 1) / kNumXcd : 0;
@@ -248,7 +248,7 @@ __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
       if (j < Pq) {
         const int m0 = 2 * (q + kNumXcd * j);
         const int rows0 = sp.route.tiles.rows[m0];
-        const bool tall = rows0 > kWideRows;
+        const bool tall = rows0 > kTallAbove;
         const int n_sib = tall ? 1 : ((m0 + 1 < n_mtiles && sp.route.tiles.rows[m0 + 1] > 0) ? 2 : 1);
         const int n_nt = tall ? (sp.g1.N + kTallCols1 - 1) / kTallCols1 : nN1;
         const int parts0 = parts_of(m0), parts1 = n_sib > 1 ? parts_of(m0 + 1) : 0;
@@ -261,7 +261,7 @@ __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
       }
       if (j >= kGemm2Lag) {
         const int m0 = 2 * (q + kNumXcd * (j - kGemm2Lag));
-        const bool tall = sp.route.tiles.rows[m0] > kWideRows;
+        const bool tall = sp.route.tiles.rows[m0] > kTallAbove;
         const int n_sib = tall ? 1 : ((m0 + 1 < n_mtiles && sp.route.tiles.rows[m0 + 1] > 0) ? 2 : 1);
         const int n_nt = tall ? (sp.g2.N + 127) / 128 : nN2;
         const int g1_tiles = tall ? (sp.g1.N + kTallCols1 - 1) / kTallCols1 : nN1;   // GEMM-1 tiles that complete a row block of A
@@ -279,7 +279,7 @@ __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
     int total = 0;
     for (int m = lane; m < n_mtiles; m += kWave) {
       const int rows = sp.route.tiles.rows[m];
-      total += rows > kWideRows ? (sp.g2.N + 127) / 128 : (rows > 0 ? nN2 : 0);
+      total += rows > kTallAbove ? (sp.g2.N + 127) / 128 : (rows > 0 ? nN2 : 0);
     }
     total = wave_incl_scan(total, lane);
     if (lane == kWave - 1) sp.meta[kMetaGemm2Total] = total;
@@ -323,11 +323,11 @@ __device__ __forceinline__ void run_tile_task(const SchedParams<BF16>& sp, const
     permute_rows<14>(sp.perm, r0, min(r0 + kPermRows, row0 + rows), wave, blockDim.x / kWave);
     sched_trigger(sp, kEvPerTile + m, wave, scope);
   } else if (type == kTaskGemm1) {
-    if constexpr (BF16) gemm_map_tile_bf16<kLayNN, kEpiSwiglu>(sp.g1, m, idx, __builtin_amdgcn_readfirstlane(sp.route.tiles.rows[m]) > kBM, smem);
+    if constexpr (BF16) gemm_map_tile_bf16<kLayNN, kEpiSwiglu>(sp.g1, m, idx, tile_is_tall(__builtin_amdgcn_readfirstlane(sp.route.tiles.rows[m])), smem);
     else gemm_tile_f32<kEpiSwiglu>(sp.g1, m, idx, reinterpret_cast<float*>(smem));
     sched_trigger(sp, kEvPerTile + sp.max_mtiles + m, wave, scope);
   } else {
-    if constexpr (BF16) gemm_map_tile_bf16<kLayNN, kEpiStore>(sp.g2, m, idx, __builtin_amdgcn_readfirstlane(sp.route.tiles.rows[m]) > kBM, smem);
+    if constexpr (BF16) gemm_map_tile_bf16<kLayNN, kEpiStore>(sp.g2, m, idx, tile_is_tall(__builtin_amdgcn_readfirstlane(sp.route.tiles.rows[m])), smem);
     else gemm_tile_f32<kEpiStore>(sp.g2, m, idx, reinterpret_cast<float*>(smem));
     // COMBINE waits for every GEMM-2 tile, so completions are counted here and published once per
     // worker after its queue has drained: a device-scope release per tile would write back the
@@ -410,7 +410,7 @@ void persistent_dgrad_kernel(SchedParams<true> sp) {
     const TaskDesc td = sp.tasks[(size_t)q * sp.max_tasks_per_q + t];
     const int type_n = __builtin_amdgcn_readfirstlane(td.type_n);
     const int type = type_n & 0xFF, idx = type_n >> 8, m = __builtin_amdgcn_readfirstlane(td.m);
-    const bool tall = __builtin_amdgcn_readfirstlane(sp.route.tiles.rows[m]) > kBM;
+    const bool tall = tile_is_tall(__builtin_amdgcn_readfirstlane(sp.route.tiles.rows[m]));
     if (type == kTaskGemm1) {
       gemm_map_tile_bf16<kLayNT, kEpiSwigluGrad>(sp.g1, m, idx, tall, smem);
       if (scope < 0) scope = sched_chain_scope(sp, q, s_box, wave);

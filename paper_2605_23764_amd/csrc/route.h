@@ -27,9 +27,10 @@ struct RouteParams {
   int T, E, E_local, expert_base, k;
   int n_sub;     // ceil(T / kSub) histogram rows
   int n_groups;  // ceil(T / kChunk) rank groups
-  int BM;        // M-tile row capacity
+  int BM;        // M-tile row capacity of the plain wide shape
+  int wide_max;  // rows a single wide M tile can take (>= BM: the bf16 kernels feed one more row block per wave row from registers)
   int tall;      // row capacity of a tall M tile (0 = the kernels have no tall shape)
-  int granule;   // an expert's tiles are equal multiples of this (last one takes the remainder)
+  int granule;   // an expert's rows are dealt to its tiles in units of this many rows
 };
 
 // Monotone map float -> uint32 (larger float = larger key); -0.0 and NaN are
@@ -206,19 +207,29 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
   return v;
 }
 
-// Tiling of one expert with c rows: n tiles of `per` rows (the last takes the
-// remainder).  Wide tiles hold up to BM rows; an expert with BM < c <= tall rows
-// (tall = 0: never) is covered by ONE tall tile, so its weights are fetched once
-// instead of once per wide tile.  Larger experts stay with wide tiles: with many
-// rows the kernel is MFMA-bound and the wide shape moves fewer operand bytes per
-// MFMA (measured: tall tiles for 1000-row experts cost 15-20 %).
-struct ExpertTiling { int n, per; bool is_tall; };
-__device__ __forceinline__ ExpertTiling expert_tiling(int c, int BM, int granule, int tall) {
+// Tiling of one expert with c rows.  A wide tile holds up to wide_max rows; an expert with
+// wide_max < c <= tall rows (tall = 0: never) is covered by ONE tall tile, so its weights are fetched once
+// instead of once per wide tile.  Larger experts are split into the fewest wide tiles, n = ceil(c / wide_max),
+// and the expert's rows are dealt to them in units of `granule` rows as evenly as possible (the first `extra`
+// tiles take one unit more; the last tile takes what is left).  The granule of the bf16 kernels is 64: both
+// wave rows of a tile then get the same number of 32-row MFMA blocks.  With many rows per expert the kernel is
+// MFMA-bound and the wide shape moves fewer operand bytes per MFMA (measured: tall tiles for 1000-row
+// experts cost 15-20 %).
+struct ExpertTiling { int n, base, extra, granule; bool is_tall; };
+__device__ __forceinline__ ExpertTiling expert_tiling(int c, int wide_max, int granule, int tall) {
   ExpertTiling t;
-  t.is_tall = c > BM && c <= tall;
-  t.n = t.is_tall ? 1 : (c + BM - 1) / BM;
-  t.per = t.n ? (((c + t.n - 1) / t.n + granule - 1) / granule) * granule : 0;
+  t.is_tall = c > wide_max && c <= tall;
+  t.n = t.is_tall ? 1 : (c + wide_max - 1) / wide_max;
+  const int units = (c + granule - 1) / granule;
+  t.base = t.n ? units / t.n : 0;
+  t.extra = t.n ? units % t.n : 0;
+  t.granule = granule;
   return t;
+}
+// First row (relative to the expert's segment) and rows of tile i.
+__device__ __forceinline__ int tile_first_row(const ExpertTiling& t, int i) { return t.granule * (i * t.base + min(i, t.extra)); }
+__device__ __forceinline__ int tile_row_count(const ExpertTiling& t, int i, int c) {
+  return min(t.granule * (t.base + (i < t.extra ? 1 : 0)), c - tile_first_row(t, i));
 }
 
 // Rows per expert -> counts, offsets (both optional outputs) and the M-tile map, by
@@ -229,13 +240,13 @@ __device__ __forceinline__ ExpertTiling expert_tiling(int c, int BM, int granule
 // share a slot; the left-over single wide tiles follow, in expert order, and pair
 // up with each other.  Consumers deal slot j to XCD j % 8 and run its two tiles side
 // by side on neighbouring CUs.
-__device__ __forceinline__ void build_tile_map(int E_local, const int32_t* cnt, int BM, int granule, int tall,
+__device__ __forceinline__ void build_tile_map(int E_local, const int32_t* cnt, int wide_max, int granule, int tall,
                                                int32_t* counts, int32_t* offsets, const TileMap& tiles) {
   const int lane = lane_id();
   int total_slots = 0;   // slots that are not made of left-over singles
   for (int e0 = 0; e0 < E_local; e0 += kWave) {
     const int e = e0 + lane;
-    const ExpertTiling t = expert_tiling(e < E_local ? cnt[e] : 0, BM, granule, tall);
+    const ExpertTiling t = expert_tiling(e < E_local ? cnt[e] : 0, wide_max, granule, tall);
     const int incl = wave_incl_scan(t.is_tall ? t.n : (t.n >> 1), lane);
     total_slots += __shfl(incl, kWave - 1, kWave);
   }
@@ -244,7 +255,7 @@ __device__ __forceinline__ void build_tile_map(int E_local, const int32_t* cnt, 
     const int e = e0 + lane;
     const int c = e < E_local ? cnt[e] : 0;
     max_rows = max(max_rows, c);
-    const ExpertTiling t = expert_tiling(c, BM, granule, tall);
+    const ExpertTiling t = expert_tiling(c, wide_max, granule, tall);
     const int ns = t.is_tall ? t.n : (t.n >> 1);          // slots
     const int n1 = t.is_tall ? 0 : (t.n & 1);             // left-over single
     const int row_incl = wave_incl_scan(c, lane);
@@ -265,8 +276,8 @@ __device__ __forceinline__ void build_tile_map(int E_local, const int32_t* cnt, 
           idx = i < 2 * ns ? 2 * sbase + i : 2 * total_slots + obase;
         }
         tiles.expert[idx] = e;
-        tiles.row0[idx] = off + i * t.per;
-        tiles.rows[idx] = min(t.per, c - i * t.per);
+        tiles.row0[idx] = off + tile_first_row(t, i);
+        tiles.rows[idx] = tile_row_count(t, i, c);
       }
     }
     row_run += __shfl(row_incl, kWave - 1, kWave);
@@ -317,7 +328,7 @@ __device__ __forceinline__ void scan_all(const RouteParams& p, int32_t* s_cnt, i
     s_cnt[e] = sum;
   }
   __syncthreads();
-  if (wave == 0) build_tile_map(p.E_local, s_cnt, p.BM, p.granule, p.tall, p.counts, p.offsets, p.tiles);
+  if (wave == 0) build_tile_map(p.E_local, s_cnt, p.wide_max, p.granule, p.tall, p.counts, p.offsets, p.tiles);
 }
 
 constexpr int kRankLdsWords = 4 * kMaxE;   // LDS words rank_chunk needs per wave
@@ -421,10 +432,10 @@ static_assert(kScanRankWaves * kRankLdsWords >= (kScanRankWaves + 1) * kMaxE + 2
 // M-tile map from the rows per expert alone (the backward rebuilds it from the
 // saved counts instead of keeping the forward's workspace alive).
 // Also zeroes `n_zero` words at `zero` (counters the kernels that follow draw tickets from).
-__global__ __launch_bounds__(kWave) void tile_map_kernel(const int32_t* counts, int E_local, int BM, int granule,
+__global__ __launch_bounds__(kWave) void tile_map_kernel(const int32_t* counts, int E_local, int wide_max, int granule,
                                                          int tall, TileMap tiles, uint32_t* zero, int n_zero) {
   for (int i = threadIdx.x; i < n_zero; i += kWave) zero[i] = 0;
-  build_tile_map(E_local, counts, BM, granule, tall, nullptr, nullptr, tiles);
+  build_tile_map(E_local, counts, wide_max, granule, tall, nullptr, nullptr, tiles);
 }
 
 }  // namespace moe

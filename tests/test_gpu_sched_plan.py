@@ -18,8 +18,9 @@ pytestmark = pytest.mark.gpu
 
 
 def crafted_case():
-    """8 local experts with chosen row counts: empty, tall (257..384), split into siblings, tiny, exactly 256."""
-    counts = [0, 300, 700, 40, 256, 257, 1, 130]
+    """8 local experts with chosen row counts: empty, one wide tile with the register-fed block (257..320 rows),
+    tall (321..384), split into siblings, tiny, exactly 256."""
+    counts = [0, 300, 700, 40, 256, 257, 1, 350]
     cfg = MoeConfig("plan_crafted", sum(counts), 512, 320, 8, 8, 0, 1, "bf16", 91)
     inp = make_inputs(cfg, with_dy=True)
     owner = np.repeat(np.arange(8), counts)
@@ -71,9 +72,10 @@ def test_device_built_schedule(case):
     print(f"schedule check {case}", flush=True)
     (plan_f, lay_f), (plan_b, lay_b) = run_both(cfg, inp, keep_xp)
     if case != "c4":
-        # the tile map behind the plan: tall tile for 257 and 300 rows, three siblings for 700, nothing for 0 rows
+        # the tile map behind the plan: one tile each for 257, 300 (wide) and 350 rows (tall), three siblings for
+        # 700, nothing for 0 rows
         got_rows = sorted(int(r) for r in plan_f.rows if r > 0)
-        assert got_rows == sorted([300, 40, 256, 257, 1, 130, 256, 256, 188]), got_rows
+        assert got_rows == sorted([300, 40, 256, 257, 1, 350, 256, 256, 188]), got_rows
     for plan, lay, backward in ((plan_f, lay_f, False), (plan_b, lay_b, True)):
         exp = expectations(cfg, plan, lay, backward, keep_xp)
         check_plan(plan, exp)
