@@ -38,7 +38,7 @@ inline long r_max(const MoeShape& s) { return (long)s.T * (s.k < s.E_local ? s.k
 inline int n_sub(const MoeShape& s) { return (s.T + kSub - 1) / kSub; }
 inline int n_groups(const MoeShape& s) { return (s.T + kChunk - 1) / kChunk; }
 // pair slots of the tile map: a tall tile (> BM rows) takes two entries, a wide tile of a split expert has > BM/2 rows
-inline long max_mtiles(const MoeShape& s) { return 2 * (r_max(s) / tile_bm(s)) + 2 * s.E_local + 2; }
+inline long max_mtiles(const MoeShape& s) { return 2 * (r_max(s) / tile_bm(s)) + 2 * s.E_local + kMapSlack; }
 inline int tile_tall(const MoeShape& s) { return s.dtype == MOE_BF16 ? kTallRows : 0; }
 inline int tile_wide_max(const MoeShape& s) { return s.dtype == MOE_BF16 ? kWideRows : kFBM; }
 inline int gemm1_ntiles(const MoeShape& s) { return s.dtype == MOE_BF16 ? (s.I + kBN / 2 - 1) / (kBN / 2) : s.I / kFBN; }

@@ -249,7 +249,7 @@ __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
         const int m0 = 2 * (q + kNumXcd * j);
         const int rows0 = sp.route.tiles.rows[m0];
         const bool tall = rows0 > kTallAbove;
-        const int n_sib = tall ? 1 : ((m0 + 1 < n_mtiles && sp.route.tiles.rows[m0 + 1] > 0) ? 2 : 1);
+        const int n_sib = rows0 <= 0 ? 0 : tall ? 1 : ((m0 + 1 < n_mtiles && sp.route.tiles.rows[m0 + 1] > 0) ? 2 : 1);   // 0: empty slot
         const int n_nt = tall ? (sp.g1.N + kTallCols1 - 1) / kTallCols1 : nN1;
         const int parts0 = parts_of(m0), parts1 = n_sib > 1 ? parts_of(m0 + 1) : 0;
         for (int i = lane; i < n_nt * n_sib; i += kWave) {
@@ -262,7 +262,7 @@ __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
       if (j >= kGemm2Lag) {
         const int m0 = 2 * (q + kNumXcd * (j - kGemm2Lag));
         const bool tall = sp.route.tiles.rows[m0] > kTallAbove;
-        const int n_sib = tall ? 1 : ((m0 + 1 < n_mtiles && sp.route.tiles.rows[m0 + 1] > 0) ? 2 : 1);
+        const int n_sib = sp.route.tiles.rows[m0] <= 0 ? 0 : tall ? 1 : ((m0 + 1 < n_mtiles && sp.route.tiles.rows[m0 + 1] > 0) ? 2 : 1);
         const int n_nt = tall ? (sp.g2.N + 127) / 128 : nN2;
         const int g1_tiles = tall ? (sp.g1.N + kTallCols1 - 1) / kTallCols1 : nN1;   // GEMM-1 tiles that complete a row block of A
         for (int i = lane; i < n_nt * n_sib; i += kWave) {

@@ -237,22 +237,76 @@ __device__ __forceinline__ int tile_row_count(const ExpertTiling& t, int i, int 
 //
 // Order of the map: it is a list of pair slots, slot j = entries 2j, 2j+1.  A tall
 // tile owns a slot (its second entry has 0 rows); wide sibling tiles of one expert
-// share a slot; the left-over single wide tiles follow, in expert order, and pair
-// up with each other.  Consumers deal slot j to XCD j % 8 and run its two tiles side
-// by side on neighbouring CUs.
+// share a slot; the left-over single wide tiles follow and pair up with each other.
+// Consumers deal slot j to XCD j % 8 and run its two tiles side by side on neighbouring CUs.
+//
+// Singles (at most one per expert) decide how even the XCDs' shares are when every expert is
+// about one tile (tiles of 257..320 rows cost a fifth more than tiles of up to 256).  With
+// balance (the kernels that use it accept empty entries anywhere in the map) they are ranked by
+// cost and dealt to the XCDs boustrophedon, continuing the round-robin of the slots before them;
+// inside an XCD consecutive singles share a slot, and every other slot swaps its halves, so that
+// the CUs that always take a slot's first tile do not always take the costlier one.  Slots and
+// halves that stay empty are marked with 0 rows.  Without balance: expert order, no gaps.
+constexpr int kMapSlack = 34;   // map entries beyond 2 * tiles that the gaps can take
+__device__ __forceinline__ int single_tile_cost(int c, int wide_max, int granule, int tall) {
+  const ExpertTiling t = expert_tiling(c, wide_max, granule, tall);
+  if (t.is_tall || !(t.n & 1)) return 0;
+  const int rows = tile_row_count(t, t.n - 1, c);
+  return max((rows + 63) & ~63, 128);   // small tiles still stream the expert's whole weight panel
+}
 __device__ __forceinline__ void build_tile_map(int E_local, const int32_t* cnt, int wide_max, int granule, int tall,
                                                int32_t* counts, int32_t* offsets, const TileMap& tiles) {
   const int lane = lane_id();
+  const bool balance = tall > 0;
+  constexpr int kPasses = kMaxE / kWave;
   int total_slots = 0;   // slots that are not made of left-over singles
-  for (int e0 = 0; e0 < E_local; e0 += kWave) {
-    const int e = e0 + lane;
-    const ExpertTiling t = expert_tiling(e < E_local ? cnt[e] : 0, wide_max, granule, tall);
+  int cost[kPasses];     // this lane's experts: cost of the single tile, 0 = none
+  int n_single = 0;
+#pragma unroll
+  for (int p = 0; p < kPasses; ++p) {
+    cost[p] = 0;
+    if (p * kWave >= E_local) continue;
+    const int e = p * kWave + lane;
+    const int c = e < E_local ? cnt[e] : 0;
+    const ExpertTiling t = expert_tiling(c, wide_max, granule, tall);
+    cost[p] = single_tile_cost(c, wide_max, granule, tall);
     const int incl = wave_incl_scan(t.is_tall ? t.n : (t.n >> 1), lane);
     total_slots += __shfl(incl, kWave - 1, kWave);
+    n_single += __popcll(__ballot(cost[p] > 0));
+  }
+  // rank of each single by (cost descending, expert ascending)
+  int rank[kPasses];
+#pragma unroll
+  for (int p = 0; p < kPasses; ++p) rank[p] = 0;
+  if (balance) {
+#pragma unroll
+    for (int q = 0; q < kPasses; ++q) {
+      if (q * kWave >= E_local) break;
+      for (int l = 0; l < kWave; ++l) {
+        const int oc = __shfl(cost[q], l, kWave), oe = q * kWave + l;
+#pragma unroll
+        for (int p = 0; p < kPasses; ++p)
+          if (p * kWave < E_local) rank[p] += (oc > cost[p] || (oc == cost[p] && oc > 0 && oe < p * kWave + lane)) ? 1 : 0;
+      }
+    }
+  }
+  // singles are dealt to 8 bins (bin b = XCD (total_slots + b) % 8) in rounds of 8, every other round backwards
+  const int full = n_single >> 3, rem = n_single & 7;
+  auto bin_count = [&](int bin) { return full + (((full & 1) ? 7 - bin : bin) < rem ? 1 : 0); };
+  const int bin_slots = ((full + (rem ? 1 : 0)) + 1) >> 1;                     // slots of the fullest bin
+  const int n_entries = balance ? 2 * (total_slots + (n_single ? 8 * bin_slots : 0)) : 2 * total_slots + n_single;
+  if (balance) {
+    for (int i = 2 * total_slots + lane; i < n_entries; i += kWave) {           // entries no single will occupy
+      const int g = (i >> 1) - total_slots, bin = g & 7, m = g >> 3, half = i & 1;
+      const int in_slot = min(max(bin_count(bin) - 2 * m, 0), 2);
+      if (half >= in_slot) { tiles.expert[i] = 0; tiles.row0[i] = 0; tiles.rows[i] = 0; }
+    }
   }
   int row_run = 0, slot_run = 0, single_run = 0, max_rows = 0;
-  for (int e0 = 0; e0 < E_local; e0 += kWave) {
-    const int e = e0 + lane;
+#pragma unroll
+  for (int p = 0; p < kPasses; ++p) {
+    if (p * kWave >= E_local) break;
+    const int e = p * kWave + lane;
     const int c = e < E_local ? cnt[e] : 0;
     max_rows = max(max_rows, c);
     const ExpertTiling t = expert_tiling(c, wide_max, granule, tall);
@@ -272,8 +326,15 @@ __device__ __forceinline__ void build_tile_map(int E_local, const int32_t* cnt, 
         if (t.is_tall) {
           idx = 2 * (sbase + i);
           tiles.expert[idx + 1] = e; tiles.row0[idx + 1] = off; tiles.rows[idx + 1] = 0;   // the slot's unused half
+        } else if (i < 2 * ns) {
+          idx = 2 * sbase + i;
+        } else if (!balance) {
+          idx = 2 * total_slots + obase;
         } else {
-          idx = i < 2 * ns ? 2 * sbase + i : 2 * total_slots + obase;
+          const int r = rank[p], round = r >> 3, pos = r & 7;
+          const int bin = (round & 1) ? 7 - pos : pos, j = round, m = j >> 1;
+          const bool alone = j == bin_count(bin) - 1 && !(j & 1);
+          idx = 2 * (total_slots + bin + 8 * m) + (alone ? 0 : ((j & 1) ^ (m & 1)));
         }
         tiles.expert[idx] = e;
         tiles.row0[idx] = off + tile_first_row(t, i);
@@ -289,7 +350,7 @@ __device__ __forceinline__ void build_tile_map(int E_local, const int32_t* cnt, 
   if (lane == 0) {
     if (offsets) offsets[E_local] = row_run;
     tiles.meta[kMetaMaxRows] = max_rows;
-    tiles.meta[kMetaMTiles] = 2 * total_slots + single_run;
+    tiles.meta[kMetaMTiles] = n_entries;
     tiles.meta[kMetaRows] = row_run;
     tiles.meta[kMetaStatus] = 0;
   }
