@@ -34,19 +34,19 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 inline int elem_bytes(const MoeShape& s) { return s.dtype == MOE_BF16 ? 2 : 4; }
 inline int tile_bm(const MoeShape& s) { return s.dtype == MOE_BF16 ? kBM : kFBM; }
+inline int tile_wide_max(const MoeShape& s) { return s.dtype == MOE_BF16 ? kWideRows : kFBM; }   // rows one wide M tile can take
 inline long r_max(const MoeShape& s) { return (long)s.T * (s.k < s.E_local ? s.k : s.E_local); }
 inline int n_sub(const MoeShape& s) { return (s.T + kSub - 1) / kSub; }
 inline int n_groups(const MoeShape& s) { return (s.T + kChunk - 1) / kChunk; }
 // pair slots of the tile map: a tall tile (> BM rows) takes two entries, a wide tile of a split expert has > BM/2 rows
 inline long max_mtiles(const MoeShape& s) { return 2 * (r_max(s) / tile_bm(s)) + 2 * s.E_local + kMapSlack; }
 inline int tile_tall(const MoeShape& s) { return s.dtype == MOE_BF16 ? kTallRows : 0; }
-inline int tile_wide_max(const MoeShape& s) { return s.dtype == MOE_BF16 ? kWideRows : kFBM; }
 inline int gemm1_ntiles(const MoeShape& s) { return s.dtype == MOE_BF16 ? (s.I + kBN / 2 - 1) / (kBN / 2) : s.I / kFBN; }
 inline int gemm2_ntiles(const MoeShape& s) { return s.dtype == MOE_BF16 ? (s.H + kBN - 1) / kBN : s.H / kFBN; }
 inline long n_events(const MoeShape& s) { return kEvPerTile + 2 * max_mtiles(s); }
 inline long max_tasks_per_queue(const MoeShape& s) {
   const long mq = (max_mtiles(s) + kNumXcd - 1) / kNumXcd + 2;   // tiles are dealt in pairs
-  return mq * ((tile_bm(s) + kPermRows - 1) / kPermRows + gemm1_ntiles(s) + gemm2_ntiles(s) + 2);
+  return mq * ((tile_wide_max(s) + kPermRows - 1) / kPermRows + gemm1_ntiles(s) + gemm2_ntiles(s) + 2);
 }
 
 int check_shape(const MoeShape* s) {
@@ -313,9 +313,10 @@ SchedParams<BF16> sched_params(const Ctx& c, const void* x, const float* logits,
   sp.max_mtiles = (int)max_mtiles(c.s);
   sp.max_tasks_per_q = (int)max_tasks_per_queue(c.s);
   sp.n_events = (int)n_events(c.s);
-  // COMBINE tasks of 32 tokens, halved (down to 4, one per wave) while there are fewer tasks than CUs
+  // COMBINE tasks of 32 tokens, halved (down to 4, one per wave) while there are fewer than four tasks per CU:
+  // all of them become ready at the same moment, so small tasks are what balances the workers
   sp.comb_tokens = kCombineTokens;
-  while (sp.comb_tokens > 4 && (c.s.T + sp.comb_tokens - 1) / sp.comb_tokens < c.n_cu) sp.comb_tokens >>= 1;
+  while (sp.comb_tokens > 4 && (c.s.T + sp.comb_tokens - 1) / sp.comb_tokens < 4 * c.n_cu) sp.comb_tokens >>= 1;
   sp.n_comb_tasks = (c.s.T + sp.comb_tokens - 1) / sp.comb_tokens;
   sp.force_device_scope = g_force_device_scope;
   sp.spin_limit = g_spin_limit;

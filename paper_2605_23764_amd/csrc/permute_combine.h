@@ -96,7 +96,10 @@ __device__ __forceinline__ void accumulate(float (&acc)[BF16 ? 8 : 4], float w, 
 // ballot of "row >= 0", two at a time, rows and weights as wave-uniform scalars, so
 // the loads of both rows are in flight together and no per-slot branch breaks up the
 // load batches.  Each element still accumulates its slots in order j = 0..k-1.
-template <bool BF16>
+// UV = 16-byte vectors per lane per pass: 7 (4 for fp32) when a CU holds dozens of waves; a worker of the
+// persistent kernel has four waves on its CU and takes a whole 7168-element row per pass (14), i.e. up to 28
+// loads in flight per lane.  The arithmetic per element is the same for every UV.
+template <bool BF16, int UV = (BF16 ? 7 : 4)>
 __device__ __forceinline__ void combine_token(const CombineParams& p, int t) {
   const int lane = lane_id();
   int rowv = -1;
@@ -107,7 +110,7 @@ __device__ __forceinline__ void combine_token(const CombineParams& p, int t) {
   }
   const uint64_t local = __ballot(rowv >= 0);
   constexpr int EPV = BF16 ? 8 : 4;                 // elements per 16-byte vector
-  constexpr int U = BF16 ? 7 : 4;                   // vectors per lane per pass
+  constexpr int U = UV;                             // vectors per lane per pass
   const int vec_per_row = p.H / EPV;
   const size_t row_bytes = (size_t)p.H * (BF16 ? 2 : 4);
   uint4* dst = reinterpret_cast<uint4*>(static_cast<char*>(p.out) + (size_t)t * row_bytes);

@@ -59,7 +59,8 @@
 
 namespace moe {
 
-constexpr int kPermRows = 32;            // rows per PERMUTE task
+constexpr int kPermRows = 16;            // rows per PERMUTE task (four per wave): small, so that a queue's PERMUTE tasks
+                                         // spread evenly over its workers whatever their number
 constexpr int kCombineTokens = 32;       // tokens per COMBINE task (fewer when that would leave CUs without one)
 constexpr int kGemm2Lag = 1;             // GEMM-2 of tile pair j is queued behind GEMM-1 of pair j + lag
 
@@ -369,15 +370,17 @@ void persistent_forward_kernel(SchedParams<BF16> sp) {
 
   // ---- queue C: combine ----
   const uint32_t g2_total = (uint32_t)__builtin_amdgcn_readfirstlane(sp.meta[kMetaGemm2Total]);
+  bool yp_ready = false;   // every GEMM-2 tile seen and acquired: once per worker (Yp never changes afterwards)
   for (;;) {
     const int t = sched_fetch(sp.qhead, kQCombine, s_box, wave);
     if (t >= sp.n_comb_tasks) break;
     MOE_TRACE_FETCH(3, t, 0)
-    if (!sched_wait(sp, kEvGemm2, g2_total, s_box, wave)) continue;
+    if (!yp_ready && !sched_wait(sp, kEvGemm2, g2_total, s_box, wave)) continue;
+    yp_ready = true;
     MOE_TRACE_START
     const int t0 = t * sp.comb_tokens;
     for (int i = wave; i < sp.comb_tokens; i += blockDim.x / kWave)
-      if (t0 + i < sp.comb.T) combine_token<BF16>(sp.comb, t0 + i);
+      if (t0 + i < sp.comb.T) combine_token<BF16, BF16 ? 14 : 8>(sp.comb, t0 + i);
     MOE_TRACE_END(sp)
   }
 }
