@@ -62,7 +62,7 @@ typedef enum MoeMode {
 
 /*
  * Problem shape.  Limits: 1 <= k <= 16, k <= E <= 256, 1 <= E_local <= 256,
- * 0 <= expert_base, expert_base + E_local <= E, H and I multiples of 64,
+ * 0 <= expert_base, expert_base + E_local <= E, H and I multiples of 64 and at most 262144,
  * T >= 0 (T == 0 is a no-op).  dtype is the storage type of x, the weights,
  * the activations and the outputs; router logits and routing weights are
  * always fp32.  bf16 computes with fp32 accumulation (MFMA); f32 computes in

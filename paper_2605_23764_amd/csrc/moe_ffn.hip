@@ -56,7 +56,7 @@ int check_shape(const MoeShape* s) {
   if (s->k < 1 || s->k > kMaxK || s->E < s->k || s->E > kMaxE) return MOE_ERR_UNSUPPORTED_SHAPE;
   if (s->E_local < 1 || s->E_local > kMaxE || s->expert_base < 0 || s->expert_base + s->E_local > s->E)
     return MOE_ERR_UNSUPPORTED_SHAPE;
-  if (s->H % 64 || s->I % 64) return MOE_ERR_UNSUPPORTED_SHAPE;
+  if (s->H % 64 || s->I % 64 || s->H > (1 << 18) || s->I > (1 << 18)) return MOE_ERR_UNSUPPORTED_SHAPE;
   // 32-bit row*stride products inside the row movers
   if ((double)r_max(*s) * (double)(2 * s->I > s->H ? 2 * s->I : s->H) * elem_bytes(*s) > 9.0e18)
     return MOE_ERR_UNSUPPORTED_SHAPE;

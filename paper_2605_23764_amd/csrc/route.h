@@ -283,7 +283,7 @@ __device__ __forceinline__ void build_tile_map(int E_local, const int32_t* cnt, 
     for (int q = 0; q < kPasses; ++q) {
       if (q * kWave >= E_local) break;
       for (int l = 0; l < kWave; ++l) {
-        const int oc = __shfl(cost[q], l, kWave), oe = q * kWave + l;
+        const int oc = __builtin_amdgcn_readlane(cost[q], l), oe = q * kWave + l;   // l is wave-uniform
 #pragma unroll
         for (int p = 0; p < kPasses; ++p)
           if (p * kWave < E_local) rank[p] += (oc > cost[p] || (oc == cost[p] && oc > 0 && oe < p * kWave + lane)) ? 1 : 0;
