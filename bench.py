@@ -28,8 +28,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 # (FETCH_SIZE x 2.0000, WRITE_SIZE x 0.9999).  Counters cannot be read inside a timed run, so the figure of the
 # last profiled build is carried here, tagged with the hash of the kernel source it was measured on; when the
 # source has changed since, `traffic` is reported as null rather than a stale number.
-MEASURED_TRAFFIC = {"c3": {"bytes": (976169.3 * 2.0000 + 98876.0 * 0.9999) * 1024,
-                           "gemm_bf16_h_sha256_16": "unprofiled"}}
+MEASURED_TRAFFIC = {"c3": {"bytes": (976062.1 * 2.0000 + 98876.0 * 0.9999) * 1024,
+                           "gemm_bf16_h_sha256_16": "26ab8857496cce84"}}
 
 
 def gemm_source_tag():
@@ -209,12 +209,14 @@ def main():
         "mfma_ones": timed(lambda: moe.moe_probe_mfma_bf16(n_wg, n_mfma, 0, sink), 5, 2),
         "copy": timed(lambda: moe.moe_probe_copy(cp_src, cp_dst, cp_src.numel()), 10, 3),
         "read": timed(lambda: moe.moe_probe_read(cp_src, cp_src.numel(), sink), 10, 3),
+        "write": timed(lambda: moe.moe_probe_write(cp_dst, cp_dst.numel(), 0x3f803f80), 10, 3),
     }
     probe_flop = n_wg * 4 * n_mfma * 32768.0
     ceilings = {"mfma_bf16_random_operands_tflops": probe_flop / (probe_ms["mfma_random"] * 1e-3) / 1e12,
                 "mfma_bf16_constant_operands_tflops": probe_flop / (probe_ms["mfma_ones"] * 1e-3) / 1e12,
                 "copy_GBs_read_plus_write": 2.0 * cp_src.numel() / (probe_ms["copy"] * 1e-3) / 1e9,
-                "read_only_GBs": cp_src.numel() / (probe_ms["read"] * 1e-3) / 1e9}
+                "read_only_GBs": cp_src.numel() / (probe_ms["read"] * 1e-3) / 1e9,
+                "write_only_GBs": cp_src.numel() / (probe_ms["write"] * 1e-3) / 1e9}
     del cp_src, cp_dst
     R = int(saved.offsets.cpu()[-1])
     bwd_ms = None

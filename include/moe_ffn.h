@@ -210,7 +210,8 @@ int moe_ffn_debug_force_device_scope(int on);
  *              event counting finished GEMM-2 tiles
  * out[12..14] = meta word indices: number of M tiles, first of the 8 queue lengths, GEMM-2 tile total
  * out[15..22] = queues, rows per PERMUTE task, GEMM-1 N tiles, GEMM-2 N tiles, wide tile rows, tall tile rows
- *              (0: none), lag (in tile pairs) of GEMM-2 tasks behind GEMM-1 tasks, bytes per descriptor
+ *              (0: none), lag (in tile pairs, clamped to a queue's
+ *              pairs) of GEMM-2 tasks behind GEMM-1 tasks, bytes per descriptor
  * out[23]    = backward: N tiles of act_grad (the chain's first GEMM)
  * out[24]    = meta word index: workers of the last single launch that fell back to device-wide fences
  * n_out must be at least MOE_LAYOUT_WORDS.  Host-only.
@@ -304,10 +305,13 @@ int moe_microbench_swiglu_add_static_scratch(int M, int N, const void* d_x, cons
  *   not overlapping).
  * moe_probe_read: the same stream without the stores (read-only); d_sink: 4 bytes of device memory,
  *   4-byte aligned, left unchanged.
+ * moe_probe_write: the same stream without the loads (write-only): every 32-bit word of the `bytes`
+ *   (a multiple of 16) at d_dst (device, 16-byte aligned) becomes `word`.
  * All return MOE_OK, MOE_ERR_INVALID_ARG or MOE_ERR_LAUNCH. */
 int moe_probe_mfma_bf16(int n_workgroups, int mfma_per_wave, int random_operands, void* d_sink, void* stream);
 int moe_probe_copy(const void* d_src, void* d_dst, size_t bytes, void* stream);
 int moe_probe_read(const void* d_src, size_t bytes, void* d_sink, void* stream);
+int moe_probe_write(void* d_dst, size_t bytes, uint32_t word, void* stream);
 
 #ifdef __cplusplus
 }

@@ -38,7 +38,7 @@ EXPORTS = (
     "moe_status_string", "moe_ffn_workspace_bytes", "moe_ffn_forward", "moe_ffn_backward",
     "moe_ffn_last_status", "moe_ffn_debug_set_spin_limit", "moe_route", "moe_permute", "moe_grouped_gemm_swiglu", "moe_grouped_gemm",
     "moe_combine", "moe_microbench_workspace_bytes", "moe_microbench_swiglu_add", "moe_microbench_last_status",
-    "moe_probe_mfma_bf16", "moe_probe_copy", "moe_probe_read", "moe_microbench_swiglu_add_static_scratch",
+    "moe_probe_mfma_bf16", "moe_probe_copy", "moe_probe_read", "moe_probe_write", "moe_microbench_swiglu_add_static_scratch",
     "moe_ffn_debug_force_device_scope", "moe_ffn_debug_layout", "moe_dispatch_to_combine",
 )
 LAYOUT_WORDS = 25   # MOE_LAYOUT_WORDS
@@ -279,6 +279,11 @@ def moe_ffn_debug_layout(shape, backward: bool = False):
 def moe_probe_read(src, nbytes, sink, stream=None) -> None:
     _check(load_library().moe_probe_read(_ptr(src), ctypes.c_size_t(nbytes), _ptr(sink), _stream(stream)),
            "moe_probe_read")
+
+
+def moe_probe_write(dst, nbytes, word=0, stream=None) -> None:
+    _check(load_library().moe_probe_write(_ptr(dst), ctypes.c_size_t(nbytes), ctypes.c_uint32(word), _stream(stream)),
+           "moe_probe_write")
 
 
 def moe_probe_copy(src, dst, nbytes, stream=None) -> None:

@@ -485,7 +485,7 @@ int run_backward(const BwdCtx& c, const void* dy, const void* x, const void* w_g
       sp.max_tasks_per_q = (int)max_tasks_per_queue(s);
       sp.n_events = (int)n_events(s);
       sp.force_device_scope = g_force_device_scope;
-      sp.spin_limit = g_spin_limit;
+          sp.spin_limit = g_spin_limit;
       sp.timeout_status = MOE_ERR_SCHED_TIMEOUT;
       hipLaunchKernelGGL(dgrad_prepare_kernel, dim3(1), dim3(kGemmThreads), 0, c.stream, sp);
       hipLaunchKernelGGL(persistent_dgrad_kernel, dim3(grid), dim3(kGemmThreads), 0, c.stream, sp);
@@ -831,6 +831,17 @@ int moe_probe_read(const void* d_src, size_t bytes, void* d_sink, void* stream) 
   const int grid = (int)(want < (size_t)(device_cus() * 8) ? want : (size_t)(device_cus() * 8));
   hipLaunchKernelGGL(probe_read_kernel, dim3(grid), dim3(kProbeThreads), 0, static_cast<hipStream_t>(stream),
                      static_cast<const u32x4*>(d_src), n16, static_cast<uint32_t*>(d_sink));
+  return launch_status();
+}
+
+int moe_probe_write(void* d_dst, size_t bytes, uint32_t word, void* stream) {
+  if (!d_dst || bytes % 16 || (reinterpret_cast<uintptr_t>(d_dst) & 15)) return MOE_ERR_INVALID_ARG;
+  if (bytes == 0) return MOE_OK;
+  const size_t n16 = bytes / 16;
+  const size_t want = (n16 + (size_t)kProbeThreads * kProbeCopyUnroll - 1) / ((size_t)kProbeThreads * kProbeCopyUnroll);
+  const int grid = (int)(want < (size_t)(device_cus() * 8) ? want : (size_t)(device_cus() * 8));
+  hipLaunchKernelGGL(probe_write_kernel, dim3(grid), dim3(kProbeThreads), 0, static_cast<hipStream_t>(stream),
+                     static_cast<u32x4*>(d_dst), n16, word);
   return launch_status();
 }
 

@@ -62,7 +62,9 @@ namespace moe {
 constexpr int kPermRows = 16;            // rows per PERMUTE task (four per wave): small, so that a queue's PERMUTE tasks
                                          // spread evenly over its workers whatever their number
 constexpr int kCombineTokens = 32;       // tokens per COMBINE task (fewer when that would leave CUs without one)
-constexpr int kGemm2Lag = 1;             // GEMM-2 of tile pair j is queued behind GEMM-1 of pair j + lag
+constexpr int kGemm2Lag = 1 << 20;       // GEMM-2 of tile pair j is queued behind GEMM-1 of pair j + lag, clamped to the queue's pairs:
+                                         // as it stands, all GEMM-1 tiles of an XCD first (its GEMM-2 tiles fill their last round and
+                                         // find their producers long done; a lag of 1..3 pairs measured equal at T = 8192, 2 % slower at T = 4096)
 
 enum TaskType { kTaskPermute = 0, kTaskGemm1 = 1, kTaskGemm2 = 2 };
 
@@ -245,7 +247,8 @@ __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
       }
     // GEMM tiles of a slot N-tile-major with the two siblings adjacent (they stream the same weight panel
     // at the same time); a tall tile fills its slot with twice as many half-width N tiles
-    for (int j = 0; j < Pq + kGemm2Lag; ++j) {
+    const int lag = min(kGemm2Lag, max(Pq, 1));
+    for (int j = 0; j < Pq + lag; ++j) {
       if (j < Pq) {
         const int m0 = 2 * (q + kNumXcd * j);
         const int rows0 = sp.route.tiles.rows[m0];
@@ -260,8 +263,8 @@ __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
         }
         n += n_nt * n_sib;
       }
-      if (j >= kGemm2Lag) {
-        const int m0 = 2 * (q + kNumXcd * (j - kGemm2Lag));
+      if (j >= lag) {
+        const int m0 = 2 * (q + kNumXcd * (j - lag));
         const bool tall = sp.route.tiles.rows[m0] > kTallAbove;
         const int n_sib = sp.route.tiles.rows[m0] <= 0 ? 0 : tall ? 1 : ((m0 + 1 < n_mtiles && sp.route.tiles.rows[m0 + 1] > 0) ? 2 : 1);
         const int n_nt = tall ? (sp.g2.N + 127) / 128 : nN2;

@@ -86,7 +86,8 @@ def test_argument_errors_and_empty():
 
 
 def test_ceiling_probes():
-    """The copy probe is a byte-exact copy (ragged size, several grid strides); the MFMA probe runs, leaves
+    """The copy probe is a byte-exact copy (ragged size, several grid strides) and the write probe fills exactly
+    its range; the MFMA probe runs, leaves
     its sink untouched and rejects bad arguments."""
     for nbytes in (0, 16, 16 * 1000 + 16, 64 * 1024 * 1024 + 48):
         src = torch.randint(0, 255, (nbytes + 16,), dtype=torch.uint8, device="cuda")
@@ -94,6 +95,10 @@ def test_ceiling_probes():
         moe.moe_probe_copy(src, dst, nbytes)
         torch.cuda.synchronize()
         assert torch.equal(dst[:nbytes], src[:nbytes]) and int(dst[nbytes:].sum()) == 0
+        moe.moe_probe_write(dst, nbytes, 0x01020304)
+        torch.cuda.synchronize()
+        want = torch.tensor([4, 3, 2, 1], dtype=torch.uint8, device="cuda").repeat(nbytes // 4)
+        assert torch.equal(dst[:nbytes], want) and int(dst[nbytes:].sum()) == 0
     sink = torch.full((1,), 3.0, dtype=torch.float32, device="cuda")
     for rnd in (0, 1):
         moe.moe_probe_mfma_bf16(64, 64, rnd, sink)
