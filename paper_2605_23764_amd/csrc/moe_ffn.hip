@@ -845,6 +845,19 @@ int moe_probe_write(void* d_dst, size_t bytes, uint32_t word, void* stream) {
   return launch_status();
 }
 
+#if defined(MOE_SCHED_TRACE)
+// Tracing variant only: reads (reset == 0, out: 16 words on the host) or clears the cycle counters of the
+// register-stationary weight-gradient kernel.
+int moe_trace_wgrad_cycles(unsigned long long* out, int reset) {
+  if (reset) {
+    const unsigned long long z[16] = {0};
+    return hipMemcpyToSymbol(HIP_SYMBOL(g_wgrad_cycles), z, sizeof(z)) == hipSuccess ? MOE_OK : MOE_ERR_LAUNCH;
+  }
+  if (!out) return MOE_ERR_INVALID_ARG;
+  return hipMemcpyFromSymbol(out, HIP_SYMBOL(g_wgrad_cycles), 16 * sizeof(unsigned long long)) == hipSuccess ? MOE_OK : MOE_ERR_LAUNCH;
+}
+#endif
+
 int moe_microbench_last_status(const void* d_workspace) {
   if (!d_workspace) return MOE_ERR_INVALID_ARG;
   uint32_t word = 0;

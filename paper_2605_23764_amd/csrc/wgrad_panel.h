@@ -26,6 +26,15 @@
 
 namespace moe {
 
+// Tracing variant only (-DMOE_SCHED_TRACE): shader-clock cycles that waves 0 and 5 of every workgroup spend per
+// phase of the tile sweep, summed over all items.  Per wave 8 words: vmcnt wait, barrier, next request (the three
+// steps of an entry hand-over), everything between two hand-overs (16 MFMAs and their operand reads), epilogues,
+// number of hand-overs, number of tiles, unused.
+#if defined(MOE_SCHED_TRACE)
+__device__ unsigned long long g_wgrad_cycles[16];
+#define MOE_WG_CLOCK() ((long long)__builtin_amdgcn_s_memtime())
+#endif
+
 constexpr int kWpM = 256;                          // output rows per panel
 constexpr int kWpN = 128;                          // output columns per tile
 constexpr int kWpBK = 64;                          // k-rows per entry
@@ -198,6 +207,8 @@ __device__ __forceinline__ void wp_item(const WpCtx& t, int row0, char* smem) {
             }
             xa[kc * 4 + ks] = __builtin_bit_cast(bf16x8, v);
           }
+        // the next hand-over lets the other waves request into this slot: the panel has to be in registers first
+        wait_lgkmcnt0();
       }
       entry_done();
     }
@@ -240,6 +251,10 @@ __device__ __forceinline__ void wp_item(const WpCtx& t, int row0, char* smem) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) read_one(cur, slot, 0, j);
   }
+#if defined(MOE_SCHED_TRACE)
+  long long cy[6] = {0, 0, 0, 0, 0, 0};
+  long long c_prev = MOE_WG_CLOCK();
+#endif
 #pragma unroll 1
   for (int tile = 0; tile < t.NT; ++tile) {
 #pragma unroll
@@ -250,7 +265,18 @@ __device__ __forceinline__ void wp_item(const WpCtx& t, int row0, char* smem) {
       const bool more = g < n_entries;
       if (more) {
         wait_lgkmcnt0();                   // this wave holds everything it needs from the entry it leaves
+#if defined(MOE_SCHED_TRACE)
+        const long long c0 = MOE_WG_CLOCK();
+        wp_wait_entry(g, n_entries, epi_mask);
+        const long long c1 = MOE_WG_CLOCK();
+        __builtin_amdgcn_s_barrier();
+        const long long c2 = MOE_WG_CLOCK();
+        if (g + kWpAhead < n_entries) wp_issue_entry<KC>(t, g + kWpAhead);
+        const long long c3 = MOE_WG_CLOCK();
+        cy[0] += c1 - c0; cy[1] += c2 - c1; cy[2] += c3 - c2; cy[3] += c0 - c_prev; cy[5] += 1; c_prev = c3;
+#else
         next_entry();
+#endif
       }
       slice(xa[kc * 4 + 3], false, more, slot, 0);
     }
@@ -267,10 +293,20 @@ __device__ __forceinline__ void wp_item(const WpCtx& t, int row0, char* smem) {
         }
       wp_store_block(region, pk, c_row + tile * kWpN, t.ldc);
     }
+#if defined(MOE_SCHED_TRACE)
+    { const long long ce = MOE_WG_CLOCK(); cy[4] += ce - c_prev; c_prev = ce; }
+#endif
     epi_mask |= 1u;
   }
   wait_lgkmcnt0();
   __builtin_amdgcn_s_barrier();            // ring and staging space are quiet before the next item's first loads
+#if defined(MOE_SCHED_TRACE)
+  if (lane == 0 && (wm == 0 || wm == 5)) {
+    unsigned long long* d = g_wgrad_cycles + (wm == 0 ? 0 : 8);
+    for (int i = 0; i < 6; ++i) atomicAdd(d + i, (unsigned long long)cy[i]);
+    atomicAdd(d + 6, (unsigned long long)t.NT);
+  }
+#endif
 }
 
 // Launch condition: p.M % 256 == 0, p.N % 128 == 0, (p.N / 128) % n_split == 0.  Experts with more than

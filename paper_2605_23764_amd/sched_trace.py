@@ -2,6 +2,7 @@
 
     python -m paper_2605_23764_amd.sched_trace --build            # on the build host: compile the tracing variant
     python -m paper_2605_23764_amd.sched_trace --workload c3      # on the GPU: run it and print the summary
+    python -m paper_2605_23764_amd.sched_trace --workload c3 --wgrad   # cycle counts of the weight-gradient kernel
 
 The tracing variant of the library (-DMOE_SCHED_TRACE, libmoe_ffn_trace.so next to the normal one) makes every
 worker record, per task, when it drew the ticket, when the task's dependency was satisfied and when the task
@@ -9,6 +10,11 @@ ended (100 MHz device clock), in a buffer behind the task tables of the workspac
 single-launch forwards, reads the buffer of the last one back and prints: per task type the first ticket, the
 first start, the last end and the mean wait / run time; per XCD the span of its GEMM tiles; the idle time per
 worker inside the GEMM phase; and the tail between the last GEMM-2 tile and the end of COMBINE.
+
+With --wgrad it runs the backward instead and prints where the register-stationary weight-gradient kernel (paper
+Section 2.2, Figure 2b: w2_grad, w1_grad) spends its shader-clock cycles: per entry hand-over (wait for the operand
+loads, workgroup barrier, address arithmetic and issue of the next request), between two hand-overs (16 MFMAs per
+wave with their operand reads) and per tile epilogue, for wave 0 and wave 5 of every workgroup.
 """
 from __future__ import annotations
 
@@ -37,6 +43,7 @@ def main():
     ap.add_argument("--build", action="store_true")
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4"])
     ap.add_argument("--no-permuted-copy", action="store_true", help="MoeSaved.Xp = NULL: GEMM-1 gathers, no PERMUTE tasks")
+    ap.add_argument("--wgrad", action="store_true", help="cycle counts of the weight-gradient kernel over 5 backward passes")
     args = ap.parse_args()
     if args.build:
         print(build_trace_library())
@@ -57,6 +64,8 @@ def main():
     moe.binding._LIB = lib            # the binding's functions now call the tracing variant
 
     cfg = CONFIGS[args.workload]
+    if args.wgrad:
+        return wgrad_cycles(lib, moe, cfg, make_inputs(cfg, with_dy=True), args)
     inp = make_inputs(cfg)
     tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
     shape = moe.make_shape(cfg.T, cfg.H, cfg.I, cfg.E, cfg.E_local, cfg.expert_base, cfg.k, tdt)
@@ -110,6 +119,47 @@ def main():
     if len(p):
         g1 = rec[rec["kind"] == 1]
         print(f"head: last PERMUTE ends {us(p['te'].max()):.1f}, first GEMM-1 tile starts {us(g1['ts'].min()):.1f} us")
+
+
+def wgrad_cycles(lib, moe, cfg, inp, args):
+    import torch
+    tdt = torch.bfloat16
+    assert cfg.dtype == "bf16", "the register-stationary kernel is the bf16 path"
+    shape = moe.make_shape(cfg.T, cfg.H, cfg.I, cfg.E, cfg.E_local, cfg.expert_base, cfg.k, tdt)
+    dev = {n: torch.from_numpy(inp[n]).cuda() for n in ("x", "logits", "w_gate_up", "w_down", "dy")}
+    for n in ("x", "w_gate_up", "w_down", "dy"):
+        dev[n] = dev[n].to(tdt)
+    saved = moe.alloc_saved(shape, store_h1=True, keep_xp=not args.no_permuted_copy)
+    ws, wsb = moe.alloc_workspace(shape), moe.alloc_workspace(shape, backward=True)
+    out = torch.empty(cfg.T, cfg.H, dtype=tdt, device="cuda")
+    dx, dw1, dw2 = torch.empty_like(dev["dy"]), torch.empty_like(dev["w_gate_up"]), torch.empty_like(dev["w_down"])
+    dtw = torch.empty(cfg.T, cfg.k, dtype=torch.float32, device="cuda")
+    moe.moe_ffn_forward(shape, dev["x"], dev["logits"], dev["w_gate_up"], dev["w_down"], out, saved, ws, moe.MODE_SERIALIZED)
+    bwd = lambda: moe.moe_ffn_backward(shape, dev["dy"], dev["x"], dev["w_gate_up"], dev["w_down"], saved, dx, dw1, dw2, dtw,
+                                       wsb, moe.MODE_SERIALIZED)
+    for _ in range(3):
+        bwd()
+    torch.cuda.synchronize()
+    lib.moe_trace_wgrad_cycles.restype = ctypes.c_int
+    lib.moe_trace_wgrad_cycles.argtypes = [ctypes.c_void_p, ctypes.c_int]
+    assert lib.moe_trace_wgrad_cycles(None, 1) == 0
+    n = 5
+    for _ in range(n):
+        bwd()
+    torch.cuda.synchronize()
+    buf = (ctypes.c_ulonglong * 16)()
+    assert lib.moe_trace_wgrad_cycles(buf, 0) == 0
+    v = list(buf)
+    print(f"workload {cfg.name}: register-stationary weight-gradient kernel, w2_grad + w1_grad of {n} backward passes, "
+          f"shader-clock cycles (tracing variant)")
+    print("wave  hand-overs     tiles | per hand-over: wait  barrier  request | between hand-overs | epilogue per tile | cycles per tile")
+    for w, o in ((0, 0), (5, 8)):
+        ne, nt = max(v[o + 5], 1), max(v[o + 6], 1)
+        per_tile = sum(v[o:o + 5]) / nt
+        print(f"{w:4d} {v[o + 5]:11d} {v[o + 6]:9d} | {v[o] / ne:19.0f} {v[o + 1] / ne:8.0f} {v[o + 2] / ne:8.0f} | "
+              f"{v[o + 3] / ne:18.0f} | {v[o + 4] / nt:17.0f} | {per_tile:15.0f}")
+    print("a tile is 256 x 128 outputs: 64 MFMAs of 32 clocks per wave and 256 reduction rows, two waves per SIMD "
+          "(4096 clocks of matrix pipe per tile at 256 rows)")
 
 
 if __name__ == "__main__":
