@@ -305,8 +305,8 @@ int moe_microbench_swiglu_add_static_scratch(int M, int N, const void* d_x, cons
  *   not overlapping).
  * moe_probe_read: the same stream without the stores (read-only); d_sink: 4 bytes of device memory,
  *   4-byte aligned, left unchanged.
- * moe_probe_write: the same stream without the loads (write-only): every 32-bit word of the `bytes`
- *   (a multiple of 16) at d_dst (device, 16-byte aligned) becomes `word`.
+ * moe_probe_write: a write-only stream (4 KB per workgroup, plain stores: the fastest pattern found): every
+ *   32-bit word of the `bytes` (a multiple of 16, below 8 TB) at d_dst (device, 16-byte aligned) becomes `word`.
  * All return MOE_OK, MOE_ERR_INVALID_ARG or MOE_ERR_LAUNCH. */
 int moe_probe_mfma_bf16(int n_workgroups, int mfma_per_wave, int random_operands, void* d_sink, void* stream);
 int moe_probe_copy(const void* d_src, void* d_dst, size_t bytes, void* stream);

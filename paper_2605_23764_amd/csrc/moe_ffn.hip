@@ -35,6 +35,9 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 inline int elem_bytes(const MoeShape& s) { return s.dtype == MOE_BF16 ? 2 : 4; }
 inline int tile_bm(const MoeShape& s) { return s.dtype == MOE_BF16 ? kBM : kFBM; }
 inline int tile_wide_max(const MoeShape& s) { return s.dtype == MOE_BF16 ? kWideRows : kFBM; }   // rows one wide M tile can take
+// rows per PERMUTE task of the single launch: kPermRows, twice that for rows below 8 KB (a task's fixed cost, ticket
+// and trigger, is a few us: T = 4096, H = 2048 ran 2 % faster with 32-row tasks, H = 7168 the same with 16 or 32)
+inline int perm_task_rows(const MoeShape& s) { return (size_t)s.H * elem_bytes(s) >= 8192 ? kPermRows : 2 * kPermRows; }
 inline long r_max(const MoeShape& s) { return (long)s.T * (s.k < s.E_local ? s.k : s.E_local); }
 inline int n_sub(const MoeShape& s) { return (s.T + kSub - 1) / kSub; }
 inline int n_groups(const MoeShape& s) { return (s.T + kChunk - 1) / kChunk; }
@@ -317,6 +320,7 @@ SchedParams<BF16> sched_params(const Ctx& c, const void* x, const float* logits,
   // all of them become ready at the same moment, so small tasks are what balances the workers
   sp.comb_tokens = kCombineTokens;
   while (sp.comb_tokens > 4 && (c.s.T + sp.comb_tokens - 1) / sp.comb_tokens < 4 * c.n_cu) sp.comb_tokens >>= 1;
+  sp.perm_rows = perm_task_rows(c.s);
   sp.n_comb_tasks = (c.s.T + sp.comb_tokens - 1) / sp.comb_tokens;
   sp.force_device_scope = g_force_device_scope;
   sp.spin_limit = g_spin_limit;
@@ -485,7 +489,8 @@ int run_backward(const BwdCtx& c, const void* dy, const void* x, const void* w_g
       sp.max_tasks_per_q = (int)max_tasks_per_queue(s);
       sp.n_events = (int)n_events(s);
       sp.force_device_scope = g_force_device_scope;
-          sp.spin_limit = g_spin_limit;
+      sp.perm_rows = perm_task_rows(s);
+      sp.spin_limit = g_spin_limit;
       sp.timeout_status = MOE_ERR_SCHED_TIMEOUT;
       hipLaunchKernelGGL(dgrad_prepare_kernel, dim3(1), dim3(kGemmThreads), 0, c.stream, sp);
       hipLaunchKernelGGL(persistent_dgrad_kernel, dim3(grid), dim3(kGemmThreads), 0, c.stream, sp);
@@ -838,9 +843,9 @@ int moe_probe_write(void* d_dst, size_t bytes, uint32_t word, void* stream) {
   if (!d_dst || bytes % 16 || (reinterpret_cast<uintptr_t>(d_dst) & 15)) return MOE_ERR_INVALID_ARG;
   if (bytes == 0) return MOE_OK;
   const size_t n16 = bytes / 16;
-  const size_t want = (n16 + (size_t)kProbeThreads * kProbeCopyUnroll - 1) / ((size_t)kProbeThreads * kProbeCopyUnroll);
-  const int grid = (int)(want < (size_t)(device_cus() * 8) ? want : (size_t)(device_cus() * 8));
-  hipLaunchKernelGGL(probe_write_kernel, dim3(grid), dim3(kProbeThreads), 0, static_cast<hipStream_t>(stream),
+  const size_t grid = (n16 + kProbeThreads - 1) / kProbeThreads;
+  if (grid > 0x7fffffffu) return MOE_ERR_INVALID_ARG;   // 8 TB
+  hipLaunchKernelGGL(probe_write_kernel, dim3((unsigned)grid), dim3(kProbeThreads), 0, static_cast<hipStream_t>(stream),
                      static_cast<u32x4*>(d_dst), n16, word);
   return launch_status();
 }
@@ -892,7 +897,7 @@ int moe_ffn_debug_layout(const MoeShape* shape, int backward, int64_t* out, int 
   }
   v[7] = max_mtiles(*shape); v[8] = max_tasks_per_queue(*shape); v[9] = n_events(*shape);
   v[10] = kEvPerTile; v[11] = kEvGemm2; v[12] = kMetaMTiles; v[13] = kMetaQueueCount0; v[14] = kMetaGemm2Total;
-  v[15] = kNumXcd; v[16] = kPermRows; v[17] = gemm1_ntiles(*shape); v[18] = gemm2_ntiles(*shape);
+  v[15] = kNumXcd; v[16] = perm_task_rows(*shape); v[17] = gemm1_ntiles(*shape); v[18] = gemm2_ntiles(*shape);
   v[19] = tile_wide_max(*shape); v[20] = tile_tall(*shape); v[21] = kGemm2Lag; v[22] = (int64_t)sizeof(TaskDesc);
   v[23] = backward ? (shape->dtype == MOE_BF16 ? (shape->I + kBN - 1) / kBN : shape->I / kFBN) : 0;   // act_grad N tiles
   v[24] = kMetaFallbackWorkers;

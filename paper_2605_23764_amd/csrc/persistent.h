@@ -59,7 +59,7 @@
 
 namespace moe {
 
-constexpr int kPermRows = 16;            // rows per PERMUTE task (four per wave): small, so that a queue's PERMUTE tasks
+constexpr int kPermRows = 16;            // least rows per PERMUTE task (four per wave): small, so that a queue's PERMUTE tasks
                                          // spread evenly over its workers whatever their number
 constexpr int kCombineTokens = 32;       // tokens per COMBINE task (fewer when that would leave CUs without one)
 constexpr int kGemm2Lag = 1 << 20;       // GEMM-2 of tile pair j is queued behind GEMM-1 of pair j + lag, clamped to the queue's pairs:
@@ -102,6 +102,7 @@ struct SchedParams {
   int n_events;
   int n_comb_tasks;
   int comb_tokens;         // tokens per COMBINE task
+  int perm_rows;           // rows per PERMUTE task
   int no_permute;          // nobody needs Xp: GEMM-1 gathers its rows from x through token_of
   int force_device_scope;  // test hook: behave as if a worker had reported a foreign XCD
   uint32_t spin_limit;     // polls before a wait gives up (MOE_ERR_SCHED_TIMEOUT)
@@ -228,7 +229,7 @@ __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
   const int nN1 = sp.g1.n_ntiles, nN2 = sp.g2.n_ntiles;
   // the tile map lists M tiles in pairs (siblings of one expert where possible); queue q owns pairs q, q+8, ...
   const int n_pairs = (n_mtiles + 1) >> 1;
-  auto parts_of = [&](int m) { return (sp.route.tiles.rows[m] + kPermRows - 1) / kPermRows; };
+  auto parts_of = [&](int m) { return (sp.route.tiles.rows[m] + sp.perm_rows - 1) / sp.perm_rows; };
   constexpr int kTallAbove = BF16 ? kWideRows : (1 << 30);   // a bf16 tile with more rows runs in the tall shape
   const bool permute = !(sp.no_permute || BWD);
   for (int q = wave; q < kNumXcd; q += n_waves) {
@@ -323,8 +324,8 @@ __device__ __forceinline__ void run_tile_task(const SchedParams<BF16>& sp, const
 #endif
   if (type == kTaskPermute) {
     const int row0 = sp.route.tiles.row0[m], rows = sp.route.tiles.rows[m];
-    const int r0 = row0 + idx * kPermRows;
-    permute_rows<14>(sp.perm, r0, min(r0 + kPermRows, row0 + rows), wave, blockDim.x / kWave);
+    const int r0 = row0 + idx * sp.perm_rows;
+    permute_rows<14>(sp.perm, r0, min(r0 + sp.perm_rows, row0 + rows), wave, blockDim.x / kWave);
     sched_trigger(sp, kEvPerTile + m, wave, scope);
   } else if (type == kTaskGemm1) {
     if constexpr (BF16) gemm_map_tile_bf16<kLayNN, kEpiSwiglu>(sp.g1, m, idx, tile_is_tall(__builtin_amdgcn_readfirstlane(sp.route.tiles.rows[m])), smem);

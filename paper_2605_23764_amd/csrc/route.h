@@ -240,42 +240,86 @@ __device__ __forceinline__ int tile_row_count(const ExpertTiling& t, int i, int 
 // share a slot; the left-over single wide tiles follow and pair up with each other.
 // Consumers deal slot j to XCD j % 8 and run its two tiles side by side on neighbouring CUs.
 //
-// Singles (at most one per expert) decide how even the XCDs' shares are when every expert is
-// about one tile (tiles of 257..320 rows cost a fifth more than tiles of up to 256).  With
-// balance (the kernels that use it accept empty entries anywhere in the map) they are ranked by
-// cost and dealt to the XCDs boustrophedon, continuing the round-robin of the slots before them;
-// inside an XCD consecutive singles share a slot, and every other slot swaps its halves, so that
-// the CUs that always take a slot's first tile do not always take the costlier one.  Slots and
-// halves that stay empty are marked with 0 rows.  Without balance: expert order, no gaps.
-constexpr int kMapSlack = 34;   // map entries beyond 2 * tiles that the gaps can take
-__device__ __forceinline__ int single_tile_cost(int c, int wide_max, int granule, int tall) {
-  const ExpertTiling t = expert_tiling(c, wide_max, granule, tall);
-  if (t.is_tall || !(t.n & 1)) return 0;
-  const int rows = tile_row_count(t, t.n - 1, c);
+// Singles decide how even the XCDs' shares are.  With balance (the kernels that use it accept
+// empty entries anywhere in the map):
+//   * the pair slots of the last, incomplete round of 8 are broken up, their tiles join the
+//     left-over singles (so that no XCD ends up a whole pair ahead of the others: with 27 pair
+//     slots three XCDs would hold 8 tiles and five of them 6 or 7);
+//   * all singles are ranked by cost (tiles of 257..320 rows cost a fifth more than tiles of up
+//     to 256) and dealt to the XCDs boustrophedon, continuing the round-robin of the slots before
+//     them; inside an XCD consecutive singles share a slot, and every other slot swaps its
+//     halves, so that the CUs that always take a slot's first tile do not always take the
+//     costlier one.  Slots and halves that stay empty are marked with 0 rows.
+// Without balance: expert order, no gaps.
+constexpr int kMapSlack = 34;      // map entries beyond 2 * tiles that the gaps can take
+constexpr int kMaxBrokenTiles = 14;   // tiles of at most 7 broken pair slots
+__device__ __forceinline__ int single_cost_of_rows(int rows) {
   return max((rows + 63) & ~63, 128);   // small tiles still stream the expert's whole weight panel
 }
 __device__ __forceinline__ void build_tile_map(int E_local, const int32_t* cnt, int wide_max, int granule, int tall,
                                                int32_t* counts, int32_t* offsets, const TileMap& tiles) {
+  __shared__ int32_t s_broken[3][16];   // expert, first row, rows of the tiles of broken pair slots
   const int lane = lane_id();
   const bool balance = tall > 0;
   constexpr int kPasses = kMaxE / kWave;
-  int total_slots = 0;   // slots that are not made of left-over singles
-  int cost[kPasses];     // this lane's experts: cost of the single tile, 0 = none
-  int n_single = 0;
+  // ---- per expert (lane = expert, kPasses passes): rows before it, tall slots and pair slots before it ----
+  int off[kPasses], tall_ex[kPasses], pair_ex[kPasses], single_ex[kPasses];
+  int cost[kPasses];     // cost of the expert's left-over single tile, 0 = none
+  int n_rows = 0, n_tall = 0, n_pair = 0, n_left = 0, max_rows = 0;
 #pragma unroll
   for (int p = 0; p < kPasses; ++p) {
-    cost[p] = 0;
+    off[p] = tall_ex[p] = pair_ex[p] = single_ex[p] = cost[p] = 0;
     if (p * kWave >= E_local) continue;
     const int e = p * kWave + lane;
     const int c = e < E_local ? cnt[e] : 0;
+    max_rows = max(max_rows, c);
     const ExpertTiling t = expert_tiling(c, wide_max, granule, tall);
-    cost[p] = single_tile_cost(c, wide_max, granule, tall);
-    const int incl = wave_incl_scan(t.is_tall ? t.n : (t.n >> 1), lane);
-    total_slots += __shfl(incl, kWave - 1, kWave);
-    n_single += __popcll(__ballot(cost[p] > 0));
+    const int nt = t.is_tall ? t.n : 0, np = t.is_tall ? 0 : (t.n >> 1), n1 = t.is_tall ? 0 : (t.n & 1);
+    if (n1) cost[p] = single_cost_of_rows(tile_row_count(t, t.n - 1, c));
+    const int row_incl = wave_incl_scan(c, lane), tall_incl = wave_incl_scan(nt, lane);
+    const int pair_incl = wave_incl_scan(np, lane), single_incl = wave_incl_scan(n1, lane);
+    off[p] = n_rows + row_incl - c;
+    tall_ex[p] = n_tall + tall_incl - nt;
+    pair_ex[p] = n_pair + pair_incl - np;
+    single_ex[p] = n_left + single_incl - n1;
+    n_rows += __shfl(row_incl, kWave - 1, kWave);
+    n_tall += __shfl(tall_incl, kWave - 1, kWave);
+    n_pair += __shfl(pair_incl, kWave - 1, kWave);
+    n_left += __shfl(single_incl, kWave - 1, kWave);
   }
-  // rank of each single by (cost descending, expert ascending)
-  int rank[kPasses];
+  // pair slots of the last incomplete round of 8 are broken up (the globally last ones, in expert order)
+  const int n_broken = balance ? min((n_tall + n_pair) & 7, n_pair) : 0;
+  const int pairs_kept = n_pair - n_broken;
+  const int total_slots = n_tall + pairs_kept;   // slots that are not made of singles
+  const int n_extra = 2 * n_broken;
+  const int n_single = n_left + n_extra;
+  if (n_broken) {
+#pragma unroll
+    for (int p = 0; p < kPasses; ++p) {
+      if (p * kWave >= E_local) break;
+      const int e = p * kWave + lane;
+      const int c = e < E_local ? cnt[e] : 0;
+      const ExpertTiling t = expert_tiling(c, wide_max, granule, tall);
+      const int np = t.is_tall ? 0 : (t.n >> 1);
+      for (int i = max(pairs_kept - pair_ex[p], 0); i < np; ++i)
+        for (int h = 0; h < 2; ++h) {
+          const int x = 2 * (pair_ex[p] + i - pairs_kept) + h;
+          s_broken[0][x] = e;
+          s_broken[1][x] = off[p] + tile_first_row(t, 2 * i + h);
+          s_broken[2][x] = tile_row_count(t, 2 * i + h, c);
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+  // lane x < n_extra holds broken tile x
+  const int x_expert = lane < n_extra ? s_broken[0][lane] : 0;
+  const int x_row0 = lane < n_extra ? s_broken[1][lane] : 0;
+  const int x_rows = lane < n_extra ? s_broken[2][lane] : 0;
+  const int x_cost = lane < n_extra ? single_cost_of_rows(x_rows) : 0;
+  // rank of each single by (cost descending; left-over singles in expert order, then the broken tiles)
+  int rank[kPasses], x_rank = 0;
 #pragma unroll
   for (int p = 0; p < kPasses; ++p) rank[p] = 0;
   if (balance) {
@@ -287,7 +331,15 @@ __device__ __forceinline__ void build_tile_map(int E_local, const int32_t* cnt, 
 #pragma unroll
         for (int p = 0; p < kPasses; ++p)
           if (p * kWave < E_local) rank[p] += (oc > cost[p] || (oc == cost[p] && oc > 0 && oe < p * kWave + lane)) ? 1 : 0;
+        x_rank += (oc > 0 && oc >= x_cost) ? 1 : 0;
       }
+    }
+    for (int l = 0; l < n_extra; ++l) {
+      const int oc = __builtin_amdgcn_readlane(x_cost, l);
+#pragma unroll
+      for (int p = 0; p < kPasses; ++p)
+        if (p * kWave < E_local) rank[p] += oc > cost[p] ? 1 : 0;
+      x_rank += (oc > x_cost || (oc == x_cost && l < lane)) ? 1 : 0;
     }
   }
   // singles are dealt to 8 bins (bin b = XCD (total_slots + b) % 8) in rounds of 8, every other round backwards
@@ -295,6 +347,12 @@ __device__ __forceinline__ void build_tile_map(int E_local, const int32_t* cnt, 
   auto bin_count = [&](int bin) { return full + (((full & 1) ? 7 - bin : bin) < rem ? 1 : 0); };
   const int bin_slots = ((full + (rem ? 1 : 0)) + 1) >> 1;                     // slots of the fullest bin
   const int n_entries = balance ? 2 * (total_slots + (n_single ? 8 * bin_slots : 0)) : 2 * total_slots + n_single;
+  auto single_entry = [&](int r) {
+    const int round = r >> 3, pos = r & 7;
+    const int bin = (round & 1) ? 7 - pos : pos, j = round, m = j >> 1;
+    const bool alone = j == bin_count(bin) - 1 && !(j & 1);
+    return 2 * (total_slots + bin + 8 * m) + (alone ? 0 : ((j & 1) ^ (m & 1)));
+  };
   if (balance) {
     for (int i = 2 * total_slots + lane; i < n_entries; i += kWave) {           // entries no single will occupy
       const int g = (i >> 1) - total_slots, bin = g & 7, m = g >> 3, half = i & 1;
@@ -302,56 +360,49 @@ __device__ __forceinline__ void build_tile_map(int E_local, const int32_t* cnt, 
       if (half >= in_slot) { tiles.expert[i] = 0; tiles.row0[i] = 0; tiles.rows[i] = 0; }
     }
   }
-  int row_run = 0, slot_run = 0, single_run = 0, max_rows = 0;
 #pragma unroll
   for (int p = 0; p < kPasses; ++p) {
     if (p * kWave >= E_local) break;
     const int e = p * kWave + lane;
-    const int c = e < E_local ? cnt[e] : 0;
-    max_rows = max(max_rows, c);
+    if (e >= E_local) continue;
+    const int c = cnt[e];
     const ExpertTiling t = expert_tiling(c, wide_max, granule, tall);
-    const int ns = t.is_tall ? t.n : (t.n >> 1);          // slots
-    const int n1 = t.is_tall ? 0 : (t.n & 1);             // left-over single
-    const int row_incl = wave_incl_scan(c, lane);
-    const int slot_incl = wave_incl_scan(ns, lane);
-    const int single_incl = wave_incl_scan(n1, lane);
-    const int off = row_run + row_incl - c;
-    const int sbase = slot_run + slot_incl - ns;
-    const int obase = single_run + single_incl - n1;
-    if (e < E_local) {
-      if (counts) counts[e] = c;
-      if (offsets) offsets[e] = off;
-      for (int i = 0; i < t.n; ++i) {
-        int idx;
-        if (t.is_tall) {
-          idx = 2 * (sbase + i);
-          tiles.expert[idx + 1] = e; tiles.row0[idx + 1] = off; tiles.rows[idx + 1] = 0;   // the slot's unused half
-        } else if (i < 2 * ns) {
-          idx = 2 * sbase + i;
-        } else if (!balance) {
-          idx = 2 * total_slots + obase;
-        } else {
-          const int r = rank[p], round = r >> 3, pos = r & 7;
-          const int bin = (round & 1) ? 7 - pos : pos, j = round, m = j >> 1;
-          const bool alone = j == bin_count(bin) - 1 && !(j & 1);
-          idx = 2 * (total_slots + bin + 8 * m) + (alone ? 0 : ((j & 1) ^ (m & 1)));
-        }
-        tiles.expert[idx] = e;
-        tiles.row0[idx] = off + tile_first_row(t, i);
-        tiles.rows[idx] = tile_row_count(t, i, c);
+    if (counts) counts[e] = c;
+    if (offsets) offsets[e] = off[p];
+    const int sbase = tall_ex[p] + min(pair_ex[p], pairs_kept);   // slots of the experts before this one
+    const int kept = t.is_tall ? 0 : max(min(pairs_kept - pair_ex[p], t.n >> 1), 0);
+    for (int i = 0; i < t.n; ++i) {
+      int idx;
+      if (t.is_tall) {
+        idx = 2 * (sbase + i);
+        tiles.expert[idx + 1] = e; tiles.row0[idx + 1] = off[p]; tiles.rows[idx + 1] = 0;   // the slot's unused half
+      } else if (i < 2 * kept) {
+        idx = 2 * sbase + i;
+      } else if (i < 2 * (t.n >> 1)) {
+        continue;                                             // tile of a broken pair slot: written below
+      } else if (!balance) {
+        idx = 2 * total_slots + single_ex[p];
+      } else {
+        idx = single_entry(rank[p]);
       }
+      tiles.expert[idx] = e;
+      tiles.row0[idx] = off[p] + tile_first_row(t, i);
+      tiles.rows[idx] = tile_row_count(t, i, c);
     }
-    row_run += __shfl(row_incl, kWave - 1, kWave);
-    slot_run += __shfl(slot_incl, kWave - 1, kWave);
-    single_run += __shfl(single_incl, kWave - 1, kWave);
+  }
+  if (lane < n_extra) {
+    const int idx = single_entry(x_rank);
+    tiles.expert[idx] = x_expert;
+    tiles.row0[idx] = x_row0;
+    tiles.rows[idx] = x_rows;
   }
 #pragma unroll
-  for (int off = kWave / 2; off > 0; off >>= 1) max_rows = max(max_rows, __shfl_xor(max_rows, off, kWave));
+  for (int o = kWave / 2; o > 0; o >>= 1) max_rows = max(max_rows, __shfl_xor(max_rows, o, kWave));
   if (lane == 0) {
-    if (offsets) offsets[E_local] = row_run;
+    if (offsets) offsets[E_local] = n_rows;
     tiles.meta[kMetaMaxRows] = max_rows;
     tiles.meta[kMetaMTiles] = n_entries;
-    tiles.meta[kMetaRows] = row_run;
+    tiles.meta[kMetaRows] = n_rows;
     tiles.meta[kMetaStatus] = 0;
   }
 }

@@ -17,6 +17,8 @@ class Plan:
     gemm2_total: int
     ev_per_tile: int
     max_mtiles: int
+    expert: np.ndarray = None   # local expert per M tile
+    row0: np.ndarray = None     # first row (in the permuted order) per M tile
 
 
 def decode_plan(ws: np.ndarray, lay) -> Plan:
@@ -32,7 +34,34 @@ def decode_plan(ws: np.ndarray, lay) -> Plan:
         assert 0 <= n <= max_q, (q, n)
         td = i32(lay[6] + q * max_q * lay[22], 4 * n).reshape(n, 4)
         queues.append([(int(t & 0xFF), int(t >> 8), int(m), int(d), int(th)) for t, m, d, th in td])
-    return Plan(n_m, rows, queues, int(meta[lay[14]]), lay[10], max_m)
+    return Plan(n_m, rows, queues, int(meta[lay[14]]), lay[10], max_m,
+                i32(lay[1], max_m)[:n_m].copy(), i32(lay[2], max_m)[:n_m].copy())
+
+
+def check_tile_map(plan: Plan, counts, wide_rows, tall_rows, n_queues=8):
+    """The M-tile map behind a plan: the tiles of every expert cover its rows of the permuted order exactly once,
+    in tiles of at most wide_rows rows (tall_rows for a tile that owns its pair slot), and the XCDs' shares are
+    even: slot j (entries 2j, 2j+1) belongs to XCD j % 8, and no XCD holds more than one tile more than another
+    apart from what the tall tiles (which cannot share a slot) add.  Returns tiles per XCD."""
+    counts = np.asarray(counts)
+    offsets = np.concatenate([[0], np.cumsum(counts)])
+    covered = np.zeros(int(offsets[-1]), dtype=np.int32)
+    per_xcd = [0] * n_queues
+    n_tall = 0
+    for m in range(plan.n_mtiles):
+        r = int(plan.rows[m])
+        if r <= 0:
+            continue
+        e, r0 = int(plan.expert[m]), int(plan.row0[m])
+        assert offsets[e] <= r0 and r0 + r <= offsets[e + 1], f"M tile {m}: rows {r0}..{r0 + r} outside expert {e}"
+        if r > wide_rows:
+            assert r <= tall_rows and m % 2 == 0 and int(plan.rows[m + 1]) == 0, f"M tile {m}: {r} rows need a slot of their own"
+            n_tall += 1
+        covered[r0: r0 + r] += 1
+        per_xcd[(m // 2) % n_queues] += 1
+    assert (covered == 1).all(), f"{int((covered != 1).sum())} rows are not covered exactly once"
+    assert max(per_xcd) - min(per_xcd) <= 1 + min(n_tall, 1), f"tiles per XCD {per_xcd}"
+    return per_xcd
 
 
 def expected_tiles(plan: Plan, n1_wide, n1_tall, n2_wide, n2_tall, wide_rows, perm_rows, permute):

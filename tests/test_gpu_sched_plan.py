@@ -11,7 +11,7 @@ import pytest
 import torch
 
 import paper_2605_23764_amd as moe
-from plan_check import GEMM1, GEMM2, check_plan, decode_plan, expected_tiles, simulate
+from plan_check import GEMM1, GEMM2, check_plan, check_tile_map, decode_plan, expected_tiles, simulate
 from workloads import CONFIGS, MoeConfig, make_inputs
 
 pytestmark = pytest.mark.gpu
@@ -76,7 +76,13 @@ def test_device_built_schedule(case):
         # 700, nothing for 0 rows
         got_rows = sorted(int(r) for r in plan_f.rows if r > 0)
         assert got_rows == sorted([300, 40, 256, 257, 1, 350, 256, 256, 188]), got_rows
+    if case == "c4":
+        from oracle.moe_ffn_oracle import route
+        idx, _ = route(inp["logits"], cfg.k)
+        counts = np.bincount(idx.reshape(-1), minlength=cfg.E)[cfg.expert_base: cfg.expert_base + cfg.E_local]
     for plan, lay, backward in ((plan_f, lay_f, False), (plan_b, lay_b, True)):
+        per_xcd = check_tile_map(plan, counts, lay[19], lay[20])
+        print(f"  {'backward' if backward else 'forward'}: M tiles per XCD {per_xcd}", flush=True)
         exp = expectations(cfg, plan, lay, backward, keep_xp)
         check_plan(plan, exp)
         simulate(plan, 1)

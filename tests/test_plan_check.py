@@ -62,3 +62,35 @@ def test_interpreter_reports_deadlock():
     plan.queues[0].insert(0, plan.queues[0].pop(7))    # a consumer at the head of an in-order queue with one worker
     with pytest.raises(AssertionError, match="deadlock"):
         simulate(plan, 1)
+
+
+def _map_plan(tiles):
+    """tiles: list of (expert, row0, rows) per map entry."""
+    from plan_check import Plan
+    return Plan(len(tiles), np.array([t[2] for t in tiles]), [[] for _ in range(8)], 0, 0, len(tiles),
+                np.array([t[0] for t in tiles]), np.array([t[1] for t in tiles]))
+
+
+def test_tile_map_check_accepts_a_legal_map_and_names_planted_mistakes():
+    from plan_check import check_tile_map
+    counts = [300, 700, 350]          # one wide tile, three siblings, one tall tile (wide 320, tall 384)
+    legal = [(2, 1000, 350), (2, 1000, 0),                   # slot 0: the tall tile owns it
+             (1, 300, 256), (1, 556, 256),                   # slot 1: siblings
+             (0, 0, 300), (0, 0, 0),                         # slot 2: a single
+             (1, 812, 188), (0, 0, 0)]                       # slot 3: the third sibling
+    assert check_tile_map(_map_plan(legal), counts, 320, 384) == [1, 2, 1, 1, 0, 0, 0, 0]
+    gap = list(legal); gap[6] = (1, 812, 187)                # a row nobody computes
+    with pytest.raises(AssertionError, match="not covered exactly once"):
+        check_tile_map(_map_plan(gap), counts, 320, 384)
+    twice = list(legal); twice[3] = (1, 500, 312)            # rows 500..555 in two tiles
+    with pytest.raises(AssertionError, match="not covered exactly once"):
+        check_tile_map(_map_plan(twice), counts, 320, 384)
+    stray = list(legal); stray[4] = (0, 100, 300)            # runs into the next expert's rows
+    with pytest.raises(AssertionError, match="outside expert"):
+        check_tile_map(_map_plan(stray), counts, 320, 384)
+    shared = list(legal); shared[1] = (0, 0, 300); shared[4] = (0, 0, 0)   # a tall tile must not share its slot
+    with pytest.raises(AssertionError, match="slot of their own"):
+        check_tile_map(_map_plan(shared), counts, 320, 384)
+    lopsided = [(0, 0, 256), (0, 256, 44), (1, 300, 256), (1, 556, 0)] + [(0, 0, 0)] * 12 + [(1, 556, 256), (1, 812, 188)]
+    with pytest.raises(AssertionError, match="tiles per XCD"):   # slots 0 and 8 both belong to XCD 0
+        check_tile_map(_map_plan(lopsided), [300, 700], 320, 384)
