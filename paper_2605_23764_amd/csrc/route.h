@@ -318,28 +318,26 @@ __device__ __forceinline__ void build_tile_map(int E_local, const int32_t* cnt, 
   const int x_row0 = lane < n_extra ? s_broken[1][lane] : 0;
   const int x_rows = lane < n_extra ? s_broken[2][lane] : 0;
   const int x_cost = lane < n_extra ? single_cost_of_rows(x_rows) : 0;
-  // rank of each single by (cost descending; left-over singles in expert order, then the broken tiles)
+  // rank of each single by (cost descending; left-over singles in expert order, then the broken tiles).  Costs
+  // are multiples of 64 between 128 and the wide tile's rows: per cost class one ballot per pass tells every
+  // single how many of its class come before it.
   int rank[kPasses], x_rank = 0;
 #pragma unroll
   for (int p = 0; p < kPasses; ++p) rank[p] = 0;
   if (balance) {
+    const uint64_t lt = (1ull << lane) - 1;
+    int run = 0;
+    for (int ck = single_cost_of_rows(wide_max); ck >= 128; ck -= 64) {
 #pragma unroll
-    for (int q = 0; q < kPasses; ++q) {
-      if (q * kWave >= E_local) break;
-      for (int l = 0; l < kWave; ++l) {
-        const int oc = __builtin_amdgcn_readlane(cost[q], l), oe = q * kWave + l;   // l is wave-uniform
-#pragma unroll
-        for (int p = 0; p < kPasses; ++p)
-          if (p * kWave < E_local) rank[p] += (oc > cost[p] || (oc == cost[p] && oc > 0 && oe < p * kWave + lane)) ? 1 : 0;
-        x_rank += (oc > 0 && oc >= x_cost) ? 1 : 0;
+      for (int p = 0; p < kPasses; ++p) {
+        if (p * kWave >= E_local) break;
+        const uint64_t bal = __ballot(cost[p] == ck);
+        if (cost[p] == ck) rank[p] = run + __popcll(bal & lt);
+        run += __popcll(bal);
       }
-    }
-    for (int l = 0; l < n_extra; ++l) {
-      const int oc = __builtin_amdgcn_readlane(x_cost, l);
-#pragma unroll
-      for (int p = 0; p < kPasses; ++p)
-        if (p * kWave < E_local) rank[p] += oc > cost[p] ? 1 : 0;
-      x_rank += (oc > x_cost || (oc == x_cost && l < lane)) ? 1 : 0;
+      const uint64_t bal = __ballot(x_cost == ck);
+      if (x_cost == ck) x_rank = run + __popcll(bal & lt);
+      run += __popcll(bal);
     }
   }
   // singles are dealt to 8 bins (bin b = XCD (total_slots + b) % 8) in rounds of 8, every other round backwards
