@@ -14,7 +14,9 @@
 // the B chunks of tile 0, tile 1, ...  A ring of 5 slots holds them; entry g + 4 is requested
 // as soon as the barrier of entry g has shown that the slot of entry g - 1 is free.  One
 // barrier per entry; the epilogue of a tile (through a wave-private LDS region, whole lines,
-// non-temporal) runs between two entries without any.
+// non-temporal) needs none: the packed block is parked in the region at the end of its tile and
+// read back and stored one row group per MFMA under the first slices of the next tile (the last
+// tile of an item is written out at once).
 //
 // Loads and stores of a wave retire in order behind one counter, so the wait for entry g has
 // to allow for everything issued after its loads: the loads of the following entries (2 per
@@ -153,6 +155,40 @@ __device__ __forceinline__ void wp_store_block(char* region, const u32x2 (&pk)[4
   __builtin_amdgcn_wave_barrier();
 }
 
+// The same epilogue in two parts, for a tile that is followed by another one: the packed block is parked in the
+// staging region at the end of its tile (wp_stage_write); the reads back and the eight stores are issued one per
+// MFMA during the first slices of the NEXT tile (wp_stage_read / wp_stage_store), where they cost no matrix-pipe time.
+__device__ __forceinline__ void wp_stage_write(char* region, const f32x16 (&acc)[4]) {
+  typedef __attribute__((address_space(3))) char* lds_ptr;
+  typedef __attribute__((address_space(3))) u32x2* lds_u32x2_ptr;
+  int lane = lane_id();
+  asm volatile("" : "+v"(lane));
+  const int l32 = lane & 31, lh = lane >> 5;
+  const lds_ptr base = (lds_ptr)region;
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the previous block has been read out
+  __builtin_amdgcn_wave_barrier();
+#pragma unroll
+  for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      *(lds_u32x2_ptr)(base + l32 * kEpiRowBytes + (nt * 32 + q * 8 + lh * 4) * 2) =
+          u32x2{pack_bf16(acc[nt][q * 4 + 0], acc[nt][q * 4 + 1]), pack_bf16(acc[nt][q * 4 + 2], acc[nt][q * 4 + 3])};
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+// rows it*4 .. it*4+3 of the parked block: 16 lanes x 16 bytes per row
+__device__ __forceinline__ u32x4 wp_stage_read(const char* region, int lane, int it) {
+  typedef __attribute__((address_space(3))) const char* lds_cptr_;
+  typedef __attribute__((address_space(3))) const u32x4* lds_u32x4_cptr;
+  const lds_cptr_ lp = (lds_cptr_)region + (lane >> 4) * kEpiRowBytes + (lane & 15) * 16;
+  return *(lds_u32x4_cptr)(lp + it * 4 * kEpiRowBytes);
+}
+__device__ __forceinline__ void wp_stage_store(const u32x4& v, __bf16* gdst, long ld, int lane, int it) {
+  __bf16* gp = gdst + (size_t)(lane >> 4) * ld + (lane & 15) * 8;
+  __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(gp + (size_t)(it * 4) * ld));
+}
+
 template <int KC>
 __device__ __forceinline__ void wp_item(const WpCtx& t, int row0, char* smem) {
   constexpr int KS = KC * 4;                                   // 16-wide k slices of the panel
@@ -246,6 +282,27 @@ __device__ __forceinline__ void wp_item(const WpCtx& t, int row0, char* smem) {
       for (int nt = 0; nt < 4; ++nt) { cur[nt][0] = nxt[nt][0]; cur[nt][1] = nxt[nt][1]; }
     }
   };
+  // The same slice with the parked epilogue of the previous tile riding along: MFMA m = m0 + j of the tile's first
+  // twelve reads row group m back from the staging region and stores row group m - 1 (two buffers in turn).
+  u32x4 ev[2];
+  __bf16* pend_dst = c_row;
+  auto slice_epi = [&](const bf16x8& x, bool first, int sl, int ks, int m0) {
+    bf16x8 wf[4];
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) wf[nt] = join_tr(cur[nt][0], cur[nt][1]);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], x, first ? zero : acc[j], 0, 0, 0);
+      read_one(nxt, sl, ks, 2 * j);
+      read_one(nxt, sl, ks, 2 * j + 1);
+      const int m = m0 + j;
+      if (m >= 1 && m <= 8) wp_stage_store(ev[(m - 1) & 1], pend_dst, t.ldc, lane, m - 1);
+      if (m < 8) ev[m & 1] = wp_stage_read(region, lane, m);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) { cur[nt][0] = nxt[nt][0]; cur[nt][1] = nxt[nt][1]; }
+  };
   if (g < n_entries) {
     next_entry();
 #pragma unroll
@@ -259,8 +316,13 @@ __device__ __forceinline__ void wp_item(const WpCtx& t, int row0, char* smem) {
   for (int tile = 0; tile < t.NT; ++tile) {
 #pragma unroll
     for (int kc = 0; kc < KC; ++kc) {
+      if (kc == 0 && tile > 0) {              // wave-uniform: the previous tile's block is parked
 #pragma unroll
-      for (int ks = 0; ks < 3; ++ks) slice(xa[kc * 4 + ks], kc == 0 && ks == 0, true, slot, ks + 1);
+        for (int ks = 0; ks < 3; ++ks) slice_epi(xa[kc * 4 + ks], ks == 0, slot, ks + 1, ks * 4);
+      } else {
+#pragma unroll
+        for (int ks = 0; ks < 3; ++ks) slice(xa[kc * 4 + ks], kc == 0 && ks == 0, true, slot, ks + 1);
+      }
       entry_done();
       const bool more = g < n_entries;
       if (more) {
@@ -281,7 +343,10 @@ __device__ __forceinline__ void wp_item(const WpCtx& t, int row0, char* smem) {
       slice(xa[kc * 4 + 3], false, more, slot, 0);
     }
     // epilogue: lane holds row lane%32 of each 32 x 32 block and, per register group q, 4 consecutive columns
-    {
+    if (KC > 0 && tile + 1 < t.NT) {
+      wp_stage_write(region, acc);            // read back and stored under the next tile's first MFMAs
+      pend_dst = c_row + tile * kWpN;
+    } else {
       u32x2 pk[4][4];
 #pragma unroll
       for (int nt = 0; nt < 4; ++nt)
