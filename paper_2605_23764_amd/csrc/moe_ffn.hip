@@ -319,7 +319,10 @@ SchedParams<BF16> sched_params(const Ctx& c, const void* x, const float* logits,
   // COMBINE tasks of 32 tokens, halved (down to 4, one per wave) while there are fewer than four tasks per CU:
   // all of them become ready at the same moment, so small tasks are what balances the workers
   sp.comb_tokens = kCombineTokens;
-  while (sp.comb_tokens > 4 && (c.s.T + sp.comb_tokens - 1) / sp.comb_tokens < 4 * c.n_cu) sp.comb_tokens >>= 1;
+#ifndef MOE_COMB_TASKS_PER_CU
+#define MOE_COMB_TASKS_PER_CU 4
+#endif
+  while (sp.comb_tokens > 4 && (c.s.T + sp.comb_tokens - 1) / sp.comb_tokens < MOE_COMB_TASKS_PER_CU * c.n_cu) sp.comb_tokens >>= 1;
   sp.perm_rows = perm_task_rows(c.s);
   sp.n_comb_tasks = (c.s.T + sp.comb_tokens - 1) / sp.comb_tokens;
   sp.force_device_scope = g_force_device_scope;

@@ -99,15 +99,11 @@ __device__ __forceinline__ void accumulate(float (&acc)[BF16 ? 8 : 4], float w, 
 // UV = 16-byte vectors per lane per pass: 7 (4 for fp32) when a CU holds dozens of waves; a worker of the
 // persistent kernel has four waves on its CU and takes a whole 7168-element row per pass (14), i.e. up to 28
 // loads in flight per lane.  The arithmetic per element is the same for every UV.
-template <bool BF16, int UV = (BF16 ? 7 : 4)>
-__device__ __forceinline__ void combine_token(const CombineParams& p, int t) {
+// combine_token_rows: the token's slots are already in registers (lane j: row of slot j or -1, its score), G rows
+// in flight at a time; the sum runs in slot order whatever G is, so every G gives the same bits.
+template <bool BF16, int UV, int G>
+__device__ __forceinline__ void combine_token_rows(const CombineParams& p, int t, int rowv, float wv) {
   const int lane = lane_id();
-  int rowv = -1;
-  float wv = 0.f;
-  if (lane < p.k) {
-    rowv = p.row_of[(size_t)t * p.k + lane];
-    wv = p.topk_w ? p.topk_w[(size_t)t * p.k + lane] : 1.f;
-  }
   const uint64_t local = __ballot(rowv >= 0);
   constexpr int EPV = BF16 ? 8 : 4;                 // elements per 16-byte vector
   constexpr int U = UV;                             // vectors per lane per pass
@@ -122,34 +118,33 @@ __device__ __forceinline__ void combine_token(const CombineParams& p, int t) {
       for (int x = 0; x < EPV; ++x) acc[u][x] = 0.f;
     uint64_t m = local;
     while (m != 0) {
-      const int j0 = __builtin_amdgcn_readfirstlane(__builtin_ctzll(m));
-      m &= m - 1;
-      const bool two = m != 0;
-      const int j1 = two ? __builtin_amdgcn_readfirstlane(__builtin_ctzll(m)) : j0;
-      m &= m - 1;   // no-op when m is already 0
-      const int r0 = __builtin_amdgcn_readlane(rowv, j0), r1 = __builtin_amdgcn_readlane(rowv, j1);
-      const float w0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wv), j0));
-      const float w1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wv), j1));
-      const uint4* y0p = reinterpret_cast<const uint4*>(static_cast<const char*>(p.Yp) + (size_t)r0 * row_bytes);
-      const uint4* y1p = reinterpret_cast<const uint4*>(static_cast<const char*>(p.Yp) + (size_t)r1 * row_bytes);
-      uint4 y0[U], y1[U];
+      const uint4* yp[G];
+      float w[G];
+      int n = 0;                                    // wave-uniform: rows of this round
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const bool ok = v0 + u * kWave < vec_per_row;
-        y0[u] = ok ? y0p[v0 + u * kWave] : make_uint4(0, 0, 0, 0);
+      for (int g = 0; g < G; ++g) {
+        const bool have = m != 0;
+        const int j = have ? __builtin_amdgcn_readfirstlane(__builtin_ctzll(m)) : 0;
+        if (have) { m &= m - 1; n = g + 1; }
+        const int r = __builtin_amdgcn_readlane(rowv, j);
+        w[g] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wv), j));
+        yp[g] = reinterpret_cast<const uint4*>(static_cast<const char*>(p.Yp) + (size_t)(have ? r : 0) * row_bytes);
       }
-      if (two) {
+      uint4 y[G][U];
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        if (g >= n) break;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
           const bool ok = v0 + u * kWave < vec_per_row;
-          y1[u] = ok ? y1p[v0 + u * kWave] : make_uint4(0, 0, 0, 0);
+          y[g][u] = ok ? yp[g][v0 + u * kWave] : make_uint4(0, 0, 0, 0);
         }
       }
 #pragma unroll
-      for (int u = 0; u < U; ++u) accumulate<BF16>(acc[u], w0, y0[u]);
-      if (two) {
+      for (int g = 0; g < G; ++g) {
+        if (g >= n) break;
 #pragma unroll
-        for (int u = 0; u < U; ++u) accumulate<BF16>(acc[u], w1, y1[u]);
+        for (int u = 0; u < U; ++u) accumulate<BF16>(acc[u], w[g], y[g][u]);
       }
     }
 #pragma unroll
@@ -166,6 +161,25 @@ __device__ __forceinline__ void combine_token(const CombineParams& p, int t) {
       dst[v0 + u * kWave] = o;
     }
   }
+}
+
+// The token's slots as the lanes hold them: lane j < k the row of slot j (-1: not on this GPU) and its score.
+__device__ __forceinline__ void combine_load_slots(const CombineParams& p, int t, int& rowv, float& wv) {
+  const int lane = lane_id();
+  rowv = -1;
+  wv = 0.f;
+  if (lane < p.k) {
+    rowv = p.row_of[(size_t)t * p.k + lane];
+    wv = p.topk_w ? p.topk_w[(size_t)t * p.k + lane] : 1.f;
+  }
+}
+
+template <bool BF16, int UV = (BF16 ? 7 : 4), int G = 2>
+__device__ __forceinline__ void combine_token(const CombineParams& p, int t) {
+  int rowv;
+  float wv;
+  combine_load_slots(p, t, rowv, wv);
+  combine_token_rows<BF16, UV, G>(p, t, rowv, wv);
 }
 
 template <bool BF16>

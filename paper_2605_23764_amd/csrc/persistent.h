@@ -382,9 +382,18 @@ void persistent_forward_kernel(SchedParams<BF16> sp) {
     if (!yp_ready && !sched_wait(sp, kEvGemm2, g2_total, s_box, wave)) continue;
     yp_ready = true;
     MOE_TRACE_START
-    const int t0 = t * sp.comb_tokens;
-    for (int i = wave; i < sp.comb_tokens; i += blockDim.x / kWave)
-      if (t0 + i < sp.comb.T) combine_token<BF16, BF16 ? 14 : 8>(sp.comb, t0 + i);
+    // Four waves per CU have to hide the latency the combine kernel hides with thirty-two: a token's slots are
+    // fetched while the token before it is reduced, and up to four of its rows are in flight at once.
+    const int t0 = t * sp.comb_tokens, t1 = min(t0 + sp.comb_tokens, sp.comb.T), nw = blockDim.x / kWave;
+    int rowv, rowv_n = -1;
+    float wv, wv_n = 0.f;
+    if (t0 + wave < t1) combine_load_slots(sp.comb, t0 + wave, rowv, wv);
+    for (int tok = t0 + wave; tok < t1; tok += nw) {
+      if (tok + nw < t1) combine_load_slots(sp.comb, tok + nw, rowv_n, wv_n);
+      combine_token_rows<BF16, BF16 ? 14 : 8, 4>(sp.comb, tok, rowv, wv);
+      rowv = rowv_n;
+      wv = wv_n;
+    }
     MOE_TRACE_END(sp)
   }
 }
