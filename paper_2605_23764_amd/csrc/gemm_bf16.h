@@ -733,14 +733,36 @@ void grouped_gemm_bf16_kernel(GemmParams p) {
   const int n_pairs = (n_m + 1) >> 1;
   const int pairs_x = n_pairs > xcd ? (n_pairs - xcd + 7) >> 3 : 0;
   const int per_pair = 2 * p.n_ntiles;
-  for (int i = lw; i < pairs_x * per_pair; i += W) {
+  // The XCD's items are dealt to its W workgroups in rounds.  When the last round would leave at least half of
+  // them without an item, its items are halved: each runs as two 128-column items in the tall shape (4 x 1 waves
+  // over the same rows) on neighbouring workgroups, which takes ~0.6 of a full item instead of a whole round.
+  const int n_items = pairs_x * per_pair;
+  const int tail = n_items % W;
+  const bool split_tail = tail > 0 && 2 * tail <= W;
+  const int n_whole = split_tail ? n_items - tail : n_items;
+  constexpr int kOutCols = EPI == kEpiSwiglu ? kBN / 2 : kBN;
+  for (int i = lw; i < n_whole; i += W) {
     // the division runs on the vector ALU; pin the (uniform) results back into scalar registers
     const int pl = __builtin_amdgcn_readfirstlane(i / per_pair);
     const int rem = i - pl * per_pair;
     int mtile, ntile;
     bool tall;
-    if (!pair_work_item(p, 2 * (pl * 8 + xcd), rem, n_m, EPI == kEpiSwiglu ? kBN / 2 : kBN, mtile, ntile, tall)) continue;
+    if (!pair_work_item(p, 2 * (pl * 8 + xcd), rem, n_m, kOutCols, mtile, ntile, tall)) continue;
     gemm_map_tile_bf16<LAY, EPI>(p, mtile, ntile, tall, smem);
+  }
+  if (split_tail && lw < 2 * tail) {
+    const int i = n_whole + (lw >> 1), half = lw & 1;
+    const int pl = __builtin_amdgcn_readfirstlane(i / per_pair);
+    const int rem = i - pl * per_pair;
+    int mtile, ntile;
+    bool tall;
+    if (pair_work_item(p, 2 * (pl * 8 + xcd), rem, n_m, kOutCols, mtile, ntile, tall)) {
+      if (tall) {                                   // already a 128-column item
+        if (half == 0) gemm_tile_bf16<LAY, EPI, true>(p, mtile, ntile, smem);
+      } else if ((2 * ntile + half) * (kOutCols / 2) < p.N) {
+        gemm_tile_bf16<LAY, EPI, true>(p, mtile, 2 * ntile + half, smem);
+      }
+    }
   }
 }
 
