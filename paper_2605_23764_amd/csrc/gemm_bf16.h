@@ -430,13 +430,19 @@ __device__ __forceinline__ char* epilogue_region(char* smem, int wave) {
 
 // pk[nt][q]: this lane's 4 packed columns nt*32 + q*8 + (lane/32)*4 .. +3 of row lane%32.
 // Writes rows [0, rows_valid) x columns [0, cols_valid) of the block to gdst (row stride ld elements).
-template <int NB, bool NT = false>
+// SPLIT: the block is two half-blocks side by side (NB/2 groups of 32 columns each) that go to different places,
+// the left half to gdst, the right half to gdst2, cols_valid columns of each (SwiGLU: the gate and the up half of
+// the stored pre-activations, one LDS round trip for both).
+// All reads back from the region are issued before the first store, and the stores are predicated, not branched
+// around: one LDS latency per call instead of one per row group.
+template <int NB, bool NT = false, bool SPLIT = false>
 __device__ __forceinline__ void store_block_via_lds(char* region, const u32x2 (&pk)[NB][4], __bf16* gdst, long ld,
-                                                    int rows_valid, int cols_valid) {
+                                                    int rows_valid, int cols_valid, __bf16* gdst2 = nullptr) {
   typedef __attribute__((address_space(3))) char* lds_ptr;
   typedef __attribute__((address_space(3))) u32x2* lds_u32x2_ptr;
   typedef __attribute__((address_space(3))) const u32x4* lds_u32x4_cptr;
   constexpr int LPR = NB * 4;                           // lanes per row at 16 bytes each
+  constexpr int RPI = kWave / LPR, NIT = 32 / RPI;      // rows per access, accesses
   // The lane id passes through an empty asm so that nothing derived from it here counts as
   // loop-invariant: hoisted out of the tile loop, the per-row addresses and bounds were spilled
   // and every reload (s_waitcnt vmcnt(0)) waited for all earlier global stores as well.
@@ -452,17 +458,19 @@ __device__ __forceinline__ void store_block_via_lds(char* region, const u32x2 (&
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   const int row_l = lane / LPR, ch = lane % LPR;
-  const bool col_ok = ch * 8 < cols_valid;
-  __bf16* gp = gdst + (size_t)row_l * ld + ch * 8;
+  const int chh = SPLIT ? ch % (LPR / 2) : ch;           // 16-byte chunk inside the (half-)block
+  const bool col_ok = chh * 8 < cols_valid;
+  __bf16* gp = (SPLIT && ch >= LPR / 2 ? gdst2 : gdst) + (size_t)row_l * ld + chh * 8;
   const lds_ptr lp = base + row_l * kEpiRowBytes + ch * 16;
+  u32x4 v[NIT];
 #pragma unroll
-  for (int it = 0; it < 32 * LPR / kWave; ++it) {
-    const int row = it * (kWave / LPR) + row_l;
-    const u32x4 v = *(lds_u32x4_cptr)(lp + it * (kWave / LPR) * kEpiRowBytes);
-    if (row < rows_valid && col_ok) {
-      u32x4* dst = reinterpret_cast<u32x4*>(gp + (size_t)(it * (kWave / LPR)) * ld);
-      if (NT) __builtin_nontemporal_store(v, dst);
-      else *dst = v;
+  for (int it = 0; it < NIT; ++it) v[it] = *(lds_u32x4_cptr)(lp + it * RPI * kEpiRowBytes);
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    if (it * RPI + row_l < rows_valid && col_ok) {
+      u32x4* dst = reinterpret_cast<u32x4*>(gp + (size_t)(it * RPI) * ld);
+      if (NT) __builtin_nontemporal_store(v[it], dst);
+      else *dst = v[it];
     }
   }
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -615,7 +623,7 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
     const size_t grow = grow0 + l32;                  // this lane's row (may be past the end: never stored)
     if (EPI == kEpiSwiglu) {
       const int c0 = ntile * (S::kCols / 2) + wn * 64;   // this wave's 64 gate columns and the 64 matching up columns
-      u32x2 pa[2][4], pg[2][4], pu[2][4];
+      u32x2 pa[2][4], ph[4][4];                       // ph: the pre-activations, gate columns then up columns
 #pragma unroll
       for (int ng = 0; ng < 2; ++ng)
 #pragma unroll
@@ -628,14 +636,13 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
             a[x] = g[x] * sigmoidf_(g[x]) * u[x];
           }
           pa[ng][q] = u32x2{pack_bf16(a[0], a[1]), pack_bf16(a[2], a[3])};
-          pg[ng][q] = u32x2{pack_bf16(g[0], g[1]), pack_bf16(g[2], g[3])};
-          pu[ng][q] = u32x2{pack_bf16(u[0], u[1]), pack_bf16(u[2], u[3])};
+          ph[ng][q] = u32x2{pack_bf16(g[0], g[1]), pack_bf16(g[2], g[3])};
+          ph[ng + 2][q] = u32x2{pack_bf16(u[0], u[1]), pack_bf16(u[2], u[3])};
         }
       store_block_via_lds<2>(region, pa, p.C + grow0 * p.ldc + c0, p.ldc, rows_valid, p.N - c0);
       if (p.C2) {
         __bf16* h = p.C2 + grow0 * (size_t)(2 * p.N) + c0;
-        store_block_via_lds<2>(region, pg, h, 2 * p.N, rows_valid, p.N - c0);
-        store_block_via_lds<2>(region, pu, h + p.N, 2 * p.N, rows_valid, p.N - c0);
+        store_block_via_lds<4, false, true>(region, ph, h, 2 * p.N, rows_valid, p.N - c0, h + p.N);
       }
     } else if (EPI == kEpiSwigluGrad) {
       // SwiGLU_grad on the act_grad tile (Section 2.2, Figure 2b): the accumulators hold dA; with the saved
