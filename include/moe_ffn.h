@@ -203,7 +203,8 @@ int moe_ffn_debug_force_device_scope(int on);
  * counts, queue order is topological): byte offsets of the scheduler's tables inside the forward
  * (backward = 0) or backward (backward != 0) workspace and the constants needed to decode them.
  * out[0..6]  = offsets of: meta words, tile_expert, tile_row0, tile_rows (int32 per M tile), event counters
- *              (uint32), queue heads, task descriptors ([8 queues][max_tasks_per_queue] x {type | index << 8,
+ *              (uint32), queue heads, task descriptors ([8 queues][max_tasks_per_queue] x {type | 0x80 if the index counts
+ *              128-column halves of a wide GEMM-2 tile (a queue's halved last round) | index << 8,
  *              M tile, dependent event (-1: none), threshold}, int32 each)
  * out[7..9]  = max M tiles, max tasks per queue, number of event counters
  * out[10,11] = first per-tile event (Xp rows of M tile m ready: +m; A rows ready: + max M tiles + m), the

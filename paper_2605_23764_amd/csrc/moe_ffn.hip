@@ -49,7 +49,7 @@ inline int gemm2_ntiles(const MoeShape& s) { return s.dtype == MOE_BF16 ? (s.H +
 inline long n_events(const MoeShape& s) { return kEvPerTile + 2 * max_mtiles(s); }
 inline long max_tasks_per_queue(const MoeShape& s) {
   const long mq = (max_mtiles(s) + kNumXcd - 1) / kNumXcd + 2;   // tiles are dealt in pairs
-  return mq * ((tile_wide_max(s) + kPermRows - 1) / kPermRows + gemm1_ntiles(s) + gemm2_ntiles(s) + 2);
+  return mq * ((tile_wide_max(s) + kPermRows - 1) / kPermRows + gemm1_ntiles(s) + gemm2_ntiles(s) + 2) + kWave / 2;   // + a halved last round
 }
 
 int check_shape(const MoeShape* s) {
@@ -324,6 +324,7 @@ SchedParams<BF16> sched_params(const Ctx& c, const void* x, const float* logits,
 #endif
   while (sp.comb_tokens > 4 && (c.s.T + sp.comb_tokens - 1) / sp.comb_tokens < MOE_COMB_TASKS_PER_CU * c.n_cu) sp.comb_tokens >>= 1;
   sp.perm_rows = perm_task_rows(c.s);
+  sp.workers_per_q = gemm_grid(c) / kNumXcd;
   sp.n_comb_tasks = (c.s.T + sp.comb_tokens - 1) / sp.comb_tokens;
   sp.force_device_scope = g_force_device_scope;
   sp.spin_limit = g_spin_limit;
@@ -493,6 +494,7 @@ int run_backward(const BwdCtx& c, const void* dy, const void* x, const void* w_g
       sp.n_events = (int)n_events(s);
       sp.force_device_scope = g_force_device_scope;
       sp.perm_rows = perm_task_rows(s);
+      sp.workers_per_q = grid / kNumXcd;
       sp.spin_limit = g_spin_limit;
       sp.timeout_status = MOE_ERR_SCHED_TIMEOUT;
       hipLaunchKernelGGL(dgrad_prepare_kernel, dim3(1), dim3(kGemmThreads), 0, c.stream, sp);

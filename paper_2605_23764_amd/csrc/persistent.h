@@ -67,6 +67,8 @@ constexpr int kGemm2Lag = 1 << 20;       // GEMM-2 of tile pair j is queued behi
                                          // find their producers long done; a lag of 1..3 pairs measured equal at T = 8192, 2 % slower at T = 4096)
 
 enum TaskType { kTaskPermute = 0, kTaskGemm1 = 1, kTaskGemm2 = 2 };
+constexpr int kTaskTypeMask = 0x7F;
+constexpr int kTaskNarrow = 0x80;        // flag in the type byte: the index counts 128-column tiles and the tile runs in the tall shape
 
 // Event counters (uint32, zero at kernel start).
 enum EventId { kEvArrive = 0, kEvGemm2 = 3, kEvPerTile = 4 };
@@ -101,6 +103,7 @@ struct SchedParams {
   int max_mtiles, max_tasks_per_q;
   int n_events;
   int n_comb_tasks;
+  int workers_per_q;       // workers per XCD queue (grid of the single launch / 8): decides whether a queue's last round of GEMM-2 tasks is halved
   int comb_tokens;         // tokens per COMBINE task
   int perm_rows;           // rows per PERMUTE task
   int no_permute;          // nobody needs Xp: GEMM-1 gathers its rows from x through token_of
@@ -220,6 +223,7 @@ __device__ __forceinline__ void sched_trigger(const SchedParams<BF16>& sp, int e
 // tiles are 128 columns wide) followed by gate_grad (as "GEMM-2").
 template <bool BF16, bool BWD = false>
 __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
+  __shared__ int s_extra[kNumXcd];   // per queue: GEMM-2 tasks added by halving its last round
   for (int i = threadIdx.x; i < sp.n_events; i += blockDim.x) sp.events[i] = 0;
   if (threadIdx.x < kNumQueues) sp.qhead[threadIdx.x] = 0;
   if (threadIdx.x == 0) sp.meta[kMetaFallbackWorkers] = 0;
@@ -235,7 +239,7 @@ __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
   for (int q = wave; q < kNumXcd; q += n_waves) {
     const int Pq = n_pairs > q ? (n_pairs - q + kNumXcd - 1) / kNumXcd : 0;
     TaskDesc* tq = sp.tasks + (size_t)q * sp.max_tasks_per_q;
-    int n = 0;
+    int n = 0, n_g2 = 0;
     constexpr int kTallCols1 = BWD ? 128 : 64;   // output columns of a narrow GEMM-1 tile of a tall M tile
     for (int j = 0; j < (permute ? Pq : 0); ++j)
       for (int s = 0; s < 2; ++s) {
@@ -275,10 +279,47 @@ __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
           tq[n + i] = TaskDesc{kTaskGemm2 | (nt << 8), m0 + sib, kEvPerTile + sp.max_mtiles + m0 + sib, g1_tiles};
         }
         n += n_nt * n_sib;
+        n_g2 += n_nt * n_sib;
       }
     }
-    if (lane == 0) sp.meta[kMetaQueueCount0 + q] = n;
+    // The queue's GEMM-2 tasks are its last n_g2 entries (they follow all of its GEMM-1 tasks) and are drawn by
+    // workers_per_q workers in what amounts to rounds.  A last round that would leave at least half of them without
+    // a task is halved, as in the serialized kernels: each of its wide tasks becomes two 128-column tasks in the
+    // tall shape (one, if the second half lies past the last column).
+    int extra = 0;
+    if (BF16 && lag >= Pq && sp.workers_per_q > 0) {
+      const int tail = n_g2 % sp.workers_per_q;
+      if (tail > 0 && 2 * tail <= sp.workers_per_q && tail <= kWave / 2) {
+        const int n_half = (sp.g2.N + 127) / 128;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // this wave's own descriptors, written by other lanes
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        TaskDesc td = TaskDesc{0, 0, kNoEvent, 0};
+        int cnt = 0;
+        if (lane < tail) {
+          td = tq[n - tail + lane];
+          const bool wide = sp.route.tiles.rows[td.m] <= kTallAbove;
+          cnt = wide && 2 * (td.type_n >> 8) + 1 < n_half ? 2 : 1;
+          if (wide) td.type_n = kTaskGemm2 | kTaskNarrow | ((2 * (td.type_n >> 8)) << 8);
+        }
+        const int incl = wave_incl_scan(cnt, lane);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // all reads of the old entries ahead of the writes below
+        __builtin_amdgcn_wave_barrier();
+        if (lane < tail) {
+          const int at = n - tail + incl - cnt;
+          tq[at] = td;
+          if (cnt == 2) tq[at + 1] = TaskDesc{td.type_n + (1 << 8), td.m, td.dep_event, td.threshold};
+        }
+        extra = __shfl(incl, kWave - 1, kWave) - tail;
+        n += extra;
+      }
+    }
+    if (lane == 0) {
+      sp.meta[kMetaQueueCount0 + q] = n;
+      s_extra[q] = extra;
+    }
   }
+  __syncthreads();
   // COMBINE waits for every GEMM-2 tile: count them
   if (wave == 0) {
     int total = 0;
@@ -286,6 +327,7 @@ __device__ __forceinline__ void build_task_tables(const SchedParams<BF16>& sp) {
       const int rows = sp.route.tiles.rows[m];
       total += rows > kTallAbove ? (sp.g2.N + 127) / 128 : (rows > 0 ? nN2 : 0);
     }
+    if (lane < kNumXcd) total += s_extra[lane];
     total = wave_incl_scan(total, lane);
     if (lane == kWave - 1) sp.meta[kMetaGemm2Total] = total;
   }
@@ -312,7 +354,8 @@ template <bool BF16>
 __device__ __forceinline__ void run_tile_task(const SchedParams<BF16>& sp, const TaskDesc& td, char* smem, volatile int* s_box,
                                               int wave, int q, long long& t_start, uint32_t& gemm2_done, int& scope) {
   const int type_n = __builtin_amdgcn_readfirstlane(td.type_n);
-  const int type = type_n & 0xFF, idx = type_n >> 8, m = __builtin_amdgcn_readfirstlane(td.m);
+  const int type = type_n & kTaskTypeMask, idx = type_n >> 8, m = __builtin_amdgcn_readfirstlane(td.m);
+  const bool narrow = (type_n & kTaskNarrow) != 0;
   const int dep = __builtin_amdgcn_readfirstlane(td.dep_event);
   if (scope < 0) scope = sched_chain_scope(sp, q, s_box, wave);
   // the chain waits on tasks of its own XCD queue
@@ -332,7 +375,7 @@ __device__ __forceinline__ void run_tile_task(const SchedParams<BF16>& sp, const
     else gemm_tile_f32<kEpiSwiglu>(sp.g1, m, idx, reinterpret_cast<float*>(smem));
     sched_trigger(sp, kEvPerTile + sp.max_mtiles + m, wave, scope);
   } else {
-    if constexpr (BF16) gemm_map_tile_bf16<kLayNN, kEpiStore>(sp.g2, m, idx, tile_is_tall(__builtin_amdgcn_readfirstlane(sp.route.tiles.rows[m])), smem);
+    if constexpr (BF16) gemm_map_tile_bf16<kLayNN, kEpiStore>(sp.g2, m, idx, narrow || tile_is_tall(__builtin_amdgcn_readfirstlane(sp.route.tiles.rows[m])), smem);
     else gemm_tile_f32<kEpiStore>(sp.g2, m, idx, reinterpret_cast<float*>(smem));
     // COMBINE waits for every GEMM-2 tile, so completions are counted here and published once per
     // worker after its queue has drained: a device-scope release per tile would write back the
@@ -361,7 +404,7 @@ void persistent_forward_kernel(SchedParams<BF16> sp) {
       const int t = sched_fetch(sp.qhead, kQXcd0 + q, s_box, wave);
       if (t >= count) break;
       const TaskDesc td = sp.tasks[(size_t)q * sp.max_tasks_per_q + t];
-      MOE_TRACE_FETCH(td.type_n & 0xFF, td.m, td.type_n >> 8)
+      MOE_TRACE_FETCH(td.type_n & kTaskTypeMask, td.m, td.type_n >> 8)
       long long t_start = 0;
       run_tile_task(sp, td, smem, s_box, wave, q, t_start, gemm2_done, scope);
 #if defined(MOE_SCHED_TRACE)
@@ -425,8 +468,8 @@ void persistent_dgrad_kernel(SchedParams<true> sp) {
     if (t >= count) break;
     const TaskDesc td = sp.tasks[(size_t)q * sp.max_tasks_per_q + t];
     const int type_n = __builtin_amdgcn_readfirstlane(td.type_n);
-    const int type = type_n & 0xFF, idx = type_n >> 8, m = __builtin_amdgcn_readfirstlane(td.m);
-    const bool tall = tile_is_tall(__builtin_amdgcn_readfirstlane(sp.route.tiles.rows[m]));
+    const int type = type_n & kTaskTypeMask, idx = type_n >> 8, m = __builtin_amdgcn_readfirstlane(td.m);
+    const bool tall = (type_n & kTaskNarrow) != 0 || tile_is_tall(__builtin_amdgcn_readfirstlane(sp.route.tiles.rows[m]));
     if (type == kTaskGemm1) {
       gemm_map_tile_bf16<kLayNT, kEpiSwigluGrad>(sp.g1, m, idx, tall, smem);
       if (scope < 0) scope = sched_chain_scope(sp, q, s_box, wave);

@@ -84,12 +84,15 @@ def test_device_built_schedule(case):
         per_xcd = check_tile_map(plan, counts, lay[19], lay[20])
         print(f"  {'backward' if backward else 'forward'}: M tiles per XCD {per_xcd}", flush=True)
         exp = expectations(cfg, plan, lay, backward, keep_xp)
-        check_plan(plan, exp)
+        workers = (torch.cuda.get_device_properties(0).multi_processor_count + 7) // 8
+        check_plan(plan, exp, workers_per_queue=workers)
+        n_narrow = sum(1 for qq in plan.queues for t in qq if t[0] & 0x80)
+        print(f"  {'backward' if backward else 'forward'}: {n_narrow} halved GEMM-2 tasks", flush=True)
         simulate(plan, 1)
         simulate(plan, 32)
         # perturbed copies of the device's tables must be rejected
         q = max(range(8), key=lambda i: len(plan.queues[i]))
-        pos = next(i for i, t in enumerate(plan.queues[q]) if t[0] == GEMM2)
+        pos = next(i for i, t in enumerate(plan.queues[q]) if t[0] & 0x7F == GEMM2)
         bad = copy.deepcopy(plan)
         ty, idx, m, dep, thr = bad.queues[q][pos]
         bad.queues[q][pos] = (ty, idx, m, dep, thr + 1)                      # threshold above the producer count

@@ -94,3 +94,34 @@ def test_tile_map_check_accepts_a_legal_map_and_names_planted_mistakes():
     lopsided = [(0, 0, 256), (0, 256, 44), (1, 300, 256), (1, 556, 0)] + [(0, 0, 0)] * 12 + [(1, 556, 256), (1, 812, 188)]
     with pytest.raises(AssertionError, match="tiles per XCD"):   # slots 0 and 8 both belong to XCD 0
         check_tile_map(_map_plan(lopsided), [300, 700], 320, 384)
+
+
+def test_halved_last_round_of_gemm2_tasks():
+    """A queue whose last round of GEMM-2 tasks is at most half full carries those tiles as 128-column halves."""
+    from plan_check import NARROW
+    rows = np.array([200, 100], dtype=np.int32)          # one pair in queue 0, both wide
+    # 3 GEMM-2 N tiles per M tile (5 halves: the last tile has only its first half) -> 6 wide tasks; 4 workers: tail 2
+    g1 = [(GEMM1, 0, 0, -1, 0), (GEMM1, 0, 1, -1, 0)]
+    whole = [(GEMM2, nt, m, EV + MAXM + m, 1) for nt in range(3) for m in range(2)]
+    halved = whole[:4] + [(GEMM2 | NARROW, 4, 0, EV + MAXM, 1), (GEMM2 | NARROW, 4, 1, EV + MAXM + 1, 1)]
+    def plan_of(g2):
+        return Plan(2, rows, [g1 + g2] + [[] for _ in range(7)], len(g2), EV, MAXM)
+    exp = lambda p: expected_tiles(p, n1_wide=1, n1_tall=1, n2_wide=3, n2_tall=5, wide_rows=256, perm_rows=32, permute=False)
+    p = plan_of(halved)
+    check_plan(p, exp(p), workers_per_queue=4)
+    simulate(p, 4)
+    with pytest.raises(AssertionError, match="not halved"):
+        check_plan(plan_of(whole), exp(p), workers_per_queue=4)       # the rule asks for halves here
+    check_plan(plan_of(whole), exp(p), workers_per_queue=3)           # 6 tasks on 3 workers: two full rounds
+    with pytest.raises(AssertionError, match="halved GEMM-2 tasks, but"):
+        check_plan(p, exp(p), workers_per_queue=3)
+    both = plan_of(halved + [(GEMM2, 2, 0, EV + MAXM, 1)])            # a tile as halves AND as a whole
+    with pytest.raises(AssertionError, match="once as a whole or as halves"):
+        check_plan(both, exp(p))
+    past = plan_of(halved + [(GEMM2 | NARROW, 5, 0, EV + MAXM, 1)])   # a half past the last column
+    with pytest.raises(AssertionError, match="past the last column"):
+        check_plan(past, exp(p))
+    # a middle tile (nt = 1) halved but with its second half missing
+    lone = plan_of([t for t in whole if t[1] != 1 or t[2] != 0] + [(GEMM2 | NARROW, 2, 0, EV + MAXM, 1)])
+    with pytest.raises(AssertionError, match="second half missing"):
+        check_plan(lone, exp(p))
