@@ -52,5 +52,10 @@ __device__ __forceinline__ float bf16_lo(uint32_t p) { return __builtin_bit_cast
 __device__ __forceinline__ float bf16_hi(uint32_t p) { return __builtin_bit_cast(float, p & 0xFFFF0000u); }
 
 __device__ __forceinline__ float sigmoidf_(float z) { return 1.0f / (1.0f + expf(-z)); }
+// For results that are rounded to bf16 anyway: hardware exp2 and reciprocal (about 1 ulp each, and the scaling by
+// log2(e) adds |z| * 2^-24 relative), a fifth of the instructions of the version above.
+__device__ __forceinline__ float sigmoid_bf16_(float z) {
+  return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504088896340736f * z));
+}
 
 }  // namespace moe

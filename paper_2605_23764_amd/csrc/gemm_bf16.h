@@ -633,7 +633,7 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
           for (int x = 0; x < 4; ++x) {
             g[x] = am[ng][q * 4 + x];
             u[x] = am[ng + 2][q * 4 + x];
-            a[x] = g[x] * sigmoidf_(g[x]) * u[x];
+            a[x] = g[x] * sigmoid_bf16_(g[x]) * u[x];
           }
           pa[ng][q] = u32x2{pack_bf16(a[0], a[1]), pack_bf16(a[2], a[3])};
           ph[ng][q] = u32x2{pack_bf16(g[0], g[1]), pack_bf16(g[2], g[3])};
@@ -667,7 +667,7 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
 #pragma unroll
           for (int x = 0; x < 4; ++x) {
             const float da = am[nt][q * 4 + x];
-            const float sg = sigmoidf_(g[x]);
+            const float sg = sigmoid_bf16_(g[x]);
             dg[x] = da * u[x] * sg * (1.f + g[x] * (1.f - sg));
             du[x] = da * g[x] * sg;
           }
