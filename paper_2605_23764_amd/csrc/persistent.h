@@ -350,6 +350,16 @@ __global__ __launch_bounds__(kScanRankWaves * kWave) void sched_prepare_kernel(S
   if (group < sp.route.n_groups) rank_chunk(sp.route, group, s_lds + wave * kRankLdsWords);
 }
 
+// Vector tasks of a 4-wave worker: 16-byte vectors per lane and pass matched to the row length (a row of H = 7168
+// bf16 is 14 per lane, of H = 2048 four): a pass wider than the row spends its instructions on vectors that do not
+// exist (COMBINE) or falls through to a one-vector-at-a-time tail (PERMUTE).
+template <typename F>
+__device__ __forceinline__ void with_row_vectors(int vec_per_row, F&& f) {
+  if (vec_per_row >= 14 * kWave) f(std::integral_constant<int, 14>{});
+  else if (vec_per_row >= 7 * kWave) f(std::integral_constant<int, 7>{});
+  else f(std::integral_constant<int, 4>{});
+}
+
 template <bool BF16>
 __device__ __forceinline__ void run_tile_task(const SchedParams<BF16>& sp, const TaskDesc& td, char* smem, volatile int* s_box,
                                               int wave, int q, long long& t_start, uint32_t& gemm2_done, int& scope) {
@@ -368,7 +378,9 @@ __device__ __forceinline__ void run_tile_task(const SchedParams<BF16>& sp, const
   if (type == kTaskPermute) {
     const int row0 = sp.route.tiles.row0[m], rows = sp.route.tiles.rows[m];
     const int r0 = row0 + idx * sp.perm_rows;
-    permute_rows<14>(sp.perm, r0, min(r0 + sp.perm_rows, row0 + rows), wave, blockDim.x / kWave);
+    with_row_vectors(sp.perm.H * sp.perm.elem_bytes / 16, [&](auto uv) {
+      permute_rows<decltype(uv)::value>(sp.perm, r0, min(r0 + sp.perm_rows, row0 + rows), wave, blockDim.x / kWave);
+    });
     sched_trigger(sp, kEvPerTile + m, wave, scope);
   } else if (type == kTaskGemm1) {
     if constexpr (BF16) gemm_map_tile_bf16<kLayNN, kEpiSwiglu>(sp.g1, m, idx, tile_is_tall(__builtin_amdgcn_readfirstlane(sp.route.tiles.rows[m])), smem);
@@ -428,15 +440,17 @@ void persistent_forward_kernel(SchedParams<BF16> sp) {
     // Four waves per CU have to hide the latency the combine kernel hides with thirty-two: a token's slots are
     // fetched while the token before it is reduced, and up to four of its rows are in flight at once.
     const int t0 = t * sp.comb_tokens, t1 = min(t0 + sp.comb_tokens, sp.comb.T), nw = blockDim.x / kWave;
-    int rowv, rowv_n = -1;
-    float wv, wv_n = 0.f;
-    if (t0 + wave < t1) combine_load_slots(sp.comb, t0 + wave, rowv, wv);
-    for (int tok = t0 + wave; tok < t1; tok += nw) {
-      if (tok + nw < t1) combine_load_slots(sp.comb, tok + nw, rowv_n, wv_n);
-      combine_token_rows<BF16, BF16 ? 14 : 8, 4>(sp.comb, tok, rowv, wv);
-      rowv = rowv_n;
-      wv = wv_n;
-    }
+    with_row_vectors(sp.comb.H / (BF16 ? 8 : 4), [&](auto uv) {
+      int rowv, rowv_n = -1;
+      float wv, wv_n = 0.f;
+      if (t0 + wave < t1) combine_load_slots(sp.comb, t0 + wave, rowv, wv);
+      for (int tok = t0 + wave; tok < t1; tok += nw) {
+        if (tok + nw < t1) combine_load_slots(sp.comb, tok + nw, rowv_n, wv_n);
+        combine_token_rows<BF16, decltype(uv)::value, 4>(sp.comb, tok, rowv, wv);
+        rowv = rowv_n;
+        wv = wv_n;
+      }
+    });
     MOE_TRACE_END(sp)
   }
 }
