@@ -28,19 +28,42 @@ __device__ __forceinline__ void permute_rows(const PermuteParams& p, int r_begin
                                              int wave, int n_waves) {
   const int lane = lane_id();
   const int vec_per_row = (p.H * p.elem_bytes) / 16;
-  for (int r = r_begin + wave; r < r_end; r += n_waves) {
-    const int t = p.token_of[r];
-    const uint4* src = reinterpret_cast<const uint4*>(static_cast<const char*>(p.x) + (size_t)t * p.H * p.elem_bytes);
-    uint4* dst = reinterpret_cast<uint4*>(static_cast<char*>(p.Xp) + (size_t)r * p.H * p.elem_bytes);
-    int v = lane;
-    for (; v + (U - 1) * kWave < vec_per_row; v += U * kWave) {
-      u32x4 q[U];
+  const size_t row_bytes = (size_t)p.H * p.elem_bytes;
+  // This wave's rows are r_begin + wave + i * n_waves.  Their tokens are fetched with one load (lane i: row i; 64
+  // rows at a time) instead of one dependent load per row, and two rows are copied per pass, the loads of both in
+  // flight before the first store: with only a few waves per CU the copy is latency bound otherwise.
+  for (int base = r_begin + wave; base < r_end; base += kWave * n_waves) {
+    const int n_rows = min(kWave, (r_end - base + n_waves - 1) / n_waves);   // wave-uniform
+    const int tok_lane = lane < n_rows ? p.token_of[base + lane * n_waves] : 0;
+    for (int i = 0; i < n_rows; i += 2) {
+      const bool two = i + 1 < n_rows;
+      const int t0 = __builtin_amdgcn_readlane(tok_lane, i), t1 = __builtin_amdgcn_readlane(tok_lane, two ? i + 1 : i);
+      const int r0 = base + i * n_waves, r1 = r0 + n_waves;
+      const uint4* src0 = reinterpret_cast<const uint4*>(static_cast<const char*>(p.x) + (size_t)t0 * row_bytes);
+      const uint4* src1 = reinterpret_cast<const uint4*>(static_cast<const char*>(p.x) + (size_t)t1 * row_bytes);
+      uint4* dst0 = reinterpret_cast<uint4*>(static_cast<char*>(p.Xp) + (size_t)r0 * row_bytes);
+      uint4* dst1 = reinterpret_cast<uint4*>(static_cast<char*>(p.Xp) + (size_t)r1 * row_bytes);
+      int v = lane;
+      for (; v + (U - 1) * kWave < vec_per_row; v += U * kWave) {
+        u32x4 q0[U], q1[U];
 #pragma unroll
-      for (int u = 0; u < U; ++u) q[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + v + u * kWave));
+        for (int u = 0; u < U; ++u) q0[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src0 + v + u * kWave));
+        if (two) {
 #pragma unroll
-      for (int u = 0; u < U; ++u) __builtin_nontemporal_store(q[u], reinterpret_cast<u32x4*>(dst + v + u * kWave));
+          for (int u = 0; u < U; ++u) q1[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src1 + v + u * kWave));
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) __builtin_nontemporal_store(q0[u], reinterpret_cast<u32x4*>(dst0 + v + u * kWave));
+        if (two) {
+#pragma unroll
+          for (int u = 0; u < U; ++u) __builtin_nontemporal_store(q1[u], reinterpret_cast<u32x4*>(dst1 + v + u * kWave));
+        }
+      }
+      for (; v < vec_per_row; v += kWave) {
+        dst0[v] = src0[v];
+        if (two) dst1[v] = src1[v];
+      }
     }
-    for (; v < vec_per_row; v += kWave) dst[v] = src[v];
   }
 }
 
