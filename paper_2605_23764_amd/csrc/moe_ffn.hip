@@ -320,7 +320,7 @@ SchedParams<BF16> sched_params(const Ctx& c, const void* x, const float* logits,
   // all of them become ready at the same moment, so small tasks are what balances the workers
   sp.comb_tokens = kCombineTokens;
 #ifndef MOE_COMB_TASKS_PER_CU
-#define MOE_COMB_TASKS_PER_CU 4
+#define MOE_COMB_TASKS_PER_CU 2
 #endif
   while (sp.comb_tokens > 4 && (c.s.T + sp.comb_tokens - 1) / sp.comb_tokens < MOE_COMB_TASKS_PER_CU * c.n_cu) sp.comb_tokens >>= 1;
   sp.perm_rows = perm_task_rows(c.s);
