@@ -92,8 +92,11 @@ def main():
     def step(mode):
         moe.moe_ffn_forward(shape, dev["x"], dev["logits"], dev["w_gate_up"], dev["w_down"], out, saved, ws, mode)
 
-    def step_bwd(mode=moe.MODE_SERIALIZED):
-        moe.moe_ffn_backward(shape, dy, dev["x"], dev["w_gate_up"], dev["w_down"], saved, dx, dw1, dw2, dtw, ws_b, mode)
+    wgrad_stream = torch.cuda.Stream() if with_bwd else None   # second stream of the two-stream backward
+
+    def step_bwd(mode=moe.MODE_SERIALIZED, two_streams=False, sv=None):
+        moe.moe_ffn_backward_two_streams(shape, dy, dev["x"], dev["w_gate_up"], dev["w_down"], sv or saved, dx, dw1, dw2,
+                                         dtw, ws_b, wgrad_stream if two_streams else None, mode)
 
     if args.hold:
         step(moe.MODE_SERIALIZED)
@@ -222,12 +225,17 @@ def main():
     bwd_ms = None
     if with_bwd:
         step(moe.MODE_SERIALIZED)          # saved activations the backward reads
-        bwd_modes = {"serialized": timed(step_bwd, args.steps, args.warmup)}
+        # name -> (launch mode of the data gradients, weight gradients on a second stream)
+        bwd_variants = {"serialized": (moe.MODE_SERIALIZED, False), "serialized_two_streams": (moe.MODE_SERIALIZED, True)}
         if cfg.dtype == "bf16" and "persistent" in modes:
             # the two data-gradient GEMMs as one launch of tile tasks, the other operators as before
-            bwd_modes["data_gradients_single_launch"] = timed(lambda: step_bwd(moe.MODE_PERSISTENT), args.steps, args.warmup)
-            if moe.moe_ffn_last_status(shape, ws_b) != 0:
-                del bwd_modes["data_gradients_single_launch"]
+            bwd_variants["data_gradients_single_launch"] = (moe.MODE_PERSISTENT, False)
+            bwd_variants["data_gradients_single_launch_two_streams"] = (moe.MODE_PERSISTENT, True)
+        bwd_modes = {}
+        for name, (bm, two) in bwd_variants.items():
+            t = timed(lambda: step_bwd(bm, two), args.steps, args.warmup)
+            if moe.moe_ffn_last_status(shape, ws_b) == 0:
+                bwd_modes[name] = t
         bwd_best = min(bwd_modes, key=bwd_modes.get)
         bwd_ms = bwd_modes[bwd_best]
     # training step that keeps no permuted copy of x (MoeSaved.Xp = NULL): GEMM-1 and w1_grad read x through the
@@ -243,9 +251,8 @@ def main():
         if with_bwd:
             moe.moe_ffn_forward(shape, dev["x"], dev["logits"], dev["w_gate_up"], dev["w_down"], out, saved_nx, ws,
                                 moe.MODE_SERIALIZED)
-            bmode = moe.MODE_SERIALIZED if bwd_best == "serialized" else moe.MODE_PERSISTENT   # the faster one above
-            noxp_bwd_ms = timed(lambda: moe.moe_ffn_backward(shape, dy, dev["x"], dev["w_gate_up"], dev["w_down"], saved_nx,
-                                                             dx, dw1, dw2, dtw, ws_b, bmode), args.steps, args.warmup)
+            bmode, btwo = bwd_variants[bwd_best]   # the fastest one above
+            noxp_bwd_ms = timed(lambda: step_bwd(bmode, btwo, saved_nx), args.steps, args.warmup)
         del saved_nx
 
     # ---- per-operator durations: the serialized sequence with HIP events between launches

@@ -174,6 +174,28 @@ int moe_ffn_backward(const MoeShape* shape, const void* d_dy, const void* d_x,
                      void* d_workspace, size_t workspace_bytes, int mode, void* stream);
 
 /*
+ * The same backward with its two branches on two streams (paper Section 2.2, Figure 2b: behind the backward
+ * Dispatch the weight gradients w2_grad, w1_grad and the data gradients act_grad -> gate_grad -> backward
+ * Combine only share inputs; Section 4.5 runs such branches side by side).  The weight-gradient launches are
+ * enqueued on `wgrad_stream` (w2_grad behind the backward Dispatch, w1_grad behind the launch that completes
+ * dH1), everything else on `stream`; their workgroups then take the CUs that the last tiles of the other
+ * branch's kernels leave idle.  The call forks from `stream` and joins back into it with events before it
+ * returns: work enqueued on `stream` afterwards sees every output, and `wgrad_stream` needs no
+ * synchronisation by the caller.  Results are bit-identical to moe_ffn_backward's.
+ *   wgrad_stream  a stream of the same device with the default priority; NULL or equal to `stream`:
+ *                 exactly moe_ffn_backward.  While `stream` is being captured into a graph the other
+ *                 stream joins the capture (fork / join through events); it must not be capturing already.
+ * Everything else as for moe_ffn_backward.  The events are the library's (three per device, created at
+ * the first such call on a device and kept); calls of this entry point are serialised against each other
+ * while they enqueue.  MOE_ERR_LAUNCH if an event cannot be created or recorded.
+ */
+int moe_ffn_backward_two_streams(const MoeShape* shape, const void* d_dy, const void* d_x,
+                                 const void* d_w_gate_up, const void* d_w_down, const MoeSaved* saved,
+                                 void* d_dx, void* d_dw_gate_up, void* d_dw_down, float* d_dtopk_w,
+                                 void* d_workspace, size_t workspace_bytes, int mode, void* stream,
+                                 void* wgrad_stream);
+
+/*
  * Reads the scheduler status word of a forward or backward workspace after the caller has
  * synchronised the stream (host-blocking 4-byte copy).  MOE_OK or
  * MOE_ERR_SCHED_TIMEOUT.

@@ -35,7 +35,7 @@ class _MoeSaved(ctypes.Structure):
 
 
 EXPORTS = (
-    "moe_status_string", "moe_ffn_workspace_bytes", "moe_ffn_forward", "moe_ffn_backward",
+    "moe_status_string", "moe_ffn_workspace_bytes", "moe_ffn_forward", "moe_ffn_backward", "moe_ffn_backward_two_streams",
     "moe_ffn_last_status", "moe_ffn_debug_set_spin_limit", "moe_route", "moe_permute", "moe_grouped_gemm_swiglu", "moe_grouped_gemm",
     "moe_combine", "moe_microbench_workspace_bytes", "moe_microbench_swiglu_add", "moe_microbench_last_status",
     "moe_probe_mfma_bf16", "moe_probe_copy", "moe_probe_read", "moe_probe_write", "moe_microbench_swiglu_add_static_scratch",
@@ -178,6 +178,18 @@ def moe_ffn_backward(shape, dy, x, w_gate_up, w_down, saved: Saved, dx, dw_gate_
         ctypes.byref(shape), _ptr(dy), _ptr(x), _ptr(w_gate_up), _ptr(w_down), ctypes.byref(sv),
         _ptr(dx), _ptr(dw_gate_up), _ptr(dw_down), _ptr(dtopk_w), wp, wb, ctypes.c_int(mode), _stream(stream))
     _check(st, "moe_ffn_backward")
+
+
+def moe_ffn_backward_two_streams(shape, dy, x, w_gate_up, w_down, saved: Saved, dx, dw_gate_up, dw_down, dtopk_w,
+                                 workspace, wgrad_stream, mode: int = MODE_SERIALIZED, stream=None) -> None:
+    """`wgrad_stream`: a torch.cuda.Stream for the weight-gradient launches, or None (one stream)."""
+    sv = saved.c_struct()
+    wp, wb = _ws(workspace)
+    side = ctypes.c_void_p(wgrad_stream.cuda_stream) if wgrad_stream is not None else ctypes.c_void_p(None)
+    st = load_library().moe_ffn_backward_two_streams(
+        ctypes.byref(shape), _ptr(dy), _ptr(x), _ptr(w_gate_up), _ptr(w_down), ctypes.byref(sv),
+        _ptr(dx), _ptr(dw_gate_up), _ptr(dw_down), _ptr(dtopk_w), wp, wb, ctypes.c_int(mode), _stream(stream), side)
+    _check(st, "moe_ffn_backward_two_streams")
 
 
 def moe_ffn_last_status(shape, workspace) -> int:

@@ -288,6 +288,13 @@ uint32_t g_spin_limit = 1u << 20;
 // several XCDs (device-scope fences on every chain event).
 int g_force_device_scope = 0;
 
+// Two-stream backward: the events of its fork and join (dYp ready, dH1 ready, weight gradients done), made on a
+// device's first such call and kept; calls hold the mutex while they enqueue, so that no other call's record of
+// the same event comes between a record and the wait that refers to it.
+constexpr int kMaxDevices = 16;
+hipEvent_t g_fork_ev[kMaxDevices][3] = {};
+std::mutex g_fork_mutex;
+
 // Everything the scheduler's kernels need; pointers the caller does not have yet may be null (the routing
 // launches only read the shapes, the tile counts and the table addresses).
 template <bool BF16>
@@ -399,6 +406,7 @@ struct BwdCtx {
   char* ws;
   MoeSaved sv;
   hipStream_t stream;
+  hipStream_t wgrad_stream;   // nullptr or == stream: everything on `stream`
   int n_cu;
   TileMap tiles;
   int mode;          // MOE_MODE_PERSISTENT: act_grad and gate_grad as one launch under the tile scheduler
@@ -450,6 +458,22 @@ int run_backward(const BwdCtx& c, const void* dy, const void* x, const void* w_g
     int g = (int)(want < (long)c.n_cu * 8 ? want : (long)c.n_cu * 8);
     hipLaunchKernelGGL(bwd_dispatch_kernel<BF16>, dim3(g), dim3(256), 0, c.stream, bd);
   }
+  // Two streams: the weight-gradient branch of the graph (w2_grad behind the backward Dispatch, w1_grad behind
+  // act_grad) is enqueued on its own stream, so that its workgroups take the CUs that the last tiles of the
+  // data-gradient kernels leave idle, and the other way round; joined again before this function returns.
+  const bool side = c.wgrad_stream != nullptr && c.wgrad_stream != c.stream;
+  hipStream_t sw = side ? c.wgrad_stream : c.stream;
+  hipEvent_t* ev = nullptr;
+  std::unique_lock<std::mutex> fork_lock(g_fork_mutex, std::defer_lock);
+  if (side) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MOE_ERR_LAUNCH;
+    fork_lock.lock();
+    ev = g_fork_ev[dev];
+    for (int i = 0; i < 3; ++i)
+      if (!ev[i] && hipEventCreateWithFlags(&ev[i], hipEventDisableTiming) != hipSuccess) return MOE_ERR_LAUNCH;
+    if (hipEventRecord(ev[0], c.stream) != hipSuccess || hipStreamWaitEvent(sw, ev[0], 0) != hipSuccess) return MOE_ERR_LAUNCH;
+  }
 
   using P = typename std::conditional<BF16, GemmParams, GemmBwdParamsF32>::type;
   T* xp_ws = reinterpret_cast<T*>(c.ws + c.L.Xp);
@@ -469,7 +493,7 @@ int run_backward(const BwdCtx& c, const void* dy, const void* x, const void* w_g
   pg.tiles = c.tiles;
 
   // w2_grad: dW_down[e] = A_e^T dYp_e (needs only dYp: runs first, while dYp is fresh in the caches)
-  {
+  auto launch_w2 = [&](hipStream_t st) {
     P p{};
     p.A = static_cast<const T*>(c.sv.A); p.B = dYp; p.C = static_cast<T*>(dw_down);
     p.strideC = (long)s.I * s.H; p.M = s.I; p.N = s.H;
@@ -477,9 +501,16 @@ int run_backward(const BwdCtx& c, const void* dy, const void* x, const void* w_g
     p.n_ntiles = ceil_div(s.H, tn);
     if constexpr (!BF16) p.n_mtiles = ceil_div(s.I, bm);
     p.E_local = s.E_local; p.offsets = c.sv.offsets;
-    if constexpr (BF16) { p.tickets = tickets; p.tiles = c.tiles; launch_wgrad_bf16(p, grid, c.n_cu, c.stream); }
-    else hipLaunchKernelGGL(grouped_wgrad_f32_kernel, dim3(grid), dim3(256), 0, c.stream, p);
-  }
+    if constexpr (BF16) { p.tickets = tickets; p.tiles = c.tiles; launch_wgrad_bf16(p, grid, c.n_cu, st); }
+    else hipLaunchKernelGGL(grouped_wgrad_f32_kernel, dim3(grid), dim3(256), 0, st, p);
+  };
+  if (!side) launch_w2(c.stream);
+  // called right behind the launch that completes dH1: w2_grad goes to the other stream, w1_grad may follow there
+  auto fork_behind_dh1 = [&]() {
+    if (!side) return true;
+    launch_w2(sw);
+    return hipEventRecord(ev[1], c.stream) == hipSuccess && hipStreamWaitEvent(sw, ev[1], 0) == hipSuccess;
+  };
   if constexpr (BF16) {
     if (c.mode == MOE_MODE_PERSISTENT) {
       SchedParams<true> sp{};
@@ -499,12 +530,15 @@ int run_backward(const BwdCtx& c, const void* dy, const void* x, const void* w_g
       sp.timeout_status = MOE_ERR_SCHED_TIMEOUT;
       hipLaunchKernelGGL(dgrad_prepare_kernel, dim3(1), dim3(kGemmThreads), 0, c.stream, sp);
       hipLaunchKernelGGL(persistent_dgrad_kernel, dim3(grid), dim3(kGemmThreads), 0, c.stream, sp);
+      if (!fork_behind_dh1()) return MOE_ERR_LAUNCH;
     } else {
       hipLaunchKernelGGL((grouped_gemm_bf16_kernel<kLayNT, kEpiSwigluGrad>), dim3(grid), dim3(kGemmThreads), 0, c.stream, pa);
+      if (!fork_behind_dh1()) return MOE_ERR_LAUNCH;
       hipLaunchKernelGGL((grouped_gemm_bf16_kernel<kLayNT, kEpiStore>), dim3(grid), dim3(kGemmThreads), 0, c.stream, pg);
     }
   } else {
     hipLaunchKernelGGL(grouped_dgrad_f32_kernel<kEpiSwigluGrad>, dim3(grid), dim3(256), 0, c.stream, pa);
+    if (!fork_behind_dh1()) return MOE_ERR_LAUNCH;
     hipLaunchKernelGGL(grouped_dgrad_f32_kernel<kEpiStore>, dim3(grid), dim3(256), 0, c.stream, pg);
   }
   // w1_grad: dW_gate_up[e] = Xp_e^T dH1_e.  When the forward kept no permuted copy (saved->Xp == NULL) the
@@ -529,15 +563,15 @@ int run_backward(const BwdCtx& c, const void* dy, const void* x, const void* w_g
       if (gather) {
         // only the rows the general kernel will read: experts above the other kernel's limit, or all of them
         const int k_lo = wgrad_panel_fits(p.M, p.N) ? kWpMaxRows + 1 : 0;
-        hipLaunchKernelGGL(permute_large_experts_kernel, dim3(g), dim3(256), 0, c.stream, pp, c.sv.offsets, s.E_local, k_lo);
+        hipLaunchKernelGGL(permute_large_experts_kernel, dim3(g), dim3(256), 0, sw, pp, c.sv.offsets, s.E_local, k_lo);
         if constexpr (BF16) { p.A = static_cast<const T*>(x); p.gather = c.sv.token_of; }
       } else {
-        hipLaunchKernelGGL(permute_kernel, dim3(g), dim3(256), 0, c.stream, pp);
+        hipLaunchKernelGGL(permute_kernel, dim3(g), dim3(256), 0, sw, pp);
         p.A = xp_ws;
       }
     }
-    if constexpr (BF16) { p.tickets = tickets + kNumXcd; p.tiles = c.tiles; launch_wgrad_bf16(p, grid, c.n_cu, c.stream, xp_ws); }
-    else hipLaunchKernelGGL(grouped_wgrad_f32_kernel, dim3(grid), dim3(256), 0, c.stream, p);
+    if constexpr (BF16) { p.tickets = tickets + kNumXcd; p.tiles = c.tiles; launch_wgrad_bf16(p, grid, c.n_cu, sw, xp_ws); }
+    else hipLaunchKernelGGL(grouped_wgrad_f32_kernel, dim3(grid), dim3(256), 0, sw, p);
   }
   // backward Combine: dX[t] = sum over local slots of dXp[row_of[t,j]]
   {
@@ -548,6 +582,8 @@ int run_backward(const BwdCtx& c, const void* dy, const void* x, const void* w_g
     int g = (int)(want < (long)c.n_cu * 8 ? want : (long)c.n_cu * 8);
     hipLaunchKernelGGL(combine_kernel<BF16>, dim3(g), dim3(256), 0, c.stream, p);
   }
+  if (side && (hipEventRecord(ev[2], sw) != hipSuccess || hipStreamWaitEvent(c.stream, ev[2], 0) != hipSuccess))
+    return MOE_ERR_LAUNCH;
   return launch_status();
 }
 
@@ -751,6 +787,14 @@ int moe_ffn_backward(const MoeShape* shape, const void* d_dy, const void* d_x, c
                      const void* d_w_down, const MoeSaved* saved, void* d_dx, void* d_dw_gate_up,
                      void* d_dw_down, float* d_dtopk_w, void* d_workspace, size_t workspace_bytes, int mode,
                      void* stream) {
+  return moe_ffn_backward_two_streams(shape, d_dy, d_x, d_w_gate_up, d_w_down, saved, d_dx, d_dw_gate_up, d_dw_down,
+                                      d_dtopk_w, d_workspace, workspace_bytes, mode, stream, nullptr);
+}
+
+int moe_ffn_backward_two_streams(const MoeShape* shape, const void* d_dy, const void* d_x, const void* d_w_gate_up,
+                                 const void* d_w_down, const MoeSaved* saved, void* d_dx, void* d_dw_gate_up,
+                                 void* d_dw_down, float* d_dtopk_w, void* d_workspace, size_t workspace_bytes,
+                                 int mode, void* stream, void* wgrad_stream) {
   int st = check_shape(shape);
   if (st != MOE_OK) return st;
   // MOE_MODE_PERSISTENT (bf16 only): the two data-gradient GEMMs run as one launch under the tile scheduler
@@ -777,6 +821,7 @@ int moe_ffn_backward(const MoeShape* shape, const void* d_dy, const void* d_x, c
   c.ws = static_cast<char*>(d_workspace);
   c.sv = *saved;
   c.stream = static_cast<hipStream_t>(stream);
+  c.wgrad_stream = static_cast<hipStream_t>(wgrad_stream);
   c.n_cu = device_cus();
   c.mode = mode;
   c.tiles.expert = reinterpret_cast<int32_t*>(c.ws + c.L.tile_expert);

@@ -97,8 +97,9 @@ class GpuBackward:
     dtopk_w: torch.Tensor
 
 
-def run_backward(cfg: MoeConfig, inp: dict, run: GpuRun, mode=moe.MODE_SERIALIZED) -> GpuBackward:
-    """Backward through the C ABI on the buffers a forward with H1 stored has filled."""
+def run_backward(cfg: MoeConfig, inp: dict, run: GpuRun, mode=moe.MODE_SERIALIZED, wgrad_stream=None) -> GpuBackward:
+    """Backward through the C ABI on the buffers a forward with H1 stored has filled (`wgrad_stream`: through the
+    two-stream entry point, the weight gradients on that stream)."""
     tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
     dy = to_device(inp["dy"], cfg.dtype)
     nan = float("nan")
@@ -107,9 +108,14 @@ def run_backward(cfg: MoeConfig, inp: dict, run: GpuRun, mode=moe.MODE_SERIALIZE
     dw2 = torch.full((cfg.E_local, cfg.I, cfg.H), nan, dtype=tdt, device="cuda")
     dtw = torch.full((cfg.T, cfg.k), nan, dtype=torch.float32, device="cuda")
     ws = moe.alloc_workspace(run.shape, backward=True)
-    moe.moe_ffn_backward(run.shape, dy, run.dev["x"], run.dev["w_gate_up"], run.dev["w_down"], run.saved,
-                         dx, dw1, dw2, dtw, ws, mode)
-    torch.cuda.synchronize()
+    if wgrad_stream is None:
+        moe.moe_ffn_backward(run.shape, dy, run.dev["x"], run.dev["w_gate_up"], run.dev["w_down"], run.saved,
+                             dx, dw1, dw2, dtw, ws, mode)
+    else:
+        moe.moe_ffn_backward_two_streams(run.shape, dy, run.dev["x"], run.dev["w_gate_up"], run.dev["w_down"],
+                                         run.saved, dx, dw1, dw2, dtw, ws, wgrad_stream, mode)
+    # the two-stream call has joined the other stream back into this one: this stream alone is waited for
+    torch.cuda.current_stream().synchronize() if wgrad_stream is not None else torch.cuda.synchronize()
     assert moe.moe_ffn_last_status(run.shape, ws) == 0
     return GpuBackward(dx, dw1, dw2, dtw)
 

@@ -187,6 +187,38 @@ def test_single_launch_data_gradients_bounded_wait():
     assert moe.moe_ffn_last_status(run.shape, ws) == 0
 
 
+TWO_STREAMS = [SMALL[i] for i in (0, 1, 3, 4, 9, 10, 12, 13)] + [
+    ("b_bf16_two_streams_big", 4096, 512, 512, 16, 16, 0, 4, "bf16", 63),   # ~1000 rows/expert: several rounds of tiles per CU
+]
+
+
+@pytest.mark.parametrize("mode", ["serialized", "persistent"])
+@pytest.mark.parametrize("keep_xp", [True, False], ids=["xp", "noxp"])
+@pytest.mark.parametrize("case", TWO_STREAMS, ids=[c[0] for c in TWO_STREAMS])
+def test_two_streams_equals_one_stream(case, keep_xp, mode):
+    """The weight-gradient branch on a second stream: the same kernels on the same values, so every gradient is
+    bit-identical to the one-stream call, on two calls in a row (the fork / join events are reused) and with
+    the caller waiting for the first stream only."""
+    import paper_2605_23764_amd as moe
+    from gpu_common import run_backward, run_forward, small_config
+    cfg = small_config(*case)
+    if cfg.dtype != "bf16" and mode == "persistent":
+        pytest.skip("the single-launch data gradients are bf16 only")
+    inp = make_inputs(cfg, with_dy=True)
+    m = moe.MODE_PERSISTENT if mode == "persistent" else moe.MODE_SERIALIZED
+    run = run_forward(cfg, inp, mode=m, store_h1=True, keep_xp=keep_xp)
+    print(cfg.name, mode, "keep_xp", keep_xp, flush=True)
+    want = run_backward(cfg, inp, run, mode=m)
+    side = torch.cuda.Stream()
+    for call in range(2):
+        got = run_backward(cfg, inp, run, mode=m, wgrad_stream=side)
+        for name in ("dx", "dw_gate_up", "dw_down", "dtopk_w"):
+            assert torch.equal(getattr(got, name), getattr(want, name)), (name, call)
+    # NULL and the first stream itself mean one stream
+    got = run_backward(cfg, inp, run, mode=m, wgrad_stream=torch.cuda.current_stream())
+    assert torch.equal(got.dw_gate_up, want.dw_gate_up) and torch.equal(got.dx, want.dx)
+
+
 # without a kept permuted copy (MoeSaved.Xp = NULL): GEMM-1 and w1_grad read x through the permutation.
 # Cases: register-stationary kernel only; both weight-gradient kernels (experts above 384 rows take the
 # partial copy); shapes the register-stationary kernel cannot take (everything through the copy); tiny

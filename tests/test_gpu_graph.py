@@ -21,8 +21,9 @@ def _device_inputs(cfg, seed):
                 w2=to_device(inp["w_down"], cfg.dtype))
 
 
+@pytest.mark.parametrize("two_streams", [False, True], ids=["one_stream", "two_streams"])
 @pytest.mark.parametrize("mode", [moe.MODE_SERIALIZED, moe.MODE_PERSISTENT], ids=["serialized", "persistent"])
-def test_forward_and_backward_replay_from_a_graph(mode):
+def test_forward_and_backward_replay_from_a_graph(mode, two_streams):
     cfg = small_config("graph", 1500, 256, 256, 8, 8, 0, 2, "bf16", 71)
     tdt = torch.bfloat16
     shape = moe.make_shape(cfg.T, cfg.H, cfg.I, cfg.E, cfg.E_local, cfg.expert_base, cfg.k, tdt)
@@ -36,9 +37,16 @@ def test_forward_and_backward_replay_from_a_graph(mode):
     dx, dw1, dw2 = torch.empty_like(x), torch.empty_like(w1), torch.empty_like(w2)
     dtw = torch.empty(cfg.T, cfg.k, dtype=torch.float32, device="cuda")
 
+    # two streams: the weight gradients fork onto a stream of their own, which joins the capture through the
+    # call's events and is joined back before the call returns
+    wgrad_stream = torch.cuda.Stream() if two_streams else None
+
     def layer():
         moe.moe_ffn_forward(shape, x, logits, w1, w2, out, saved, ws_f, mode)
-        moe.moe_ffn_backward(shape, dy, x, w1, w2, saved, dx, dw1, dw2, dtw, ws_b, mode)   # same mode: see moe_ffn.h
+        if two_streams:
+            moe.moe_ffn_backward_two_streams(shape, dy, x, w1, w2, saved, dx, dw1, dw2, dtw, ws_b, wgrad_stream, mode)
+        else:
+            moe.moe_ffn_backward(shape, dy, x, w1, w2, saved, dx, dw1, dw2, dtw, ws_b, mode)   # same mode: see moe_ffn.h
 
     def snapshot():
         torch.cuda.synchronize()
