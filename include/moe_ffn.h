@@ -275,7 +275,9 @@ int moe_combine(const MoeShape* shape, const MoeSaved* saved, void* d_out,
  * launch per operator (Section 2.3's kernel-by-kernel execution); MOE_MODE_PERSISTENT: exactly one launch of
  * tile tasks with event counters (Sections 4.3-4.4; alignment rule at the top of this file), which consumes
  * the counters and queues moe_route prepared: one call per moe_route call (a second one finds every ticket
- * taken and does nothing).  Results are bit-identical.  moe_ffn_forward(mode) = moe_route + this. */
+ * taken and does nothing).  Results are bit-identical.  moe_ffn_forward(mode) = moe_route + this, except that
+ * its routing launches leave the counters and queues out when mode is MOE_MODE_SERIALIZED (nobody reads them
+ * then): MOE_MODE_PERSISTENT here needs a moe_route call, or a MOE_MODE_PERSISTENT forward's routing, in front. */
 int moe_dispatch_to_combine(const MoeShape* shape, const void* d_x, const void* d_w_gate_up, const void* d_w_down,
                             void* d_out, const MoeSaved* saved, void* d_workspace, size_t workspace_bytes, int mode,
                             void* stream);

@@ -5,6 +5,7 @@
 #pragma once
 #include "common.h"
 #include "gemm_f32.h"
+#include "route.h"
 
 namespace moe {
 
@@ -16,6 +17,13 @@ struct BwdDispatchParams {
   const float* topk_w;     // [T,k]
   float* d_topk_w;         // [T,k]
   int T, H, k;
+  // The backward's M-tile map, rebuilt from the saved rows per expert, and the counters the later kernels draw
+  // tickets from: nothing in this kernel needs them, so its last workgroup makes them on the side (one wave).
+  const int32_t* counts;   // [E_local]
+  int E_local, wide_max, granule, tall;
+  TileMap tiles;
+  uint32_t* zero;
+  int n_zero;
 };
 
 __device__ __forceinline__ float wave_sum(float v) {
@@ -105,7 +113,15 @@ template <bool BF16>
 __global__ __launch_bounds__(256) void bwd_dispatch_kernel(BwdDispatchParams p) {
   const int n_waves = blockDim.x / kWave;
   const int wave = threadIdx.x / kWave;
-  for (int t = blockIdx.x * n_waves + wave; t < p.T; t += gridDim.x * n_waves) bwd_dispatch_token<BF16>(p, t);
+  const int n_blocks = (int)gridDim.x - 1;
+  if ((int)blockIdx.x == n_blocks) {
+    if (wave == 0) {
+      for (int i = threadIdx.x; i < p.n_zero; i += kWave) p.zero[i] = 0;
+      build_tile_map(p.E_local, p.counts, p.wide_max, p.granule, p.tall, nullptr, nullptr, p.tiles);
+    }
+    return;
+  }
+  for (int t = blockIdx.x * n_waves + wave; t < p.T; t += n_blocks * n_waves) bwd_dispatch_token<BF16>(p, t);
 }
 
 // ---- fp32 backward GEMMs: one 64 x 64 x 16 LDS-tiled kernel with element strides,

@@ -309,6 +309,7 @@ SchedParams<BF16> sched_params(const Ctx& c, const void* x, const float* logits,
   sp.g2 = gemm2_params<P, T>(c, w_down);
   sp.comb = combine_params(c, out);
   sp.no_permute = 0;
+  sp.skip_tables = 0;
   if constexpr (BF16) {
     if (gathers_x(c)) {
       sp.g1.A = static_cast<const T*>(x);
@@ -343,16 +344,19 @@ SchedParams<BF16> sched_params(const Ctx& c, const void* x, const float* logits,
 // stable ranks.  The second launch also zeroes the tile scheduler's counters and writes its task tables (one
 // workgroup, beside the rank groups), so that either launch mode can follow.
 template <bool BF16>
-int run_route_t(const Ctx& c, const float* logits) {
-  const SchedParams<BF16> sp = sched_params<BF16>(c, nullptr, logits, nullptr, nullptr, nullptr);
+int run_route_t(const Ctx& c, const float* logits, bool tables) {
+  SchedParams<BF16> sp = sched_params<BF16>(c, nullptr, logits, nullptr, nullptr, nullptr);
+  sp.skip_tables = tables ? 0 : 1;
   const RouteParams& rp = sp.route;
   hipLaunchKernelGGL(route_kernel, dim3(rp.n_sub), dim3(512), 0, c.stream, rp);
   hipLaunchKernelGGL(sched_prepare_kernel<BF16>, dim3(1 + (rp.n_groups + kScanRankWaves - 1) / kScanRankWaves),
                      dim3(kScanRankWaves * kWave), 0, c.stream, sp);
   return launch_status();
 }
-int run_route(const Ctx& c, const float* logits) {
-  return c.s.dtype == MOE_BF16 ? run_route_t<true>(c, logits) : run_route_t<false>(c, logits);
+// tables = false: the caller knows that one launch per operator follows (the task tables take workgroup 0 of the
+// second launch, which is the launch's critical path, about as long again as the prefix sums and the tile map).
+int run_route(const Ctx& c, const float* logits, bool tables = true) {
+  return c.s.dtype == MOE_BF16 ? run_route_t<true>(c, logits, tables) : run_route_t<false>(c, logits, tables);
 }
 
 // Dispatch to Combine as ONE launch of tile tasks (after run_route on the same MoeSaved).
@@ -446,17 +450,17 @@ int run_backward(const BwdCtx& c, const void* dy, const void* x, const void* w_g
   const int grid = BF16 ? (c.n_cu + 7) / 8 * 8 : c.n_cu * 4;
 
   uint32_t* tickets = reinterpret_cast<uint32_t*>(c.ws + c.L.tickets);   // [0, 8): w2_grad, [8, 16): w1_grad
-  hipLaunchKernelGGL(tile_map_kernel, dim3(1), dim3(kWave), 0, c.stream, c.sv.counts, s.E_local, tile_wide_max(s),
-                     BF16 ? kRowGranule : kFBM, tile_tall(s), c.tiles, tickets, 2 * kNumXcd);
 
-  // backward Dispatch
+  // backward Dispatch; its extra workgroup rebuilds the M-tile map from the saved counts and zeroes the tickets
   BwdDispatchParams bd;
   bd.dY = dy; bd.Yp = c.sv.Yp; bd.dYp = dYp; bd.row_of = c.sv.row_of; bd.topk_w = c.sv.topk_w;
   bd.d_topk_w = d_topk_w; bd.T = s.T; bd.H = s.H; bd.k = s.k;
+  bd.counts = c.sv.counts; bd.E_local = s.E_local; bd.wide_max = tile_wide_max(s); bd.granule = BF16 ? kRowGranule : kFBM;
+  bd.tall = tile_tall(s); bd.tiles = c.tiles; bd.zero = tickets; bd.n_zero = 2 * kNumXcd;
   {
     long want = ((long)s.T + 3) / 4;
     int g = (int)(want < (long)c.n_cu * 8 ? want : (long)c.n_cu * 8);
-    hipLaunchKernelGGL(bwd_dispatch_kernel<BF16>, dim3(g), dim3(256), 0, c.stream, bd);
+    hipLaunchKernelGGL(bwd_dispatch_kernel<BF16>, dim3(g + 1), dim3(256), 0, c.stream, bd);
   }
   // Two streams: the weight-gradient branch of the graph (w2_grad behind the backward Dispatch, w1_grad behind
   // act_grad) is enqueued on its own stream, so that its workgroups take the CUs that the last tiles of the
@@ -779,7 +783,7 @@ int moe_ffn_forward(const MoeShape* shape, const void* d_x, const float* d_logit
     if (!q || !aligned16(q)) return MOE_ERR_INVALID_ARG;
   if (mode == MOE_MODE_PERSISTENT && (!aligned128(c.ws) || !aligned128(c.sv.Xp) || !aligned128(c.sv.A)))
     return MOE_ERR_INVALID_ARG;   // before anything is enqueued
-  if ((st = run_route(c, d_logits)) != MOE_OK) return st;
+  if ((st = run_route(c, d_logits, mode == MOE_MODE_PERSISTENT)) != MOE_OK) return st;
   return run_dispatch_to_combine(c, d_x, d_w_gate_up, d_w_down, d_out, mode);
 }
 

@@ -108,6 +108,7 @@ struct SchedParams {
   int perm_rows;           // rows per PERMUTE task
   int no_permute;          // nobody needs Xp: GEMM-1 gathers its rows from x through token_of
   int force_device_scope;  // test hook: behave as if a worker had reported a foreign XCD
+  int skip_tables;         // routing launch: the serialized operators follow, nobody reads counters or task tables
   uint32_t spin_limit;     // polls before a wait gives up (MOE_ERR_SCHED_TIMEOUT)
   int32_t timeout_status;
 };
@@ -342,7 +343,7 @@ __global__ __launch_bounds__(kScanRankWaves * kWave) void sched_prepare_kernel(S
     scan_all(sp.route, s_lds, s_lds + kMaxE + 64);
     __threadfence_block();
     __syncthreads();   // tile map (written by wave 0) complete before every wave reads it
-    build_task_tables<BF16>(sp);
+    if (!sp.skip_tables) build_task_tables<BF16>(sp);
     return;
   }
   const int wave = threadIdx.x / kWave;

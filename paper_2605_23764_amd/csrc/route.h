@@ -539,13 +539,4 @@ __global__ __launch_bounds__(512) void route_kernel(RouteParams p) {
 constexpr int kScanRankWaves = 4;
 static_assert(kScanRankWaves * kRankLdsWords >= (kScanRankWaves + 1) * kMaxE + 2 + 64, "LDS of the scan step");
 
-// M-tile map from the rows per expert alone (the backward rebuilds it from the
-// saved counts instead of keeping the forward's workspace alive).
-// Also zeroes `n_zero` words at `zero` (counters the kernels that follow draw tickets from).
-__global__ __launch_bounds__(kWave) void tile_map_kernel(const int32_t* counts, int E_local, int wide_max, int granule,
-                                                         int tall, TileMap tiles, uint32_t* zero, int n_zero) {
-  for (int i = threadIdx.x; i < n_zero; i += kWave) zero[i] = 0;
-  build_tile_map(E_local, counts, wide_max, granule, tall, nullptr, nullptr, tiles);
-}
-
 }  // namespace moe

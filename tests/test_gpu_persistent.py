@@ -108,3 +108,26 @@ def test_starved_dependency_times_out_and_recovers():
     torch.cuda.synchronize()
     assert moe.moe_ffn_last_status(good.shape, good.workspace) == 0
     assert torch.equal(out, good.out)
+
+
+@pytest.mark.parametrize("case", CASES[1:4], ids=[c[0] for c in CASES[1:4]])
+def test_route_then_dispatch_to_combine_equals_forward(case):
+    """The layer in two calls (the routing launches, then the paper's timed interval) in either launch mode
+    gives what the one-call forward gives, bit for bit; the single launch consumes the queues the routing call
+    prepared, and a serialized one-call forward (which prepares none) in between does not disturb the next pair."""
+    from gpu_common import run_forward, small_config
+    cfg = small_config(*case)
+    inp = make_inputs(cfg)
+    want = run_forward(cfg, inp, mode=moe.MODE_SERIALIZED, store_h1=True)
+    R = int(want.saved.offsets.cpu()[-1])
+    for mode in (moe.MODE_SERIALIZED, moe.MODE_PERSISTENT, moe.MODE_PERSISTENT):
+        print(cfg.name, "mode", mode, flush=True)
+        run = run_forward(cfg, inp, mode=moe.MODE_SERIALIZED, store_h1=True)     # same buffers, one-call forward first
+        for t in (run.out, run.saved.Yp, run.saved.A, run.saved.H1):
+            t.fill_(float("nan"))
+        moe.moe_route(run.shape, run.dev["logits"], run.saved, run.workspace)
+        moe.moe_dispatch_to_combine(run.shape, run.dev["x"], run.dev["w_gate_up"], run.dev["w_down"], run.out, run.saved,
+                                    run.workspace, mode)
+        torch.cuda.synchronize()
+        assert moe.moe_ffn_last_status(run.shape, run.workspace) == 0
+        _assert_bit_identical(want, run, R)
