@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the Dispatch-to-Combine MoE-FFN layer on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3] [--no-cpu-baseline] [--no-backward]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3] [--no-cpu-baseline] [--no-backward] [--one-stream]
 
 A step is one pass of the whole forward hot path (routing, dispatch permute,
 grouped GEMM-1 + SwiGLU, grouped GEMM-2, weighted combine) over one batch of
@@ -11,6 +11,7 @@ backward graph is timed as well and reported under "detail", beside per-iteratio
 median / minimum times and a cold-cache variant of the forward.  Prints ONE JSON line.
 """
 import argparse
+import gc
 import json
 import os
 import sys
@@ -46,6 +47,9 @@ def main():
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-backward", action="store_true")
+    ap.add_argument("--one-stream", action="store_true",
+                    help="leave the two-stream forms of the backward out (for kernel traces: launches that share the "
+                         "chip have durations that say little about the kernel)")
     ap.add_argument("--headline-only", action="store_true",
                     help="time only the ceiling probes, the headline step, the backward and the stages (no inference / "
                          "cold / no-copy variants): the form the rocprofv3 summaries are taken from")
@@ -71,6 +75,11 @@ def main():
     moe.load_library()   # fails loudly if the HIP library is missing
     with_bwd = cfg.name == "c5" or not args.no_backward
     inp = make_inputs(cfg, with_dy=with_bwd)
+    # The timed loops enqueue from this thread: a cyclic-garbage pass of the interpreter (several ms with torch
+    # loaded) in the middle of one lets the GPU run dry and shows up as one launch of several ms in the per-stage
+    # event times.  Reference counting still frees everything this script drops.
+    gc.collect()
+    gc.disable()
     tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
     eb = 2 if cfg.dtype == "bf16" else 4
     shape = moe.make_shape(cfg.T, cfg.H, cfg.I, cfg.E, cfg.E_local, cfg.expert_base, cfg.k, tdt)
@@ -231,6 +240,8 @@ def main():
             # the two data-gradient GEMMs as one launch of tile tasks, the other operators as before
             bwd_variants["data_gradients_single_launch"] = (moe.MODE_PERSISTENT, False)
             bwd_variants["data_gradients_single_launch_two_streams"] = (moe.MODE_PERSISTENT, True)
+        if args.one_stream:
+            bwd_variants = {k: v for k, v in bwd_variants.items() if not v[1]}
         bwd_modes = {}
         for name, (bm, two) in bwd_variants.items():
             t = timed(lambda: step_bwd(bm, two), args.steps, args.warmup)
@@ -274,9 +285,11 @@ def main():
             fn()
             ev[it][i + 1].record(stream)
     torch.cuda.synchronize()
-    stage_us = {}
+    stage_us, stage_us_median, stage_us_max = {}, {}, {}
     for i, (name, _) in enumerate(stages):
-        stage_us[name] = float(np.mean([ev[it][i].elapsed_time(ev[it][i + 1]) for it in range(args.steps)]) * 1e3)
+        per_it = [ev[it][i].elapsed_time(ev[it][i + 1]) * 1e3 for it in range(args.steps)]
+        stage_us[name] = float(np.mean(per_it))
+        stage_us_median[name], stage_us_max[name] = float(np.median(per_it)), float(np.max(per_it))
 
     # ---- the paper's interval, Dispatch to Combine (Section 5.2), in both launch modes: routing once, then HIP events
     # around moe_dispatch_to_combine (serialized: four launches; persistent: exactly one)
@@ -347,7 +360,7 @@ def main():
             "backward_us_no_permuted_copy": noxp_bwd_ms * 1e3 if noxp_bwd_ms is not None else None,
             "us_per_layer_events": spread,
             "us_per_layer_cold": cold,
-            "stage_us": stage_us,
+            "stage_us": stage_us, "stage_us_median": stage_us_median, "stage_us_max": stage_us_max,
             "dispatch_to_combine_us": d2c_us,
             "dispatch_to_combine_us_sum_of_stages": sum(v for k, v in stage_us.items() if k != "route"),
             # every operand read once, every result written once (the figures the roofline fractions are quoted on)
