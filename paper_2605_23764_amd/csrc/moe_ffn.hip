@@ -425,11 +425,8 @@ bool wgrad_panel_fits(int M, int N) { return M % kWpM == 0 && N % kWpN == 0; }
 void launch_wgrad_bf16(GemmParams p, int grid, int n_cu, hipStream_t stream, const __bf16* a_general = nullptr) {
   p.k_lo = 0;
   if (wgrad_panel_fits(p.M, p.N)) {
-    const int n_nt = p.N / kWpN, panels = p.E_local * (p.M / kWpM);
-    int n_split = 1;   // smallest divisor of the tile count that gives every CU about four items
-    for (int d = 1; d <= n_nt; ++d)
-      if (n_nt % d == 0) { n_split = d; if ((long)panels * d >= 4L * n_cu) break; }
-    hipLaunchKernelGGL(grouped_wgrad_panel_bf16_kernel, dim3(grid), dim3(kWpThreads), 0, stream, p, n_split);
+    // the kernel splits every expert's tile row into column ranges so that each CU gets about four items
+    hipLaunchKernelGGL(grouped_wgrad_panel_bf16_kernel, dim3(grid), dim3(kWpThreads), 0, stream, p, 4 * n_cu);
     p.k_lo = kWpMaxRows + 1;
   }
   if (p.gather) { p.A = a_general; p.gather = nullptr; }

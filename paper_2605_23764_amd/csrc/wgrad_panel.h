@@ -374,14 +374,34 @@ __device__ __forceinline__ void wp_item(const WpCtx& t, int row0, char* smem) {
 #endif
 }
 
-// Launch condition: p.M % 256 == 0, p.N % 128 == 0, (p.N / 128) % n_split == 0.  Experts with more than
-// 384 rows are left alone (the general kernel takes them); experts without rows get zeros.
+// Launch condition: p.M % 256 == 0, p.N % 128 == 0.  Experts with more than 384 rows are left alone (the
+// general kernel takes them); experts without rows get zeros.  An item is (expert, one of n_split column
+// ranges, row panel); n_split is the smallest divisor of the N-tile count that gives the experts this kernel
+// really multiplies (1 .. 384 rows: counted here, the host never sees the counts) at least `want_items` items.
 // p.gather != nullptr: row k of expert e's segment of A is row p.gather[offsets[e] + k] of p.A (the
 // dispatch permutation applied while loading; the caller guarantees that p.A spans < 4 GB).
 __global__ __launch_bounds__(kWpThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void grouped_wgrad_panel_bf16_kernel(GemmParams p, int n_split) {
+void grouped_wgrad_panel_bf16_kernel(GemmParams p, int want_items) {
   __shared__ __attribute__((aligned(1024))) char smem[kWpLdsBytes];
-  const int n_mp = p.M / kWpM, NT = (p.N / kWpN) / n_split;
+  const int n_mp = p.M / kWpM, n_nt = p.N / kWpN;
+  int n_split = 1;
+  {
+    int mine = 0;   // every wave counts for itself: a wave-uniform result without a barrier
+    for (int e = lane_id(); e < p.E_local; e += kWave) {
+      const int cnt = p.offsets[e + 1] - p.offsets[e];
+      mine += cnt > 0 && cnt <= kWpMaxRows;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mine += __shfl_xor(mine, off, kWave);
+    // none to multiply (only zeros to write, or nothing): one range per expert, the fewest tickets
+    const int per_split = __builtin_amdgcn_readfirstlane(mine) * n_mp;
+    for (int d = 1; d <= (per_split > 0 ? n_nt : 1); ++d)
+      if (n_nt % d == 0) {
+        n_split = d;
+        if (per_split * d >= want_items) break;
+      }
+  }
+  const int NT = n_nt / n_split;
   const int per_e = n_split * n_mp;
   const int total = p.E_local * per_e;
   const int G = gridDim.x;
