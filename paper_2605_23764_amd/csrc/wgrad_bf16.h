@@ -207,25 +207,54 @@ __device__ __forceinline__ void wgrad_tile_bf16(const GemmParams& p, int e, int 
 }
 
 // Experts without rows get zeros (unless k_lo > 0 leaves them, like every expert with fewer than
-// k_lo rows, to the register-stationary kernel).  Tiles run N-tile-major inside an M tile inside an expert; an
-// XCD takes a contiguous range of them per sweep, so the CUs that share operand panels sit
-// behind one L2.
+// k_lo rows, to the register-stationary kernel).
+//
+// Work distribution.  A tile costs as much as its expert has rows, and with skewed routing the experts this
+// kernel takes differ by an order of magnitude while others are not its business at all.  Every workgroup
+// therefore first ranks the experts it has to do by rows, largest first, which gives one list of tiles,
+// N-tile-major inside an M tile inside an expert, without gaps and with neighbours of equal cost: a sweep of
+// G consecutive tiles over the G workgroups is then balanced by construction (all tiles of a sweep belong to
+// one expert or to two of neighbouring size), and the last, partly filled sweep holds the cheapest tiles.  An
+// XCD takes a contiguous range of every sweep, so the CUs that share operand panels sit behind one L2.
 __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void grouped_wgrad2_bf16_kernel(GemmParams p) {
   __shared__ __attribute__((aligned(1024))) char smem[kWgLdsBytes];
+  __shared__ int s_rows[kMaxE];      // rows of expert e if this kernel takes it, else -1
+  __shared__ int s_order[kMaxE];     // the experts it takes, most rows first
+  __shared__ int s_box[1];           // number of such experts
   const int n_mt = (p.M + kWgBM - 1) / kWgBM, n_nt = (p.N + kWgBN - 1) / kWgBN;
   const int per_e = n_mt * n_nt;
-  const int total = p.E_local * per_e;
-  const int G = gridDim.x;
   // nothing to do when the other kernel takes every expert (p.tiles.meta: the M-tile map's header, or nullptr)
   if (p.k_lo > 0 && p.tiles.meta && __builtin_amdgcn_readfirstlane(p.tiles.meta[kMetaMaxRows]) < p.k_lo) return;
+  for (int e = threadIdx.x; e < p.E_local; e += kGemmThreads) {
+    const int cnt = p.offsets[e + 1] - p.offsets[e];
+    s_rows[e] = cnt >= p.k_lo ? cnt : -1;
+  }
+  __syncthreads();
+  int n_mine = 0;
+  for (int e = threadIdx.x; e < p.E_local; e += kGemmThreads) {
+    const int cnt = s_rows[e];
+    int rank = 0;    // experts ahead of e: more rows, or as many and a lower id
+    for (int o = 0; o < p.E_local; ++o) {
+      const int c = s_rows[o];
+      rank += c >= 0 && (c > cnt || (c == cnt && o < e));
+    }
+    if (cnt >= 0) s_order[rank] = e;
+    n_mine += cnt >= 0;
+  }
+  if (threadIdx.x == 0) s_box[0] = 0;
+  __syncthreads();
+  if (n_mine) atomicAdd(&s_box[0], n_mine);
+  __syncthreads();
+  const int total = s_box[0] * per_e;
+  const int G = gridDim.x;
   for (int it = 0; it * G < total; ++it) {
     const int tile = xcd_tile_id(it, blockIdx.x, G);
     if (tile >= total) continue;
-    const int e = __builtin_amdgcn_readfirstlane(tile / per_e);
-    const int rem = tile - e * per_e;
+    const int r = tile / per_e;
+    const int e = __builtin_amdgcn_readfirstlane(s_order[r]);
+    const int rem = tile - r * per_e;
     const int mt = __builtin_amdgcn_readfirstlane(rem / n_nt);
-    if (__builtin_amdgcn_readfirstlane(p.offsets[e + 1] - p.offsets[e]) < p.k_lo) continue;
     wgrad_tile_bf16(p, e, mt, rem - mt * n_nt, smem);
   }
 }
