@@ -206,13 +206,35 @@ __device__ __forceinline__ void wgrad_tile_bf16(const GemmParams& p, int e, int 
   __builtin_amdgcn_s_barrier();                 // staging space is read out before the next tile's loads land in it
 }
 
+// Tile number r of an expert -> (M tile, N tile).  The tiles that run at the same time behind one L2 (64
+// consecutive numbers) should share as many operand panels as possible: a k step of an a x b block of tiles
+// reads a A-panels of 8 KB and b B-panels of 16 KB, which for 64 tiles is least around 8 x 8 (192 KB; a whole
+// row of N tiles at a time would be 288 KB at 16 N tiles and 466 KB at 28).  So the numbering runs block by
+// block: bands of 8 M tiles, inside a band blocks of 8 N tiles (the last block of a band narrower, the last
+// band lower), inside a block N-tile-major; no gaps.
+constexpr int kWgBlock = 8;
+__device__ __forceinline__ void wgrad_tile_of(int r, int n_mt, int n_nt, int& mt, int& nt) {
+  const int band = r / (kWgBlock * n_nt), rr = r - band * kWgBlock * n_nt;
+  const int h = min(kWgBlock, n_mt - kWgBlock * band);
+  const int full = n_nt / kWgBlock;
+  if (rr < h * kWgBlock * full) {
+    const int sbn = rr / (h * kWgBlock), i = rr - sbn * h * kWgBlock;
+    mt = band * kWgBlock + i / kWgBlock;
+    nt = sbn * kWgBlock + i % kWgBlock;
+  } else {
+    const int rem = rr - h * kWgBlock * full, w = n_nt - full * kWgBlock;
+    mt = band * kWgBlock + rem / w;
+    nt = full * kWgBlock + rem % w;
+  }
+}
+
 // Experts without rows get zeros (unless k_lo > 0 leaves them, like every expert with fewer than
 // k_lo rows, to the register-stationary kernel).
 //
 // Work distribution.  A tile costs as much as its expert has rows, and with skewed routing the experts this
 // kernel takes differ by an order of magnitude while others are not its business at all.  Every workgroup
 // therefore first ranks the experts it has to do by rows, largest first, which gives one list of tiles,
-// N-tile-major inside an M tile inside an expert, without gaps and with neighbours of equal cost: a sweep of
+// expert by expert (wgrad_tile_of inside an expert), without gaps and with neighbours of equal cost: a sweep of
 // G consecutive tiles over the G workgroups is then balanced by construction (all tiles of a sweep belong to
 // one expert or to two of neighbouring size), and the last, partly filled sweep holds the cheapest tiles.  An
 // XCD takes a contiguous range of every sweep, so the CUs that share operand panels sit behind one L2.
@@ -253,9 +275,9 @@ void grouped_wgrad2_bf16_kernel(GemmParams p) {
     if (tile >= total) continue;
     const int r = tile / per_e;
     const int e = __builtin_amdgcn_readfirstlane(s_order[r]);
-    const int rem = tile - r * per_e;
-    const int mt = __builtin_amdgcn_readfirstlane(rem / n_nt);
-    wgrad_tile_bf16(p, e, mt, rem - mt * n_nt, smem);
+    int mt, nt;
+    wgrad_tile_of(tile - r * per_e, n_mt, n_nt, mt, nt);
+    wgrad_tile_bf16(p, e, __builtin_amdgcn_readfirstlane(mt), __builtin_amdgcn_readfirstlane(nt), smem);
   }
 }
 
