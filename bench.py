@@ -185,6 +185,22 @@ def main():
             infer_ms[name] = timed(lambda: moe.moe_ffn_forward(shape, dev["x"], dev["logits"], dev["w_gate_up"],
                                                                dev["w_down"], out, None, ws, mode),
                                    args.steps, args.warmup)
+    # GEMM-2 with Combine in its epilogue (packed-bf16 atomic adds into the zeroed output; inference only, no Yp):
+    # whole layer with and without a permuted copy, and the stage pair (fill + GEMM-2) against GEMM-2 + Combine
+    scatter_ms = {}
+    if cfg.dtype == "bf16" and not args.headline_only:
+        for name, sv in (("with_permuted_copy", saved), ("inference", None)):
+            scatter_ms[name] = timed(lambda: moe.moe_ffn_forward_scatter(shape, dev["x"], dev["logits"], dev["w_gate_up"],
+                                                                         dev["w_down"], out, sv, ws),
+                                     args.steps, args.warmup)
+        step(moe.MODE_SERIALIZED)   # saved.A and the routing results of this `saved` for the stage calls
+        scatter_ms["stage_fill_plus_gemm2_scatter"] = timed(
+            lambda: moe.moe_grouped_gemm_scatter(shape, dev["w_down"], saved, out, ws), args.steps, args.warmup)
+
+        def gemm2_then_combine():
+            moe.moe_grouped_gemm(shape, dev["w_down"], saved, ws)
+            moe.moe_combine(shape, saved, out, ws)
+        scatter_ms["stage_gemm2_plus_combine"] = timed(gemm2_then_combine, args.steps, args.warmup)
     # per-iteration spread of the same step (events), and a cold variant: three sets of inputs, saved tensors,
     # workspace and output used in rotation, with a 1 GiB fill (4x the 256 MB Infinity Cache) ahead of each timed
     # iteration, so that neither the 4 MB L2s nor the Infinity Cache hold anything of the step from before
@@ -357,6 +373,7 @@ def main():
             "us_per_layer": {k: v * 1e3 for k, v in ms.items()},
             "us_per_layer_inference": {k: v * 1e3 for k, v in infer_ms.items()},
             "us_per_layer_no_permuted_copy": {k: v * 1e3 for k, v in noxp_ms.items()},
+            "us_scatter_epilogue": {k: v * 1e3 for k, v in scatter_ms.items()},
             "backward_us_no_permuted_copy": noxp_bwd_ms * 1e3 if noxp_bwd_ms is not None else None,
             "us_per_layer_events": spread,
             "us_per_layer_cold": cold,

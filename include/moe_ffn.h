@@ -270,6 +270,24 @@ int moe_grouped_gemm(const MoeShape* shape, const void* d_w_down, const MoeSaved
 int moe_combine(const MoeShape* shape, const MoeSaved* saved, void* d_out,
                 void* d_workspace, size_t workspace_bytes, void* stream);
 
+/* Grouped GEMM-2 with Combine in its epilogue (Section 4.4: the expert outputs reach their destination rows
+ * from the epilogue of the tile that made them, without a trip through HBM as a permuted tensor): zeroes
+ * out [T,H], then adds topk_w[t,j] * (A W_down[e])[r,:] to out[t,:] for every row r = row_of[t,j] with
+ * packed-bf16 atomic adds (device scope).  Two launches (fill, GEMM).  saved->Yp is NOT written, so a backward
+ * cannot follow (d_topk_w needs Yp): an inference path.  Rows of one token meet in no fixed order and every add
+ * rounds to bf16: the result equals moe_grouped_gemm + moe_combine up to bf16 rounding of the partial sums, not
+ * bit for bit, and is not reproducible bit for bit between runs for tokens with several local slots.
+ * bf16 only (MOE_ERR_INVALID_ARG for MOE_F32). */
+int moe_grouped_gemm_scatter(const MoeShape* shape, const void* d_w_down, const MoeSaved* saved, void* d_out,
+                             void* d_workspace, size_t workspace_bytes, void* stream);
+
+/* The forward pass with that epilogue: routing, Dispatch (or GEMM-1 reading x through the permutation when
+ * saved is NULL or saved->Xp is NULL), GEMM-1 + SwiGLU, then moe_grouped_gemm_scatter; no Combine launch.
+ * Arguments as moe_ffn_forward (one launch per operator); same limits as moe_grouped_gemm_scatter. */
+int moe_ffn_forward_scatter(const MoeShape* shape, const void* d_x, const float* d_logits, const void* d_w_gate_up,
+                            const void* d_w_down, void* d_out, const MoeSaved* saved, void* d_workspace,
+                            size_t workspace_bytes, void* stream);
+
 /* Dispatch to Combine, the interval the paper times (Section 5.2), on the routing results moe_route left in the
  * SAME `saved` and workspace: Dispatch permute, GEMM-1 + SwiGLU, GEMM-2, Combine.  mode MOE_MODE_SERIALIZED: one
  * launch per operator (Section 2.3's kernel-by-kernel execution); MOE_MODE_PERSISTENT: exactly one launch of

@@ -40,6 +40,7 @@ EXPORTS = (
     "moe_combine", "moe_microbench_workspace_bytes", "moe_microbench_swiglu_add", "moe_microbench_last_status",
     "moe_probe_mfma_bf16", "moe_probe_copy", "moe_probe_read", "moe_probe_write", "moe_microbench_swiglu_add_static_scratch",
     "moe_ffn_debug_force_device_scope", "moe_ffn_debug_layout", "moe_dispatch_to_combine",
+    "moe_grouped_gemm_scatter", "moe_ffn_forward_scatter",
 )
 LAYOUT_WORDS = 25   # MOE_LAYOUT_WORDS
 
@@ -226,6 +227,23 @@ def moe_grouped_gemm(shape, w_down, saved: Saved, workspace, stream=None) -> Non
     wp, wb = _ws(workspace)
     _check(load_library().moe_grouped_gemm(ctypes.byref(shape), _ptr(w_down), ctypes.byref(sv), wp, wb,
                                            _stream(stream)), "moe_grouped_gemm")
+
+
+def moe_grouped_gemm_scatter(shape, w_down, saved: Saved, out, workspace, stream=None) -> None:
+    sv = saved.c_struct()
+    wp, wb = _ws(workspace)
+    _check(load_library().moe_grouped_gemm_scatter(ctypes.byref(shape), _ptr(w_down), ctypes.byref(sv), _ptr(out), wp, wb,
+                                                   _stream(stream)), "moe_grouped_gemm_scatter")
+
+
+def moe_ffn_forward_scatter(shape, x, logits, w_gate_up, w_down, out, saved: Optional[Saved], workspace,
+                            stream=None) -> None:
+    sv = saved.c_struct() if saved is not None else None
+    wp, wb = _ws(workspace)
+    st = load_library().moe_ffn_forward_scatter(
+        ctypes.byref(shape), _ptr(x), _ptr(logits), _ptr(w_gate_up), _ptr(w_down), _ptr(out),
+        ctypes.byref(sv) if sv is not None else None, wp, wb, _stream(stream))
+    _check(st, "moe_ffn_forward_scatter")
 
 
 def moe_combine(shape, saved: Saved, out, workspace, stream=None) -> None:

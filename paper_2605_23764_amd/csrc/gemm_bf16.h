@@ -44,7 +44,7 @@ namespace moe {
 // The weight gradients (reduction over the expert's rows) have kernels of their own
 // (wgrad_panel.h, wgrad_bf16.h); they share GemmParams and the epilogue staging.
 enum GemmLayout { kLayNN = 0, kLayNT = 1 };
-enum GemmEpilogue { kEpiStore = 0, kEpiSwiglu = 1, kEpiSwigluGrad = 2 };
+enum GemmEpilogue { kEpiStore = 0, kEpiSwiglu = 1, kEpiSwigluGrad = 2, kEpiScatter = 3 };
 
 constexpr int kBM = 256;            // tile row capacity (one M tile of the tile map)
 constexpr int kBN = 256;            // weight columns staged per tile
@@ -76,6 +76,13 @@ struct GemmParams {
   const __bf16* G;    // SwiGLU-grad only: pre-activations saved by the forward [rows, 2N]
   const int32_t* gather;   // NN, optional: row r of the tile map is row gather[r] of A (A = the unpermuted tokens:
                            // the Dispatch permutation applied while loading, no permuted copy needed)
+  // kEpiScatter (GEMM-2 with Combine in its epilogue, Section 4.4): row r of the tile map is added, times
+  // sc_w[sc_token[r] * sc_k + sc_slot[r]], to row sc_token[r] of C (the layer output, zeroed beforehand)
+  const int32_t* sc_token;
+  const int32_t* sc_slot;
+  const int32_t* sc_row_of;   // [T, sc_k]: a token with one local slot (one entry >= 0) gets a plain store
+  const float* sc_w;
+  int sc_k;
   long strideB;       // elements between consecutive experts' weights (NN, NT)
   long strideC;       // weight gradients: elements between consecutive experts' outputs
   int K, N;           // N = output columns (SwiGLU: I, weights have 2N columns); weight gradients: K unused (rows of the expert)
@@ -477,6 +484,52 @@ __device__ __forceinline__ void store_block_via_lds(char* region, const u32x2 (&
   __builtin_amdgcn_wave_barrier();
 }
 
+// Combine in the epilogue (Section 4.4: the result rows never make the round trip through HBM as a permuted
+// tensor).  The block is staged like a stored block; then each of its rows goes out as ONE wave-wide packed-bf16
+// atomic add, lane l adding columns 2l, 2l + 1 of the row to the token's output row: whole 128-byte lines per
+// instruction, device scope, no return value.  tok: the token of this lane's row l32 (lanes r and r + 32 agree).
+// Several expert rows of one token may meet in any order, and every add rounds to bf16: results are equal to the
+// fixed-order Combine only up to that rounding.
+// one: bit r set = the token of row r has no other row on this GPU; the add into its zeroed output row is then
+// a plain store (no read-modify-write, and bit-reproducible).
+__device__ __forceinline__ void scatter_block_via_lds(char* region, const u32x2 (&pk)[4][4], __bf16* out, long ld,
+                                                      int tok, uint32_t one, int rows_valid, int cols_valid) {
+  typedef __attribute__((address_space(3))) char* lds_ptr;
+  typedef __attribute__((address_space(3))) u32x2* lds_u32x2_ptr;
+  typedef __attribute__((address_space(3))) const uint32_t* lds_u32_cptr;
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  typedef __attribute__((address_space(1))) bf16x2* global_bf16x2_ptr;
+  int lane = lane_id();
+  asm volatile("" : "+v"(lane));
+  const int l32 = lane & 31, lh = lane >> 5;
+  const lds_ptr base = (lds_ptr)region;
+#pragma unroll
+  for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) *(lds_u32x2_ptr)(base + l32 * kEpiRowBytes + (nt * 32 + q * 8 + lh * 4) * 2) = pk[nt][q];
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  uint32_t v[32];
+#pragma unroll
+  for (int r = 0; r < 32; ++r) v[r] = *(lds_u32_cptr)(base + r * kEpiRowBytes + lane * 4);
+  const bool col_ok = lane * 2 < cols_valid;
+#pragma unroll
+  for (int r = 0; r < 32; ++r) {
+    if (r < rows_valid) {                                        // wave-uniform
+      const int tr = __builtin_amdgcn_readlane(tok, r);
+      __bf16* dst = out + (size_t)tr * ld + lane * 2;
+      if (one >> r & 1) {                                          // wave-uniform
+        if (col_ok) *reinterpret_cast<uint32_t*>(dst) = v[r];
+      } else if (col_ok) {
+        __builtin_amdgcn_global_atomic_fadd_v2bf16((global_bf16x2_ptr)dst, __builtin_bit_cast(bf16x2, v[r]));
+      }
+    }
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
 // One output tile: (t0, t1) = (M tile of the tile map, N tile of TileShape<TALL>::kCols
 // columns; SwiGLU: half as many output columns).  X5: a wide tile of 257..320 rows (rows past 256 go
 // through the register-fed block of each wave row).
@@ -613,6 +666,31 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
   // ---- epilogue: lane holds row l32 of each 32 x 32 block and, per register group q,
   // the 4 consecutive columns q*8 + lh*4 .. +3; blocks leave through the wave's LDS region ----
   char* region = epilogue_region(smem, wave);
+  // Scatter epilogue: token, routing weight and single-slot flag of this lane's row in every block, fetched before
+  // the first block leaves (a load issued between the blocks would wait for all the adds in front of it: one
+  // in-order counter per wave).
+  int sc_tok[kAccMT];
+  float sc_wt[kAccMT];
+  uint32_t sc_one[kAccMT];
+  if constexpr (EPI == kEpiScatter) {
+#pragma unroll
+    for (int mt = 0; mt < kAccMT; ++mt) {
+      const int m0 = mt < kMaxMT ? row_base + mt * 32 : x_row0;
+      const bool live = !(mt < kMaxMT ? mt >= n_mt : !has_x) && l32 < rows - m0;
+      sc_tok[mt] = 0;
+      sc_wt[mt] = 0.f;
+      int others = 1;
+      if (live) {
+        const size_t r = (size_t)(row0 + m0 + l32);
+        const int tok = p.sc_token[r], slot = p.sc_slot[r];
+        sc_tok[mt] = tok;
+        sc_wt[mt] = p.sc_w[(size_t)tok * p.sc_k + slot];
+        others = 0;
+        for (int j = 0; j < p.sc_k; ++j) others += (j != slot && p.sc_row_of[(size_t)tok * p.sc_k + j] >= 0) ? 1 : 0;
+      }
+      sc_one[mt] = (uint32_t)__builtin_amdgcn_ballot_w64(others == 0);   // lanes r and r + 32 agree: the low half
+    }
+  }
 #pragma unroll
   for (int mt = 0; mt < kAccMT; ++mt) {
     const int m0 = mt < kMaxMT ? row_base + mt * 32 : x_row0;   // first row of the block inside the tile
@@ -677,6 +755,17 @@ __device__ __forceinline__ void gemm_tile_bf16(const GemmParams& p, int t0, int 
       __bf16* o = p.C + grow0 * p.ldc + c0;
       store_block_via_lds<4>(region, pdg, o, p.ldc, rows_valid, p.N - c0);
       store_block_via_lds<4>(region, pdu, o + p.N, p.ldc, rows_valid, p.N - c0);
+    } else if (EPI == kEpiScatter) {
+      const int c0 = ntile * S::kCols + wn * 128;
+      const float w = sc_wt[mt];
+      u32x2 pk[4][4];
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          pk[nt][q] = u32x2{pack_bf16(w * am[nt][q * 4 + 0], w * am[nt][q * 4 + 1]),
+                            pack_bf16(w * am[nt][q * 4 + 2], w * am[nt][q * 4 + 3])};
+      scatter_block_via_lds(region, pk, p.C + c0, p.ldc, sc_tok[mt], sc_one[mt], rows_valid, p.N - c0);
     } else {
       const int c0 = ntile * S::kCols + wn * 128;
       u32x2 pk[4][4];

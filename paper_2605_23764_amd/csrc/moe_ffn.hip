@@ -265,6 +265,22 @@ int run_gemm2(const Ctx& c, const void* w_down) {
   return launch_status();
 }
 
+// GEMM-2 with Combine in its epilogue: `out` is zeroed, then every result row is added, weighted, to its token's
+// row (packed-bf16 atomics).  Yp is not written.  bf16 only.
+int run_gemm2_scatter(const Ctx& c, const void* w_down, void* out, bool zeroed = false) {
+  if (!zeroed) {
+    const size_t n16 = (size_t)c.s.T * c.s.H * 2 / 16;
+    const size_t want = (n16 + 255) / 256;
+    const int grid = (int)(want < (size_t)c.n_cu * 8 ? (want > 0 ? want : 1) : (size_t)c.n_cu * 8);
+    hipLaunchKernelGGL(zero_fill_kernel, dim3(grid), dim3(256), 0, c.stream, static_cast<uint4*>(out), n16);
+  }
+  GemmParams p = gemm2_params<GemmParams, __bf16>(c, w_down);
+  p.C = static_cast<__bf16*>(out);
+  p.sc_token = c.sv.token_of; p.sc_slot = c.sv.slot_of; p.sc_row_of = c.sv.row_of; p.sc_w = c.sv.topk_w; p.sc_k = c.s.k;
+  hipLaunchKernelGGL((grouped_gemm_bf16_kernel<kLayNN, kEpiScatter>), dim3(gemm_grid(c)), dim3(kGemmThreads), 0, c.stream, p);
+  return launch_status();
+}
+
 CombineParams combine_params(const Ctx& c, void* out) {
   CombineParams p;
   p.Yp = c.sv.Yp; p.out = out; p.row_of = c.sv.row_of; p.topk_w = c.sv.topk_w;
@@ -310,6 +326,8 @@ SchedParams<BF16> sched_params(const Ctx& c, const void* x, const float* logits,
   sp.comb = combine_params(c, out);
   sp.no_permute = 0;
   sp.skip_tables = 0;
+  sp.zero_dst = nullptr;
+  sp.zero_n16 = 0;
   if constexpr (BF16) {
     if (gathers_x(c)) {
       sp.g1.A = static_cast<const T*>(x);
@@ -344,19 +362,28 @@ SchedParams<BF16> sched_params(const Ctx& c, const void* x, const float* logits,
 // stable ranks.  The second launch also zeroes the tile scheduler's counters and writes its task tables (one
 // workgroup, beside the rank groups), so that either launch mode can follow.
 template <bool BF16>
-int run_route_t(const Ctx& c, const float* logits, bool tables) {
+int run_route_t(const Ctx& c, const float* logits, bool tables, void* zero_out) {
   SchedParams<BF16> sp = sched_params<BF16>(c, nullptr, logits, nullptr, nullptr, nullptr);
   sp.skip_tables = tables ? 0 : 1;
   const RouteParams& rp = sp.route;
+  int fill_wgs = 0;
+  if (zero_out) {
+    sp.zero_dst = static_cast<uint4*>(zero_out);
+    sp.zero_n16 = (size_t)c.s.T * c.s.H * elem_bytes(c.s) / 16;
+    const size_t want = (sp.zero_n16 + kScanRankWaves * kWave - 1) / (kScanRankWaves * kWave);
+    fill_wgs = (int)(want < (size_t)c.n_cu * 4 ? want : (size_t)c.n_cu * 4);
+  }
   hipLaunchKernelGGL(route_kernel, dim3(rp.n_sub), dim3(512), 0, c.stream, rp);
-  hipLaunchKernelGGL(sched_prepare_kernel<BF16>, dim3(1 + (rp.n_groups + kScanRankWaves - 1) / kScanRankWaves),
+  hipLaunchKernelGGL(sched_prepare_kernel<BF16>, dim3(1 + (rp.n_groups + kScanRankWaves - 1) / kScanRankWaves + fill_wgs),
                      dim3(kScanRankWaves * kWave), 0, c.stream, sp);
   return launch_status();
 }
 // tables = false: the caller knows that one launch per operator follows (the task tables take workgroup 0 of the
 // second launch, which is the launch's critical path, about as long again as the prefix sums and the tile map).
-int run_route(const Ctx& c, const float* logits, bool tables = true) {
-  return c.s.dtype == MOE_BF16 ? run_route_t<true>(c, logits, tables) : run_route_t<false>(c, logits, tables);
+// zero_out: the layer output, zeroed by further workgroups of the second launch (scatter epilogue follows).
+int run_route(const Ctx& c, const float* logits, bool tables = true, void* zero_out = nullptr) {
+  return c.s.dtype == MOE_BF16 ? run_route_t<true>(c, logits, tables, zero_out)
+                               : run_route_t<false>(c, logits, tables, zero_out);
 }
 
 // Dispatch to Combine as ONE launch of tile tasks (after run_route on the same MoeSaved).
@@ -734,6 +761,34 @@ int moe_combine(const MoeShape* shape, const MoeSaved* saved, void* d_out, void*
   if (st != MOE_OK || c.s.T == 0) return st;
   if (!d_out || !aligned16(d_out) || !saved) return MOE_ERR_INVALID_ARG;
   return run_combine(c, d_out);
+}
+
+int moe_grouped_gemm_scatter(const MoeShape* shape, const void* d_w_down, const MoeSaved* saved, void* d_out,
+                             void* d_workspace, size_t workspace_bytes, void* stream) {
+  Ctx c;
+  int st = make_ctx(c, shape, saved, d_workspace, workspace_bytes, stream);
+  if (st != MOE_OK) return st;
+  if (c.s.dtype != MOE_BF16) return MOE_ERR_INVALID_ARG;
+  if (c.s.T == 0) return MOE_OK;
+  if (!d_w_down || !aligned16(d_w_down) || !d_out || !aligned16(d_out) || !saved) return MOE_ERR_INVALID_ARG;
+  return run_gemm2_scatter(c, d_w_down, d_out);
+}
+
+int moe_ffn_forward_scatter(const MoeShape* shape, const void* d_x, const float* d_logits, const void* d_w_gate_up,
+                            const void* d_w_down, void* d_out, const MoeSaved* saved, void* d_workspace,
+                            size_t workspace_bytes, void* stream) {
+  Ctx c;
+  int st = make_ctx(c, shape, saved, d_workspace, workspace_bytes, stream);
+  if (st != MOE_OK) return st;
+  if (c.s.dtype != MOE_BF16) return MOE_ERR_INVALID_ARG;
+  if (c.s.T == 0) return MOE_OK;
+  const void* ptrs[] = {d_x, d_logits, d_w_gate_up, d_w_down, d_out};
+  for (const void* q : ptrs)
+    if (!q || !aligned16(q)) return MOE_ERR_INVALID_ARG;
+  if ((st = run_route(c, d_logits, false, d_out)) != MOE_OK) return st;   // the output is zeroed beside the rank step
+  if (!gathers_x(c) && (st = run_permute(c, d_x)) != MOE_OK) return st;
+  if ((st = run_gemm1(c, d_w_gate_up, gathers_x(c) ? d_x : nullptr)) != MOE_OK) return st;
+  return run_gemm2_scatter(c, d_w_down, d_out, true);
 }
 
 // Dispatch -> GEMM-1 + SwiGLU -> GEMM-2 -> Combine on routing results that are already in `saved` / the workspace.

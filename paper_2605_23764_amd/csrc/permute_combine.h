@@ -212,4 +212,11 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineParams p) {
   for (int t = blockIdx.x * n_waves + wave; t < p.T; t += gridDim.x * n_waves) combine_token<BF16>(p, t);
 }
 
+// Zeroes n16 16-byte vectors at dst: the layer output ahead of a GEMM-2 whose epilogue adds its rows into it
+// (a kernel, not a memset node, so that the sequence can be captured in a graph).
+__global__ __launch_bounds__(256) void zero_fill_kernel(uint4* dst, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = make_uint4(0, 0, 0, 0);
+}
+
 }  // namespace moe

@@ -109,6 +109,8 @@ struct SchedParams {
   int no_permute;          // nobody needs Xp: GEMM-1 gathers its rows from x through token_of
   int force_device_scope;  // test hook: behave as if a worker had reported a foreign XCD
   int skip_tables;         // routing launch: the serialized operators follow, nobody reads counters or task tables
+  uint4* zero_dst;         // routing launch, optional: zero_n16 16-byte vectors that further workgroups of the launch
+  size_t zero_n16;         // set to zero (the layer output ahead of a GEMM-2 that adds its rows into it)
   uint32_t spin_limit;     // polls before a wait gives up (MOE_ERR_SCHED_TIMEOUT)
   int32_t timeout_status;
 };
@@ -344,6 +346,13 @@ __global__ __launch_bounds__(kScanRankWaves * kWave) void sched_prepare_kernel(S
     __threadfence_block();
     __syncthreads();   // tile map (written by wave 0) complete before every wave reads it
     if (!sp.skip_tables) build_task_tables<BF16>(sp);
+    return;
+  }
+  const int rank_wgs = (sp.route.n_groups + kScanRankWaves - 1) / kScanRankWaves;
+  if ((int)blockIdx.x > rank_wgs) {       // fill workgroups: the launch lasts as long as workgroup 0's chain anyway
+    const size_t stride = (size_t)(gridDim.x - 1 - rank_wgs) * blockDim.x;
+    for (size_t i = (size_t)(blockIdx.x - 1 - rank_wgs) * blockDim.x + threadIdx.x; i < sp.zero_n16; i += stride)
+      sp.zero_dst[i] = make_uint4(0, 0, 0, 0);
     return;
   }
   const int wave = threadIdx.x / kWave;

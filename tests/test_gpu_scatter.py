@@ -1,0 +1,120 @@
+"""GPU parity of the forward whose GEMM-2 epilogue does the Combine (Section 4.4: scatter / weighted epilogue,
+packed-bf16 atomic adds into the zeroed layer output) against the fp64 oracle, and against the fixed-order path.
+
+Tolerance.  The fixed-order Combine adds a token's k_loc local contributions in fp32 and rounds once; here every
+contribution is rounded to bf16 (2^-9 relative) and so is every partial sum, in whatever order the rows arrive:
+on top of the GEMM chain's own error (measured 2e-3..7e-3 of max|ref|) that is at most (2 k_loc - 1) * 2^-9 of the
+largest partial sum, random in sign.  1e-2 of max|ref| for k_loc <= 8, 2e-2 for k_loc = 16 (all 16 slots local)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from workloads import CONFIGS, make_inputs
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # name, T, H, I, E, E_local, base, k, dtype, seed
+    ("sc_a", 700, 256, 192, 8, 8, 0, 2, "bf16", 13),
+    ("sc_multi", 1500, 128, 128, 4, 4, 0, 2, "bf16", 14),
+    ("sc_shard", 513, 320, 64, 64, 7, 50, 8, "bf16", 15),
+    ("sc_k1", 65, 64, 64, 3, 3, 0, 1, "bf16", 16),
+    ("sc_kE", 130, 64, 128, 4, 4, 0, 4, "bf16", 17),
+    ("sc_limits", 97, 128, 64, 256, 256, 0, 16, "bf16", 19),
+    ("sc_tall", 1200, 192, 128, 4, 4, 0, 1, "bf16", 23),
+    ("sc_wide5", 1150, 192, 128, 4, 4, 0, 1, "bf16", 24),     # ~290 rows per expert: wide tiles with the fifth row block
+]
+
+
+def _scatter_forward(cfg, inp, saved_mode):
+    """saved_mode: 'saved' (MoeSaved with a permuted copy), 'no_xp' (MoeSaved without), 'none' (saved = NULL)."""
+    import paper_2605_23764_amd as moe
+    from gpu_common import to_device
+    shape = moe.make_shape(cfg.T, cfg.H, cfg.I, cfg.E, cfg.E_local, cfg.expert_base, cfg.k, torch.bfloat16)
+    dev = dict(x=to_device(inp["x"], "bf16"), logits=torch.from_numpy(inp["logits"]).cuda(),
+               w_gate_up=to_device(inp["w_gate_up"], "bf16"), w_down=to_device(inp["w_down"], "bf16"))
+    saved = None if saved_mode == "none" else moe.alloc_saved(shape, store_h1=False, keep_xp=(saved_mode == "saved"))
+    ws = moe.alloc_workspace(shape)
+    out = torch.full((cfg.T, cfg.H), float("nan"), dtype=torch.bfloat16, device="cuda")
+    moe.moe_ffn_forward_scatter(shape, dev["x"], dev["logits"], dev["w_gate_up"], dev["w_down"], out, saved, ws)
+    torch.cuda.synchronize()
+    return out, saved, shape, dev, ws
+
+
+@pytest.mark.parametrize("saved_mode", ["saved", "no_xp", "none"])
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_scatter_forward_small_shapes(case, saved_mode):
+    from gpu_common import rel_err, small_config, to_f64
+    cfg = small_config(*case)
+    inp = make_inputs(cfg)
+    ref = oracle.forward(inp["x"], inp["logits"], inp["w_gate_up"], inp["w_down"], cfg.k, cfg.expert_base, cfg.E_local)
+    out, saved, *_ = _scatter_forward(cfg, inp, saved_mode)
+    assert not torch.isnan(out.float()).any()
+    err = rel_err(to_f64(out), ref["out"])
+    tol = 2e-2 if cfg.k > 8 else 1e-2
+    print(cfg.name, saved_mode, "out %.2e" % err, flush=True)
+    assert err <= tol, f"out: {err:.3e} > {tol}"
+    none_local = np.all(ref["row_of"] < 0, axis=1)
+    if none_local.any():
+        assert torch.all(out[torch.from_numpy(none_local).cuda()] == 0)
+    if saved is not None:
+        np.testing.assert_array_equal(saved.row_of.cpu().numpy(), ref["row_of"])
+
+
+def test_scatter_equals_fixed_order_for_single_slot_tokens():
+    """A token with exactly one local slot receives one add into a zero: its row must equal the bf16 rounding of
+    weight * fp32 result, which differs from the fixed-order path (Yp rounded first, then weighted) by at most two
+    bf16 roundings; tokens without a local slot are exact zeros in both."""
+    import paper_2605_23764_amd as moe
+    from gpu_common import run_forward, small_config
+    cfg = small_config("sc_single", 900, 256, 128, 32, 4, 8, 2, "bf16", 31)
+    inp = make_inputs(cfg)
+    run = run_forward(cfg, inp)
+    out, *_ = _scatter_forward(cfg, inp, "saved")
+    n_loc = (run.saved.row_of >= 0).sum(dim=1)
+    single, none = n_loc == 1, n_loc == 0
+    assert single.any() and none.any()
+    assert torch.all(out[none] == 0) and torch.all(run.out[none] == 0)
+    a, b = out[single].float(), run.out[single].float()
+    assert torch.all((a - b).abs() <= 2.0 ** -7 * b.abs() + 1e-30)
+    out2, *_ = _scatter_forward(cfg, inp, "none")      # such rows are stored, not added: the same bits every time
+    assert torch.equal(out2[single], out[single])
+
+
+def test_scatter_stage_call_on_saved_routing():
+    """moe_grouped_gemm_scatter on the routing results and the A a forward left behind, twice in a row into the same
+    output (the call zeroes it itself)."""
+    import paper_2605_23764_amd as moe
+    from gpu_common import rel_err, run_forward, small_config, to_f64
+    cfg = small_config("sc_stage", 700, 256, 192, 8, 8, 0, 2, "bf16", 13)
+    inp = make_inputs(cfg)
+    ref = oracle.forward(inp["x"], inp["logits"], inp["w_gate_up"], inp["w_down"], cfg.k, cfg.expert_base, cfg.E_local)
+    run = run_forward(cfg, inp)
+    out = torch.full_like(run.out, float("nan"))
+    for _ in range(2):
+        moe.moe_grouped_gemm_scatter(run.shape, run.dev["w_down"], run.saved, out, run.workspace)
+    torch.cuda.synchronize()
+    assert rel_err(to_f64(out), ref["out"]) <= 1e-2
+
+
+def test_scatter_rejects_fp32():
+    import paper_2605_23764_amd as moe
+    shape = moe.make_shape(64, 64, 64, 4, 4, 0, 2, torch.float32)
+    ws = moe.alloc_workspace(shape)
+    x = torch.zeros(64 * 64 * 4, device="cuda")
+    with pytest.raises(moe.MoeError) as ei:
+        moe.moe_ffn_forward_scatter(shape, x, x, x, x, x, None, ws)
+    assert ei.value.status == -1
+
+
+@pytest.mark.parametrize("name", ["c3", "c4"])
+def test_scatter_forward_full_size(name):
+    from gpu_common import rel_err, to_f64
+    cfg = CONFIGS[name]
+    inp = make_inputs(cfg)
+    ref = oracle.forward(inp["x"], inp["logits"], inp["w_gate_up"], inp["w_down"], cfg.k, cfg.expert_base, cfg.E_local)
+    out, *_ = _scatter_forward(cfg, inp, "none")
+    err = rel_err(to_f64(out), ref["out"])
+    print(name, "out %.2e" % err, flush=True)
+    assert err <= 1e-2
