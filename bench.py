@@ -53,6 +53,9 @@ def main():
     ap.add_argument("--headline-only", action="store_true",
                     help="time only the ceiling probes, the headline step, the backward and the stages (no inference / "
                          "cold / no-copy variants): the form the rocprofv3 summaries are taken from")
+    ap.add_argument("--scatter", action="store_true",
+                    help="with --headline-only: also time the forward whose GEMM-2 epilogue does the Combine (for kernel "
+                         "traces and counter passes of that path; a full run times it anyway)")
     ap.add_argument("--hold", default=None, metavar="STAGE:SECONDS[,STAGE:SECONDS...]",
                     help="instead of the benchmark, run each named stage (idle, route, permute, gemm1_swiglu, gemm2, "
                          "combine, forward, backward, probe_mfma_random, probe_mfma_ones, probe_copy, probe_read, "
@@ -188,7 +191,7 @@ def main():
     # GEMM-2 with Combine in its epilogue (packed-bf16 atomic adds into the zeroed output; inference only, no Yp):
     # whole layer with and without a permuted copy, and the stage pair (fill + GEMM-2) against GEMM-2 + Combine
     scatter_ms = {}
-    if cfg.dtype == "bf16" and not args.headline_only:
+    if cfg.dtype == "bf16" and (args.scatter or not args.headline_only):
         for name, sv in (("with_permuted_copy", saved), ("inference", None)):
             scatter_ms[name] = timed(lambda: moe.moe_ffn_forward_scatter(shape, dev["x"], dev["logits"], dev["w_gate_up"],
                                                                          dev["w_down"], out, sv, ws),
