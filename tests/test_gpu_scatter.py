@@ -118,3 +118,59 @@ def test_scatter_forward_full_size(name):
     err = rel_err(to_f64(out), ref["out"])
     print(name, "out %.2e" % err, flush=True)
     assert err <= 1e-2
+
+
+@pytest.mark.parametrize("k", [1, 4])
+def test_scatter_forward_replays_from_a_graph(k):
+    """The call is kernel launches only (the output is zeroed by workgroups of the routing launch): captured once,
+    every replay with fresh inputs and eager work in between must reproduce the eager call, bit for bit where the
+    result has one order (k = 1: plain stores only), within the bf16 tolerance of the whole tensor otherwise (the order
+    of a token's adds differs from run to run)."""
+    import dataclasses
+    import paper_2605_23764_amd as moe
+    from gpu_common import small_config, to_device
+    cfg = small_config("sc_graph", 1500, 256, 256, 8, 8, 0, k, "bf16", 71)
+    shape = moe.make_shape(cfg.T, cfg.H, cfg.I, cfg.E, cfg.E_local, cfg.expert_base, cfg.k, torch.bfloat16)
+
+    def device_inputs(seed):
+        inp = make_inputs(dataclasses.replace(cfg, seed=seed))
+        return dict(x=to_device(inp["x"], "bf16"), logits=torch.from_numpy(inp["logits"]).cuda(),
+                    w1=to_device(inp["w_gate_up"], "bf16"), w2=to_device(inp["w_down"], "bf16"))
+    first = device_inputs(71)
+    x, logits, w1, w2 = first["x"].clone(), first["logits"].clone(), first["w1"], first["w2"]
+    ws = moe.alloc_workspace(shape)
+    out = torch.empty(cfg.T, cfg.H, dtype=torch.bfloat16, device="cuda")
+
+    def layer():
+        moe.moe_ffn_forward_scatter(shape, x, logits, w1, w2, out, None, ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        layer()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        layer()
+    torch.cuda.synchronize()
+    for replay, seed in enumerate((72, 73, 71)):
+        print(f"scatter graph k={k} replay={replay} seed={seed}", flush=True)
+        fresh = device_inputs(seed)
+        x.copy_(fresh["x"]); logits.copy_(fresh["logits"])
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = out.clone()
+        out.fill_(float("nan"))
+        layer()
+        torch.cuda.synchronize()
+        if k == 1:
+            assert torch.equal(got, out)
+        else:
+            a, b = got.float(), out.float()
+            assert not torch.isnan(a).any()
+            err = float((a - b).abs().max() / b.abs().max())
+            print("replay against eager: max|diff|/max|eager| = %.2e" % err, flush=True)
+            assert err <= 1e-2
