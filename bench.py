@@ -53,6 +53,7 @@ def main():
     ap.add_argument("--headline-only", action="store_true",
                     help="time only the ceiling probes, the headline step, the backward and the stages (no inference / "
                          "cold / no-copy variants): the form the rocprofv3 summaries are taken from")
+    ap.add_argument("--graph", action="store_true", help="with --headline-only: also time the step replayed from a HIP graph")
     ap.add_argument("--scatter", action="store_true",
                     help="with --headline-only: also time the forward whose GEMM-2 epilogue does the Combine (for kernel "
                          "traces and counter passes of that path; a full run times it anyway)")
@@ -179,6 +180,23 @@ def main():
                 raise moe.MoeError(st, name)
         except moe.MoeError as e:
             print(f"bench.py: mode {name} unavailable: {e}", file=sys.stderr)
+    # the same step replayed from a HIP graph (captured once: the calls only enqueue kernels, no memset nodes)
+    graph_ms = {}
+    if not args.headline_only or args.graph:
+        for name, mode in modes.items():
+            if name not in ms:
+                continue
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                step(mode)
+            torch.cuda.synchronize()
+            graph_ms[name] = timed(graph.replay, args.steps, args.warmup)
+            st = moe.moe_ffn_last_status(shape, ws)
+            if st != 0:
+                raise moe.MoeError(st, name + " (graph replay)")
+            del graph
     best = min(ms, key=ms.get)
     # inference (no saved tensors): GEMM-1 gathers the token rows itself, the permuted copy is not made;
     # reported beside the headline, which keeps the saved tensors a training step needs
@@ -374,6 +392,7 @@ def main():
         "roofline": roof,
         "detail": {
             "us_per_layer": {k: v * 1e3 for k, v in ms.items()},
+            "us_per_layer_graph_replay": {k: v * 1e3 for k, v in graph_ms.items()},
             "us_per_layer_inference": {k: v * 1e3 for k, v in infer_ms.items()},
             "us_per_layer_no_permuted_copy": {k: v * 1e3 for k, v in noxp_ms.items()},
             "us_scatter_epilogue": {k: v * 1e3 for k, v in scatter_ms.items()},
