@@ -211,9 +211,13 @@ def main():
     scatter_ms = {}
     if cfg.dtype == "bf16" and (args.scatter or not args.headline_only):
         for name, sv in (("with_permuted_copy", saved), ("inference", None)):
-            scatter_ms[name] = timed(lambda: moe.moe_ffn_forward_scatter(shape, dev["x"], dev["logits"], dev["w_gate_up"],
-                                                                         dev["w_down"], out, sv, ws),
-                                     args.steps, args.warmup)
+            for mname, mode in modes.items():
+                scatter_ms[name + "_" + mname] = timed(
+                    lambda: moe.moe_ffn_forward_scatter(shape, dev["x"], dev["logits"], dev["w_gate_up"], dev["w_down"],
+                                                        out, sv, ws, mode), args.steps, args.warmup)
+                st = moe.moe_ffn_last_status(shape, ws)
+                if st != 0:
+                    raise moe.MoeError(st, "scatter " + mname)
         step(moe.MODE_SERIALIZED)   # saved.A and the routing results of this `saved` for the stage calls
         scatter_ms["stage_fill_plus_gemm2_scatter"] = timed(
             lambda: moe.moe_grouped_gemm_scatter(shape, dev["w_down"], saved, out, ws), args.steps, args.warmup)

@@ -281,12 +281,15 @@ int moe_combine(const MoeShape* shape, const MoeSaved* saved, void* d_out,
 int moe_grouped_gemm_scatter(const MoeShape* shape, const void* d_w_down, const MoeSaved* saved, void* d_out,
                              void* d_workspace, size_t workspace_bytes, void* stream);
 
-/* The forward pass with that epilogue: routing, Dispatch (or GEMM-1 reading x through the permutation when
- * saved is NULL or saved->Xp is NULL), GEMM-1 + SwiGLU, then moe_grouped_gemm_scatter; no Combine launch.
- * Arguments as moe_ffn_forward (one launch per operator); same limits as moe_grouped_gemm_scatter. */
+/* The forward pass with that epilogue: routing (whose second launch also zeroes out), Dispatch (or GEMM-1
+ * reading x through the permutation when saved is NULL or saved->Xp is NULL), GEMM-1 + SwiGLU, GEMM-2 adding
+ * into out; no Combine.  mode MOE_MODE_SERIALIZED: one launch per operator; MOE_MODE_PERSISTENT: Dispatch to
+ * GEMM-2 as one launch of tile tasks without COMBINE tasks, so no task waits for the whole chip (alignment
+ * rule and moe_ffn_last_status as for moe_ffn_forward).  Other arguments as moe_ffn_forward; same limits as
+ * moe_grouped_gemm_scatter. */
 int moe_ffn_forward_scatter(const MoeShape* shape, const void* d_x, const float* d_logits, const void* d_w_gate_up,
                             const void* d_w_down, void* d_out, const MoeSaved* saved, void* d_workspace,
-                            size_t workspace_bytes, void* stream);
+                            size_t workspace_bytes, int mode, void* stream);
 
 /* Dispatch to Combine, the interval the paper times (Section 5.2), on the routing results moe_route left in the
  * SAME `saved` and workspace: Dispatch permute, GEMM-1 + SwiGLU, GEMM-2, Combine.  mode MOE_MODE_SERIALIZED: one

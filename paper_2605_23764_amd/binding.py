@@ -237,12 +237,12 @@ def moe_grouped_gemm_scatter(shape, w_down, saved: Saved, out, workspace, stream
 
 
 def moe_ffn_forward_scatter(shape, x, logits, w_gate_up, w_down, out, saved: Optional[Saved], workspace,
-                            stream=None) -> None:
+                            mode: int = MODE_SERIALIZED, stream=None) -> None:
     sv = saved.c_struct() if saved is not None else None
     wp, wb = _ws(workspace)
     st = load_library().moe_ffn_forward_scatter(
         ctypes.byref(shape), _ptr(x), _ptr(logits), _ptr(w_gate_up), _ptr(w_down), _ptr(out),
-        ctypes.byref(sv) if sv is not None else None, wp, wb, _stream(stream))
+        ctypes.byref(sv) if sv is not None else None, wp, wb, ctypes.c_int(mode), _stream(stream))
     _check(st, "moe_ffn_forward_scatter")
 
 

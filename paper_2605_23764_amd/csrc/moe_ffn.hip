@@ -394,6 +394,16 @@ int run_persistent(const Ctx& c, const void* x, const void* w_gate_up, const voi
   return launch_status();
 }
 
+// The same launch with Combine in the GEMM-2 tiles' epilogue (bf16; `out` zeroed by the routing launch).
+int run_persistent_scatter(const Ctx& c, const void* x, const void* w_gate_up, const void* w_down, void* out) {
+  SchedParams<true> sp = sched_params<true>(c, x, nullptr, w_gate_up, w_down, out);
+  sp.g2.C = static_cast<__bf16*>(out);
+  sp.g2.sc_token = c.sv.token_of; sp.g2.sc_slot = c.sv.slot_of; sp.g2.sc_row_of = c.sv.row_of;
+  sp.g2.sc_w = c.sv.topk_w; sp.g2.sc_k = c.s.k;
+  hipLaunchKernelGGL((persistent_forward_kernel<true, true>), dim3(gemm_grid(c)), dim3(kGemmThreads), 0, c.stream, sp);
+  return launch_status();
+}
+
 int run_combine(const Ctx& c, void* out) {
   CombineParams p = combine_params(c, out);
   long want = ((long)c.s.T + 3) / 4;
@@ -776,15 +786,21 @@ int moe_grouped_gemm_scatter(const MoeShape* shape, const void* d_w_down, const 
 
 int moe_ffn_forward_scatter(const MoeShape* shape, const void* d_x, const float* d_logits, const void* d_w_gate_up,
                             const void* d_w_down, void* d_out, const MoeSaved* saved, void* d_workspace,
-                            size_t workspace_bytes, void* stream) {
+                            size_t workspace_bytes, int mode, void* stream) {
   Ctx c;
   int st = make_ctx(c, shape, saved, d_workspace, workspace_bytes, stream);
   if (st != MOE_OK) return st;
   if (c.s.dtype != MOE_BF16) return MOE_ERR_INVALID_ARG;
+  if (mode != MOE_MODE_SERIALIZED && mode != MOE_MODE_PERSISTENT) return MOE_ERR_INVALID_ARG;
   if (c.s.T == 0) return MOE_OK;
   const void* ptrs[] = {d_x, d_logits, d_w_gate_up, d_w_down, d_out};
   for (const void* q : ptrs)
     if (!q || !aligned16(q)) return MOE_ERR_INVALID_ARG;
+  if (mode == MOE_MODE_PERSISTENT) {
+    if (!aligned128(c.ws) || !aligned128(c.sv.Xp) || !aligned128(c.sv.A)) return MOE_ERR_INVALID_ARG;
+    if ((st = run_route(c, d_logits, true, d_out)) != MOE_OK) return st;
+    return run_persistent_scatter(c, d_x, d_w_gate_up, d_w_down, d_out);
+  }
   if ((st = run_route(c, d_logits, false, d_out)) != MOE_OK) return st;   // the output is zeroed beside the rank step
   if (!gathers_x(c) && (st = run_permute(c, d_x)) != MOE_OK) return st;
   if ((st = run_gemm1(c, d_w_gate_up, gathers_x(c) ? d_x : nullptr)) != MOE_OK) return st;

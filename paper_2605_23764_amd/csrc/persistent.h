@@ -370,7 +370,9 @@ __device__ __forceinline__ void with_row_vectors(int vec_per_row, F&& f) {
   else f(std::integral_constant<int, 4>{});
 }
 
-template <bool BF16>
+// SCATTER (bf16): GEMM-2 tiles add their weighted rows into the zeroed layer output from their epilogue
+// (kEpiScatter), and the launch has no COMBINE tasks: nothing waits for the whole chip's GEMM-2 tiles.
+template <bool BF16, bool SCATTER = false>
 __device__ __forceinline__ void run_tile_task(const SchedParams<BF16>& sp, const TaskDesc& td, char* smem, volatile int* s_box,
                                               int wave, int q, long long& t_start, uint32_t& gemm2_done, int& scope) {
   const int type_n = __builtin_amdgcn_readfirstlane(td.type_n);
@@ -397,7 +399,7 @@ __device__ __forceinline__ void run_tile_task(const SchedParams<BF16>& sp, const
     else gemm_tile_f32<kEpiSwiglu>(sp.g1, m, idx, reinterpret_cast<float*>(smem));
     sched_trigger(sp, kEvPerTile + sp.max_mtiles + m, wave, scope);
   } else {
-    if constexpr (BF16) gemm_map_tile_bf16<kLayNN, kEpiStore>(sp.g2, m, idx, narrow || tile_is_tall(__builtin_amdgcn_readfirstlane(sp.route.tiles.rows[m])), smem);
+    if constexpr (BF16) gemm_map_tile_bf16<kLayNN, SCATTER ? kEpiScatter : kEpiStore>(sp.g2, m, idx, narrow || tile_is_tall(__builtin_amdgcn_readfirstlane(sp.route.tiles.rows[m])), smem);
     else gemm_tile_f32<kEpiStore>(sp.g2, m, idx, reinterpret_cast<float*>(smem));
     // COMBINE waits for every GEMM-2 tile, so completions are counted here and published once per
     // worker after its queue has drained: a device-scope release per tile would write back the
@@ -406,9 +408,10 @@ __device__ __forceinline__ void run_tile_task(const SchedParams<BF16>& sp, const
   }
 }
 
-template <bool BF16>
+template <bool BF16, bool SCATTER = false>
 __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void persistent_forward_kernel(SchedParams<BF16> sp) {
+  static_assert(BF16 || !SCATTER, "the scatter epilogue exists for bf16 only");
   __shared__ __attribute__((aligned(1024))) char smem[kGemmLdsBytes];
   // between tasks the staging area is idle: its first words carry the ticket and the wait result
   volatile int* s_box = reinterpret_cast<volatile int*>(smem);
@@ -428,12 +431,13 @@ void persistent_forward_kernel(SchedParams<BF16> sp) {
       const TaskDesc td = sp.tasks[(size_t)q * sp.max_tasks_per_q + t];
       MOE_TRACE_FETCH(td.type_n & kTaskTypeMask, td.m, td.type_n >> 8)
       long long t_start = 0;
-      run_tile_task(sp, td, smem, s_box, wave, q, t_start, gemm2_done, scope);
+      run_tile_task<BF16, SCATTER>(sp, td, smem, s_box, wave, q, t_start, gemm2_done, scope);
 #if defined(MOE_SCHED_TRACE)
       tr_.t_start = t_start;
 #endif
       MOE_TRACE_END(sp)
     }
+    if (SCATTER) return;   // no COMBINE tasks; the adds are complete when the launch is
     if (gemm2_done) sched_trigger(sp, kEvGemm2, wave, kScopeDevice, gemm2_done);
   }
 

@@ -27,7 +27,7 @@ CASES = [
 ]
 
 
-def _scatter_forward(cfg, inp, saved_mode):
+def _scatter_forward(cfg, inp, saved_mode, mode=0):
     """saved_mode: 'saved' (MoeSaved with a permuted copy), 'no_xp' (MoeSaved without), 'none' (saved = NULL)."""
     import paper_2605_23764_amd as moe
     from gpu_common import to_device
@@ -37,23 +37,26 @@ def _scatter_forward(cfg, inp, saved_mode):
     saved = None if saved_mode == "none" else moe.alloc_saved(shape, store_h1=False, keep_xp=(saved_mode == "saved"))
     ws = moe.alloc_workspace(shape)
     out = torch.full((cfg.T, cfg.H), float("nan"), dtype=torch.bfloat16, device="cuda")
-    moe.moe_ffn_forward_scatter(shape, dev["x"], dev["logits"], dev["w_gate_up"], dev["w_down"], out, saved, ws)
+    moe.moe_ffn_forward_scatter(shape, dev["x"], dev["logits"], dev["w_gate_up"], dev["w_down"], out, saved, ws, mode)
     torch.cuda.synchronize()
+    if mode == 1:
+        assert moe.moe_ffn_last_status(shape, ws) == 0
     return out, saved, shape, dev, ws
 
 
+@pytest.mark.parametrize("mode", [0, 1], ids=["serialized", "persistent"])
 @pytest.mark.parametrize("saved_mode", ["saved", "no_xp", "none"])
 @pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
-def test_scatter_forward_small_shapes(case, saved_mode):
+def test_scatter_forward_small_shapes(case, saved_mode, mode):
     from gpu_common import rel_err, small_config, to_f64
     cfg = small_config(*case)
     inp = make_inputs(cfg)
     ref = oracle.forward(inp["x"], inp["logits"], inp["w_gate_up"], inp["w_down"], cfg.k, cfg.expert_base, cfg.E_local)
-    out, saved, *_ = _scatter_forward(cfg, inp, saved_mode)
+    out, saved, *_ = _scatter_forward(cfg, inp, saved_mode, mode)
     assert not torch.isnan(out.float()).any()
     err = rel_err(to_f64(out), ref["out"])
     tol = 2e-2 if cfg.k > 8 else 1e-2
-    print(cfg.name, saved_mode, "out %.2e" % err, flush=True)
+    print(cfg.name, saved_mode, mode, "out %.2e" % err, flush=True)
     assert err <= tol, f"out: {err:.3e} > {tol}"
     none_local = np.all(ref["row_of"] < 0, axis=1)
     if none_local.any():
@@ -78,8 +81,10 @@ def test_scatter_equals_fixed_order_for_single_slot_tokens():
     assert torch.all(out[none] == 0) and torch.all(run.out[none] == 0)
     a, b = out[single].float(), run.out[single].float()
     assert torch.all((a - b).abs() <= 2.0 ** -7 * b.abs() + 1e-30)
-    out2, *_ = _scatter_forward(cfg, inp, "none")      # such rows are stored, not added: the same bits every time
-    assert torch.equal(out2[single], out[single])
+    for mode in (0, 1):                                # such rows are stored, not added: the same bits every time
+        out2, *_ = _scatter_forward(cfg, inp, "none", mode)
+        assert torch.equal(out2[single], out[single]), mode
+        assert torch.all(out2[none] == 0)
 
 
 def test_scatter_stage_call_on_saved_routing():
@@ -106,6 +111,10 @@ def test_scatter_rejects_fp32():
     with pytest.raises(moe.MoeError) as ei:
         moe.moe_ffn_forward_scatter(shape, x, x, x, x, x, None, ws)
     assert ei.value.status == -1
+    bf = moe.make_shape(64, 64, 64, 4, 4, 0, 2, torch.bfloat16)
+    with pytest.raises(moe.MoeError) as ei:
+        moe.moe_ffn_forward_scatter(bf, x, x, x, x, x, None, moe.alloc_workspace(bf), 2)   # no such mode
+    assert ei.value.status == -1
 
 
 @pytest.mark.parametrize("name", ["c3", "c4"])
@@ -114,14 +123,16 @@ def test_scatter_forward_full_size(name):
     cfg = CONFIGS[name]
     inp = make_inputs(cfg)
     ref = oracle.forward(inp["x"], inp["logits"], inp["w_gate_up"], inp["w_down"], cfg.k, cfg.expert_base, cfg.E_local)
-    out, *_ = _scatter_forward(cfg, inp, "none")
-    err = rel_err(to_f64(out), ref["out"])
-    print(name, "out %.2e" % err, flush=True)
-    assert err <= 1e-2
+    for mode in (0, 1):
+        out, *_ = _scatter_forward(cfg, inp, "none", mode)
+        err = rel_err(to_f64(out), ref["out"])
+        print(name, "mode", mode, "out %.2e" % err, flush=True)
+        assert err <= 1e-2
 
 
+@pytest.mark.parametrize("mode", [0, 1], ids=["serialized", "persistent"])
 @pytest.mark.parametrize("k", [1, 4])
-def test_scatter_forward_replays_from_a_graph(k):
+def test_scatter_forward_replays_from_a_graph(k, mode):
     """The call is kernel launches only (the output is zeroed by workgroups of the routing launch): captured once,
     every replay with fresh inputs and eager work in between must reproduce the eager call, bit for bit where the
     result has one order (k = 1: plain stores only), within the bf16 tolerance of the whole tensor otherwise (the order
@@ -142,7 +153,7 @@ def test_scatter_forward_replays_from_a_graph(k):
     out = torch.empty(cfg.T, cfg.H, dtype=torch.bfloat16, device="cuda")
 
     def layer():
-        moe.moe_ffn_forward_scatter(shape, x, logits, w1, w2, out, None, ws)
+        moe.moe_ffn_forward_scatter(shape, x, logits, w1, w2, out, None, ws, mode)
 
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
@@ -155,13 +166,15 @@ def test_scatter_forward_replays_from_a_graph(k):
         layer()
     torch.cuda.synchronize()
     for replay, seed in enumerate((72, 73, 71)):
-        print(f"scatter graph k={k} replay={replay} seed={seed}", flush=True)
+        print(f"scatter graph k={k} mode={mode} replay={replay} seed={seed}", flush=True)
         fresh = device_inputs(seed)
         x.copy_(fresh["x"]); logits.copy_(fresh["logits"])
         out.fill_(float("nan"))
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
+        if mode == 1:
+            assert moe.moe_ffn_last_status(shape, ws) == 0
         got = out.clone()
         out.fill_(float("nan"))
         layer()
