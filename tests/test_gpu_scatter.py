@@ -4,7 +4,9 @@ packed-bf16 atomic adds into the zeroed layer output) against the fp64 oracle, a
 Tolerance.  The fixed-order Combine adds a token's k_loc local contributions in fp32 and rounds once; here every
 contribution is rounded to bf16 (2^-9 relative) and so is every partial sum, in whatever order the rows arrive:
 on top of the GEMM chain's own error (measured 2e-3..7e-3 of max|ref|) that is at most (2 k_loc - 1) * 2^-9 of the
-largest partial sum, random in sign.  1e-2 of max|ref| for k_loc <= 8, 2e-2 for k_loc = 16 (all 16 slots local)."""
+largest partial sum, random in sign and different from run to run.  1e-2 of max|ref| where no token has more than
+4 local slots (measured <= 5.4e-3), 2.5e-2 otherwise (measured up to 1.44e-2 with 8 local slots per token in 80
+random shapes, 8.6e-3..9.9e-3 with 16; the worst case of the bound is 2.9e-2 for 8)."""
 import numpy as np
 import pytest
 import torch
@@ -22,6 +24,7 @@ CASES = [
     ("sc_k1", 65, 64, 64, 3, 3, 0, 1, "bf16", 16),
     ("sc_kE", 130, 64, 128, 4, 4, 0, 4, "bf16", 17),
     ("sc_limits", 97, 128, 64, 256, 256, 0, 16, "bf16", 19),
+    ("sc_all8", 600, 192, 128, 8, 8, 0, 8, "bf16", 25),       # every token adds 8 rows
     ("sc_tall", 1200, 192, 128, 4, 4, 0, 1, "bf16", 23),
     ("sc_wide5", 1150, 192, 128, 4, 4, 0, 1, "bf16", 24),     # ~290 rows per expert: wide tiles with the fifth row block
 ]
@@ -55,7 +58,7 @@ def test_scatter_forward_small_shapes(case, saved_mode, mode):
     out, saved, *_ = _scatter_forward(cfg, inp, saved_mode, mode)
     assert not torch.isnan(out.float()).any()
     err = rel_err(to_f64(out), ref["out"])
-    tol = 2e-2 if cfg.k > 8 else 1e-2
+    tol = 1e-2 if int((ref["row_of"] >= 0).sum(axis=1).max()) <= 4 else 2.5e-2
     print(cfg.name, saved_mode, mode, "out %.2e" % err, flush=True)
     assert err <= tol, f"out: {err:.3e} > {tol}"
     none_local = np.all(ref["row_of"] < 0, axis=1)
